@@ -1,0 +1,257 @@
+"""CPU oracle for the actor's experience-generation phase (TEST INFRASTRUCTURE).
+
+This file is the slow, plain definition of what the HIP engine must compute.
+Only tests, the smoke check and the benchmark's `cpu_baseline` leg may import
+it; the product never does.  It shares no code with the HIP path.
+
+What the paper fixes (Section 4; Section 5.3 (I)): the actor model is run in
+inference mode, first over the whole prompt, then once per generated token
+with the keys/values of earlier positions kept in a cache; exactly `G` tokens
+are produced after an `S`-token prompt.  The paper names the model family
+(OPT, Section 2 and Tables 1-3) but prints none of its equations, so the
+decoder below is the published OPT architecture as the benchmark definition
+constrains it: pre-LayerNorm, learned absolute positions, multi-head causal
+self-attention with biases, ReLU feed-forward, a final LayerNorm and an LM
+head that may be tied to the token embedding.
+
+All arithmetic is float64 (numpy); `@` (BLAS matmul) is the only library
+primitive.  A KV-cached decode reaches, up to rounding order, exactly the
+result of the cache-free forward, so `forward_full` IS the definition and
+`CachedDecoder` is checked against it in the tests.
+
+Pins (tests/test_oracle_*.py): cached == cache-free; softmax rows sum to 1;
+causal exactness; closed forms for degenerate weights; every primitive against
+torch's float64 CPU routine; whole model against an independently written
+OPT implementation (transformers, random init); Philox known-answer vectors;
+Gumbel-max token frequencies against softmax.  The bf16 tolerance (2e-2) is
+fixed by the benchmark definition, not by the paper: parity unpinned for that
+number only.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+# --------------------------------------------------------------------------
+# primitives
+# --------------------------------------------------------------------------
+
+
+def layer_norm(u, gamma, beta, eps):
+    """(u - mean) / sqrt(biased variance + eps) * gamma + beta over the last axis."""
+    u = np.asarray(u, F64)
+    mu = u.mean(axis=-1, keepdims=True)
+    var = ((u - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (u - mu) / np.sqrt(var + eps) * np.asarray(gamma, F64) + np.asarray(beta, F64)
+
+
+def linear(x, W, b=None):
+    """y = x W^T + b with W stored [out, in]."""
+    y = np.asarray(x, F64) @ np.asarray(W, F64).T
+    if b is not None:
+        y = y + np.asarray(b, F64)
+    return y
+
+
+def softmax_masked(s, allowed):
+    """Row softmax over the allowed entries only; the others get probability 0."""
+    s = np.where(allowed, s, -np.inf)
+    m = s.max(axis=-1, keepdims=True)
+    e = np.exp(s - m)  # exp(-inf) == 0 exactly
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention(q, k, v, q_pos):
+    """One head.  q [Tq,d] (already scaled) sits at absolute positions q_pos[i];
+    k, v [Tk,d] sit at positions 0..Tk-1.  Query i sees keys j <= q_pos[i]."""
+    s = q @ k.T
+    allowed = np.arange(k.shape[0])[None, :] <= np.asarray(q_pos)[:, None]
+    p = softmax_masked(s, allowed)
+    return p @ v, p
+
+
+def log_softmax(z):
+    m = z.max(axis=-1, keepdims=True)
+    return z - (m + np.log(np.exp(z - m).sum(axis=-1, keepdims=True)))
+
+
+# --------------------------------------------------------------------------
+# the decoder
+# --------------------------------------------------------------------------
+
+
+def _layer(x, lw, n_heads, eps, k_past, v_past, pos0):
+    """One pre-LN decoder layer over x [B,M,H] whose rows sit at positions
+    pos0..pos0+M-1; k_past/v_past [B,pos0,H] are earlier positions (or None).
+    Returns (x_out, k_all, v_all)."""
+    B, M, H = x.shape
+    d = H // n_heads
+    a = layer_norm(x, lw["ln1_g"], lw["ln1_b"], eps)
+    qkv = linear(a, lw["wqkv"], lw["bqkv"])
+    q = qkv[..., 0:H] * d ** -0.5
+    k = qkv[..., H:2 * H]
+    v = qkv[..., 2 * H:3 * H]
+    if k_past is not None:
+        k = np.concatenate([k_past, k], axis=1)
+        v = np.concatenate([v_past, v], axis=1)
+    q_pos = pos0 + np.arange(M)
+    o = np.empty((B, M, H), F64)
+    for b in range(B):
+        for h in range(n_heads):
+            sl = slice(h * d, (h + 1) * d)
+            o[b, :, sl], _ = attention(q[b, :, sl], k[b, :, sl], v[b, :, sl], q_pos)
+    x = x + linear(o, lw["wo"], lw["bo"])
+    a2 = layer_norm(x, lw["ln2_g"], lw["ln2_b"], eps)
+    hdn = np.maximum(linear(a2, lw["w1"], lw["b1"]), 0.0)
+    x = x + linear(hdn, lw["w2"], lw["b2"])
+    return x, k, v
+
+
+def embed(w, ids, pos0, pos_offset):
+    ids = np.asarray(ids)
+    M = ids.shape[1]
+    tok = np.asarray(w["tok_emb"], F64)[ids]
+    pos = np.asarray(w["pos_emb"], F64)[pos_offset + pos0 + np.arange(M)]
+    return tok + pos[None, :, :]
+
+
+def lm_logits(w, x, eps):
+    xf = layer_norm(x, w["lnf_g"], w["lnf_b"], eps)
+    return linear(xf, w["lm_head"])
+
+
+def forward_full(w, ids, n_heads, eps=1e-5, pos_offset=0):
+    """Cache-free forward over ids [B,T]: logits [B,T,V] at every position."""
+    x = embed(w, ids, 0, pos_offset)
+    for lw in w["layers"]:
+        x, _, _ = _layer(x, lw, n_heads, eps, None, None, 0)
+    return lm_logits(w, x, eps)
+
+
+class CachedDecoder:
+    """Prefill + one-token steps with per-layer K/V kept for earlier positions."""
+
+    def __init__(self, w, n_heads, eps=1e-5, pos_offset=0):
+        self.w, self.n_heads, self.eps, self.pos_offset = w, n_heads, eps, pos_offset
+        self.k = [None] * len(w["layers"])
+        self.v = [None] * len(w["layers"])
+        self.length = 0
+
+    def _run(self, ids, all_positions):
+        x = embed(self.w, ids, self.length, self.pos_offset)
+        for i, lw in enumerate(self.w["layers"]):
+            x, self.k[i], self.v[i] = _layer(x, lw, self.n_heads, self.eps, self.k[i], self.v[i], self.length)
+        self.length += np.asarray(ids).shape[1]
+        if not all_positions:
+            x = x[:, -1:, :]
+        return lm_logits(self.w, x, self.eps)
+
+    def prefill(self, ids, all_positions=False):
+        """ids [B,S] -> logits of the last position [B,V] (or all [B,S,V])."""
+        assert self.length == 0
+        z = self._run(ids, all_positions)
+        return z if all_positions else z[:, 0, :]
+
+    def step(self, ids):
+        """ids [B] (one new token per sequence) -> logits [B,V]."""
+        return self._run(np.asarray(ids).reshape(-1, 1), False)[:, 0, :]
+
+
+# --------------------------------------------------------------------------
+# counter-based RNG and sampling
+# --------------------------------------------------------------------------
+
+_PHILOX_M0 = np.uint64(0xD2511F53)
+_PHILOX_M1 = np.uint64(0xCD9E8D57)
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+_MASK32 = np.uint64(0xFFFFFFFF)
+
+
+def philox4x32_10(c0, c1, c2, c3, k0, k1):
+    """Philox-4x32 with 10 rounds (Salmon et al., SC'11).  Counter words c0..c3
+    and key words k0,k1 are uint32 (arrays broadcast); returns 4 uint32 arrays."""
+    c0, c1, c2, c3 = (np.asarray(c, np.uint64) & _MASK32 for c in (c0, c1, c2, c3))
+    k0 = int(k0) & 0xFFFFFFFF
+    k1 = int(k1) & 0xFFFFFFFF
+    for r in range(10):
+        p0 = _PHILOX_M0 * c0  # 32x32 -> 64 bit products, exact in uint64
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & _MASK32
+        hi1, lo1 = p1 >> np.uint64(32), p1 & _MASK32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ np.uint64(k0)), lo1, (hi0 ^ c3 ^ np.uint64(k1)), lo0
+        k0 = (k0 + _PHILOX_W0) & 0xFFFFFFFF
+        k1 = (k1 + _PHILOX_W1) & 0xFFFFFFFF
+    return tuple(c.astype(np.uint32) for c in (c0, c1, c2, c3))
+
+
+def random_u32(seed, b, n, v):
+    """The engine's random word for (sequence b, generation step n, vocab id v):
+    word 0 of Philox4x32-10 with counter (v, n, b, 0) and key (seed lo, seed hi)."""
+    seed = int(seed) & 0xFFFFFFFFFFFFFFFF
+    return philox4x32_10(v, n, b, 0, seed & 0xFFFFFFFF, seed >> 32)[0]
+
+
+def uniform_open(x_u32):
+    """u = ((x >> 9) + 1/2) * 2^-23, strictly inside (0,1), exact in fp32."""
+    return ((np.asarray(x_u32, np.uint32) >> np.uint32(9)).astype(F64) + 0.5) * 2.0 ** -23
+
+
+def gumbel_noise(seed, b, n, V):
+    """g_v = -log(-log(u_v)) for v = 0..V-1."""
+    u = uniform_open(random_u32(seed, b, n, np.arange(V, dtype=np.uint32)))
+    return -np.log(-np.log(u))
+
+
+def sample(z, mode, temperature, seed, n):
+    """z [B,V] logits of generation step n.  Returns (tok int32 [B],
+    logprob [B], margin [B]): greedy takes argmax z; 'gumbel' takes
+    argmax(z/temperature + g).  Ties go to the lowest index.  logprob is the
+    untempered log-softmax of z at tok; margin is the gap between the best and
+    second-best arg-maxed score (ids are only unique where it is large)."""
+    z = np.asarray(z, F64)
+    B, V = z.shape
+    lp = log_softmax(z)
+    tok = np.empty(B, np.int32)
+    margin = np.empty(B, F64)
+    for b in range(B):
+        if mode == "greedy":
+            score = z[b]
+        elif mode == "gumbel":
+            score = z[b] / temperature + gumbel_noise(seed, b, n, V)
+        else:
+            raise ValueError(mode)
+        t = int(np.argmax(score))  # first maximum = lowest index
+        tok[b] = t
+        if V > 1:
+            rest = np.delete(score, t)
+            margin[b] = score[t] - rest.max()
+        else:
+            margin[b] = np.inf
+    return tok, lp[np.arange(B), tok], margin
+
+
+def generate(w, prompt_ids, G, n_heads, mode="greedy", temperature=1.0, seed=0,
+             eps=1e-5, pos_offset=0, forced_ids=None):
+    """Prefill the prompt [B,S], then G-1 cached steps: exactly G tokens, no
+    stop token.  Token 0 comes from the prompt's last position.  If forced_ids
+    [B,G] is given, those ids are fed forward instead of the sampled ones
+    (teacher forcing) while the sampled ids are still reported.
+
+    Returns dict(ids [B,G], logprobs [B,G], margins [B,G], logits [G,B,V])."""
+    prompt_ids = np.asarray(prompt_ids)
+    B = prompt_ids.shape[0]
+    dec = CachedDecoder(w, n_heads, eps, pos_offset)
+    ids = np.empty((B, G), np.int32)
+    lps = np.empty((B, G), F64)
+    mar = np.empty((B, G), F64)
+    logits = []
+    z = dec.prefill(prompt_ids)
+    for n in range(G):
+        logits.append(z)
+        ids[:, n], lps[:, n], mar[:, n] = sample(z, mode, temperature, seed, n)
+        if n + 1 < G:
+            feed = ids[:, n] if forced_ids is None else np.asarray(forced_ids)[:, n]
+            z = dec.step(feed)
+    return {"ids": ids, "logprobs": lps, "margins": mar, "logits": np.stack(logits)}

@@ -1,0 +1,346 @@
+"""Pins for the CPU oracle: each test ties it to something other than itself
+(brute force, invariants, closed forms, library routines, an independently
+written OPT implementation, published known-answer vectors).  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import opt_oracle as O
+from paper_2308_01320_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny_dims(**kw):
+    base = dict(name="t", n_layers=2, hidden=32, n_heads=4, ffn=64, vocab=50, max_positions=24,
+                batch=2, prompt_len=5, gen_len=4, dtype="f32", sampling="greedy")
+    base.update(kw)
+    return synth.ModelDims(**base)
+
+
+# ---------------------------------------------------------------- P1 brute force
+
+@pytest.mark.parametrize("L,H,nh,S,G,tied", [
+    (0, 32, 4, 3, 3, True), (1, 32, 2, 1, 5, True), (2, 64, 4, 7, 6, False), (3, 48, 6, 9, 4, True),
+])
+def test_cached_decode_equals_cache_free_recompute(L, H, nh, S, G, tied):
+    d = tiny_dims(n_layers=L, hidden=H, n_heads=nh, ffn=2 * H, prompt_len=S, gen_len=G, batch=3)
+    w = synth.make_weights(d, seed=L + S, tied=tied, std=0.3)
+    prompts = synth.make_prompts(d, seed=7, batch=3)
+    out = O.generate(w, prompts, G, nh, mode="greedy")
+    seq = np.concatenate([prompts, out["ids"]], axis=1)
+    full = O.forward_full(w, seq[:, :-1], nh)  # logits at every position
+    for n in range(G):
+        np.testing.assert_allclose(out["logits"][n], full[:, S - 1 + n, :], rtol=0, atol=1e-10)
+        assert np.array_equal(out["ids"][:, n], full[:, S - 1 + n, :].argmax(-1))
+    lp = O.log_softmax(full)
+    for n in range(G):
+        want = lp[np.arange(3), S - 1 + n, out["ids"][:, n]]
+        np.testing.assert_allclose(out["logprobs"][:, n], want, atol=1e-10)
+
+
+def _scalar_forward(w, ids, nh, eps):
+    """The same decoder in scalar Python loops, written separately from the
+    oracle's array code (index-by-index sums, explicit j <= i mask)."""
+    T = len(ids)
+    H = len(w["lnf_g"])
+    d = H // nh
+
+    def ln(u, g, b):
+        m = sum(u) / H
+        var = sum((t - m) ** 2 for t in u) / H
+        return [(u[i] - m) / math.sqrt(var + eps) * g[i] + b[i] for i in range(H)]
+
+    def lin(x, W, b):
+        return [sum(W[o][i] * x[i] for i in range(len(x))) + (b[o] if b is not None else 0.0) for o in range(len(W))]
+
+    x = [[float(w["tok_emb"][ids[t]][i]) + float(w["pos_emb"][t][i]) for i in range(H)] for t in range(T)]
+    for lw in w["layers"]:
+        L = {k: np.asarray(v, np.float64).tolist() for k, v in lw.items()}
+        qkv = [lin(ln(x[t], L["ln1_g"], L["ln1_b"]), L["wqkv"], L["bqkv"]) for t in range(T)]
+        att = [[0.0] * H for _ in range(T)]
+        for h in range(nh):
+            for i in range(T):
+                sc = [sum(qkv[i][h * d + e] * d ** -0.5 * qkv[j][H + h * d + e] for e in range(d)) for j in range(i + 1)]
+                m = max(sc)
+                ex = [math.exp(s - m) for s in sc]
+                den = sum(ex)
+                for e in range(d):
+                    att[i][h * d + e] = sum(ex[j] / den * qkv[j][2 * H + h * d + e] for j in range(i + 1))
+        for t in range(T):
+            y = lin(att[t], L["wo"], L["bo"])
+            x[t] = [x[t][i] + y[i] for i in range(H)]
+            hid = [max(v, 0.0) for v in lin(ln(x[t], L["ln2_g"], L["ln2_b"]), L["w1"], L["b1"])]
+            y = lin(hid, L["w2"], L["b2"])
+            x[t] = [x[t][i] + y[i] for i in range(H)]
+    lm = np.asarray(w["lm_head"], np.float64).tolist()
+    g, b = np.asarray(w["lnf_g"], np.float64).tolist(), np.asarray(w["lnf_b"], np.float64).tolist()
+    return [lin(ln(x[t], g, b), lm, None) for t in range(T)]
+
+
+def test_against_scalar_loop_brute_force():
+    d = tiny_dims(n_layers=2, hidden=8, n_heads=2, ffn=12, vocab=11, max_positions=8)
+    w = synth.make_weights(d, seed=3, tied=False, std=0.5)
+    ids = [3, 10, 0, 7, 7]
+    want = np.array(_scalar_forward(w, ids, 2, 1e-5))
+    got = O.forward_full(w, np.array([ids]), 2)[0]
+    np.testing.assert_allclose(got, want, atol=1e-11)
+    dec = O.CachedDecoder(w, 2)
+    z = dec.prefill(np.array([ids[:3]]))
+    np.testing.assert_allclose(z[0], want[2], atol=1e-11)
+    np.testing.assert_allclose(dec.step([ids[3]])[0], want[3], atol=1e-11)
+    np.testing.assert_allclose(dec.step([ids[4]])[0], want[4], atol=1e-11)
+
+
+# ---------------------------------------------------------------- P2 / P3 invariants
+
+def test_softmax_rows_sum_to_one_and_masked_are_zero():
+    rng = np.random.default_rng(0)
+    q, k, v = rng.standard_normal((6, 8)) * 3, rng.standard_normal((9, 8)) * 3, rng.standard_normal((9, 8))
+    _, p = O.attention(q, k, v, q_pos=3 + np.arange(6))
+    np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-12)
+    for i in range(6):
+        assert np.all(p[i, 3 + i + 1:] == 0.0)
+        assert np.all(p[i, :3 + i + 1] > 0.0)
+    z = rng.standard_normal((4, 100)) * 5
+    lp = O.log_softmax(z)
+    np.testing.assert_allclose(np.log(np.exp(lp).sum(-1)), 0.0, atol=1e-12)
+
+
+def test_causal_exactness_bit_identical():
+    d = tiny_dims(n_layers=2)
+    w = synth.make_weights(d, seed=1, std=0.3)
+    ids = synth.make_prompts(d, seed=2, batch=2, prompt_len=10)
+    base = O.forward_full(w, ids, d.n_heads)
+    for j in (3, 9):
+        ids2 = ids.copy()
+        ids2[:, j] = (ids2[:, j] + 1) % d.vocab
+        out = O.forward_full(w, ids2, d.n_heads)
+        assert np.array_equal(out[:, :j], base[:, :j])  # bit-identical before j
+        assert not np.array_equal(out[:, j], base[:, j])
+
+
+def test_batch_rows_are_independent():
+    d = tiny_dims()
+    w = synth.make_weights(d, seed=4, std=0.3)
+    ids = synth.make_prompts(d, seed=5, batch=3, prompt_len=6)
+    both = O.generate(w, ids, 4, d.n_heads, mode="gumbel", seed=9)
+    for b in range(3):
+        # sampling noise is keyed by the row index, so feed row b alone at index 0
+        # through greedy logits only
+        one = O.forward_full(w, ids[b:b + 1], d.n_heads)
+        np.testing.assert_allclose(both["logits"][0][b], one[0, -1], atol=1e-12)
+
+
+# ---------------------------------------------------------------- P4 closed forms
+
+def test_zero_layers_closed_form():
+    d = tiny_dims(n_layers=0)
+    w = synth.make_weights(d, seed=6, std=0.4)
+    ids = np.array([[4, 9, 1]])
+    z = O.forward_full(w, ids, d.n_heads)
+    for t in range(3):
+        u = w["tok_emb"][ids[0, t]].astype(np.float64) + w["pos_emb"][t].astype(np.float64)
+        a = (u - u.mean()) / np.sqrt(u.var() + 1e-5) * w["lnf_g"] + w["lnf_b"]
+        np.testing.assert_allclose(z[0, t], w["tok_emb"].astype(np.float64) @ a, atol=1e-12)
+
+
+def test_position_offset_shifts_rows():
+    d = tiny_dims(n_layers=1, pos_offset=2)
+    w = synth.make_weights(d, seed=6, std=0.4)
+    ids = np.array([[4, 9, 1]])
+    z2 = O.forward_full(w, ids, d.n_heads, pos_offset=2)
+    w0 = dict(w)
+    w0["pos_emb"] = w["pos_emb"][2:]
+    np.testing.assert_array_equal(z2, O.forward_full(w0, ids, d.n_heads, pos_offset=0))
+
+
+def test_dead_branches_make_layers_identity():
+    d = tiny_dims(n_layers=3)
+    w = synth.make_weights(d, seed=7, std=0.4)
+    for lw in w["layers"]:
+        for k in ("wo", "bo", "w2", "b2"):
+            lw[k] = np.zeros_like(lw[k])
+    w0 = dict(w)
+    w0["layers"] = []
+    ids = synth.make_prompts(d, seed=1, batch=2, prompt_len=5)
+    np.testing.assert_array_equal(O.forward_full(w, ids, d.n_heads), O.forward_full(w0, ids, d.n_heads))
+
+
+def test_attention_special_cases():
+    rng = np.random.default_rng(1)
+    q, k, v = rng.standard_normal((1, 8)), rng.standard_normal((1, 8)), rng.standard_normal((1, 8))
+    o, _ = O.attention(q, k, v, [0])
+    np.testing.assert_allclose(o, v, atol=1e-15)  # one key: output is its value
+    k = np.tile(rng.standard_normal((1, 8)), (5, 1))  # equal keys: uniform weights
+    v = rng.standard_normal((5, 8))
+    o, _ = O.attention(rng.standard_normal((1, 8)), k, v, [4])
+    np.testing.assert_allclose(o[0], v.mean(0), atol=1e-14)
+    # a hugely favoured key takes all the weight
+    k = rng.standard_normal((5, 8))
+    qq = 200.0 * k[2:3]
+    o, p = O.attention(qq, k, v, [4])
+    assert p[0].argmax() == 2 and p[0, 2] > 1 - 1e-9
+
+
+def test_layer_norm_statistics():
+    rng = np.random.default_rng(2)
+    u = rng.standard_normal((5, 64)) * 7 + 3
+    y = O.layer_norm(u, np.ones(64), np.zeros(64), 1e-5)
+    np.testing.assert_allclose(y.mean(-1), 0.0, atol=1e-13)
+    np.testing.assert_allclose(y.var(-1), u.var(-1) / (u.var(-1) + 1e-5), rtol=1e-12)
+
+
+def test_relu_ffn_and_residual_by_hand():
+    # one layer, attention branch dead, FFN = hand-computed
+    d = tiny_dims(n_layers=1, hidden=8, n_heads=2, ffn=6, vocab=9)
+    w = synth.make_weights(d, seed=8, std=0.6)
+    lw = w["layers"][0]
+    lw["wo"][:] = 0
+    lw["bo"][:] = 0
+    ids = np.array([[2]])
+    x = w["tok_emb"][2].astype(np.float64) + w["pos_emb"][0]
+    a2 = O.layer_norm(x, lw["ln2_g"], lw["ln2_b"], 1e-5)
+    h = np.array([max(0.0, float(np.dot(lw["w1"][o].astype(np.float64), a2)) + float(lw["b1"][o])) for o in range(6)])
+    assert (h == 0).any() and (h > 0).any()  # the clamp is exercised
+    x = x + np.array([np.dot(lw["w2"][o].astype(np.float64), h) + float(lw["b2"][o]) for o in range(8)])
+    want = w["lm_head"].astype(np.float64) @ O.layer_norm(x, w["lnf_g"], w["lnf_b"], 1e-5)
+    np.testing.assert_allclose(O.forward_full(w, ids, 2)[0, 0], want, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P5 library routines
+
+def test_primitives_against_torch_float64():
+    rng = np.random.default_rng(3)
+    u = rng.standard_normal((3, 5, 32))
+    g, b = rng.standard_normal(32), rng.standard_normal(32)
+    want = torch.nn.functional.layer_norm(torch.from_numpy(u), (32,), torch.from_numpy(g), torch.from_numpy(b), 1e-5)
+    np.testing.assert_allclose(O.layer_norm(u, g, b, 1e-5), want.numpy(), atol=1e-12)
+    W, bb = rng.standard_normal((7, 32)), rng.standard_normal(7)
+    want = torch.nn.functional.linear(torch.from_numpy(u), torch.from_numpy(W), torch.from_numpy(bb))
+    np.testing.assert_allclose(O.linear(u, W, bb), want.numpy(), atol=1e-12)
+    q, k, v = (rng.standard_normal((6, 16)) for _ in range(3))
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None], is_causal=True, scale=1.0)
+    o, _ = O.attention(q, k, v, np.arange(6))
+    np.testing.assert_allclose(o, want[0].numpy(), atol=1e-12)
+    z = rng.standard_normal((4, 33)) * 4
+    np.testing.assert_allclose(O.log_softmax(z), torch.log_softmax(torch.from_numpy(z), -1).numpy(), atol=1e-12)
+
+
+# ---------------------------------------------------------------- P6 independent implementation
+
+def test_whole_model_against_transformers_opt():
+    tr = pytest.importorskip("transformers")
+    d = tiny_dims(n_layers=2, hidden=32, n_heads=4, ffn=64, vocab=50, max_positions=24, pos_offset=2)
+    w = synth.make_weights(d, seed=11, tied=True, std=0.2)
+    cfg = tr.OPTConfig(vocab_size=d.vocab, hidden_size=d.hidden, num_hidden_layers=d.n_layers, ffn_dim=d.ffn,
+                       num_attention_heads=d.n_heads, max_position_embeddings=d.max_positions,
+                       word_embed_proj_dim=d.hidden, do_layer_norm_before=True, activation_function="relu",
+                       dropout=0.0, attention_dropout=0.0, layerdrop=0.0, tie_word_embeddings=True)
+    cfg._attn_implementation = "eager"
+    model = tr.OPTForCausalLM(cfg).double().eval()
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    H = d.hidden
+    sd = {"model.decoder.embed_tokens.weight": t(w["tok_emb"]),
+          "model.decoder.embed_positions.weight": t(w["pos_emb"]),
+          "model.decoder.final_layer_norm.weight": t(w["lnf_g"]),
+          "model.decoder.final_layer_norm.bias": t(w["lnf_b"]),
+          "lm_head.weight": t(w["lm_head"])}
+    for i, lw in enumerate(w["layers"]):
+        p = f"model.decoder.layers.{i}."
+        for j, nm in enumerate(("q_proj", "k_proj", "v_proj")):
+            sd[p + f"self_attn.{nm}.weight"] = t(lw["wqkv"][j * H:(j + 1) * H])
+            sd[p + f"self_attn.{nm}.bias"] = t(lw["bqkv"][j * H:(j + 1) * H])
+        sd[p + "self_attn.out_proj.weight"], sd[p + "self_attn.out_proj.bias"] = t(lw["wo"]), t(lw["bo"])
+        sd[p + "self_attn_layer_norm.weight"], sd[p + "self_attn_layer_norm.bias"] = t(lw["ln1_g"]), t(lw["ln1_b"])
+        sd[p + "fc1.weight"], sd[p + "fc1.bias"] = t(lw["w1"]), t(lw["b1"])
+        sd[p + "fc2.weight"], sd[p + "fc2.bias"] = t(lw["w2"]), t(lw["b2"])
+        sd[p + "final_layer_norm.weight"], sd[p + "final_layer_norm.bias"] = t(lw["ln2_g"]), t(lw["ln2_b"])
+    missing, unexpected = model.load_state_dict(sd, strict=False)
+    assert not unexpected and all("lm_head" in m or "embed_tokens" in m for m in missing), (missing, unexpected)
+    ids = synth.make_prompts(d, seed=3, batch=2, prompt_len=9)
+    with torch.no_grad():
+        want = model(input_ids=torch.from_numpy(ids).long()).logits.numpy()
+    got = O.forward_full(w, ids, d.n_heads, eps=1e-5, pos_offset=2)
+    # that implementation evaluates its attention softmax in float32 even for a
+    # float64 model, hence 2e-6 rather than 1e-12 (logits are O(1))
+    np.testing.assert_allclose(got, want, atol=2e-6)
+
+
+# ---------------------------------------------------------------- RNG and sampling
+
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        got = O.philox4x32_10(*v[:6])
+        assert [int(g) for g in got] == v[6:]
+    # vectorised call agrees with scalar calls
+    a = O.philox4x32_10(np.arange(5, dtype=np.uint32), 7, 9, 0, 1, 2)[0]
+    for i in range(5):
+        assert int(a[i]) == int(O.philox4x32_10(i, 7, 9, 0, 1, 2)[0])
+
+
+def test_uniform_is_strictly_inside_unit_interval_and_exact_in_fp32():
+    x = np.array([0, 1, 511, 512, 0xFFFFFFFF, 0xFFFFFE00], np.uint32)
+    u = O.uniform_open(x)
+    assert u.min() == 2.0 ** -24 and u.max() == 1 - 2.0 ** -24
+    assert np.array_equal(u.astype(np.float32).astype(np.float64), u)
+    words = O.random_u32(123, 1, 2, np.arange(200000, dtype=np.uint32))
+    uu = O.uniform_open(words)
+    assert abs(uu.mean() - 0.5) < 4e-3 and abs(uu.var() - 1 / 12) < 2e-3
+    assert len(np.unique(words)) > 199900  # no systematic repeats along v
+    # neighbours in b, n and seed give unrelated words
+    assert not np.array_equal(words[:100], O.random_u32(123, 2, 2, np.arange(100, dtype=np.uint32)))
+    assert not np.array_equal(words[:100], O.random_u32(123, 1, 3, np.arange(100, dtype=np.uint32)))
+    assert not np.array_equal(words[:100], O.random_u32(123 + (1 << 32), 1, 2, np.arange(100, dtype=np.uint32)))
+
+
+def test_gumbel_max_samples_from_softmax():
+    rng = np.random.default_rng(5)
+    V, N = 12, 40000
+    z = rng.standard_normal(V) * 1.5
+    for temp in (1.0, 0.7):
+        p = np.exp(z / temp - (z / temp).max())
+        p /= p.sum()
+        counts = np.zeros(V)
+        zz = np.tile(z, (1, 1))
+        for n in range(N):
+            tok, lp, _ = O.sample(zz, "gumbel", temp, seed=77, n=n)
+            counts[tok[0]] += 1
+        chi2 = ((counts - N * p) ** 2 / (N * p)).sum()
+        assert chi2 < 40.0, chi2  # 11 dof: P(chi2 > 40) ~ 4e-5
+    # reported log-prob is the untempered log-softmax at the chosen token
+    tok, lp, _ = O.sample(zz, "gumbel", 0.7, seed=1, n=0)
+    assert abs(lp[0] - (z[tok[0]] - np.log(np.exp(z).sum()))) < 1e-12
+
+
+def test_greedy_ties_go_to_lowest_index_and_margin():
+    z = np.array([[0.0, 2.0, 2.0, 1.0], [5.0, 1.0, 4.5, 0.0]])
+    tok, lp, m = O.sample(z, "greedy", 1.0, 0, 0)
+    assert tok.tolist() == [1, 0]
+    np.testing.assert_allclose(m, [0.0, 0.5])
+    # tiny temperature: Gumbel sampling degenerates to greedy
+    tok2, _, _ = O.sample(z[1:], "gumbel", 1e-6, 3, 0)
+    assert tok2.tolist() == [0]
+
+
+def test_generate_is_prefill_plus_g_minus_1_steps_and_teacher_forcing():
+    d = tiny_dims()
+    w = synth.make_weights(d, seed=2, std=0.3)
+    p = synth.make_prompts(d, seed=3, batch=2, prompt_len=4)
+    free = O.generate(w, p, 5, d.n_heads, mode="gumbel", seed=5)
+    assert free["ids"].shape == (2, 5) and free["logits"].shape == (5, 2, d.vocab)
+    forced = O.generate(w, p, 5, d.n_heads, mode="gumbel", seed=5, forced_ids=free["ids"])
+    np.testing.assert_array_equal(forced["ids"], free["ids"])
+    np.testing.assert_array_equal(forced["logits"], free["logits"])
+    other = (free["ids"] + 1) % d.vocab
+    f2 = O.generate(w, p, 5, d.n_heads, mode="gumbel", seed=5, forced_ids=other)
+    np.testing.assert_array_equal(f2["logits"][0], free["logits"][0])
+    full = O.forward_full(w, np.concatenate([p, other[:, :4]], 1), d.n_heads)
+    np.testing.assert_allclose(f2["logits"][4], full[:, -1], atol=1e-10)
