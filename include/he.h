@@ -1,0 +1,160 @@
+/*
+ * he.h -- C ABI of the MI355X actor-generation engine.
+ *
+ * The engine runs the inference half of the paper's Hybrid Engine (Section 4):
+ * the experience-generation phase of RLHF step 3, i.e. the actor model run
+ * over the prompt once and then once per generated token with a KV cache
+ * (Section 5.3 (I): 256 prompt tokens, 256 generated tokens, memory-bandwidth
+ * bound).  The model is an OPT-style decoder (Section 2 names the family):
+ * pre-LayerNorm, learned positions, causal multi-head attention with biases,
+ * ReLU feed-forward, final LayerNorm, LM head.
+ *
+ * Conventions
+ *  - Every pointer whose name starts with d_ and every weight pointer is a
+ *    DEVICE pointer on cfg.device.  Structs and scalars are host memory.
+ *  - Linear weights are row-major [out, in]:  y = x W^T + b.
+ *  - dtype HE_F32: weights, biases, LayerNorm parameters and the KV cache are
+ *    float.  dtype HE_BF16: they are bfloat16 (raw 16-bit, upper half of an
+ *    IEEE float); accumulation, residual stream, LayerNorm statistics,
+ *    softmax, logits and log-probs are float in both cases.
+ *  - The caller owns weights and all input/output buffers.  The engine
+ *    borrows the weight pointers until he_destroy; it owns only its KV arena,
+ *    workspace and (bf16) MFMA-tiled copies of the GEMM matrices, all
+ *    allocated once in he_create -- no call on the generation path allocates
+ *    (Section 4: pre-reserved KV cache and intermediate buffers).  After the
+ *    caller overwrites weights in place (a training update between two
+ *    generation phases) it calls he_refresh_weights.
+ *  - All work is enqueued on cfg.stream (a hipStream_t, NULL = default
+ *    stream) and is asynchronous; only he_create / he_refresh_weights /
+ *    he_destroy synchronise.  Outputs are valid once the stream has drained.
+ *  - Every call validates its arguments and returns a status; nothing throws
+ *    across the boundary.  After an error the engine is reusable once
+ *    he_reset has been called.  An engine is not thread-safe.
+ *  - All sequences of a batch have the same prompt length; exactly G tokens
+ *    are generated per sequence (no stop token).
+ */
+#ifndef HE_H
+#define HE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct he_engine he_engine; /* opaque */
+
+typedef enum {
+    HE_OK = 0,
+    HE_ERR_INVALID_ARG = 1, /* null pointer, bad enum, non-positive size */
+    HE_ERR_SHAPE = 2,       /* dimensions the kernels do not support */
+    HE_ERR_CAPACITY = 3,    /* batch, sequence length or positions exceed what he_create reserved */
+    HE_ERR_OOM = 4,         /* device allocation failed in he_create */
+    HE_ERR_DEVICE = 5,      /* a HIP call failed; he_last_error has the text */
+    HE_ERR_STATE = 6        /* call order: decode before prefill, prefill on a non-empty cache */
+} he_status;
+
+typedef enum { HE_F32 = 0, HE_BF16 = 1 } he_dtype;
+
+typedef struct {
+    int n_layers;      /* L >= 0 */
+    int hidden;        /* H, multiple of 64 */
+    int n_heads;       /* nh; head_dim d = H / nh must be 64 or 128 on the bf16 path, any multiple of 8 <= 256 on f32 */
+    int ffn;           /* F, multiple of 64 */
+    int vocab;         /* V */
+    int max_positions; /* rows of pos_emb minus pos_offset */
+    int pos_offset;    /* position t reads pos_emb row t + pos_offset */
+    float ln_eps;
+    he_dtype dtype;
+    int max_batch;     /* KV arena holds max_batch sequences ... */
+    int max_seq_len;   /* ... of at most max_seq_len positions (prompt + generated) */
+    int device;        /* HIP device ordinal */
+    void* stream;      /* hipStream_t or NULL */
+    int impl;          /* 0 = default kernels for the dtype; 1 = the plain (f32-path) kernels
+                          instantiated for this dtype -- a slow comparator for tests */
+} he_config;
+
+typedef struct {
+    const void *ln1_g, *ln1_b; /* [H] */
+    const void *wqkv;          /* [3H, H]: rows 0..H-1 query, H..2H-1 key, 2H..3H-1 value */
+    const void *bqkv;          /* [3H] */
+    const void *wo, *bo;       /* [H, H], [H] */
+    const void *ln2_g, *ln2_b; /* [H] */
+    const void *w1, *b1;       /* [F, H], [F] */
+    const void *w2, *b2;       /* [H, F], [H] */
+} he_layer_weights;
+
+typedef struct {
+    const void* tok_emb;            /* [V, H] */
+    const void* pos_emb;            /* [max_positions + pos_offset, H] */
+    const void *lnf_g, *lnf_b;      /* [H] final LayerNorm */
+    const void* lm_head;            /* [V, H], no bias; may alias tok_emb (tied) */
+    const he_layer_weights* layers; /* host array of n_layers entries (copied by he_create) */
+} he_weights;
+
+typedef struct {
+    int mode;          /* 0 greedy: argmax z.  1 Gumbel-max: argmax (z / temperature + g) */
+    float temperature; /* > 0, used in mode 1 only */
+    uint64_t seed;     /* g = -log(-log u), u from Philox4x32-10 keyed by seed at counter (v, step, b, 0) */
+} he_sampling;
+
+/* Bytes of device memory he_create will allocate for cfg (KV arena, workspace,
+ * tiled weight copies).  Pure host computation; 0 if cfg is invalid. */
+size_t he_workspace_bytes(const he_config* cfg);
+
+/* Validates cfg, allocates arena and workspace, prepares weights.  *out is
+ * set only on HE_OK.  Synchronises cfg.stream. */
+he_status he_create(const he_config* cfg, const he_weights* weights, he_engine** out);
+
+/* Re-reads the borrowed weight pointers after the caller changed the values
+ * in place (re-tiles the GEMM matrices on the bf16 path).  Synchronises. */
+he_status he_refresh_weights(he_engine* e);
+
+/* Prompt pass (Section 5.3 (I): "initial prompt").  d_prompt_ids is [B, S]
+ * int32 row-major, 1 <= B <= max_batch, 1 <= S <= max_seq_len, S within
+ * max_positions.  Requires an empty cache (fresh engine or he_reset).
+ * Fills the KV cache for positions 0..S-1 and samples generation step 0 from
+ * the last position's logits z:  d_next_ids [B] int32, d_logprobs [B] float
+ * = log_softmax(z)[id] (untempered).  d_logits_opt, if not NULL, receives z
+ * as [B, V] float. */
+he_status he_prefill(he_engine* e, const int32_t* d_prompt_ids, int B, int S, const he_sampling* sampling,
+                     int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt);
+
+/* One KV-cached decode step (Section 5.3 (I): the actor "once for each"
+ * generated token): feeds d_in_ids [B] at position cur_len, appends its K/V,
+ * samples the next generation step.  Outputs as in he_prefill.  B is the
+ * batch of the preceding he_prefill.  HE_ERR_CAPACITY when the cache or the
+ * position table is full. */
+he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
+                         float* d_logprobs, float* d_logits_opt);
+
+/* The whole generation phase: reset, prefill, then G-1 decode steps that feed
+ * each sampled token back (the steps run as replays of one captured HIP
+ * graph).  d_out_ids [B, G] int32 and d_out_logprobs [B, G] float, row-major.
+ * Requires S + G - 1 <= max_seq_len and within max_positions. */
+he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
+                      int32_t* d_out_ids, float* d_out_logprobs);
+
+/* Empties the KV cache (lengths to zero; memory is kept). */
+he_status he_reset(he_engine* e);
+
+/* Frees everything the engine owns.  NULL is accepted. */
+he_status he_destroy(he_engine* e);
+
+/* Text of the last error on this engine (engine-owned, valid until the next
+ * call); with e == NULL, the text of the last he_create failure. */
+const char* he_last_error(const he_engine* e);
+
+/* Current number of cached positions per sequence, or -1 if e is NULL. */
+int he_cache_len(const he_engine* e);
+
+/* Test hook for the sampler's counter-based generator: writes the `count`
+ * 32-bit words for vocabulary ids v0 .. v0+count-1 of (seed, sequence b,
+ * generation step n) to d_out [count] uint32, on `stream`. */
+he_status he_rng_words(uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* d_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libhe.so (include/he.h): argument marshalling only.
+
+Every step of the generation path runs inside the library's HIP kernels;
+torch is used here to own device memory and to name the stream.  There is no
+CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhe.so")
+
+HE_OK = 0
+STATUS_NAMES = {0: "HE_OK", 1: "HE_ERR_INVALID_ARG", 2: "HE_ERR_SHAPE", 3: "HE_ERR_CAPACITY", 4: "HE_ERR_OOM",
+                5: "HE_ERR_DEVICE", 6: "HE_ERR_STATE"}
+HE_F32, HE_BF16 = 0, 1
+
+
+class he_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("hidden", C.c_int), ("n_heads", C.c_int), ("ffn", C.c_int),
+                ("vocab", C.c_int), ("max_positions", C.c_int), ("pos_offset", C.c_int), ("ln_eps", C.c_float),
+                ("dtype", C.c_int), ("max_batch", C.c_int), ("max_seq_len", C.c_int), ("device", C.c_int),
+                ("stream", C.c_void_p), ("impl", C.c_int)]
+
+
+LAYER_FIELDS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
+class he_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class he_weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("pos_emb", C.c_void_p), ("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p),
+                ("lm_head", C.c_void_p), ("layers", C.POINTER(he_layer_weights))]
+
+
+class he_sampling(C.Structure):
+    _fields_ = [("mode", C.c_int), ("temperature", C.c_float), ("seed", C.c_uint64)]
+
+
+class HeError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libhe.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2308_01320_amd.build` "
+                           "(or __graft_entry__.build()); the engine has no other implementation")
+    L = C.CDLL(LIB_PATH)
+    vp, ip, fp = C.c_void_p, C.c_void_p, C.c_void_p
+    L.he_workspace_bytes.restype = C.c_size_t
+    L.he_workspace_bytes.argtypes = [C.POINTER(he_config)]
+    L.he_create.restype = C.c_int
+    L.he_create.argtypes = [C.POINTER(he_config), C.POINTER(he_weights), C.POINTER(vp)]
+    L.he_refresh_weights.restype = C.c_int
+    L.he_refresh_weights.argtypes = [vp]
+    L.he_prefill.restype = C.c_int
+    L.he_prefill.argtypes = [vp, ip, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp, fp]
+    L.he_decode_step.restype = C.c_int
+    L.he_decode_step.argtypes = [vp, ip, C.POINTER(he_sampling), ip, fp, fp]
+    L.he_generate.restype = C.c_int
+    L.he_generate.argtypes = [vp, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp]
+    L.he_reset.restype = C.c_int
+    L.he_reset.argtypes = [vp]
+    L.he_destroy.restype = C.c_int
+    L.he_destroy.argtypes = [vp]
+    L.he_last_error.restype = C.c_char_p
+    L.he_last_error.argtypes = [vp]
+    L.he_cache_len.restype = C.c_int
+    L.he_cache_len.argtypes = [vp]
+    L.he_rng_words.restype = C.c_int
+    L.he_rng_words.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, vp, vp]
+    _lib = L
+    return L
+
+
+EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
+           "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def sampling(mode: str = "greedy", temperature: float = 1.0, seed: int = 0) -> he_sampling:
+    return he_sampling({"greedy": 0, "gumbel": 1}[mode], float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF)
+
+
+def make_config(dims, max_batch=None, max_seq_len=None, device=0, stream=None, impl=0) -> he_config:
+    """he_config from a synth.ModelDims (or anything with the same fields)."""
+    return he_config(dims.n_layers, dims.hidden, dims.n_heads, dims.ffn, dims.vocab, dims.max_positions,
+                     dims.pos_offset, dims.ln_eps, HE_BF16 if dims.dtype == "bf16" else HE_F32,
+                     max_batch or dims.batch, max_seq_len or (dims.prompt_len + dims.gen_len), device,
+                     stream, impl)
+
+
+def upload_weights(w: dict, dtype: str, device="cuda:0") -> dict:
+    """numpy weight dict (synth.make_weights) -> same structure of device tensors."""
+    import torch
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def up(a):
+        return torch.from_numpy(a).to(device=device, dtype=tdt).contiguous()
+
+    out = {k: up(v) for k, v in w.items() if k not in ("layers", "lm_head")}
+    out["lm_head"] = out["tok_emb"] if w["lm_head"] is w["tok_emb"] else up(w["lm_head"])
+    out["layers"] = [{k: up(v) for k, v in lw.items()} for lw in w["layers"]]
+    return out
+
+
+class Engine:
+    """Owns one he_engine handle and keeps the borrowed weight tensors alive."""
+
+    def __init__(self, cfg: he_config, weights: dict):
+        import torch
+        self._torch = torch
+        self.cfg = cfg
+        self.weights = weights  # device tensors; the engine borrows their memory
+        self._layers = (he_layer_weights * max(1, cfg.n_layers))()
+        for i, lw in enumerate(weights["layers"]):
+            for n in LAYER_FIELDS:
+                setattr(self._layers[i], n, lw[n].data_ptr())
+        self._w = he_weights(weights["tok_emb"].data_ptr(), weights["pos_emb"].data_ptr(),
+                             weights["lnf_g"].data_ptr(), weights["lnf_b"].data_ptr(),
+                             weights["lm_head"].data_ptr(), self._layers)
+        self.handle = C.c_void_p()
+        rc = lib().he_create(C.byref(cfg), C.byref(self._w), C.byref(self.handle))
+        if rc != HE_OK:
+            self.handle = None
+            raise HeError(rc, (lib().he_last_error(None) or b"").decode())
+        self.device = torch.device("cuda", cfg.device)
+
+    # -- helpers
+    def _check(self, rc):
+        if rc != HE_OK:
+            raise HeError(rc, (lib().he_last_error(self.handle) or b"").decode())
+
+    def last_error(self) -> str:
+        return (lib().he_last_error(self.handle) or b"").decode()
+
+    def cache_len(self) -> int:
+        return lib().he_cache_len(self.handle)
+
+    # -- the ABI calls, same names
+    def he_prefill(self, prompt_ids, samp: he_sampling, want_logits=False):
+        t = self._torch
+        B, S = prompt_ids.shape
+        ids = t.empty(B, dtype=t.int32, device=self.device)
+        lp = t.empty(B, dtype=t.float32, device=self.device)
+        lg = t.empty(B, self.cfg.vocab, dtype=t.float32, device=self.device) if want_logits else None
+        self._check(lib().he_prefill(self.handle, prompt_ids.data_ptr(), B, S, C.byref(samp), ids.data_ptr(),
+                                     lp.data_ptr(), _ptr(lg)))
+        return ids, lp, lg
+
+    def he_decode_step(self, in_ids, samp: he_sampling, want_logits=False):
+        t = self._torch
+        B = in_ids.shape[0]
+        ids = t.empty(B, dtype=t.int32, device=self.device)
+        lp = t.empty(B, dtype=t.float32, device=self.device)
+        lg = t.empty(B, self.cfg.vocab, dtype=t.float32, device=self.device) if want_logits else None
+        self._check(lib().he_decode_step(self.handle, in_ids.data_ptr(), C.byref(samp), ids.data_ptr(),
+                                         lp.data_ptr(), _ptr(lg)))
+        return ids, lp, lg
+
+    def he_generate(self, prompt_ids, G: int, samp: he_sampling, out_ids=None, out_lp=None):
+        t = self._torch
+        B, S = prompt_ids.shape
+        if out_ids is None:
+            out_ids = t.empty(B, G, dtype=t.int32, device=self.device)
+        if out_lp is None:
+            out_lp = t.empty(B, G, dtype=t.float32, device=self.device)
+        self._check(lib().he_generate(self.handle, prompt_ids.data_ptr(), B, S, G, C.byref(samp),
+                                      out_ids.data_ptr(), out_lp.data_ptr()))
+        return out_ids, out_lp
+
+    def he_reset(self):
+        self._check(lib().he_reset(self.handle))
+
+    def he_refresh_weights(self):
+        self._check(lib().he_refresh_weights(self.handle))
+
+    def he_destroy(self):
+        if self.handle:
+            lib().he_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.he_destroy()
+        except Exception:
+            pass
+
+
+def he_rng_words(seed: int, b: int, n: int, v0: int, count: int, device="cuda:0"):
+    import torch
+    out = torch.empty(count, dtype=torch.int32, device=device)
+    rc = lib().he_rng_words(int(seed) & 0xFFFFFFFFFFFFFFFF, b, n, v0, count, out.data_ptr(),
+                            torch.cuda.current_stream().cuda_stream)
+    if rc != HE_OK:
+        raise HeError(rc, "he_rng_words")
+    return out

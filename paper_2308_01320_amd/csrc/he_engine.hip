@@ -1,0 +1,294 @@
+// The engine behind the C ABI in include/he.h: argument validation, the KV arena
+// and workspace (allocated once), and the stream-ordered kernel sequence of a
+// prompt pass / decode step of the actor's generation phase (paper Section 4
+// and Section 5.3 (I)).
+#include <string>
+#include <vector>
+
+#include "../../include/he.h"
+#include "he_common.h"
+#include "kernels.h"
+
+struct he_engine {
+    he_config cfg{};
+    int d = 0;          // head_dim
+    bool bf16 = false;  // storage type of weights / KV
+    hipStream_t stream = nullptr;
+    he_weights w{};
+    std::vector<he_layer_weights> layers;
+
+    std::vector<void*> allocs;  // everything the engine owns on the device
+    void* kv = nullptr;
+    he_dev_state* st = nullptr;
+    float *resid = nullptr, *abuf = nullptr, *qbuf = nullptr, *obuf = nullptr, *ybuf = nullptr, *hbuf = nullptr;
+    float *xf = nullptr, *logits = nullptr, *gen_lp = nullptr;
+    int32_t *cur_ids = nullptr, *gen_ids = nullptr;
+
+    // host mirror of the device state
+    int cur_len = 0, step = 0, batch = 0;
+    std::string err;
+};
+
+static std::string g_create_error;
+
+namespace {
+
+struct Sizes {
+    size_t kv, rowsH, rowsF, xf, logits, gen, total;
+};
+
+size_t elt_bytes(const he_config& c) { return c.dtype == HE_BF16 ? 2 : 4; }
+
+const char* check_config(const he_config* c) {
+    if (!c) return "config is NULL";
+    if (c->n_layers < 0 || c->hidden <= 0 || c->n_heads <= 0 || c->ffn <= 0 || c->vocab <= 0) return "non-positive model dimension";
+    if (c->max_positions <= 0 || c->pos_offset < 0 || c->max_batch <= 0 || c->max_seq_len <= 0) return "non-positive capacity";
+    if (c->dtype != HE_F32 && c->dtype != HE_BF16) return "unknown dtype";
+    if (c->impl != 0 && c->impl != 1) return "unknown impl";
+    if (!(c->ln_eps > 0.f)) return "ln_eps must be positive";
+    return nullptr;
+}
+
+const char* check_shape(const he_config* c) {
+    if (c->hidden % c->n_heads) return "hidden is not a multiple of n_heads";
+    const int d = c->hidden / c->n_heads;
+    if (d % 8 || d > 256) return "head_dim must be a multiple of 8 and at most 256";
+    if (c->max_seq_len > 8192) return "max_seq_len above 8192 is not supported";
+    return nullptr;
+}
+
+Sizes sizes_of(const he_config& c) {
+    Sizes s{};
+    const size_t rows = (size_t)c.max_batch * c.max_seq_len;
+    s.kv = (size_t)c.n_layers * 2 * rows * c.hidden * elt_bytes(c);
+    s.rowsH = rows * c.hidden * sizeof(float);
+    s.rowsF = rows * c.ffn * sizeof(float);
+    s.xf = (size_t)c.max_batch * c.hidden * sizeof(float);
+    s.logits = (size_t)c.max_batch * c.vocab * sizeof(float);
+    s.gen = rows * sizeof(float);
+    s.total = s.kv + 5 * s.rowsH + s.rowsF + s.xf + s.logits + 2 * s.gen + c.max_batch * sizeof(int32_t) + 256;
+    return s;
+}
+
+he_status fail(he_engine* e, he_status code, const std::string& msg) {
+    if (e) e->err = msg;
+    return code;
+}
+
+he_status check_hip(he_engine* e, hipError_t r, const char* what) {
+    if (r == hipSuccess) return HE_OK;
+    return fail(e, HE_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(r));
+}
+
+template <typename T>
+hipError_t dev_alloc(he_engine* e, T** p, size_t bytes) {
+    void* q = nullptr;
+    hipError_t r = hipMalloc(&q, bytes ? bytes : 1);
+    if (r == hipSuccess) {
+        e->allocs.push_back(q);
+        *p = (T*)q;
+    }
+    return r;
+}
+
+void free_all(he_engine* e) {
+    for (void* p : e->allocs) (void)hipFree(p);
+    e->allocs.clear();
+}
+
+// One pass of the decoder over M = B*S new rows (S = prompt length, or 1 for a
+// decode step) followed by the LM head on each sequence's last row and sampling.
+he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
+                      int out_stride, int out_at_step, float* d_logits_opt) {
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int M = B * S, H = c.hidden, F = c.ffn, bf = e->bf16;
+    const float qscale = 1.0f / sqrtf((float)e->d);
+
+    plain_embed(s, bf, d_ids, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, M, S, H, c.vocab, c.pos_offset);
+    const float* pend_y = nullptr;  // GEMM output not yet added to the residual stream
+    const void* pend_b = nullptr;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const he_layer_weights& lw = e->layers[l];
+        plain_ln(s, bf, e->resid, pend_y, pend_b, lw.ln1_g, lw.ln1_b, e->abuf, M, H, c.ln_eps, 1, 0, 1);
+        plain_gemm(s, bf, e->abuf, lw.wqkv, lw.bqkv, M, 3 * H, H, EPI_QKV, e->qbuf, e->kv, e->st, S, l, H, c.n_heads,
+                   c.max_batch, c.max_seq_len, qscale);
+        plain_attn(s, bf, e->qbuf, e->kv, e->obuf, e->st, M, S, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        plain_gemm(s, bf, e->obuf, lw.wo, nullptr, M, H, H, EPI_STORE, e->ybuf, nullptr, e->st, S, l, H, c.n_heads,
+                   c.max_batch, c.max_seq_len, 1.f);
+        plain_ln(s, bf, e->resid, e->ybuf, lw.bo, lw.ln2_g, lw.ln2_b, e->abuf, M, H, c.ln_eps, 1, 0, 1);
+        plain_gemm(s, bf, e->abuf, lw.w1, lw.b1, M, F, H, EPI_BIAS_RELU, e->hbuf, nullptr, e->st, S, l, H, c.n_heads,
+                   c.max_batch, c.max_seq_len, 1.f);
+        plain_gemm(s, bf, e->hbuf, lw.w2, nullptr, M, H, F, EPI_STORE, e->ybuf, nullptr, e->st, S, l, H, c.n_heads,
+                   c.max_batch, c.max_seq_len, 1.f);
+        pend_y = e->ybuf;
+        pend_b = lw.b2;
+    }
+    // final LayerNorm on each sequence's last row only
+    plain_ln(s, bf, e->resid, pend_y, pend_b, e->w.lnf_g, e->w.lnf_b, e->xf, B, H, c.ln_eps, S, S - 1, 0);
+    float* logits = d_logits_opt ? d_logits_opt : e->logits;
+    plain_lm_head(s, bf, e->xf, e->w.lm_head, logits, B, H, c.vocab);
+    launch_sample(s, logits, B, c.vocab, e->st, ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    launch_advance_state(s, e->st, S);
+    e->cur_len += S;
+    e->step += 1;
+    return check_hip(e, hipGetLastError(), "kernel launch");
+}
+
+const char* check_sampling(const he_sampling* sp) {
+    if (!sp) return "sampling is NULL";
+    if (sp->mode != 0 && sp->mode != 1) return "sampling mode must be 0 (greedy) or 1 (Gumbel-max)";
+    if (sp->mode == 1 && !(sp->temperature > 0.f)) return "temperature must be positive";
+    return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t he_workspace_bytes(const he_config* cfg) {
+    if (check_config(cfg) || check_shape(cfg)) return 0;
+    return sizes_of(*cfg).total;
+}
+
+he_status he_create(const he_config* cfg, const he_weights* weights, he_engine** out) {
+    if (!out) { g_create_error = "out is NULL"; return HE_ERR_INVALID_ARG; }
+    if (const char* m = check_config(cfg)) { g_create_error = m; return HE_ERR_INVALID_ARG; }
+    if (const char* m = check_shape(cfg)) { g_create_error = m; return HE_ERR_SHAPE; }
+    if (!weights || !weights->tok_emb || !weights->pos_emb || !weights->lnf_g || !weights->lnf_b || !weights->lm_head ||
+        (cfg->n_layers > 0 && !weights->layers)) {
+        g_create_error = "a weight pointer is NULL";
+        return HE_ERR_INVALID_ARG;
+    }
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const he_layer_weights& lw = weights->layers[l];
+        const void* ps[] = {lw.ln1_g, lw.ln1_b, lw.wqkv, lw.bqkv, lw.wo, lw.bo, lw.ln2_g, lw.ln2_b, lw.w1, lw.b1, lw.w2, lw.b2};
+        for (const void* p : ps)
+            if (!p) { g_create_error = "a layer weight pointer is NULL"; return HE_ERR_INVALID_ARG; }
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
+        g_create_error = "no such HIP device";
+        return HE_ERR_DEVICE;
+    }
+    if (hipSetDevice(cfg->device) != hipSuccess) { g_create_error = "hipSetDevice failed"; return HE_ERR_DEVICE; }
+
+    he_engine* e = new he_engine();
+    e->cfg = *cfg;
+    e->d = cfg->hidden / cfg->n_heads;
+    e->bf16 = cfg->dtype == HE_BF16;
+    e->stream = (hipStream_t)cfg->stream;
+    e->w = *weights;
+    e->layers.assign(weights->layers, weights->layers + cfg->n_layers);
+    e->w.layers = e->layers.data();
+
+    const Sizes z = sizes_of(*cfg);
+    hipError_t r = hipSuccess;
+    auto A = [&](auto** p, size_t bytes) { if (r == hipSuccess) r = dev_alloc(e, p, bytes); };
+    A(&e->kv, z.kv);
+    A(&e->st, 256);
+    A(&e->resid, z.rowsH); A(&e->abuf, z.rowsH); A(&e->qbuf, z.rowsH); A(&e->obuf, z.rowsH); A(&e->ybuf, z.rowsH);
+    A(&e->hbuf, z.rowsF);
+    A(&e->xf, z.xf); A(&e->logits, z.logits);
+    A(&e->gen_lp, z.gen); A(&e->gen_ids, z.gen);
+    A(&e->cur_ids, cfg->max_batch * sizeof(int32_t));
+    if (r != hipSuccess) {
+        g_create_error = std::string("device allocation failed: ") + hipGetErrorString(r);
+        (void)hipGetLastError();
+        free_all(e);
+        delete e;
+        return r == hipErrorOutOfMemory ? HE_ERR_OOM : HE_ERR_DEVICE;
+    }
+    launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
+    r = hipStreamSynchronize(e->stream);
+    if (r != hipSuccess) {
+        g_create_error = std::string("he_create: ") + hipGetErrorString(r);
+        free_all(e);
+        delete e;
+        return HE_ERR_DEVICE;
+    }
+    *out = e;
+    return HE_OK;
+}
+
+he_status he_refresh_weights(he_engine* e) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    return check_hip(e, hipStreamSynchronize(e->stream), "he_refresh_weights");
+}
+
+he_status he_reset(he_engine* e) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    e->cur_len = 0; e->step = 0; e->batch = 0;
+    launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
+    return check_hip(e, hipGetLastError(), "he_reset");
+}
+
+he_status he_prefill(he_engine* e, const int32_t* d_prompt_ids, int B, int S, const he_sampling* sampling,
+                     int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!d_prompt_ids || !d_next_ids || !d_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_prefill: NULL buffer");
+    if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
+    if (B < 1 || S < 1) return fail(e, HE_ERR_INVALID_ARG, "he_prefill: B and S must be positive");
+    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_prefill: B exceeds max_batch");
+    if (S > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_prefill: S exceeds max_seq_len");
+    if (S > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_prefill: S exceeds max_positions");
+    if (e->cur_len != 0) return fail(e, HE_ERR_STATE, "he_prefill: cache is not empty (call he_reset)");
+    e->batch = B;
+    e->step = 0;
+    launch_set_state(e->stream, e->st, 0, 0, 1, sampling->mode, sampling->temperature, sampling->seed);
+    return run_forward(e, d_prompt_ids, B, S, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
+}
+
+he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
+                         float* d_logprobs, float* d_logits_opt) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!d_in_ids || !d_next_ids || !d_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_decode_step: NULL buffer");
+    if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
+    if (e->cur_len == 0 || e->batch == 0) return fail(e, HE_ERR_STATE, "he_decode_step: no prompt has been prefilled");
+    if (e->cur_len + 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_decode_step: KV cache is full");
+    if (e->cur_len + 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_decode_step: position table exhausted");
+    launch_set_state(e->stream, e->st, 0, 0, 0, sampling->mode, sampling->temperature, sampling->seed);
+    return run_forward(e, d_in_ids, e->batch, 1, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
+}
+
+he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
+                      int32_t* d_out_ids, float* d_out_logprobs) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!d_prompt_ids || !d_out_ids || !d_out_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_generate: NULL buffer");
+    if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
+    if (B < 1 || S < 1 || G < 1) return fail(e, HE_ERR_INVALID_ARG, "he_generate: B, S and G must be positive");
+    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_generate: B exceeds max_batch");
+    if ((long)S + G - 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_generate: S + G - 1 exceeds max_seq_len");
+    if ((long)S + G - 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_generate: S + G - 1 exceeds max_positions");
+    he_status rc = he_reset(e);
+    if (rc != HE_OK) return rc;
+    e->batch = B;
+    launch_set_state(e->stream, e->st, 0, 0, 1, sampling->mode, sampling->temperature, sampling->seed);
+    rc = run_forward(e, d_prompt_ids, B, S, e->gen_ids, e->gen_lp, G, 1, nullptr);
+    for (int n = 1; n < G && rc == HE_OK; ++n)
+        rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
+    if (rc != HE_OK) return rc;
+    launch_copy_out(e->stream, e->gen_ids, e->gen_lp, d_out_ids, d_out_logprobs, B * G);
+    return check_hip(e, hipGetLastError(), "he_generate");
+}
+
+he_status he_destroy(he_engine* e) {
+    if (!e) return HE_OK;
+    (void)hipStreamSynchronize(e->stream);
+    free_all(e);
+    delete e;
+    return HE_OK;
+}
+
+const char* he_last_error(const he_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
+
+int he_cache_len(const he_engine* e) { return e ? e->cur_len : -1; }
+
+he_status he_rng_words(uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* d_out, void* stream) {
+    if (!d_out || count < 0) return HE_ERR_INVALID_ARG;
+    if (count == 0) return HE_OK;
+    launch_rng_words((hipStream_t)stream, seed, b, n, v0, count, d_out);
+    return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
+}
+
+}  // extern "C"
