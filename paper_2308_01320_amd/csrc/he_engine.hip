@@ -24,6 +24,15 @@ struct he_engine {
     float *xf = nullptr, *logits = nullptr, *gen_lp = nullptr;
     int32_t *cur_ids = nullptr, *gen_ids = nullptr;
 
+    // bf16 path: MFMA-tiled copies of the GEMM matrices and tiled activation buffers
+    bool fast = false;
+    struct Tiled { void *wqkv, *wo, *w1, *w2; };
+    std::vector<Tiled> tiled;
+    void *lm_tiled = nullptr, *ablk = nullptr, *oblk = nullptr, *hblk = nullptr, *xfblk = nullptr;
+    void *ablk_lo = nullptr, *oblk_lo = nullptr, *hblk_lo = nullptr, *xfblk_lo = nullptr;  // second bf16 term
+    float *part = nullptr, *stats = nullptr;
+    int* stats_idx = nullptr;
+
     // host mirror of the device state
     int cur_len = 0, step = 0, batch = 0;
     std::string err;
@@ -35,7 +44,12 @@ namespace {
 
 struct Sizes {
     size_t kv, rowsH, rowsF, xf, logits, gen, total;
+    // bf16 path
+    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx;
 };
+
+bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
+constexpr int kMaxKSplit = 8;
 
 size_t elt_bytes(const he_config& c) { return c.dtype == HE_BF16 ? 2 : 4; }
 
@@ -54,6 +68,10 @@ const char* check_shape(const he_config* c) {
     const int d = c->hidden / c->n_heads;
     if (d % 8 || d > 256) return "head_dim must be a multiple of 8 and at most 256";
     if (c->max_seq_len > 8192) return "max_seq_len above 8192 is not supported";
+    if (is_fast(*c)) {
+        if (c->hidden % 64 || c->ffn % 64) return "bf16 path: hidden and ffn must be multiples of 64";
+        if (d != 64 && d != 128) return "bf16 path: head_dim must be 64 or 128";
+    }
     return nullptr;
 }
 
@@ -66,7 +84,24 @@ Sizes sizes_of(const he_config& c) {
     s.xf = (size_t)c.max_batch * c.hidden * sizeof(float);
     s.logits = (size_t)c.max_batch * c.vocab * sizeof(float);
     s.gen = rows * sizeof(float);
-    s.total = s.kv + 5 * s.rowsH + s.rowsF + s.xf + s.logits + 2 * s.gen + c.max_batch * sizeof(int32_t) + 256;
+    s.total = s.kv + s.logits + 2 * s.gen + c.max_batch * sizeof(int32_t) + 256;
+    if (!is_fast(c)) {
+        s.total += 5 * s.rowsH + s.rowsF + s.xf;
+        return s;
+    }
+    const int H = c.hidden, F = c.ffn;
+    s.tiled_layer = bf16_tiled_bytes(3 * H, H) + bf16_tiled_bytes(H, H) + bf16_tiled_bytes(F, H) + bf16_tiled_bytes(H, F);
+    s.tiled_lm = bf16_tiled_bytes(c.vocab, H);
+    s.ablk = bf16_tiled_bytes((int)rows, H);
+    s.hblk = bf16_tiled_bytes((int)rows, F);
+    s.xfblk = bf16_tiled_bytes(c.max_batch, H);
+    const size_t prow = rows > (size_t)kMaxKSplit * c.max_batch ? rows : (size_t)kMaxKSplit * c.max_batch;
+    s.part = prow * H * sizeof(float);
+    const size_t ntile = (size_t)(c.vocab + 31) / 32;
+    s.stats = (size_t)c.max_batch * ntile * 4 * sizeof(float);
+    s.stats_idx = (size_t)c.max_batch * ntile * sizeof(int);
+    s.total += 2 * s.rowsH /* resid, q */ + (size_t)c.n_layers * s.tiled_layer + s.tiled_lm + 4 * s.ablk + 2 * s.hblk +
+               2 * s.xfblk + s.part + s.stats + s.stats_idx;
     return s;
 }
 
@@ -96,16 +131,115 @@ void free_all(he_engine* e) {
     e->allocs.clear();
 }
 
+// bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  Only the
+// K/V cache is wanted from these rows (the last prompt token takes the decode-shaped pass
+// below), so the final layer stops once its keys and values are stored.
+void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int Sp) {
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int M = B * Sp, H = c.hidden, F = c.ffn;
+    bf16_gemm_args base;
+    base.st = e->st; base.S = Sp; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
+    base.max_seq = c.max_seq_len;
+    plain_embed(s, 1, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, M, Sp, H, c.vocab, c.pos_offset);
+    const float* pend = nullptr;  // GEMM output not yet added to the residual stream
+    const void* pend_b = nullptr;
+    const size_t split = (size_t)M * H;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const he_layer_weights& lw = e->layers[l];
+        const he_engine::Tiled& tw = e->tiled[l];
+        bf16_ln(s, e->resid, pend, 1, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, M, H, c.ln_eps, 1, 0, 1);
+        bf16_gemm_args a = base;
+        a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
+        bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, M, 3 * H, H, a);
+        if (l == c.n_layers - 1) break;
+        bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        a = base; a.out = e->part; a.out_split = split;
+        bf16_gemm_tiled(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, M, H, H, a);
+        bf16_ln(s, e->resid, e->part, 1, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, M, H, c.ln_eps, 1, 0, 1);
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        bf16_gemm_tiled(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, M, F, H, a);
+        a = base; a.out = e->part; a.out_split = split;
+        bf16_gemm_tiled(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, M, H, F, a);
+        pend = e->part; pend_b = lw.b2;
+    }
+    launch_advance_state(s, e->st, Sp, 0);
+    e->cur_len += Sp;
+}
+
+// bf16 path, one new token per sequence (a decode step, or the last prompt token):
+// weight-streaming GEMMs with two-term activations, attention over the cache, LM head
+// fused with log-softmax and sampling.
+void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int32_t* ids_out, float* lp_out,
+                      int out_stride, int out_at_step, float* d_logits_opt) {
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int H = c.hidden, F = c.ffn;
+    bf16_gemm_args base;
+    base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
+    base.max_seq = c.max_seq_len;
+    plain_embed(s, 1, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, B, 1, H, c.vocab, c.pos_offset);
+    const float* pend = nullptr;  // k-split partial sums not yet added to the residual stream
+    int pend_ks = 0;
+    const void* pend_b = nullptr;
+    const size_t split = (size_t)B * H;
+    const int ks1 = bf16_gemm_ksplit(H, H), ks2 = bf16_gemm_ksplit(H, F);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const he_layer_weights& lw = e->layers[l];
+        const he_engine::Tiled& tw = e->tiled[l];
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        bf16_gemm_args a = base;
+        a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
+        bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
+        bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        a = base; a.out = e->part; a.out_split = split;
+        bf16_gemm_skinny(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
+        bf16_ln(s, e->resid, e->part, ks1, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+        a = base; a.out = e->part; a.out_split = split;
+        bf16_gemm_skinny(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
+        pend = e->part; pend_ks = ks2; pend_b = lw.b2;
+    }
+    bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
+    bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
+                 ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    launch_advance_state(s, e->st, 1, 1);
+    e->cur_len += 1;
+    e->step += 1;
+}
+
+he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
+                           int out_stride, int out_at_step, float* d_logits_opt) {
+    if (S > 1) pass_tiled_bf16(e, d_ids, S, B, S - 1);
+    pass_decode_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
+    return check_hip(e, hipGetLastError(), "kernel launch");
+}
+
+// (Re)builds the MFMA-tiled copies from the caller's row-major matrices.
+void tile_weights(he_engine* e) {
+    const he_config& c = e->cfg;
+    const int H = c.hidden, F = c.ffn;
+    for (int l = 0; l < c.n_layers; ++l) {
+        bf16_tile_rows(e->stream, e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H);
+        bf16_tile_rows(e->stream, e->layers[l].wo, e->tiled[l].wo, H, H);
+        bf16_tile_rows(e->stream, e->layers[l].w1, e->tiled[l].w1, F, H);
+        bf16_tile_rows(e->stream, e->layers[l].w2, e->tiled[l].w2, H, F);
+    }
+    bf16_tile_rows(e->stream, e->w.lm_head, e->lm_tiled, c.vocab, H);
+}
+
 // One pass of the decoder over M = B*S new rows (S = prompt length, or 1 for a
 // decode step) followed by the LM head on each sequence's last row and sampling.
 he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
                       int out_stride, int out_at_step, float* d_logits_opt) {
+    if (e->fast) return run_forward_bf16(e, d_ids, B, S, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
     const he_config& c = e->cfg;
     hipStream_t s = e->stream;
     const int M = B * S, H = c.hidden, F = c.ffn, bf = e->bf16;
     const float qscale = 1.0f / sqrtf((float)e->d);
 
-    plain_embed(s, bf, d_ids, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, M, S, H, c.vocab, c.pos_offset);
+    plain_embed(s, bf, d_ids, S, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, M, S, H, c.vocab, c.pos_offset);
     const float* pend_y = nullptr;  // GEMM output not yet added to the residual stream
     const void* pend_b = nullptr;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -129,7 +263,7 @@ he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t*
     float* logits = d_logits_opt ? d_logits_opt : e->logits;
     plain_lm_head(s, bf, e->xf, e->w.lm_head, logits, B, H, c.vocab);
     launch_sample(s, logits, B, c.vocab, e->st, ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
-    launch_advance_state(s, e->st, S);
+    launch_advance_state(s, e->st, S, 1);
     e->cur_len += S;
     e->step += 1;
     return check_hip(e, hipGetLastError(), "kernel launch");
@@ -185,11 +319,27 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     const Sizes z = sizes_of(*cfg);
     hipError_t r = hipSuccess;
     auto A = [&](auto** p, size_t bytes) { if (r == hipSuccess) r = dev_alloc(e, p, bytes); };
+    e->fast = is_fast(*cfg);
     A(&e->kv, z.kv);
     A(&e->st, 256);
-    A(&e->resid, z.rowsH); A(&e->abuf, z.rowsH); A(&e->qbuf, z.rowsH); A(&e->obuf, z.rowsH); A(&e->ybuf, z.rowsH);
-    A(&e->hbuf, z.rowsF);
-    A(&e->xf, z.xf); A(&e->logits, z.logits);
+    A(&e->resid, z.rowsH); A(&e->qbuf, z.rowsH);
+    A(&e->logits, z.logits);
+    if (!e->fast) {
+        A(&e->abuf, z.rowsH); A(&e->obuf, z.rowsH); A(&e->ybuf, z.rowsH);
+        A(&e->hbuf, z.rowsF);
+        A(&e->xf, z.xf);
+    } else {
+        const int H = cfg->hidden, F = cfg->ffn;
+        e->tiled.resize(cfg->n_layers);
+        for (auto& t : e->tiled) {
+            A(&t.wqkv, bf16_tiled_bytes(3 * H, H)); A(&t.wo, bf16_tiled_bytes(H, H));
+            A(&t.w1, bf16_tiled_bytes(F, H)); A(&t.w2, bf16_tiled_bytes(H, F));
+        }
+        A(&e->lm_tiled, z.tiled_lm);
+        A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
+        A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
+        A(&e->part, z.part); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
+    }
     A(&e->gen_lp, z.gen); A(&e->gen_ids, z.gen);
     A(&e->cur_ids, cfg->max_batch * sizeof(int32_t));
     if (r != hipSuccess) {
@@ -200,7 +350,21 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         return r == hipErrorOutOfMemory ? HE_ERR_OOM : HE_ERR_DEVICE;
     }
     launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
+    if (e->fast) {
+        // rows of the last 32-row tile beyond the batch are read by the matrix cores (their
+        // products are never stored): give them defined contents once
+        (void)hipMemsetAsync(e->ablk, 0, z.ablk, e->stream);
+        (void)hipMemsetAsync(e->oblk, 0, z.ablk, e->stream);
+        (void)hipMemsetAsync(e->hblk, 0, z.hblk, e->stream);
+        (void)hipMemsetAsync(e->xfblk, 0, z.xfblk, e->stream);
+        (void)hipMemsetAsync(e->ablk_lo, 0, z.ablk, e->stream);
+        (void)hipMemsetAsync(e->oblk_lo, 0, z.ablk, e->stream);
+        (void)hipMemsetAsync(e->xfblk_lo, 0, z.xfblk, e->stream);
+        (void)hipMemsetAsync(e->hblk_lo, 0, z.hblk, e->stream);
+        tile_weights(e);
+    }
     r = hipStreamSynchronize(e->stream);
+    if (r == hipSuccess) r = hipGetLastError();
     if (r != hipSuccess) {
         g_create_error = std::string("he_create: ") + hipGetErrorString(r);
         free_all(e);
@@ -213,6 +377,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
 
 he_status he_refresh_weights(he_engine* e) {
     if (!e) return HE_ERR_INVALID_ARG;
+    if (e->fast) tile_weights(e);
     return check_hip(e, hipStreamSynchronize(e->stream), "he_refresh_weights");
 }
 

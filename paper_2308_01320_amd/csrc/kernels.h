@@ -8,7 +8,7 @@ struct he_dev_state;
 enum { EPI_STORE = 0, EPI_BIAS_RELU = 1, EPI_QKV = 2 };
 
 // ---- plain kernels (kernels_plain.hip): float activations, row-major; bf16 != 0 selects bf16 storage
-void plain_embed(hipStream_t s, int bf16, const int32_t* ids, const void* tok, const void* pos, float* x,
+void plain_embed(hipStream_t s, int bf16, const int32_t* ids, int id_stride, const void* tok, const void* pos, float* x,
                  const he_dev_state* st, int M, int S, int H, int V, int pos_offset);
 void plain_ln(hipStream_t s, int bf16, float* r, const float* y, const void* ybias, const void* g, const void* b,
               float* a, int rows, int H, float eps, int in_mul, int in_add, int writeback);
@@ -24,6 +24,36 @@ void launch_sample(hipStream_t s, const float* logits, int B, int V, const he_de
                    float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids);
 void launch_set_state(hipStream_t s, he_dev_state* st, int cur_len, int step, int set_pos, int mode, float temperature,
                       uint64_t seed);
-void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens);
+void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps);
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out);
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count);
+
+// ---- bf16 path (kernels_bf16.hip): operands are tiled bf16 blocks, see that file
+struct bf16_gemm_args {
+    const void* bias = nullptr;      // bf16 [N]
+    float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
+    size_t out_split = 0;            // elements between k-splits
+    void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled bf16 output (hi term)
+    void* out_blocks_lo = nullptr;   // EPI_BIAS_RELU: lo term
+    void* kv = nullptr;              // EPI_QKV
+    const he_dev_state* st = nullptr;
+    int S = 1, layer = 0, H = 0, n_heads = 0, max_batch = 0, max_seq = 0;
+    float qscale = 1.f;
+};
+size_t bf16_tiled_bytes(int rows, int K);
+void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K);
+int bf16_gemm_ksplit(int N, int K);
+// rows in slices of 32 (decode, LM head): activations as hi + lo bf16 terms
+void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                      int ksplit, const bf16_gemm_args& a);
+// many rows (prompt pass)
+void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                     const bf16_gemm_args& a);
+void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
+                  const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
+                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids);
+void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
+             const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
+             int in_mul, int in_add, int writeback);
+void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
+               const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq);

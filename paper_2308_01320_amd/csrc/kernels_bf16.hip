@@ -1,0 +1,664 @@
+// bf16 path kernels for gfx950 (CDNA4, 64-wide wavefronts, MFMA 32x32x16 bf16).
+//
+// Tiled operand layout ("blocks"): a bf16 matrix R[rows, K] is stored as
+// [rows/32][K/16][64 lanes][8 values]; lane = 32*((k%16)/8) + r%32 holds
+// R[r][16*kb + 8*(lane/32) + 0..7].  One block is 1 KiB, contiguous, and is
+// exactly the per-lane register image of one MFMA operand, so a wavefront
+// fetches an operand with a single fully coalesced 16-byte-per-lane load and
+// feeds it to the matrix core with no shuffling.  Weights are tiled once at
+// engine creation; activations are written in this layout by the kernel that
+// produces them (LayerNorm, ReLU epilogue, attention).
+//
+// Every GEMM computes D[n][m] = sum_k W[n][k] X[m][k] with W blocks as the A
+// operand and X blocks as the B operand: lane l then holds, for column
+// m = l%32, rows n = 8*(r/4) + 4*(l/32) + r%4 (r = 0..15 accumulators),
+// i.e. runs of four consecutive n -- what the epilogues store.
+//
+// All
+// GEMM activations are carried as two bf16 terms, x = hi + lo with
+// lo = bf16(x - hi): a second MFMA per block against the same weight registers
+// takes the activation rounding error from 2^-9 to 2^-17.  Decode-shaped GEMMs
+// are bound by the weight stream, so there it costs no time; the prompt pass
+// pays twice the matrix-core work for it.
+#include "he_common.h"
+#include "kernels.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one lane's 16 bytes of a block
+
+__device__ __forceinline__ f32x16 mfma_bf16(const u32x4& a, const u32x4& b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// x = hi + lo in two bf16 terms
+__device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
+    const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);
+    hi = (uint32_t)ha | ((uint32_t)hb << 16);
+    lo = pack2(a - bf16_to_f32(ha), b - bf16_to_f32(hb));
+}
+
+// index (in 16-byte units) of the slot holding R[r][k0..k0+7], k0 % 8 == 0
+__device__ __forceinline__ size_t block_slot(int r, int k0, int KB) {
+    return ((size_t)(r >> 5) * KB + (k0 >> 4)) * 64 + (((k0 >> 3) & 1) << 5) + (r & 31);
+}
+
+// ----------------------------------------------------------------- weight tiling
+
+__global__ void tile_rows_kernel(const bf16_t* __restrict__ src, u32x4* __restrict__ dst, int R, int K, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int KB = K >> 4;
+    const int lane = (int)(idx & 63);
+    const int kb = (int)((idx >> 6) % KB);
+    const int rt = (int)((idx >> 6) / KB);
+    const int r = rt * 32 + (lane & 31), k = kb * 16 + (lane >> 5) * 8;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (r < R) v = *reinterpret_cast<const u32x4*>(src + (size_t)r * K + k);
+    dst[idx] = v;
+}
+
+// ----------------------------------------------------------------- epilogues
+
+struct Epi {
+    int M, N;               // valid rows (m) and columns (n) of the product
+    const bf16_t* bias;     // [N] or null
+    float* out;             // STORE: partial sums [ksplit][M][N]; QKV: q [M][H]
+    size_t out_split;       // elements between two k-splits of `out`
+    u32x4* out_blocks;      // BIAS_RELU: tiled bf16 [M/32][N/16] blocks (hi term)
+    u32x4* out_blocks_lo;   // BIAS_RELU: lo term, or null
+    bf16_t* kv;             // QKV: the KV arena
+    const he_dev_state* st;
+    int S, layer, H, n_heads, d, max_batch, max_seq;
+    float qscale;
+    // LM head
+    float* logits;          // optional [M][N]
+    float* stats;           // [M][n_tiles][4]: max z, sum exp(z - max), best score, z at best
+    int* stats_idx;         // [M][n_tiles]: id of best score
+    int n_tiles;
+};
+
+enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3 };
+
+// four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0)
+template <int MODE>
+__device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, float v0, float v1, float v2, float v3) {
+    if (m >= p.M || n0 >= p.N) return;  // N is a multiple of 4 wherever this is used
+    if (MODE == MODE_STORE) {
+        *reinterpret_cast<float4*>(p.out + (size_t)ks * p.out_split + (size_t)m * p.N + n0) =
+            make_float4(v0, v1, v2, v3);
+    } else if (MODE == MODE_BIAS_RELU) {
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
+        v0 = fmaxf(v0 + __uint_as_float(bb.x << 16), 0.f);
+        v1 = fmaxf(v1 + __uint_as_float(bb.x & 0xFFFF0000u), 0.f);
+        v2 = fmaxf(v2 + __uint_as_float(bb.y << 16), 0.f);
+        v3 = fmaxf(v3 + __uint_as_float(bb.y & 0xFFFF0000u), 0.f);
+        const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
+        uint32_t h0, h1, l0, l1;
+        split2(v0, v1, h0, l0);
+        split2(v2, v3, h1, l1);
+        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
+        if (p.out_blocks_lo) reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
+    } else if (MODE == MODE_QKV) {
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
+        v0 += __uint_as_float(bb.x << 16);
+        v1 += __uint_as_float(bb.x & 0xFFFF0000u);
+        v2 += __uint_as_float(bb.y << 16);
+        v3 += __uint_as_float(bb.y & 0xFFFF0000u);
+        if (n0 < p.H) {
+            *reinterpret_cast<float4*>(p.out + (size_t)m * p.H + n0) =
+                make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
+        } else {
+            const int which = n0 >= 2 * p.H, c = n0 - (which ? 2 * p.H : p.H);
+            const int b = m / p.S, t = p.st->cur_len + (m % p.S);
+            bf16_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
+            *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+        }
+    }
+}
+
+// ----------------------------------------------------------------- skinny GEMM (decode, LM head)
+//
+// At most 32 rows per grid.y slice: weights are streamed exactly once from HBM,
+// straight from global memory into MFMA operand registers.  A workgroup of four
+// wavefronts owns a pair of 32-row weight tiles and one k-split; its wavefronts
+// divide the k range, keep kUnroll blocks per stream in flight (two weight
+// streams, the hi and lo activation streams out of L2), and combine their
+// accumulators through LDS.  The sum over k-splits (STORE mode) is taken, in a
+// fixed order, by the LayerNorm kernel that consumes it.
+
+constexpr int kUnroll = 4;
+
+struct SkinnyRegs {
+    u32x4 w0[kUnroll], w1[kUnroll], xh[kUnroll], xl[kUnroll];
+};
+
+__device__ __forceinline__ void skinny_load(SkinnyRegs& r, const u32x4* w0, const u32x4* w1, const u32x4* xh,
+                                            const u32x4* xl) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        r.w0[u] = __builtin_nontemporal_load(w0 + u * 64);
+        r.w1[u] = __builtin_nontemporal_load(w1 + u * 64);
+        r.xh[u] = xh[u * 64];
+        r.xl[u] = xl[u * 64];
+    }
+}
+
+__device__ __forceinline__ void skinny_mma(const SkinnyRegs& r, f32x16& a0, f32x16& a1) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        a0 = mfma_bf16(r.w0[u], r.xh[u], a0);
+        a1 = mfma_bf16(r.w1[u], r.xh[u], a1);
+        a0 = mfma_bf16(r.w0[u], r.xl[u], a0);
+        a1 = mfma_bf16(r.w1[u], r.xl[u], a1);
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+                                                          const u32x4* __restrict__ Xlo, int KB, int n_tiles,
+                                                          int ksplit, Epi p) {
+    __shared__ float red[4][2][16][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int pair = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
+    const int mt = blockIdx.y;
+    const int t0 = pair * 2, t1 = min(pair * 2 + 1, n_tiles - 1);  // a lone last tile is computed twice, stored once
+    const int parts = ksplit * 4, part = ks * 4 + wave;
+    const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
+    const u32x4* w0 = Wp + ((size_t)t0 * KB + kb0) * 64 + lane;
+    const u32x4* w1 = Wp + ((size_t)t1 * KB + kb0) * 64 + lane;
+    const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
+    const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
+    f32x16 acc0 = {}, acc1 = {};
+    int n = kb1 - kb0;
+    if (n >= kUnroll) {
+        SkinnyRegs ra;
+        skinny_load(ra, w0, w1, xh, xl);
+        w0 += kUnroll * 64; w1 += kUnroll * 64; xh += kUnroll * 64; xl += kUnroll * 64; n -= kUnroll;
+        while (n >= kUnroll) {
+            SkinnyRegs rb;
+            skinny_load(rb, w0, w1, xh, xl);
+            w0 += kUnroll * 64; w1 += kUnroll * 64; xh += kUnroll * 64; xl += kUnroll * 64; n -= kUnroll;
+            skinny_mma(ra, acc0, acc1);
+            ra = rb;
+        }
+        skinny_mma(ra, acc0, acc1);
+    }
+    for (; n > 0; --n) {
+        const u32x4 a = __builtin_nontemporal_load(w0), b = __builtin_nontemporal_load(w1), h = *xh, l = *xl;
+        w0 += 64; w1 += 64; xh += 64; xl += 64;
+        acc0 = mfma_bf16(a, h, acc0);
+        acc1 = mfma_bf16(b, h, acc1);
+        acc0 = mfma_bf16(a, l, acc0);
+        acc1 = mfma_bf16(b, l, acc1);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { red[wave][0][r][lane] = acc0[r]; red[wave][1][r][lane] = acc1[r]; }
+    __syncthreads();
+    float v[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[j][r] = (red[0][j][wave * 4 + r][lane] + red[1][j][wave * 4 + r][lane]) +
+                      (red[2][j][wave * 4 + r][lane] + red[3][j][wave * 4 + r][lane]);
+    const int m = mt * 32 + (lane & 31);
+    const int nl = 8 * wave + 4 * (lane >> 5);  // first of this lane's four rows inside a tile
+    const bool two = pair * 2 + 1 < n_tiles;
+    if (MODE != MODE_LMHEAD) {
+        epilogue4<MODE>(p, m, t0 * 32 + nl, ks, v[0][0], v[0][1], v[0][2], v[0][3]);
+        if (two) epilogue4<MODE>(p, m, (t0 + 1) * 32 + nl, ks, v[1][0], v[1][1], v[1][2], v[1][3]);
+    } else {
+        // logits tiles -> per-(row, tile) softmax and arg-max partials
+        __shared__ float zt[2][32][33];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) zt[j][nl + r][lane & 31] = v[j][r];
+        __syncthreads();
+        const int j = threadIdx.x >> 5, mm = mt * 32 + (threadIdx.x & 31), tile = t0 + j;
+        if (threadIdx.x < 64 && mm < p.M && (j == 0 || two)) {
+            const int mode = p.st->mode, step = p.st->step;
+            const float temp = p.st->temperature;
+            const uint32_t k0 = p.st->seed_lo, k1 = p.st->seed_hi;
+            float mx = -INFINITY, best = -INFINITY, bestz = 0.f;
+            int besti = 0x7FFFFFFF;
+            const int nv = min(32, p.N - tile * 32);
+            for (int i = 0; i < nv; ++i) {
+                const float z = zt[j][i][threadIdx.x & 31];
+                const int vid = tile * 32 + i;
+                if (p.logits) p.logits[(size_t)mm * p.N + vid] = z;
+                mx = fmaxf(mx, z);
+                float s = z;
+                if (mode == 1)
+                    s = z / temp + gumbel_from_word(philox_word0((uint32_t)vid, (uint32_t)step, (uint32_t)mm, k0, k1));
+                if (s > best) { best = s; besti = vid; bestz = z; }  // ascending ids: strict > keeps the lowest
+            }
+            float sum = 0.f;
+            for (int i = 0; i < nv; ++i) sum += expf(zt[j][i][threadIdx.x & 31] - mx);
+            float* sp = p.stats + ((size_t)mm * p.n_tiles + tile) * 4;
+            sp[0] = mx; sp[1] = sum; sp[2] = best; sp[3] = bestz;
+            p.stats_idx[(size_t)mm * p.n_tiles + tile] = besti;
+        }
+    }
+}
+
+// One block per sequence: combines the LM-head tile partials in tile order
+// (deterministic), writes token id and its untempered log-probability.
+__global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __restrict__ stats_idx, int n_tiles,
+                                 const he_dev_state* __restrict__ st, int32_t* __restrict__ ids_out,
+                                 float* __restrict__ lp_out, int out_stride, int out_at_step,
+                                 int32_t* __restrict__ cur_ids) {
+    __shared__ float smx[4], ssum[4], sbest[4], sz[4];
+    __shared__ int sidx[4];
+    const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float* sp = stats + (size_t)b * n_tiles * 4;
+    const int* ip = stats_idx + (size_t)b * n_tiles;
+    float mx = -INFINITY;
+    for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) mx = fmaxf(mx, sp[t * 4]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) smx[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
+    float sum = 0.f, best = -INFINITY, bz = 0.f;
+    int bi = 0x7FFFFFFF;
+    for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) {
+        sum += sp[t * 4 + 1] * expf(sp[t * 4] - mx);
+        const float s = sp[t * 4 + 2];
+        const int i = ip[t];
+        if (s > best || (s == best && i < bi)) { best = s; bi = i; bz = sp[t * 4 + 3]; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        sum += __shfl_xor(sum, o);
+        const float os = __shfl_xor(best, o), oz = __shfl_xor(bz, o);
+        const int oi = __shfl_xor(bi, o);
+        if (os > best || (os == best && oi < bi)) { best = os; bi = oi; bz = oz; }
+    }
+    if (lane == 0) { ssum[wave] = sum; sbest[wave] = best; sidx[wave] = bi; sz[wave] = bz; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sum = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+        best = sbest[0]; bi = sidx[0]; bz = sz[0];
+        for (int w = 1; w < 4; ++w)
+            if (sbest[w] > best || (sbest[w] == best && sidx[w] < bi)) { best = sbest[w]; bi = sidx[w]; bz = sz[w]; }
+        const size_t at = (size_t)b * out_stride + (out_at_step ? st->step : 0);
+        ids_out[at] = bi;
+        lp_out[at] = bz - (mx + logf(sum));
+        if (cur_ids) cur_ids[b] = bi;
+    }
+}
+
+// ----------------------------------------------------------------- tiled GEMM (prompt pass)
+//
+// 128 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
+// 64x64 sub-tiles (2x2 MFMA tiles each).  Operands arrive as 1 KiB blocks:
+// global -> registers -> LDS unchanged (conflict-free 16-byte accesses), two
+// k-blocks per stage, double buffered with one barrier per stage.  Activations
+// are the two-term form here as well (hi and lo blocks against the same weight
+// registers), which keeps keys and values of the prompt within a rounding of the
+// exact ones before they are stored as bf16.
+
+constexpr int TN = 128, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of k) per stage
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+                                                         const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
+                                                         int tiles_n, int tiles_m, Epi p) {
+    // [stage][operand: W, X hi, X lo][row-tile 0..3][k-block 0..1][lane]
+    __shared__ u32x4 lds[2][3][4][KSTAGE][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
+    // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.
+    const int nblk = tiles_n * tiles_m;
+    const int per_xcd = (nblk + 7) / 8;
+    const int lin = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (lin >= nblk) return;
+    const int GROUP = 8;  // m-tiles per super-row
+    const int gsize = GROUP * tiles_n;
+    const int g = lin / gsize, first_m = g * GROUP;
+    const int gm = min(GROUP, tiles_m - first_m);
+    const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
+
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 64x64 sub-tile
+    f32x16 acc[2][2] = {};
+
+    // this wavefront stages row-tile `wave` of each operand (KSTAGE blocks each)
+    const int wrt = min(tn * 4 + wave, NT32 - 1), xrt = min(tm * 4 + wave, MT32 - 1);
+    const u32x4* wsrc = Wp + (size_t)wrt * KB * 64 + lane;
+    const u32x4* hsrc = Xhi + (size_t)xrt * KB * 64 + lane;
+    const u32x4* lsrc = Xlo + (size_t)xrt * KB * 64 + lane;
+    u32x4 wreg[KSTAGE], hreg[KSTAGE], lreg[KSTAGE];
+    const int nstage = KB / KSTAGE;  // KB is even (K % 32 == 0)
+#pragma unroll
+    for (int j = 0; j < KSTAGE; ++j) { wreg[j] = wsrc[j * 64]; hreg[j] = hsrc[j * 64]; lreg[j] = lsrc[j * 64]; }
+#pragma unroll
+    for (int j = 0; j < KSTAGE; ++j) {
+        lds[0][0][wave][j][lane] = wreg[j]; lds[0][1][wave][j][lane] = hreg[j]; lds[0][2][wave][j][lane] = lreg[j];
+    }
+    __syncthreads();
+    for (int s = 0; s < nstage; ++s) {
+        const int cur = s & 1;
+        if (s + 1 < nstage) {
+#pragma unroll
+            for (int j = 0; j < KSTAGE; ++j) {
+                const size_t off = ((size_t)(s + 1) * KSTAGE + j) * 64;
+                wreg[j] = wsrc[off]; hreg[j] = hsrc[off]; lreg[j] = lsrc[off];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KSTAGE; ++j) {
+            const u32x4 a0 = lds[cur][0][wn * 2 + 0][j][lane], a1 = lds[cur][0][wn * 2 + 1][j][lane];
+#pragma unroll
+            for (int t = 1; t <= 2; ++t) {
+                const u32x4 b0 = lds[cur][t][wm * 2 + 0][j][lane], b1 = lds[cur][t][wm * 2 + 1][j][lane];
+                acc[0][0] = mfma_bf16(a0, b0, acc[0][0]);
+                acc[0][1] = mfma_bf16(a0, b1, acc[0][1]);
+                acc[1][0] = mfma_bf16(a1, b0, acc[1][0]);
+                acc[1][1] = mfma_bf16(a1, b1, acc[1][1]);
+            }
+        }
+        if (s + 1 < nstage) {
+#pragma unroll
+            for (int j = 0; j < KSTAGE; ++j) {
+                lds[cur ^ 1][0][wave][j][lane] = wreg[j];
+                lds[cur ^ 1][1][wave][j][lane] = hreg[j];
+                lds[cur ^ 1][2][wave][j][lane] = lreg[j];
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int m = tm * TM + (wm * 2 + j) * 32 + (lane & 31);
+            const int nb = tn * TN + (wn * 2 + i) * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                epilogue4<MODE>(p, m, nb + 8 * q, 0, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
+                                acc[i][j][q * 4 + 3]);
+        }
+}
+
+// ----------------------------------------------------------------- LayerNorm (+ residual update)
+//
+// Row `src = m*in_mul + in_add`: r += sum of k-split partials + bias (fixed order),
+// written back when asked; a = LayerNorm(r) is emitted as tiled bf16 blocks.
+__global__ __launch_bounds__(256) void ln_blocks_kernel(float* __restrict__ r, const float* __restrict__ part,
+                                                        int ksplit, size_t part_split,
+                                                        const bf16_t* __restrict__ pbias,
+                                                        const bf16_t* __restrict__ gamma,
+                                                        const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
+                                                        u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
+                                                        int in_add, int writeback) {
+    extern __shared__ __align__(16) float row[];
+    __shared__ float red[4];
+    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t src = (size_t)m * in_mul + in_add;
+    float4* rr = reinterpret_cast<float4*>(r + src * H);
+    float s = 0.f;
+    for (int i = threadIdx.x; i < H / 4; i += blockDim.x) {
+        float4 v = rr[i];
+        if (part) {
+            for (int k = 0; k < ksplit; ++k) {
+                const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * part_split + src * H + 4 * i);
+                v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+            }
+            const uint2 bb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
+            v.x += __uint_as_float(bb.x << 16); v.y += __uint_as_float(bb.x & 0xFFFF0000u);
+            v.z += __uint_as_float(bb.y << 16); v.w += __uint_as_float(bb.y & 0xFFFF0000u);
+            if (writeback) rr[i] = v;
+        }
+        reinterpret_cast<float4*>(row)[i] = v;
+        s += (v.x + v.y) + (v.z + v.w);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    const float mean = ((red[0] + red[1]) + (red[2] + red[3])) / H;
+    float q = 0.f;
+    for (int i = threadIdx.x; i < H; i += blockDim.x) { const float dlt = row[i] - mean; q += dlt * dlt; }
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    __syncthreads();
+    if (lane == 0) red[wave] = q;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf(((red[0] + red[1]) + (red[2] + red[3])) / H + eps);
+    const int KB = H >> 4;
+    for (int c = threadIdx.x; c < H / 8; c += blockDim.x) {
+        const int k0 = c * 8;
+        const u32x4 gg = *reinterpret_cast<const u32x4*>(gamma + k0), bb = *reinterpret_cast<const u32x4*>(beta + k0);
+        const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w}, bw[4] = {bb.x, bb.y, bb.z, bb.w};
+        uint32_t o[4], ol[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float e0 = (row[k0 + 2 * j] - mean) * rstd * __uint_as_float(gw[j] << 16) + __uint_as_float(bw[j] << 16);
+            const float e1 = (row[k0 + 2 * j + 1] - mean) * rstd * __uint_as_float(gw[j] & 0xFFFF0000u) +
+                             __uint_as_float(bw[j] & 0xFFFF0000u);
+            split2(e0, e1, o[j], ol[j]);
+        }
+        const size_t slot = block_slot(m, k0, KB);
+        a[slot] = u32x4{o[0], o[1], o[2], o[3]};
+        if (a_lo) a_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+    }
+}
+
+// ----------------------------------------------------------------- attention over the KV cache
+//
+// One workgroup per (row m, head h); the query at position cur_len + (m % S)
+// sees keys 0..that position.  D/8 adjacent lanes own one key (16 bytes each, a
+// whole row of K or V per group, coalesced); scores are reduced with wavefront
+// shuffles, kept in LDS, soft-maxed, then the same lanes accumulate p_j * V[j].
+// The output goes out as tiled bf16 blocks for the out-projection GEMM.
+template <int D>
+__global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kv,
+                                                   u32x4* __restrict__ o, u32x4* __restrict__ o_lo,
+                                                   const he_dev_state* __restrict__ st, int S, int layer, int H,
+                                                   int n_heads, int max_batch, int max_seq) {
+    constexpr int LPK = D / 8;     // lanes per key
+    constexpr int KPW = 64 / LPK;  // keys per wavefront load
+    constexpr int KR = 4 * KPW;    // keys per workgroup round
+    constexpr int U = 4;
+    extern __shared__ float sc[];  // [max_seq] scores, then probabilities
+    __shared__ float red[8];
+    __shared__ float ored[4][LPK * 8];
+    const int m = blockIdx.x, h = blockIdx.y;
+    const int b = m / S, T = st->cur_len + (m % S) + 1;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sub = lane % LPK, grp = lane / LPK;
+    const float4 qa = *reinterpret_cast<const float4*>(q + (size_t)m * H + h * D + sub * 8);
+    const float4 qb = *reinterpret_cast<const float4*>(q + (size_t)m * H + h * D + sub * 8 + 4);
+    const u32x4* Kp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D));
+    const u32x4* Vp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D));
+    const int jw = wave * KPW + grp;
+    float mx = -INFINITY;
+    for (int base = 0; base < T; base += KR * U) {
+        u32x4 kk[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            kk[u] = j < T ? Kp[(size_t)j * LPK + sub] : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            float s = qa.x * __uint_as_float(kk[u].x << 16);
+            s = fmaf(qa.y, __uint_as_float(kk[u].x & 0xFFFF0000u), s);
+            s = fmaf(qa.z, __uint_as_float(kk[u].y << 16), s);
+            s = fmaf(qa.w, __uint_as_float(kk[u].y & 0xFFFF0000u), s);
+            s = fmaf(qb.x, __uint_as_float(kk[u].z << 16), s);
+            s = fmaf(qb.y, __uint_as_float(kk[u].z & 0xFFFF0000u), s);
+            s = fmaf(qb.z, __uint_as_float(kk[u].w << 16), s);
+            s = fmaf(qb.w, __uint_as_float(kk[u].w & 0xFFFF0000u), s);
+#pragma unroll
+            for (int o2 = 1; o2 < LPK; o2 <<= 1) s += __shfl_xor(s, o2);
+            if (j < T) {
+                if (sub == 0) sc[j] = s;
+                mx = fmaxf(mx, s);
+            }
+        }
+    }
+    for (int o2 = 32; o2 > 0; o2 >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o2));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();  // also publishes sc[]
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float sum = 0.f;
+    for (int j = threadIdx.x; j < T; j += 256) {
+        const float pj = expf(sc[j] - mx);
+        sc[j] = pj;
+        sum += pj;
+    }
+    for (int o2 = 32; o2 > 0; o2 >>= 1) sum += __shfl_xor(sum, o2);
+    if (lane == 0) red[4 + wave] = sum;
+    __syncthreads();  // also publishes the probabilities
+    sum = (red[4] + red[5]) + (red[6] + red[7]);
+    float acc[8] = {};
+    for (int base = 0; base < T; base += KR * U) {
+        u32x4 vv[U];
+        float pj[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            vv[u] = j < T ? Vp[(size_t)j * LPK + sub] : u32x4{0u, 0u, 0u, 0u};
+            pj[u] = j < T ? sc[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc[0] = fmaf(pj[u], __uint_as_float(vv[u].x << 16), acc[0]);
+            acc[1] = fmaf(pj[u], __uint_as_float(vv[u].x & 0xFFFF0000u), acc[1]);
+            acc[2] = fmaf(pj[u], __uint_as_float(vv[u].y << 16), acc[2]);
+            acc[3] = fmaf(pj[u], __uint_as_float(vv[u].y & 0xFFFF0000u), acc[3]);
+            acc[4] = fmaf(pj[u], __uint_as_float(vv[u].z << 16), acc[4]);
+            acc[5] = fmaf(pj[u], __uint_as_float(vv[u].z & 0xFFFF0000u), acc[5]);
+            acc[6] = fmaf(pj[u], __uint_as_float(vv[u].w << 16), acc[6]);
+            acc[7] = fmaf(pj[u], __uint_as_float(vv[u].w & 0xFFFF0000u), acc[7]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+        for (int o2 = LPK; o2 < 64; o2 <<= 1) acc[e] += __shfl_xor(acc[e], o2);
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ored[wave][sub * 8 + e] = acc[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < LPK) {
+        float ov[8];
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int i = threadIdx.x * 8 + e;
+            ov[e] = ((ored[0][i] + ored[1][i]) + (ored[2][i] + ored[3][i])) * inv;
+        }
+        uint32_t oh[4], ol[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split2(ov[2 * e], ov[2 * e + 1], oh[e], ol[e]);
+        const size_t slot = block_slot(m, h * D + threadIdx.x * 8, H >> 4);
+        o[slot] = u32x4{oh[0], oh[1], oh[2], oh[3]};
+        if (o_lo) o_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+    }
+}
+
+template <int MODE>
+void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles, int m_tiles,
+                   int ksplit, const Epi& p) {
+    dim3 grid(((n_tiles + 1) / 2) * ksplit, m_tiles);
+    gemm_skinny_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles,
+                                                  ksplit, p);
+}
+
+template <int MODE>
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p) {
+    const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
+    const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
+    const int nblk = tiles_n * tiles_m;
+    const int grid = ((nblk + 7) / 8) * 8;
+    gemm_tiled_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32, MT32,
+                                                 tiles_n, tiles_m, p);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+size_t bf16_tiled_bytes(int rows, int K) { return (size_t)((rows + 31) / 32) * (K / 16) * 1024; }
+
+void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K) {
+    const size_t total = (size_t)((R + 31) / 32) * (K / 16) * 64;
+    tile_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total);
+}
+
+int bf16_gemm_ksplit(int N, int K) {
+    // k-splits of a decode-shaped STORE GEMM: enough workgroups to keep every CU streaming,
+    // while each wavefront still runs a few unrolled rounds
+    const int pairs = (N + 63) / 64;
+    int ks = 1;
+    while (pairs * ks < 256 && ks < 8 && (K / 16) / (ks * 2 * 4) >= 2 * kUnroll) ks *= 2;
+    return ks;
+}
+
+static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
+    Epi p{};
+    p.M = M; p.N = N; p.bias = (const bf16_t*)a.bias; p.out = a.out; p.out_split = a.out_split;
+    p.out_blocks = (u32x4*)a.out_blocks; p.out_blocks_lo = (u32x4*)a.out_blocks_lo; p.kv = (bf16_t*)a.kv; p.st = a.st;
+    p.S = a.S; p.layer = a.layer; p.H = a.H; p.n_heads = a.n_heads; p.d = a.n_heads ? a.H / a.n_heads : 0;
+    p.max_batch = a.max_batch; p.max_seq = a.max_seq; p.qscale = a.qscale;
+    return p;
+}
+
+void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                      int ksplit, const bf16_gemm_args& a) {
+    const Epi p = make_epi(M, N, a);
+    const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
+    if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p);
+    else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, 1, p);
+    else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, 1, p);
+}
+
+void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                     const bf16_gemm_args& a) {
+    const Epi p = make_epi(M, N, a);
+    if (mode == EPI_STORE) launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+    else if (mode == EPI_BIAS_RELU) launch_tiled<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+    else launch_tiled<MODE_QKV>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+}
+
+void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
+                  const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
+                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids) {
+    Epi p{};
+    p.M = B; p.N = V; p.st = st; p.logits = logits_opt; p.stats = stats; p.stats_idx = stats_idx;
+    p.n_tiles = (V + 31) / 32;
+    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, Xlo, K / 16, p.n_tiles, (B + 31) / 32, 1, p);
+    lm_reduce_kernel<<<B, 256, 0, s>>>(stats, stats_idx, p.n_tiles, st, ids_out, lp_out, out_stride, out_at_step,
+                                       cur_ids);
+}
+
+void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
+             const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
+             int in_mul, int in_add, int writeback) {
+    ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
+        r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
+        (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback);
+}
+
+void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
+               const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq) {
+    dim3 grid(M, n_heads);
+    const size_t shm = (size_t)max_seq * sizeof(float);
+    if (H / n_heads == 128)
+        attn_kernel<128><<<grid, 256, shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks, (u32x4*)o_blocks_lo, st, S,
+                                                layer, H, n_heads, max_batch, max_seq);
+    else
+        attn_kernel<64><<<grid, 256, shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks, (u32x4*)o_blocks_lo, st, S,
+                                               layer, H, n_heads, max_batch, max_seq);
+}

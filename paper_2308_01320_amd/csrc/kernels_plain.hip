@@ -30,13 +30,13 @@ __device__ __forceinline__ float block_max(float v, float* red) {
     return t;
 }
 
-// x[m,:] = tok_emb[id[m],:] + pos_emb[cur_len + (m % S) + pos_offset,:]
+// Row m = b*S + t:  x[m,:] = tok_emb[ids[b*id_stride + t],:] + pos_emb[cur_len + t + pos_offset,:]
 template <typename ST>
-__global__ void embed_kernel(const int32_t* __restrict__ ids, const ST* __restrict__ tok, const ST* __restrict__ pos,
-                             float* __restrict__ x, const he_dev_state* __restrict__ st, int S, int H, int V,
-                             int pos_offset) {
+__global__ void embed_kernel(const int32_t* __restrict__ ids, int id_stride, const ST* __restrict__ tok,
+                             const ST* __restrict__ pos, float* __restrict__ x, const he_dev_state* __restrict__ st,
+                             int S, int H, int V, int pos_offset) {
     const int m = blockIdx.x;
-    int id = ids[m];
+    int id = ids[(size_t)(m / S) * id_stride + (m % S)];
     id = id < 0 ? 0 : (id >= V ? V - 1 : id);  // out-of-range ids are clamped, never read out of bounds
     const size_t p = (size_t)(st->cur_len + (m % S) + pos_offset);
     for (int i = threadIdx.x; i < H; i += blockDim.x)
@@ -241,9 +241,9 @@ __global__ void set_state_kernel(he_dev_state* st, int cur_len, int step, int se
     st->mode = mode; st->temperature = temperature; st->seed_lo = seed_lo; st->seed_hi = seed_hi;
 }
 
-__global__ void advance_state_kernel(he_dev_state* st, int tokens) {
+__global__ void advance_state_kernel(he_dev_state* st, int tokens, int steps) {
     st->cur_len += tokens;
-    st->step += 1;
+    st->step += steps;
 }
 
 __global__ void rng_words_kernel(uint32_t* out, int count, uint32_t v0, uint32_t n, uint32_t b, uint32_t k0,
@@ -263,14 +263,14 @@ __global__ void copy_out_kernel(const int32_t* __restrict__ ids, const float* __
 // ------------------------------------------------------------------ launchers
 
 template <typename ST>
-static void plain_embed_t(hipStream_t s, const int32_t* ids, const void* tok, const void* pos, float* x,
-                          const he_dev_state* st, int M, int S, int H, int V, int pos_offset) {
-    embed_kernel<ST><<<M, kThreads, 0, s>>>(ids, (const ST*)tok, (const ST*)pos, x, st, S, H, V, pos_offset);
+static void plain_embed_t(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
+                          float* x, const he_dev_state* st, int M, int S, int H, int V, int pos_offset) {
+    embed_kernel<ST><<<M, kThreads, 0, s>>>(ids, id_stride, (const ST*)tok, (const ST*)pos, x, st, S, H, V, pos_offset);
 }
-void plain_embed(hipStream_t s, int bf16, const int32_t* ids, const void* tok, const void* pos, float* x,
+void plain_embed(hipStream_t s, int bf16, const int32_t* ids, int id_stride, const void* tok, const void* pos, float* x,
                  const he_dev_state* st, int M, int S, int H, int V, int pos_offset) {
-    if (bf16) plain_embed_t<bf16_t>(s, ids, tok, pos, x, st, M, S, H, V, pos_offset);
-    else plain_embed_t<float>(s, ids, tok, pos, x, st, M, S, H, V, pos_offset);
+    if (bf16) plain_embed_t<bf16_t>(s, ids, id_stride, tok, pos, x, st, M, S, H, V, pos_offset);
+    else plain_embed_t<float>(s, ids, id_stride, tok, pos, x, st, M, S, H, V, pos_offset);
 }
 
 void plain_ln(hipStream_t s, int bf16, float* r, const float* y, const void* ybias, const void* g, const void* b,
@@ -324,8 +324,8 @@ void launch_set_state(hipStream_t s, he_dev_state* st, int cur_len, int step, in
                                      (uint32_t)(seed >> 32));
 }
 
-void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens) {
-    advance_state_kernel<<<1, 1, 0, s>>>(st, tokens);
+void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps) {
+    advance_state_kernel<<<1, 1, 0, s>>>(st, tokens, steps);
 }
 
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out) {

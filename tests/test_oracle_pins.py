@@ -344,3 +344,34 @@ def test_generate_is_prefill_plus_g_minus_1_steps_and_teacher_forcing():
     np.testing.assert_array_equal(f2["logits"][0], free["logits"][0])
     full = O.forward_full(w, np.concatenate([p, other[:, :4]], 1), d.n_heads)
     np.testing.assert_allclose(f2["logits"][4], full[:, -1], atol=1e-10)
+
+
+# ---------------------------------------------------------------- bf16 KV cache format
+
+def test_round_bf16_against_torch_and_ties():
+    rng = np.random.default_rng(9)
+    x32 = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()  # float32 -> bf16 is one rounding
+    np.testing.assert_array_equal(O.round_bf16(x32.astype(np.float64)), want)
+    # ties go to the even neighbour; just above / below a tie go to the nearer one
+    ulp = 2.0 ** -7
+    assert O.round_bf16(np.array([1.0 + ulp / 2]))[0] == 1.0
+    assert O.round_bf16(np.array([1.0 + 3 * ulp / 2]))[0] == 1.0 + 2 * ulp
+    assert O.round_bf16(np.array([1.0 + ulp / 2 + 1e-12]))[0] == 1.0 + ulp
+    assert O.round_bf16(np.array([-(1.0 + ulp / 2 - 1e-12)]))[0] == -1.0
+    y = O.round_bf16(rng.standard_normal(1000))
+    np.testing.assert_array_equal(O.round_bf16(y), y)  # idempotent
+
+
+def test_bf16_cache_cached_equals_cache_free_and_differs_from_f64():
+    d = tiny_dims(n_layers=2, hidden=32, n_heads=4)
+    w = synth.make_weights(d, seed=2, std=0.3)
+    p = synth.make_prompts(d, seed=3, batch=2, prompt_len=6)
+    out = O.generate(w, p, 4, d.n_heads, kv_dtype="bf16")
+    seq = np.concatenate([p, out["ids"]], axis=1)
+    full = O.forward_full(w, seq[:, :-1], d.n_heads, kv_dtype="bf16")
+    for n in range(4):
+        np.testing.assert_allclose(out["logits"][n], full[:, 5 + n], atol=1e-10)
+    exact = O.forward_full(w, seq[:, :-1], d.n_heads)
+    diff = np.abs(full - exact).max()
+    assert 1e-5 < diff < 0.1  # the cache format matters, by about bf16's precision

@@ -6,9 +6,13 @@ from oracle import opt_oracle as O
 from paper_2308_01320_amd import binding, synth
 
 
-def oracle_run(d, w, prompts, G, mode, temperature=1.0, seed=0):
+def oracle_run(d, w, prompts, G, mode, temperature=1.0, seed=0, kv_dtype=None):
+    """The oracle on the configuration's own storage formats: weights as given (already
+    bf16-representable for dtype bf16) and a bf16 KV cache for dtype bf16."""
+    if kv_dtype is None:
+        kv_dtype = "bf16" if d.dtype == "bf16" else "f64"
     return O.generate(w, prompts, G, d.n_heads, mode=mode, temperature=temperature, seed=seed,
-                      eps=d.ln_eps, pos_offset=d.pos_offset)
+                      eps=d.ln_eps, pos_offset=d.pos_offset, kv_dtype=kv_dtype)
 
 
 def engine_teacher_forced(eng, prompts_np, forced_ids, G, samp):
