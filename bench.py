@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the generation phase: `python bench.py --gpus 1 --steps K --warmup W`.
+
+A step is one whole generation job (he_generate: prompt pass + G-1 KV-cached
+decode steps + sampling) of the headline workload -- an OPT-13B-shaped actor,
+batch 32, 256 prompt tokens, 256 generated tokens, bf16 weights with random
+init, seeded Gumbel-max sampling.  All inputs are synthetic and resident in
+HBM before the timed region.  Prints ONE JSON line: generated tokens/s, plus
+`roofline` (the dominant decode kernel against the 8 TB/s HBM peak, its
+duration taken live with HIP events) and `cpu_baseline` (the CPU oracle timed
+on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12        # B/s, MI355X published
+MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
+
+
+def device_weights(d, torch, seed=0, std=0.02):
+    """Random-init bf16 weights generated on the device, tensor by tensor."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = torch.bfloat16
+
+    def draw(shape, mean=0.0):
+        t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+        return (t * std + mean).to(dt).contiguous()
+
+    H, F = d.hidden, d.ffn
+    w = {"tok_emb": draw((d.vocab, H)), "pos_emb": draw((d.max_positions + d.pos_offset, H)), "layers": []}
+    for _ in range(d.n_layers):
+        w["layers"].append({
+            "ln1_g": draw((H,), 1.0), "ln1_b": draw((H,)), "wqkv": draw((3 * H, H)), "bqkv": draw((3 * H,)),
+            "wo": draw((H, H)), "bo": draw((H,)), "ln2_g": draw((H,), 1.0), "ln2_b": draw((H,)),
+            "w1": draw((F, H)), "b1": draw((F,)), "w2": draw((H, F)), "b2": draw((H,))})
+    w["lnf_g"], w["lnf_b"] = draw((H,), 1.0), draw((H,))
+    w["lm_head"] = w["tok_emb"]
+    return w
+
+
+def algorithmic_bytes(d):
+    """Bytes the method itself must move per decode step (weights once for the whole
+    batch; K/V of every cached position read, the new position written)."""
+    H, F, L, V = d.hidden, d.ffn, d.n_layers, d.vocab
+    wbytes = 2 * (L * (4 * H * H + 2 * H * F + 9 * H + F) + 2 * H + V * H)
+    kvtok = L * 2 * H * 2
+    return wbytes, kvtok
+
+
+def prefill_flops(d):
+    H, F, L, V, B, S = d.hidden, d.ffn, d.n_layers, d.vocab, d.batch, d.prompt_len
+    return 2 * B * S * L * (4 * H * H + 2 * H * F) + L * B * 2 * S * S * H + 2 * B * V * H
+
+
+def cpu_baseline(d, seconds_hint=20.0):
+    """The oracle, as it stands, on a bounded sample of the workload: 2 of L layers,
+    4 of B sequences, the full prompt, 3 decode steps; extrapolated linearly in
+    layers, batch and steps to the whole job."""
+    import numpy as np
+    from oracle import opt_oracle as O
+    from paper_2308_01320_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ls, Bs, steps = min(2, d.n_layers), min(4, d.batch), 3
+    ds = d.sliced(n_layers=Ls, batch=Bs, max_positions=d.prompt_len + steps + 1)
+    w = synth.make_weights(ds, seed=1)
+    w = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
+         for k, v in w.items()}
+    w["lm_head"] = w["tok_emb"]
+    prompts = synth.make_prompts(ds, seed=2)
+    dec = O.CachedDecoder(w, ds.n_heads, ds.ln_eps, ds.pos_offset, "bf16")
+    t0 = time.perf_counter()
+    z = dec.prefill(prompts)
+    t_prefill = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for n in range(steps):
+        tok, _, _ = O.sample(z, d.sampling, 1.0, 42, n)
+        z = dec.step(tok)
+    t_step = (time.perf_counter() - t0) / steps
+    # the head (final LayerNorm + LM head + sampling) does not scale with layers
+    x = np.zeros((Bs, 1, ds.hidden))
+    t0 = time.perf_counter()
+    zz = O.lm_logits(w, x, ds.ln_eps)
+    O.sample(zz[:, 0, :], d.sampling, 1.0, 42, 0)
+    t_head = time.perf_counter() - t0
+    scale_l, scale_b = d.n_layers / Ls, d.batch / Bs
+    full = scale_b * ((max(t_prefill - t_head, 0.0) * scale_l + t_head) +
+                      (d.gen_len - 1) * (max(t_step - t_head, 0.0) * scale_l + t_head))
+    return {"value": d.batch * d.gen_len / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{Ls} of {d.n_layers} layers, {Bs} of {d.batch} sequences, prompt {d.prompt_len}, "
+                      f"{steps} decode steps; extrapolated linearly in layers, batch and steps",
+            "measured_s": {"prefill": t_prefill, "decode_step": t_step, "head": t_head}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="opt-13b", help="tiny | opt-1.3b | opt-6.7b | opt-13b | opt-66b")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (a reduced model: not the headline number)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timing-steps", type=int, default=24, help="decode steps run with per-kernel HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no cross-GPU sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2308_01320_amd import binding, synth
+
+    d = synth.CONFIGS[args.workload]
+    if args.layers:
+        d = d.sliced(n_layers=args.layers)
+    if d.dtype != "bf16":
+        raise SystemExit("bench.py times the bf16 workloads; the tiny f32 configuration is a parity case")
+    B, S, G = d.batch, d.prompt_len, d.gen_len
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()  # default priority; the engine captures its decode step on it
+    weights = device_weights(d, torch)
+    cfg = binding.make_config(d, stream=stream.cuda_stream)
+    eng = binding.Engine(cfg, weights)
+    prompts = torch.from_numpy(synth.make_prompts(d, seed=1234 + 3)).cuda()
+    samp = binding.sampling(d.sampling, 1.0, 42)
+    out_ids = torch.empty(B, G, dtype=torch.int32, device="cuda")
+    out_lp = torch.empty(B, G, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            eng.he_generate(prompts, G, samp, out_ids, out_lp)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(args.steps):
+            eng.he_generate(prompts, G, samp, out_ids, out_lp)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        dev_ms = ev0.elapsed_time(ev1)
+        ms_per_step = wall * 1e3 / args.steps
+
+        # split of one job: prompt pass (he_prefill) and the decode loop, HIP events on the same stream
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        eng.he_reset()
+        e0.record(stream)
+        ids, _, _ = eng.he_prefill(prompts, samp)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        prefill_ms = e0.elapsed_time(e1)
+        decode_ms = dev_ms / args.steps - prefill_ms
+
+        # per-kernel durations of the decode step, live, with HIP events around every launch
+        eng.he_timing_enable(True)
+        nt = max(1, min(args.timing_steps, G - 1))
+        for _ in range(nt):
+            ids, _, _ = eng.he_decode_step(ids, samp)
+        timing = eng.he_timing_read()
+        eng.he_timing_enable(False)
+        torch.cuda.synchronize()
+
+    wbytes, kvtok = algorithmic_bytes(d)
+    # decode steps of a job see contexts S+1 .. S+G-1 (after appending the new position)
+    step_bytes = [wbytes + B * T * kvtok + B * kvtok for T in range(S + 1, S + G)]
+    decode_gbs = sum(step_bytes) / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 else 0.0
+    pf = prefill_flops(d)
+
+    H, F = d.hidden, d.ffn
+    kern_bytes = {  # algorithmic bytes per launch: the weights (and biases) the kernel must stream
+        "qkv": 2 * (3 * H * H + 3 * H), "out_proj": 2 * (H * H + H), "fc1": 2 * (F * H + F), "fc2": 2 * (H * F + H),
+        "lm_head": 2 * d.vocab * H,
+        # attention during the timed decode steps: contexts S+1 .. S+nt, K and V of one layer
+        "attention": sum(2 * B * T * H * 2 for T in range(S + 1, S + nt + 1)) / nt,
+    }
+    kernels = {}
+    for k, (ms, cnt) in timing.items():
+        if cnt:
+            avg = ms / cnt
+            kernels[k] = {"avg_us": avg * 1e3, "launches": cnt}
+            if k in kern_bytes:
+                kernels[k]["GB/s"] = kern_bytes[k] / (avg * 1e-3) / 1e9
+    dom = "fc1"
+    dom_avg_s = timing[dom][0] / max(1, timing[dom][1]) * 1e-3
+    achieved = kern_bytes[dom] / dom_avg_s / 1e9 if dom_avg_s > 0 else 0.0
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": None,
+                "kernel": "gemm_skinny_kernel<MODE_BIAS_RELU> (decode FC1 + bias + ReLU)",
+                "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6}
+
+    result = {
+        "metric": "generated tokens/s (1 GPU) + decode HBM GB/s as % of 8 TB/s peak",
+        "value": B * G * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{d.name}-shaped actor, {d.n_layers} layers, hidden {H}, {d.n_heads} heads, ffn {F}, "
+                               f"vocab {d.vocab}; batch {B}, prompt {S}, generate {G}, {d.sampling} sampling",
+                   "global_batch": B, "prompt_len": S, "gen_len": G},
+        "roofline": roofline,
+        "decode": {"ms_per_token_step": decode_ms / (G - 1), "hbm_GB/s": decode_gbs,
+                   "hbm_frac": decode_gbs / (HBM_PEAK / 1e9), "tokens/s": B * (G - 1) / (decode_ms * 1e-3)},
+        "prefill": {"ms": prefill_ms, "TFLOP/s": pf / (prefill_ms * 1e-3) / 1e12,
+                    "mfma_frac": pf / (prefill_ms * 1e-3) / MFMA_BF16_PEAK},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(d)
+    eng.he_destroy()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -149,6 +149,26 @@ const char* he_last_error(const he_engine* e);
 /* Current number of cached positions per sequence, or -1 if e is NULL. */
 int he_cache_len(const he_engine* e);
 
+/* Measurement hook (bf16 path).  While on, he_prefill / he_decode_step / he_generate
+ * launch their decode-shaped kernels one by one (no graph replay) and bracket every
+ * launch of each kernel class below with a pair of HIP events on cfg.stream.
+ * he_timing_read synchronises the stream, returns the summed elapsed milliseconds
+ * and launch counts per class since the last read, and clears them.  Events are
+ * created on demand while the hook is on (the one place the engine allocates after
+ * he_create); results are unaffected. */
+enum {
+    HE_K_LAYERNORM = 0, /* residual update + LayerNorm */
+    HE_K_QKV = 1,       /* fused QKV projection, K/V appended to the cache */
+    HE_K_ATTENTION = 2, /* attention over the cache */
+    HE_K_OUT_PROJ = 3,
+    HE_K_FC1 = 4,       /* + bias + ReLU */
+    HE_K_FC2 = 5,
+    HE_K_LM_HEAD = 6,   /* LM head + log-softmax + sampling (both of its kernels) */
+    HE_K_COUNT = 7
+};
+he_status he_timing_enable(he_engine* e, int on);
+he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_class, int n_classes);
+
 /* Test hook for the sampler's counter-based generator: writes the `count`
  * 32-bit words for vocabulary ids v0 .. v0+count-1 of (seed, sequence b,
  * generation step n) to d_out [count] uint32, on `stream`. */

@@ -81,6 +81,10 @@ def lib() -> C.CDLL:
     L.he_last_error.argtypes = [vp]
     L.he_cache_len.restype = C.c_int
     L.he_cache_len.argtypes = [vp]
+    L.he_timing_enable.restype = C.c_int
+    L.he_timing_enable.argtypes = [vp, C.c_int]
+    L.he_timing_read.restype = C.c_int
+    L.he_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_long), C.c_int]
     L.he_rng_words.restype = C.c_int
     L.he_rng_words.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, vp, vp]
     _lib = L
@@ -88,7 +92,10 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
-           "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words")
+           "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
+           "he_timing_read")
+
+KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head")
 
 
 def _ptr(t) -> Optional[int]:
@@ -191,6 +198,16 @@ class Engine:
 
     def he_refresh_weights(self):
         self._check(lib().he_refresh_weights(self.handle))
+
+    def he_timing_enable(self, on: bool):
+        self._check(lib().he_timing_enable(self.handle, 1 if on else 0))
+
+    def he_timing_read(self) -> dict:
+        n = len(KERNEL_CLASSES)
+        ms = (C.c_double * n)()
+        cnt = (C.c_long * n)()
+        self._check(lib().he_timing_read(self.handle, ms, cnt, n))
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
     def he_destroy(self):
         if self.handle:

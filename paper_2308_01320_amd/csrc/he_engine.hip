@@ -33,6 +33,16 @@ struct he_engine {
     float *part = nullptr, *stats = nullptr;
     int* stats_idx = nullptr;
 
+    // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
+    hipGraphExec_t step_graph = nullptr;
+    int graph_B = 0, graph_G = 0;
+
+    // measurement hook: HIP events around every launch of a kernel class of the decode step
+    bool timing = false;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<std::pair<int, size_t>> ev_used;  // (class, index of the start event)
+    size_t ev_next = 0;
+
     // host mirror of the device state
     int cur_len = 0, step = 0, batch = 0;
     std::string err;
@@ -131,6 +141,27 @@ void free_all(he_engine* e) {
     e->allocs.clear();
 }
 
+// Brackets the launches made during its lifetime with a pair of events when timing is on.
+struct LaunchTimer {
+    he_engine* e;
+    bool on;
+    LaunchTimer(he_engine* eng, int cls) : e(eng), on(eng->timing) {
+        if (!on) return;
+        while (e->ev_pool.size() < e->ev_next + 2) {
+            hipEvent_t ev;
+            if (hipEventCreate(&ev) != hipSuccess) { on = false; return; }
+            e->ev_pool.push_back(ev);
+        }
+        e->ev_used.emplace_back(cls, e->ev_next);
+        (void)hipEventRecord(e->ev_pool[e->ev_next], e->stream);
+    }
+    ~LaunchTimer() {
+        if (!on) return;
+        (void)hipEventRecord(e->ev_pool[e->ev_next + 1], e->stream);
+        e->ev_next += 2;
+    }
+};
+
 // bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  Only the
 // K/V cache is wanted from these rows (the last prompt token takes the decode-shaped pass
 // below), so the final layer stops once its keys and values are stored.
@@ -187,23 +218,50 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
         const he_engine::Tiled& tw = e->tiled[l];
-        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        {
+            LaunchTimer t(e, HE_K_LAYERNORM);
+            bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        }
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
-        bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
-        bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        {
+            LaunchTimer t(e, HE_K_QKV);
+            bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
+        }
+        {
+            LaunchTimer t(e, HE_K_ATTENTION);
+            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        }
         a = base; a.out = e->part; a.out_split = split;
-        bf16_gemm_skinny(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
-        bf16_ln(s, e->resid, e->part, ks1, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        {
+            LaunchTimer t(e, HE_K_OUT_PROJ);
+            bf16_gemm_skinny(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
+        }
+        {
+            LaunchTimer t(e, HE_K_LAYERNORM);
+            bf16_ln(s, e->resid, e->part, ks1, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        }
         a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
-        bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+        {
+            LaunchTimer t(e, HE_K_FC1);
+            bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+        }
         a = base; a.out = e->part; a.out_split = split;
-        bf16_gemm_skinny(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
+        {
+            LaunchTimer t(e, HE_K_FC2);
+            bf16_gemm_skinny(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
+        }
         pend = e->part; pend_ks = ks2; pend_b = lw.b2;
     }
-    bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
-    bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
-                 ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    {
+        LaunchTimer t(e, HE_K_LAYERNORM);
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
+    }
+    {
+        LaunchTimer t(e, HE_K_LM_HEAD);
+        bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
+                     ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    }
     launch_advance_state(s, e->st, 1, 1);
     e->cur_len += 1;
     e->step += 1;
@@ -267,6 +325,41 @@ he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t*
     e->cur_len += S;
     e->step += 1;
     return check_hip(e, hipGetLastError(), "kernel launch");
+}
+
+void drop_step_graph(he_engine* e) {
+    if (e->step_graph) (void)hipGraphExecDestroy(e->step_graph);
+    e->step_graph = nullptr;
+    e->graph_B = e->graph_G = 0;
+}
+
+// Captures one decode step of he_generate (input ids from cur_ids, outputs into the
+// engine's [B, G] generation buffers at the device-side step index).
+he_status ensure_step_graph(he_engine* e, int B, int G) {
+    if (e->step_graph && e->graph_B == B && e->graph_G == G) return HE_OK;
+    drop_step_graph(e);
+    const int len = e->cur_len, step = e->step;
+    hipError_t r = hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal);
+    if (r != hipSuccess) return check_hip(e, r, "hipStreamBeginCapture");
+    const he_status rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
+    e->cur_len = len;  // capturing runs nothing
+    e->step = step;
+    hipGraph_t g = nullptr;
+    r = hipStreamEndCapture(e->stream, &g);
+    if (rc != HE_OK) {
+        if (g) (void)hipGraphDestroy(g);
+        return rc;
+    }
+    if (r != hipSuccess) return check_hip(e, r, "hipStreamEndCapture");
+    r = hipGraphInstantiate(&e->step_graph, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    if (r != hipSuccess) {
+        e->step_graph = nullptr;
+        return check_hip(e, r, "hipGraphInstantiate");
+    }
+    e->graph_B = B;
+    e->graph_G = G;
+    return HE_OK;
 }
 
 const char* check_sampling(const he_sampling* sp) {
@@ -430,9 +523,26 @@ he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, i
     e->batch = B;
     launch_set_state(e->stream, e->st, 0, 0, 1, sampling->mode, sampling->temperature, sampling->seed);
     rc = run_forward(e, d_prompt_ids, B, S, e->gen_ids, e->gen_lp, G, 1, nullptr);
-    for (int n = 1; n < G && rc == HE_OK; ++n)
-        rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
     if (rc != HE_OK) return rc;
+    // Every later step is the same launch sequence (positions, step number and sampling
+    // parameters live in device memory), so it is captured once and replayed.  Capture needs a
+    // stream of its own: on the NULL stream, and while per-kernel timing is on, the steps are
+    // launched one by one instead -- same kernels, same results.
+    const bool use_graph = e->stream != nullptr && !e->timing && G > 2;
+    if (use_graph) {
+        rc = ensure_step_graph(e, B, G);
+        if (rc != HE_OK) return rc;
+        for (int n = 1; n < G; ++n) {
+            const hipError_t r = hipGraphLaunch(e->step_graph, e->stream);
+            if (r != hipSuccess) return check_hip(e, r, "hipGraphLaunch");
+            e->cur_len += 1;
+            e->step += 1;
+        }
+    } else {
+        for (int n = 1; n < G && rc == HE_OK; ++n)
+            rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
+        if (rc != HE_OK) return rc;
+    }
     launch_copy_out(e->stream, e->gen_ids, e->gen_lp, d_out_ids, d_out_logprobs, B * G);
     return check_hip(e, hipGetLastError(), "he_generate");
 }
@@ -440,8 +550,34 @@ he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, i
 he_status he_destroy(he_engine* e) {
     if (!e) return HE_OK;
     (void)hipStreamSynchronize(e->stream);
+    drop_step_graph(e);
+    for (hipEvent_t ev : e->ev_pool) (void)hipEventDestroy(ev);
     free_all(e);
     delete e;
+    return HE_OK;
+}
+
+he_status he_timing_enable(he_engine* e, int on) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    e->timing = on != 0;
+    e->ev_used.clear();
+    e->ev_next = 0;
+    return HE_OK;
+}
+
+he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_class, int n_classes) {
+    if (!e || !ms_per_class || !launches_per_class || n_classes < HE_K_COUNT) return HE_ERR_INVALID_ARG;
+    for (int i = 0; i < n_classes; ++i) { ms_per_class[i] = 0.0; launches_per_class[i] = 0; }
+    const hipError_t r = hipStreamSynchronize(e->stream);
+    if (r != hipSuccess) return check_hip(e, r, "he_timing_read");
+    for (const auto& u : e->ev_used) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e->ev_pool[u.second], e->ev_pool[u.second + 1]) != hipSuccess) continue;
+        ms_per_class[u.first] += ms;
+        launches_per_class[u.first] += 1;
+    }
+    e->ev_used.clear();
+    e->ev_next = 0;
     return HE_OK;
 }
 

@@ -160,3 +160,67 @@ def test_bf16_real_layer_shapes(name, L, B, S, G):
     rep = _bf16_case(d, True, G, base.sampling, 1.0, 0, seed=42)
     print(name, rep)
     assert rep["id_match"] > 0.9
+
+
+def test_generate_graph_replay_matches_step_by_step():
+    """he_generate on a stream of its own replays a captured decode step; on the NULL stream it
+    launches step by step.  Same kernels, so ids and log-probs must be bit-identical -- on
+    every one of several calls, with other work and synchronisations in between."""
+    import torch
+    d = synth.ModelDims("x", 2, 256, 4, 512, 1000, 128, 5, 9, 12, "bf16", "gumbel")
+    w = synth.make_weights(d, seed=5)
+    prompts = torch.from_numpy(synth.make_prompts(d, seed=6)).cuda()
+    samp = binding.sampling("gumbel", 1.0, 11)
+    ref_eng = util.make_engine(d, w)
+    ref_ids, ref_lp = ref_eng.he_generate(prompts, d.gen_len, samp)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    w_dev = binding.upload_weights(w, d.dtype)
+    eng = binding.Engine(binding.make_config(d, stream=stream.cuda_stream), w_dev)
+    for rep in range(4):
+        with torch.cuda.stream(stream):
+            ids, lp = eng.he_generate(prompts, d.gen_len, samp)
+        stream.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(lp, ref_lp), rep
+        junk = torch.randn(1 << 16, device="cuda").sum().item()  # eager work between replays
+        assert junk == junk
+    # a different batch size and length re-captures
+    with torch.cuda.stream(stream):
+        ids2, lp2 = eng.he_generate(prompts[:3].contiguous(), 7, samp)
+    stream.synchronize()
+    r2, l2 = ref_eng.he_generate(prompts[:3].contiguous(), 7, samp)
+    torch.cuda.synchronize()
+    assert torch.equal(ids2, r2) and torch.equal(lp2, l2)
+    # f32 path through the same mechanism
+    d32 = synth.CONFIGS["tiny"]
+    w32 = synth.make_weights(d32, seed=0)
+    p32 = torch.from_numpy(synth.make_prompts(d32, seed=1234)).cuda()
+    e_null = util.make_engine(d32, w32)
+    a, al = e_null.he_generate(p32, d32.gen_len, binding.sampling("greedy"))
+    torch.cuda.synchronize()
+    e_str = binding.Engine(binding.make_config(d32, stream=stream.cuda_stream), binding.upload_weights(w32, "f32"))
+    for rep in range(3):
+        with torch.cuda.stream(stream):
+            b, bl = e_str.he_generate(p32, d32.gen_len, binding.sampling("greedy"))
+        stream.synchronize()
+        assert torch.equal(a, b) and torch.equal(al, bl)
+    for e in (ref_eng, eng, e_null, e_str):
+        e.he_destroy()
+
+
+def test_timing_hook_counts_launches():
+    import torch
+    d = synth.ModelDims("x", 3, 256, 4, 512, 1000, 128, 4, 6, 4, "bf16", "greedy")
+    eng = util.make_engine(d, synth.make_weights(d, seed=5))
+    p = torch.from_numpy(synth.make_prompts(d, seed=6)).cuda()
+    s = binding.sampling()
+    ids0, lp0 = eng.he_generate(p, 4, s)
+    eng.he_timing_enable(True)
+    ids1, lp1 = eng.he_generate(p, 4, s)
+    t = eng.he_timing_read()
+    eng.he_timing_enable(False)
+    assert torch.equal(ids0, ids1) and torch.equal(lp0, lp1)
+    # 4 decode-shaped passes (last prompt token + 3 steps) x 3 layers
+    assert t["fc1"][1] == 12 and t["qkv"][1] == 12 and t["lm_head"][1] == 4 and t["layernorm"][1] == 4 * 7
+    assert all(ms > 0 for ms, n in t.values() if n)
+    eng.he_destroy()
