@@ -59,7 +59,7 @@ struct Sizes {
 };
 
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
-constexpr int kMaxKSplit = 8;
+constexpr int kMaxKSplit = 8;  // bf16_gemm_ksplit never returns more
 
 size_t elt_bytes(const he_config& c) { return c.dtype == HE_BF16 ? 2 : 4; }
 

@@ -128,104 +128,120 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
 //
 // At most 32 rows per grid.y slice: weights are streamed exactly once from HBM,
 // straight from global memory into MFMA operand registers.  A workgroup of four
-// wavefronts owns a pair of 32-row weight tiles and one k-split; its wavefronts
-// divide the k range, keep kUnroll blocks per stream in flight (two weight
-// streams, the hi and lo activation streams out of L2), and combine their
-// accumulators through LDS.  The sum over k-splits (STORE mode) is taken, in a
-// fixed order, by the LayerNorm kernel that consumes it.
+// wavefronts owns NT consecutive 32-row weight tiles and one k-split; its
+// wavefronts divide the k range, keep U blocks per stream in flight (NT weight
+// streams plus the hi and lo activation streams out of L2, which every weight
+// tile reuses from registers), and combine their accumulators through LDS.  The
+// sum over k-splits (STORE mode) is taken, in a fixed order, by the LayerNorm
+// kernel that consumes it.
+//
+// What bounds this kernel is the number of bytes one CU can keep in flight, so
+// the launcher picks NT (and the k-split) to put one equally loaded workgroup on
+// as many of the CUs as the shape allows: more workgroups than CUs double up
+// on some CUs and the whole launch waits for those.
 
-constexpr int kUnroll = 4;
-
+template <int NT, int U>
 struct SkinnyRegs {
-    u32x4 w0[kUnroll], w1[kUnroll], xh[kUnroll], xl[kUnroll];
+    u32x4 w[NT][U], xh[U], xl[U];
 };
 
-__device__ __forceinline__ void skinny_load(SkinnyRegs& r, const u32x4* w0, const u32x4* w1, const u32x4* xh,
-                                            const u32x4* xl) {
+template <int NT, int U>
+__device__ __forceinline__ void skinny_load(SkinnyRegs<NT, U>& r, const u32x4* (&w)[NT], const u32x4*& xh,
+                                            const u32x4*& xl) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        r.w0[u] = __builtin_nontemporal_load(w0 + u * 64);
-        r.w1[u] = __builtin_nontemporal_load(w1 + u * 64);
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * 64);
         r.xh[u] = xh[u * 64];
         r.xl[u] = xl[u * 64];
     }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) w[t] += U * 64;
+    xh += U * 64;
+    xl += U * 64;
 }
 
-__device__ __forceinline__ void skinny_mma(const SkinnyRegs& r, f32x16& a0, f32x16& a1) {
+template <int NT, int U>
+__device__ __forceinline__ void skinny_mma(const SkinnyRegs<NT, U>& r, f32x16 (&acc)[NT]) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        a0 = mfma_bf16(r.w0[u], r.xh[u], a0);
-        a1 = mfma_bf16(r.w1[u], r.xh[u], a1);
-        a0 = mfma_bf16(r.w0[u], r.xl[u], a0);
-        a1 = mfma_bf16(r.w1[u], r.xl[u], a1);
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xh[u], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xl[u], acc[t]);
     }
 }
 
-template <int MODE>
+template <int MODE, int NT, int U>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                           const u32x4* __restrict__ Xlo, int KB, int n_tiles,
                                                           int ksplit, Epi p) {
-    __shared__ float red[4][2][16][64];
+    __shared__ float red[4][NT][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int pair = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
+    const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
-    const int t0 = pair * 2, t1 = min(pair * 2 + 1, n_tiles - 1);  // a lone last tile is computed twice, stored once
     const int parts = ksplit * 4, part = ks * 4 + wave;
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
-    const u32x4* w0 = Wp + ((size_t)t0 * KB + kb0) * 64 + lane;
-    const u32x4* w1 = Wp + ((size_t)t1 * KB + kb0) * 64 + lane;
+    const u32x4* w[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
+        w[t] = Wp + ((size_t)min(grp * NT + t, n_tiles - 1) * KB + kb0) * 64 + lane;
     const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
     const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
-    f32x16 acc0 = {}, acc1 = {};
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x16{};
     int n = kb1 - kb0;
-    if (n >= kUnroll) {
-        SkinnyRegs ra;
-        skinny_load(ra, w0, w1, xh, xl);
-        w0 += kUnroll * 64; w1 += kUnroll * 64; xh += kUnroll * 64; xl += kUnroll * 64; n -= kUnroll;
-        while (n >= kUnroll) {
-            SkinnyRegs rb;
-            skinny_load(rb, w0, w1, xh, xl);
-            w0 += kUnroll * 64; w1 += kUnroll * 64; xh += kUnroll * 64; xl += kUnroll * 64; n -= kUnroll;
-            skinny_mma(ra, acc0, acc1);
+    if (n >= U) {
+        SkinnyRegs<NT, U> ra;
+        skinny_load<NT, U>(ra, w, xh, xl);
+        n -= U;
+        while (n >= U) {
+            SkinnyRegs<NT, U> rb;
+            skinny_load<NT, U>(rb, w, xh, xl);
+            n -= U;
+            skinny_mma<NT, U>(ra, acc);
             ra = rb;
         }
-        skinny_mma(ra, acc0, acc1);
+        skinny_mma<NT, U>(ra, acc);
     }
     for (; n > 0; --n) {
-        const u32x4 a = __builtin_nontemporal_load(w0), b = __builtin_nontemporal_load(w1), h = *xh, l = *xl;
-        w0 += 64; w1 += 64; xh += 64; xl += 64;
-        acc0 = mfma_bf16(a, h, acc0);
-        acc1 = mfma_bf16(b, h, acc1);
-        acc0 = mfma_bf16(a, l, acc0);
-        acc1 = mfma_bf16(b, l, acc1);
+        SkinnyRegs<NT, 1> r1;
+        skinny_load<NT, 1>(r1, w, xh, xl);
+        skinny_mma<NT, 1>(r1, acc);
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { red[wave][0][r][lane] = acc0[r]; red[wave][1][r][lane] = acc1[r]; }
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
     __syncthreads();
-    float v[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            v[j][r] = (red[0][j][wave * 4 + r][lane] + red[1][j][wave * 4 + r][lane]) +
-                      (red[2][j][wave * 4 + r][lane] + red[3][j][wave * 4 + r][lane]);
     const int m = mt * 32 + (lane & 31);
     const int nl = 8 * wave + 4 * (lane >> 5);  // first of this lane's four rows inside a tile
-    const bool two = pair * 2 + 1 < n_tiles;
-    if (MODE != MODE_LMHEAD) {
-        epilogue4<MODE>(p, m, t0 * 32 + nl, ks, v[0][0], v[0][1], v[0][2], v[0][3]);
-        if (two) epilogue4<MODE>(p, m, (t0 + 1) * 32 + nl, ks, v[1][0], v[1][1], v[1][2], v[1][3]);
-    } else {
+    float v[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[t][r] = (red[0][t][wave * 4 + r][lane] + red[1][t][wave * 4 + r][lane]) +
+                      (red[2][t][wave * 4 + r][lane] + red[3][t][wave * 4 + r][lane]);
+    float (*zt)[32][33] = reinterpret_cast<float (*)[32][33]>(&red[0][0][0][0]);  // logits tiles reuse the LDS
+    if (MODE == MODE_LMHEAD) __syncthreads();                                      // once every partial is read
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int tile = grp * NT + t;
+        if (MODE != MODE_LMHEAD) {
+            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[t][0], v[t][1], v[t][2], v[t][3]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) zt[t][nl + r][lane & 31] = v[t][r];
+        }
+    }
+    if (MODE == MODE_LMHEAD) {
         // logits tiles -> per-(row, tile) softmax and arg-max partials
-        __shared__ float zt[2][32][33];
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) zt[j][nl + r][lane & 31] = v[j][r];
-        __syncthreads();
-        const int j = threadIdx.x >> 5, mm = mt * 32 + (threadIdx.x & 31), tile = t0 + j;
-        if (threadIdx.x < 64 && mm < p.M && (j == 0 || two)) {
+        for (int i0 = threadIdx.x; i0 < NT * 32; i0 += 256) {
+            const int t = i0 >> 5, mm = mt * 32 + (i0 & 31), tile = grp * NT + t;
+            if (mm >= p.M || tile >= n_tiles) continue;
             const int mode = p.st->mode, step = p.st->step;
             const float temp = p.st->temperature;
             const uint32_t k0 = p.st->seed_lo, k1 = p.st->seed_hi;
@@ -233,7 +249,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
             int besti = 0x7FFFFFFF;
             const int nv = min(32, p.N - tile * 32);
             for (int i = 0; i < nv; ++i) {
-                const float z = zt[j][i][threadIdx.x & 31];
+                const float z = zt[t][i][i0 & 31];
                 const int vid = tile * 32 + i;
                 if (p.logits) p.logits[(size_t)mm * p.N + vid] = z;
                 mx = fmaxf(mx, z);
@@ -243,7 +259,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
                 if (s > best) { best = s; besti = vid; bestz = z; }  // ascending ids: strict > keeps the lowest
             }
             float sum = 0.f;
-            for (int i = 0; i < nv; ++i) sum += expf(zt[j][i][threadIdx.x & 31] - mx);
+            for (int i = 0; i < nv; ++i) sum += expf(zt[t][i][i0 & 31] - mx);
             float* sp = p.stats + ((size_t)mm * p.n_tiles + tile) * 4;
             sp[0] = mx; sp[1] = sum; sp[2] = best; sp[3] = bestz;
             p.stats_idx[(size_t)mm * p.n_tiles + tile] = besti;
@@ -392,7 +408,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
 //
 // Row `src = m*in_mul + in_add`: r += sum of k-split partials + bias (fixed order),
 // written back when asked; a = LayerNorm(r) is emitted as tiled bf16 blocks.
-__global__ __launch_bounds__(256) void ln_blocks_kernel(float* __restrict__ r, const float* __restrict__ part,
+__global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, const float* __restrict__ part,
                                                         int ksplit, size_t part_split,
                                                         const bf16_t* __restrict__ pbias,
                                                         const bf16_t* __restrict__ gamma,
@@ -400,8 +416,8 @@ __global__ __launch_bounds__(256) void ln_blocks_kernel(float* __restrict__ r, c
                                                         u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
                                                         int in_add, int writeback) {
     extern __shared__ __align__(16) float row[];
-    __shared__ float red[4];
-    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __shared__ float red[16];
+    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwave = blockDim.x >> 6;
     const size_t src = (size_t)m * in_mul + in_add;
     float4* rr = reinterpret_cast<float4*>(r + src * H);
     float s = 0.f;
@@ -423,14 +439,18 @@ __global__ __launch_bounds__(256) void ln_blocks_kernel(float* __restrict__ r, c
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
     if (lane == 0) red[wave] = s;
     __syncthreads();
-    const float mean = ((red[0] + red[1]) + (red[2] + red[3])) / H;
+    float tot = 0.f;
+    for (int i = 0; i < nwave; ++i) tot += red[i];
+    const float mean = tot / H;
     float q = 0.f;
     for (int i = threadIdx.x; i < H; i += blockDim.x) { const float dlt = row[i] - mean; q += dlt * dlt; }
     for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
     __syncthreads();
     if (lane == 0) red[wave] = q;
     __syncthreads();
-    const float rstd = 1.0f / sqrtf(((red[0] + red[1]) + (red[2] + red[3])) / H + eps);
+    tot = 0.f;
+    for (int i = 0; i < nwave; ++i) tot += red[i];
+    const float rstd = 1.0f / sqrtf(tot / H + eps);
     const int KB = H >> 4;
     for (int c = threadIdx.x; c < H / 8; c += blockDim.x) {
         const int k0 = c * 8;
@@ -447,6 +467,96 @@ __global__ __launch_bounds__(256) void ln_blocks_kernel(float* __restrict__ r, c
         const size_t slot = block_slot(m, k0, KB);
         a[slot] = u32x4{o[0], o[1], o[2], o[3]};
         if (a_lo) a_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+    }
+}
+
+// The same operation for the few rows of a decode step: one 1024-thread workgroup per row,
+// every value held in registers (NV float4 per thread), all loads -- residual, k-split
+// partials, bias, gamma, beta -- issued before the first reduction, since with so little
+// work the kernel's time is the length of its dependent-load chain.
+template <int NV>
+__global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, const float* __restrict__ part, int ksplit,
+                                                      size_t part_split, const bf16_t* __restrict__ pbias,
+                                                      const bf16_t* __restrict__ gamma,
+                                                      const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
+                                                      u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
+                                                      int in_add, int writeback) {
+    __shared__ float red[2][16];
+    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t src = (size_t)m * in_mul + in_add;
+    const int nq = H >> 2;  // float4 per row
+    float4 v[NV];
+    uint2 gg[NV], bb[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * 1024;
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        gg[j] = bb[j] = make_uint2(0, 0);
+        if (i < nq) {
+            v[j] = *reinterpret_cast<const float4*>(r + src * H + 4 * i);
+            gg[j] = *reinterpret_cast<const uint2*>(gamma + 4 * i);
+            bb[j] = *reinterpret_cast<const uint2*>(beta + 4 * i);
+        }
+    }
+    if (part) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + j * 1024;
+            if (i >= nq) continue;
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < ksplit; ++k) {  // fixed order: the sum does not depend on scheduling
+                const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * part_split + src * H + 4 * i);
+                acc.x += y.x; acc.y += y.y; acc.z += y.z; acc.w += y.w;
+            }
+            const uint2 pb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
+            v[j].x += acc.x + __uint_as_float(pb.x << 16);
+            v[j].y += acc.y + __uint_as_float(pb.x & 0xFFFF0000u);
+            v[j].z += acc.z + __uint_as_float(pb.y << 16);
+            v[j].w += acc.w + __uint_as_float(pb.y & 0xFFFF0000u);
+            if (writeback) *reinterpret_cast<float4*>(r + src * H + 4 * i) = v[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) s += (v[j].x + v[j].y) + (v[j].z + v[j].w);  // lanes past the row hold zeros
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) red[0][wave] = s;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += red[0][i];
+    const float mean = tot / H;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        if (threadIdx.x + j * 1024 < nq) {
+            const float d0 = v[j].x - mean, d1 = v[j].y - mean, d2 = v[j].z - mean, d3 = v[j].w - mean;
+            q += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    if (lane == 0) red[1][wave] = q;
+    __syncthreads();
+    tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += red[1][i];
+    const float rstd = 1.0f / sqrtf(tot / H + eps);
+    const int KB = H >> 4;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * 1024;
+        if (i >= nq) continue;
+        const float e0 = (v[j].x - mean) * rstd * __uint_as_float(gg[j].x << 16) + __uint_as_float(bb[j].x << 16);
+        const float e1 = (v[j].y - mean) * rstd * __uint_as_float(gg[j].x & 0xFFFF0000u) + __uint_as_float(bb[j].x & 0xFFFF0000u);
+        const float e2 = (v[j].z - mean) * rstd * __uint_as_float(gg[j].y << 16) + __uint_as_float(bb[j].y << 16);
+        const float e3 = (v[j].w - mean) * rstd * __uint_as_float(gg[j].y & 0xFFFF0000u) + __uint_as_float(bb[j].y & 0xFFFF0000u);
+        uint32_t h0, h1, l0, l1;
+        split2(e0, e1, h0, l0);
+        split2(e2, e3, h1, l1);
+        const int k0 = 4 * i;  // four values: half of a 16-byte slot
+        const size_t slot = block_slot(m, k0 & ~7, KB);
+        reinterpret_cast<uint2*>(a + slot)[(k0 >> 2) & 1] = make_uint2(h0, h1);
+        if (a_lo) reinterpret_cast<uint2*>(a_lo + slot)[(k0 >> 2) & 1] = make_uint2(l0, l1);
     }
 }
 
@@ -478,25 +588,33 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     const u32x4* Kp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D));
     const u32x4* Vp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D));
     const int jw = wave * KPW + grp;
-    float mx = -INFINITY;
-    for (int base = 0; base < T; base += KR * U) {
-        u32x4 kk[U];
+    constexpr int STEP = KR * U;  // keys per workgroup iteration
+    auto load_rows = [&](u32x4 (&dst)[U], const u32x4* src, int base) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
-            kk[u] = j < T ? Kp[(size_t)j * LPK + sub] : u32x4{0u, 0u, 0u, 0u};
+            dst[u] = j < T ? __builtin_nontemporal_load(src + (size_t)j * LPK + sub) : u32x4{0u, 0u, 0u, 0u};
         }
+    };
+    // loads run one iteration ahead of the arithmetic, and the first values are requested
+    // before the soft-max barrier, so the memory pipe never drains between the phases
+    float mx = -INFINITY;
+    u32x4 cur[U], nxt[U];
+    load_rows(cur, Kp, 0);
+    for (int base = 0; base < T; base += STEP) {
+        if (base + STEP < T) load_rows(nxt, Kp, base + STEP);
+        else load_rows(nxt, Vp, 0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
-            float s = qa.x * __uint_as_float(kk[u].x << 16);
-            s = fmaf(qa.y, __uint_as_float(kk[u].x & 0xFFFF0000u), s);
-            s = fmaf(qa.z, __uint_as_float(kk[u].y << 16), s);
-            s = fmaf(qa.w, __uint_as_float(kk[u].y & 0xFFFF0000u), s);
-            s = fmaf(qb.x, __uint_as_float(kk[u].z << 16), s);
-            s = fmaf(qb.y, __uint_as_float(kk[u].z & 0xFFFF0000u), s);
-            s = fmaf(qb.z, __uint_as_float(kk[u].w << 16), s);
-            s = fmaf(qb.w, __uint_as_float(kk[u].w & 0xFFFF0000u), s);
+            float s = qa.x * __uint_as_float(cur[u].x << 16);
+            s = fmaf(qa.y, __uint_as_float(cur[u].x & 0xFFFF0000u), s);
+            s = fmaf(qa.z, __uint_as_float(cur[u].y << 16), s);
+            s = fmaf(qa.w, __uint_as_float(cur[u].y & 0xFFFF0000u), s);
+            s = fmaf(qb.x, __uint_as_float(cur[u].z << 16), s);
+            s = fmaf(qb.y, __uint_as_float(cur[u].z & 0xFFFF0000u), s);
+            s = fmaf(qb.z, __uint_as_float(cur[u].w << 16), s);
+            s = fmaf(qb.w, __uint_as_float(cur[u].w & 0xFFFF0000u), s);
 #pragma unroll
             for (int o2 = 1; o2 < LPK; o2 <<= 1) s += __shfl_xor(s, o2);
             if (j < T) {
@@ -504,7 +622,10 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
                 mx = fmaxf(mx, s);
             }
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
+    // cur now holds the first values
     for (int o2 = 32; o2 > 0; o2 >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o2));
     if (lane == 0) red[wave] = mx;
     __syncthreads();  // also publishes sc[]
@@ -520,26 +641,23 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     __syncthreads();  // also publishes the probabilities
     sum = (red[4] + red[5]) + (red[6] + red[7]);
     float acc[8] = {};
-    for (int base = 0; base < T; base += KR * U) {
-        u32x4 vv[U];
-        float pj[U];
+    for (int base = 0; base < T; base += STEP) {
+        if (base + STEP < T) load_rows(nxt, Vp, base + STEP);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
-            vv[u] = j < T ? Vp[(size_t)j * LPK + sub] : u32x4{0u, 0u, 0u, 0u};
-            pj[u] = j < T ? sc[j] : 0.f;
+            const float pj = j < T ? sc[j] : 0.f;
+            acc[0] = fmaf(pj, __uint_as_float(cur[u].x << 16), acc[0]);
+            acc[1] = fmaf(pj, __uint_as_float(cur[u].x & 0xFFFF0000u), acc[1]);
+            acc[2] = fmaf(pj, __uint_as_float(cur[u].y << 16), acc[2]);
+            acc[3] = fmaf(pj, __uint_as_float(cur[u].y & 0xFFFF0000u), acc[3]);
+            acc[4] = fmaf(pj, __uint_as_float(cur[u].z << 16), acc[4]);
+            acc[5] = fmaf(pj, __uint_as_float(cur[u].z & 0xFFFF0000u), acc[5]);
+            acc[6] = fmaf(pj, __uint_as_float(cur[u].w << 16), acc[6]);
+            acc[7] = fmaf(pj, __uint_as_float(cur[u].w & 0xFFFF0000u), acc[7]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            acc[0] = fmaf(pj[u], __uint_as_float(vv[u].x << 16), acc[0]);
-            acc[1] = fmaf(pj[u], __uint_as_float(vv[u].x & 0xFFFF0000u), acc[1]);
-            acc[2] = fmaf(pj[u], __uint_as_float(vv[u].y << 16), acc[2]);
-            acc[3] = fmaf(pj[u], __uint_as_float(vv[u].y & 0xFFFF0000u), acc[3]);
-            acc[4] = fmaf(pj[u], __uint_as_float(vv[u].z << 16), acc[4]);
-            acc[5] = fmaf(pj[u], __uint_as_float(vv[u].z & 0xFFFF0000u), acc[5]);
-            acc[6] = fmaf(pj[u], __uint_as_float(vv[u].w << 16), acc[6]);
-            acc[7] = fmaf(pj[u], __uint_as_float(vv[u].w & 0xFFFF0000u), acc[7]);
-        }
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -568,12 +686,50 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     }
 }
 
+static int g_num_cus = 0;
+
+int num_cus() {
+    if (g_num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        g_num_cus = n;
+    }
+    return g_num_cus;
+}
+
+template <int MODE, int NT>
+void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles,
+                      int m_tiles, int ksplit, const Epi& p) {
+    constexpr int U = NT <= 4 ? 4 : 2;
+    dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
+    gemm_skinny_kernel<MODE, NT, U><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
+                                                         n_tiles, ksplit, p);
+}
+
+// nt weight tiles per workgroup (1..8)
 template <int MODE>
 void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles, int m_tiles,
-                   int ksplit, const Epi& p) {
-    dim3 grid(((n_tiles + 1) / 2) * ksplit, m_tiles);
-    gemm_skinny_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles,
-                                                  ksplit, p);
+                   int nt, int ksplit, const Epi& p) {
+    switch (nt) {
+        case 1: launch_skinny_nt<MODE, 1>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 2: launch_skinny_nt<MODE, 2>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 3: launch_skinny_nt<MODE, 3>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 4: launch_skinny_nt<MODE, 4>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 5: launch_skinny_nt<MODE, 5>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 6: launch_skinny_nt<MODE, 6>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 7: launch_skinny_nt<MODE, 7>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        default: launch_skinny_nt<MODE, 8>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+    }
+}
+
+// Tiles per workgroup for a GEMM whose epilogue needs the whole sum in one workgroup: the
+// smallest count that fits all workgroups on the chip at once (one per CU), at most 8.
+int skinny_nt_fused(int n_tiles, int m_tiles) {
+    const int cus = num_cus();
+    int nt = (n_tiles * m_tiles + cus - 1) / cus;
+    return nt < 1 ? 1 : (nt > 8 ? 8 : nt);
 }
 
 template <int MODE>
@@ -597,13 +753,14 @@ void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K) {
     tile_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total);
 }
 
+// k-splits of a decode-shaped STORE GEMM with 4 tiles per workgroup: as many as put one
+// workgroup on (nearly) every CU, while each wavefront keeps a few unrolled rounds
 int bf16_gemm_ksplit(int N, int K) {
-    // k-splits of a decode-shaped STORE GEMM: enough workgroups to keep every CU streaming,
-    // while each wavefront still runs a few unrolled rounds
-    const int pairs = (N + 63) / 64;
-    int ks = 1;
-    while (pairs * ks < 256 && ks < 8 && (K / 16) / (ks * 2 * 4) >= 2 * kUnroll) ks *= 2;
-    return ks;
+    const int groups = ((N + 31) / 32 + 3) / 4;
+    int ks = num_cus() / groups;
+    const int by_k = (K / 16) / (4 * 8);
+    if (ks > by_k) ks = by_k;
+    return ks < 1 ? 1 : (ks > 8 ? 8 : ks);
 }
 
 static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
@@ -619,9 +776,10 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
                       int ksplit, const bf16_gemm_args& a) {
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
-    if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p);
-    else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, 1, p);
-    else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, 1, p);
+    const int nt = skinny_nt_fused(n_tiles, m_tiles);
+    if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit > 1 ? 4 : nt, ksplit, p);
+    else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
+    else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
 }
 
 void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
@@ -638,7 +796,8 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
     Epi p{};
     p.M = B; p.N = V; p.st = st; p.logits = logits_opt; p.stats = stats; p.stats_idx = stats_idx;
     p.n_tiles = (V + 31) / 32;
-    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, Xlo, K / 16, p.n_tiles, (B + 31) / 32, 1, p);
+    const int m_tiles = (B + 31) / 32;
+    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, Xlo, K / 16, p.n_tiles, m_tiles, skinny_nt_fused(p.n_tiles, m_tiles), 1, p);
     lm_reduce_kernel<<<B, 256, 0, s>>>(stats, stats_idx, p.n_tiles, st, ids_out, lp_out, out_stride, out_at_step,
                                        cur_ids);
 }
@@ -646,6 +805,18 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
              int in_mul, int in_add, int writeback) {
+    const int nv = (H / 4 + 1023) / 1024;
+    if (rows <= 256 && nv <= 3) {  // a decode step
+#define HE_LN_ROW(NV)                                                                                             \
+    ln_row_kernel<NV><<<rows, 1024, 0, s>>>(r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, \
+                                            (const bf16_t*)beta, (u32x4*)a_blocks, (u32x4*)a_blocks_lo, H, eps,     \
+                                            in_mul, in_add, writeback)
+        if (nv == 1) HE_LN_ROW(1);
+        else if (nv == 2) HE_LN_ROW(2);
+        else HE_LN_ROW(3);
+#undef HE_LN_ROW
+        return;
+    }
     ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
         (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback);
