@@ -172,6 +172,21 @@ def main():
             ids, _, _ = eng.he_decode_step(ids, samp)
         timing = eng.he_timing_read()
         eng.he_timing_enable(False)
+        # the dominant kernel's launch duration: one event pair around a sweep that launches it once
+        # per layer (each launch streams a different layer's matrix, as in a decode step)
+        sweep_reps = 4
+        eng.he_kernel_sweep("fc1", 1)  # warm
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record(stream)
+        eng.he_kernel_sweep("fc1", sweep_reps)
+        s1.record(stream)
+        torch.cuda.synchronize()
+        fc1_sweep_us = s0.elapsed_time(s1) * 1e3 / (sweep_reps * d.n_layers)
+        # a plain copy of known size (256 MiB read + 256 MiB written): the reference that
+        # rocprofv3's FETCH_SIZE / WRITE_SIZE readings of this same command are scaled by
+        cal_src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        cal_dst = torch.empty_like(cal_src)
+        binding.he_calibration_copy(cal_src, cal_dst, stream.cuda_stream)
         torch.cuda.synchronize()
 
     wbytes, kvtok = algorithmic_bytes(d)
@@ -187,15 +202,19 @@ def main():
         # attention during the timed decode steps: contexts S+1 .. S+nt, K and V of one layer
         "attention": sum(2 * B * T * H * 2 for T in range(S + 1, S + nt + 1)) / nt,
     }
-    kernels = {}
+    # an event pair brackets more than the kernel (the two timestamp packets); the same pair
+    # around nothing measures that, and it is taken off every bracket
+    pair_ms = timing["empty"][0] / max(1, timing["empty"][1])
+    kernels = {"event_pair_us": pair_ms * 1e3}
     for k, (ms, cnt) in timing.items():
-        if cnt:
-            avg = ms / cnt
+        if cnt and k != "empty":
+            avg = max(ms / cnt - pair_ms, 1e-6)
             kernels[k] = {"avg_us": avg * 1e3, "launches": cnt}
             if k in kern_bytes:
                 kernels[k]["GB/s"] = kern_bytes[k] / (avg * 1e-3) / 1e9
     dom = "fc1"
-    dom_avg_s = timing[dom][0] / max(1, timing[dom][1]) * 1e-3
+    kernels["fc1_sweep_us"] = fc1_sweep_us
+    dom_avg_s = fc1_sweep_us * 1e-6
     achieved = kern_bytes[dom] / dom_avg_s / 1e9 if dom_avg_s > 0 else 0.0
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": achieved / (HBM_PEAK / 1e9), "traffic": None,

@@ -164,10 +164,25 @@ enum {
     HE_K_FC1 = 4,       /* + bias + ReLU */
     HE_K_FC2 = 5,
     HE_K_LM_HEAD = 6,   /* LM head + log-softmax + sampling (both of its kernels) */
-    HE_K_COUNT = 7
+    HE_K_EMPTY = 7,     /* an event pair with no launch between (once per pass): what the pair itself costs */
+    HE_K_COUNT = 8
 };
 he_status he_timing_enable(he_engine* e, int on);
 he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_class, int n_classes);
+
+/* Measurement hook (bf16 path, after a prefill): launches the decode-shaped GEMM of one
+ * class (HE_K_OUT_PROJ, HE_K_FC1 or HE_K_FC2) once per layer, layer after layer, `reps`
+ * times, on cfg.stream -- each launch streams a different layer's matrix, as in a decode
+ * step, with the engine's current activations as the other operand.  Only workspace that the
+ * next decode step overwrites anyway is written; the KV cache and the generation state are
+ * untouched.  One event pair around the call gives the kernel's launch duration without the
+ * per-launch cost of an event pair. */
+he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps);
+
+/* Measurement hook: a plain copy kernel (reads `bytes`, writes `bytes`, a multiple of 16,
+ * device pointers, on `stream`).  Hardware byte counters (rocprofv3 FETCH_SIZE /
+ * WRITE_SIZE) are scaled by what they read for this kernel of known size. */
+he_status he_calibration_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);
 
 /* Test hook for the sampler's counter-based generator: writes the `count`
  * 32-bit words for vocabulary ids v0 .. v0+count-1 of (seed, sequence b,

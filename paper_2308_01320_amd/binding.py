@@ -85,6 +85,10 @@ def lib() -> C.CDLL:
     L.he_timing_enable.argtypes = [vp, C.c_int]
     L.he_timing_read.restype = C.c_int
     L.he_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_long), C.c_int]
+    L.he_kernel_sweep.restype = C.c_int
+    L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
+    L.he_calibration_copy.restype = C.c_int
+    L.he_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.he_rng_words.restype = C.c_int
     L.he_rng_words.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, vp, vp]
     _lib = L
@@ -93,9 +97,9 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
-           "he_timing_read")
+           "he_timing_read", "he_calibration_copy", "he_kernel_sweep")
 
-KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head")
+KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
 
 def _ptr(t) -> Optional[int]:
@@ -209,6 +213,9 @@ class Engine:
         self._check(lib().he_timing_read(self.handle, ms, cnt, n))
         return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
+    def he_kernel_sweep(self, kernel_class: str, reps: int = 1):
+        self._check(lib().he_kernel_sweep(self.handle, KERNEL_CLASSES.index(kernel_class), reps))
+
     def he_destroy(self):
         if self.handle:
             lib().he_destroy(self.handle)
@@ -229,3 +236,12 @@ def he_rng_words(seed: int, b: int, n: int, v0: int, count: int, device="cuda:0"
     if rc != HE_OK:
         raise HeError(rc, "he_rng_words")
     return out
+
+
+def he_calibration_copy(src, dst, stream=None):
+    """Plain copy kernel of known size (src -> dst, equal-sized device tensors)."""
+    nbytes = src.numel() * src.element_size()
+    rc = lib().he_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream)
+    if rc != HE_OK:
+        raise HeError(rc, "he_calibration_copy")
+    return nbytes

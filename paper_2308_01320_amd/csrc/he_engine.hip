@@ -262,6 +262,7 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
         bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
                      ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
     }
+    { LaunchTimer t(e, HE_K_EMPTY); }
     launch_advance_state(s, e->st, 1, 1);
     e->cur_len += 1;
     e->step += 1;
@@ -584,6 +585,44 @@ he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_
 const char* he_last_error(const he_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
 
 int he_cache_len(const he_engine* e) { return e ? e->cur_len : -1; }
+
+he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!e->fast) return fail(e, HE_ERR_STATE, "he_kernel_sweep: bf16 path only");
+    if (kernel_class != HE_K_OUT_PROJ && kernel_class != HE_K_FC1 && kernel_class != HE_K_FC2)
+        return fail(e, HE_ERR_INVALID_ARG, "he_kernel_sweep: class must be HE_K_OUT_PROJ, HE_K_FC1 or HE_K_FC2");
+    if (e->batch == 0 || reps < 1) return fail(e, HE_ERR_STATE, "he_kernel_sweep: needs a prefilled batch and reps >= 1");
+    const he_config& c = e->cfg;
+    const int B = e->batch, H = c.hidden, F = c.ffn;
+    bf16_gemm_args base;
+    base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
+    base.max_seq = c.max_seq_len;
+    const size_t split = (size_t)B * H;
+    for (int r = 0; r < reps; ++r)
+        for (int l = 0; l < c.n_layers; ++l) {
+            bf16_gemm_args a = base;
+            if (kernel_class == HE_K_FC1) {
+                a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+                bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+            } else if (kernel_class == HE_K_FC2) {
+                a.out = e->part; a.out_split = split;
+                bf16_gemm_skinny(e->stream, EPI_STORE, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F,
+                                 bf16_gemm_ksplit(H, F), a);
+            } else {
+                a.out = e->part; a.out_split = split;
+                bf16_gemm_skinny(e->stream, EPI_STORE, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H,
+                                 bf16_gemm_ksplit(H, H), a);
+            }
+        }
+    return check_hip(e, hipGetLastError(), "he_kernel_sweep");
+}
+
+he_status he_calibration_copy(const void* d_src, void* d_dst, size_t bytes, void* stream) {
+    if (!d_src || !d_dst || bytes % 16) return HE_ERR_INVALID_ARG;
+    if (bytes == 0) return HE_OK;
+    launch_calibration_copy((hipStream_t)stream, d_src, d_dst, bytes);
+    return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
+}
 
 he_status he_rng_words(uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* d_out, void* stream) {
     if (!d_out || count < 0) return HE_ERR_INVALID_ARG;

@@ -26,6 +26,7 @@ void launch_set_state(hipStream_t s, he_dev_state* st, int cur_len, int step, in
                       uint64_t seed);
 void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps);
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out);
+void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count);
 
 // ---- bf16 path (kernels_bf16.hip): operands are tiled bf16 blocks, see that file

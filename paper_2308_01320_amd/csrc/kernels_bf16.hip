@@ -87,15 +87,26 @@ struct Epi {
 
 enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3 };
 
-// four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0)
+// bias words for outputs n0..n0+3 and the cache length, fetched ahead of the epilogue
 template <int MODE>
-__device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, float v0, float v1, float v2, float v3) {
+__device__ __forceinline__ uint2 epilogue_bias(const Epi& p, int n0) {
+    if ((MODE == MODE_BIAS_RELU || MODE == MODE_QKV) && n0 < p.N) return *reinterpret_cast<const uint2*>(p.bias + n0);
+    return make_uint2(0, 0);
+}
+template <int MODE>
+__device__ __forceinline__ int epilogue_len(const Epi& p) {
+    return MODE == MODE_QKV ? p.st->cur_len : 0;
+}
+
+// four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0); bb = their bias, cur_len = cached positions
+template <int MODE>
+__device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, float v0, float v1, float v2, float v3,
+                                          uint2 bb, int cur_len) {
     if (m >= p.M || n0 >= p.N) return;  // N is a multiple of 4 wherever this is used
     if (MODE == MODE_STORE) {
         *reinterpret_cast<float4*>(p.out + (size_t)ks * p.out_split + (size_t)m * p.N + n0) =
             make_float4(v0, v1, v2, v3);
     } else if (MODE == MODE_BIAS_RELU) {
-        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
         v0 = fmaxf(v0 + __uint_as_float(bb.x << 16), 0.f);
         v1 = fmaxf(v1 + __uint_as_float(bb.x & 0xFFFF0000u), 0.f);
         v2 = fmaxf(v2 + __uint_as_float(bb.y << 16), 0.f);
@@ -107,7 +118,6 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
         reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
         if (p.out_blocks_lo) reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
     } else if (MODE == MODE_QKV) {
-        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
         v0 += __uint_as_float(bb.x << 16);
         v1 += __uint_as_float(bb.x & 0xFFFF0000u);
         v2 += __uint_as_float(bb.y << 16);
@@ -117,7 +127,7 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
                 make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
         } else {
             const int which = n0 >= 2 * p.H, c = n0 - (which ? 2 * p.H : p.H);
-            const int b = m / p.S, t = p.st->cur_len + (m % p.S);
+            const int b = m / p.S, t = cur_len + (m % p.S);
             bf16_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
             *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
         }
@@ -188,6 +198,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
         w[t] = Wp + ((size_t)min(grp * NT + t, n_tiles - 1) * KB + kb0) * 64 + lane;
     const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
     const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
+    // epilogue operands are requested now, long before they are used
+    const int nl = 8 * wave + 4 * (lane >> 5);  // first of this lane's four rows inside a tile
+    uint2 bias_w[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        bias_w[t] = grp * NT + t < n_tiles ? epilogue_bias<MODE>(p, (grp * NT + t) * 32 + nl) : make_uint2(0, 0);
+    const int cur_len = epilogue_len<MODE>(p);
     f32x16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x16{};
@@ -216,7 +233,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
         for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
     __syncthreads();
     const int m = mt * 32 + (lane & 31);
-    const int nl = 8 * wave + 4 * (lane >> 5);  // first of this lane's four rows inside a tile
     float v[NT][4];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -230,7 +246,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
     for (int t = 0; t < NT; ++t) {
         const int tile = grp * NT + t;
         if (MODE != MODE_LMHEAD) {
-            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[t][0], v[t][1], v[t][2], v[t][3]);
+            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[t][0], v[t][1], v[t][2], v[t][3], bias_w[t], cur_len);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r) zt[t][nl + r][lane & 31] = v[t][r];
@@ -314,22 +330,28 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
 
 // ----------------------------------------------------------------- tiled GEMM (prompt pass)
 //
-// 128 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
-// 64x64 sub-tiles (2x2 MFMA tiles each).  Operands arrive as 1 KiB blocks:
-// global -> registers -> LDS unchanged (conflict-free 16-byte accesses), two
-// k-blocks per stage, double buffered with one barrier per stage.  Activations
-// are the two-term form here as well (hi and lo blocks against the same weight
-// registers), which keeps keys and values of the prompt within a rounding of the
-// exact ones before they are stored as bf16.
+// 256 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
+// 128x64 sub-tiles (4x2 MFMA tiles each: 12 LDS operand reads feed 16 MFMAs per
+// k-block).  Operands arrive as 1 KiB blocks: global -> registers -> LDS
+// unchanged (conflict-free 16-byte accesses), two k-blocks per stage, double
+// buffered with one barrier per stage.  Activations are the two-term form here
+// as well (hi and lo blocks against the same weight registers), which keeps keys
+// and values of the prompt within a rounding of the exact ones before they are
+// stored as bf16.
 
-constexpr int TN = 128, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of k) per stage
+constexpr int TN = 256, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of k) per stage
+constexpr int TNB = TN / 32, TMB = TM / 32;   // 32-row operand blocks per tile side
 
 template <int MODE>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+__global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, Epi p) {
-    // [stage][operand: W, X hi, X lo][row-tile 0..3][k-block 0..1][lane]
-    __shared__ u32x4 lds[2][3][4][KSTAGE][64];
+    // per stage: W [8 row-tiles][2 k-blocks], X hi [4][2], X lo [4][2], 64 lanes of 16 bytes each
+    extern __shared__ __align__(16) unsigned char tiled_smem[];
+    typedef u32x4 (*WStage)[TNB][KSTAGE][64];
+    typedef u32x4 (*XStage)[2][TMB][KSTAGE][64];
+    WStage ldw = reinterpret_cast<WStage>(tiled_smem);                                          // [2 stages]
+    XStage ldx = reinterpret_cast<XStage>(tiled_smem + 2 * sizeof(u32x4) * TNB * KSTAGE * 64);  // [2 stages][hi|lo]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
     // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.
@@ -343,66 +365,78 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int gm = min(GROUP, tiles_m - first_m);
     const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
 
-    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 64x64 sub-tile
-    f32x16 acc[2][2] = {};
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 64 (m) sub-tile
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{};
 
-    // this wavefront stages row-tile `wave` of each operand (KSTAGE blocks each)
-    const int wrt = min(tn * 4 + wave, NT32 - 1), xrt = min(tm * 4 + wave, MT32 - 1);
-    const u32x4* wsrc = Wp + (size_t)wrt * KB * 64 + lane;
+    // staging: wavefront w copies W row-tiles 2w, 2w+1 and row-tile w of X hi and X lo
+    const u32x4* wsrc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wsrc[i] = Wp + (size_t)min(tn * TNB + wave * 2 + i, NT32 - 1) * KB * 64 + lane;
+    const int xrt = min(tm * TMB + wave, MT32 - 1);
     const u32x4* hsrc = Xhi + (size_t)xrt * KB * 64 + lane;
     const u32x4* lsrc = Xlo + (size_t)xrt * KB * 64 + lane;
-    u32x4 wreg[KSTAGE], hreg[KSTAGE], lreg[KSTAGE];
+    u32x4 wreg[2][KSTAGE], hreg[KSTAGE], lreg[KSTAGE];
     const int nstage = KB / KSTAGE;  // KB is even (K % 32 == 0)
+    auto fetch = [&](int st) {
 #pragma unroll
-    for (int j = 0; j < KSTAGE; ++j) { wreg[j] = wsrc[j * 64]; hreg[j] = hsrc[j * 64]; lreg[j] = lsrc[j * 64]; }
+        for (int j = 0; j < KSTAGE; ++j) {
+            const size_t off = ((size_t)st * KSTAGE + j) * 64;
+            wreg[0][j] = wsrc[0][off]; wreg[1][j] = wsrc[1][off];
+            hreg[j] = hsrc[off]; lreg[j] = lsrc[off];
+        }
+    };
+    auto stash = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < KSTAGE; ++j) {
-        lds[0][0][wave][j][lane] = wreg[j]; lds[0][1][wave][j][lane] = hreg[j]; lds[0][2][wave][j][lane] = lreg[j];
-    }
+        for (int j = 0; j < KSTAGE; ++j) {
+            ldw[buf][wave * 2 + 0][j][lane] = wreg[0][j];
+            ldw[buf][wave * 2 + 1][j][lane] = wreg[1][j];
+            ldx[buf][0][wave][j][lane] = hreg[j];
+            ldx[buf][1][wave][j][lane] = lreg[j];
+        }
+    };
+    fetch(0);
+    stash(0);
     __syncthreads();
     for (int s = 0; s < nstage; ++s) {
         const int cur = s & 1;
-        if (s + 1 < nstage) {
-#pragma unroll
-            for (int j = 0; j < KSTAGE; ++j) {
-                const size_t off = ((size_t)(s + 1) * KSTAGE + j) * 64;
-                wreg[j] = wsrc[off]; hreg[j] = hsrc[off]; lreg[j] = lsrc[off];
-            }
-        }
+        if (s + 1 < nstage) fetch(s + 1);
 #pragma unroll
         for (int j = 0; j < KSTAGE; ++j) {
-            const u32x4 a0 = lds[cur][0][wn * 2 + 0][j][lane], a1 = lds[cur][0][wn * 2 + 1][j][lane];
+            u32x4 a[4];
 #pragma unroll
-            for (int t = 1; t <= 2; ++t) {
-                const u32x4 b0 = lds[cur][t][wm * 2 + 0][j][lane], b1 = lds[cur][t][wm * 2 + 1][j][lane];
-                acc[0][0] = mfma_bf16(a0, b0, acc[0][0]);
-                acc[0][1] = mfma_bf16(a0, b1, acc[0][1]);
-                acc[1][0] = mfma_bf16(a1, b0, acc[1][0]);
-                acc[1][1] = mfma_bf16(a1, b1, acc[1][1]);
+            for (int i = 0; i < 4; ++i) a[i] = ldw[cur][wn * 4 + i][j][lane];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const u32x4 b0 = ldx[cur][t][wm * 2 + 0][j][lane], b1 = ldx[cur][t][wm * 2 + 1][j][lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[i][0] = mfma_bf16(a[i], b0, acc[i][0]);
+                    acc[i][1] = mfma_bf16(a[i], b1, acc[i][1]);
+                }
             }
         }
-        if (s + 1 < nstage) {
-#pragma unroll
-            for (int j = 0; j < KSTAGE; ++j) {
-                lds[cur ^ 1][0][wave][j][lane] = wreg[j];
-                lds[cur ^ 1][1][wave][j][lane] = hreg[j];
-                lds[cur ^ 1][2][wave][j][lane] = lreg[j];
-            }
-        }
+        if (s + 1 < nstage) stash(cur ^ 1);
         __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int m = tm * TM + (wm * 2 + j) * 32 + (lane & 31);
-            const int nb = tn * TN + (wn * 2 + i) * 32 + 4 * (lane >> 5);
+            const int nb = tn * TN + (wn * 4 + i) * 32 + 4 * (lane >> 5);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 epilogue4<MODE>(p, m, nb + 8 * q, 0, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
-                                acc[i][j][q * 4 + 3]);
+                                acc[i][j][q * 4 + 3], epilogue_bias<MODE>(p, nb + 8 * q), cur_len);
         }
 }
+
+constexpr size_t kTiledSmem = 2 * sizeof(u32x4) * (TNB + 2 * TMB) * KSTAGE * 64;  // 64 KiB
 
 // ----------------------------------------------------------------- LayerNorm (+ residual update)
 //
@@ -686,6 +720,179 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     }
 }
 
+// ----------------------------------------------------------------- attention, prompt rows
+//
+// Same arithmetic as attn_kernel for a block of QB consecutive queries of one (sequence, head):
+// every K and V row fetched once serves all QB queries, which cuts the L2 traffic of the prompt
+// pass by QB.  The QB partial dot products of a key are reduced over the D/8 lanes that share
+// the key with a halving butterfly (each step sends half of the values and keeps the other
+// half), so the lanes end up owning different queries.  Query t0+i sees keys <= cur_len + t0 + i.
+constexpr int QB = 8;
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kv,
+                                                          u32x4* __restrict__ o, u32x4* __restrict__ o_lo,
+                                                          const he_dev_state* __restrict__ st, int S, int layer, int H,
+                                                          int n_heads, int max_batch, int max_seq) {
+    constexpr int LPK = D / 8, KPW = 64 / LPK, KR = 4 * KPW, U = 2, STEP = KR * U;
+    extern __shared__ float sc[];  // [QB][max_seq] scores, then probabilities
+    __shared__ float ored[4][QB][D];
+    __shared__ float inv_sum[QB];
+    const int t0 = blockIdx.x * QB, h = blockIdx.y, b = blockIdx.z;
+    const int nq = min(QB, S - t0);
+    const int cur = st->cur_len;
+    const int T = cur + t0 + nq;  // keys any query of the block may see
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sub = lane % LPK, grp = lane / LPK;
+    float qv[QB][8];
+#pragma unroll
+    for (int i = 0; i < QB; ++i) {
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+        if (i < nq) {
+            const float* qp = q + (size_t)(b * S + t0 + i) * H + h * D + sub * 8;
+            a = *reinterpret_cast<const float4*>(qp);
+            c = *reinterpret_cast<const float4*>(qp + 4);
+        }
+        qv[i][0] = a.x; qv[i][1] = a.y; qv[i][2] = a.z; qv[i][3] = a.w;
+        qv[i][4] = c.x; qv[i][5] = c.y; qv[i][6] = c.z; qv[i][7] = c.w;
+    }
+    const u32x4* Kp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D));
+    const u32x4* Vp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D));
+    const int jw = wave * KPW + grp;
+    auto load_rows = [&](u32x4 (&dst)[U], const u32x4* src, int base) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            dst[u] = j < T ? src[(size_t)j * LPK + sub] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    // which query this lane owns after the butterfly
+    int qown = 0;
+    {
+        int nval = QB;
+#pragma unroll
+        for (int off = LPK / 2; off >= 1; off >>= 1)
+            if (nval > 1) { nval >>= 1; if (sub & off) qown += nval; }
+    }
+    constexpr bool kPairs = LPK > QB;  // two lanes end up with the same query: the even one stores
+    u32x4 cur_r[U], nxt_r[U];
+    load_rows(cur_r, Kp, 0);
+    for (int base = 0; base < T; base += STEP) {
+        if (base + STEP < T) load_rows(nxt_r, Kp, base + STEP);
+        else load_rows(nxt_r, Vp, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            const float k0 = __uint_as_float(cur_r[u].x << 16), k1 = __uint_as_float(cur_r[u].x & 0xFFFF0000u);
+            const float k2 = __uint_as_float(cur_r[u].y << 16), k3 = __uint_as_float(cur_r[u].y & 0xFFFF0000u);
+            const float k4 = __uint_as_float(cur_r[u].z << 16), k5 = __uint_as_float(cur_r[u].z & 0xFFFF0000u);
+            const float k6 = __uint_as_float(cur_r[u].w << 16), k7 = __uint_as_float(cur_r[u].w & 0xFFFF0000u);
+            float part[QB];
+#pragma unroll
+            for (int i = 0; i < QB; ++i) {
+                float s = qv[i][0] * k0;
+                s = fmaf(qv[i][1], k1, s); s = fmaf(qv[i][2], k2, s); s = fmaf(qv[i][3], k3, s);
+                s = fmaf(qv[i][4], k4, s); s = fmaf(qv[i][5], k5, s); s = fmaf(qv[i][6], k6, s);
+                part[i] = fmaf(qv[i][7], k7, s);
+            }
+            int nval = QB;
+#pragma unroll
+            for (int off = LPK / 2; off >= 1; off >>= 1) {
+                if (nval > 1) {
+                    nval >>= 1;
+                    const bool upper = (sub & off) != 0;
+#pragma unroll
+                    for (int c = 0; c < QB / 2; ++c) {
+                        if (c < nval) {
+                            const float send = upper ? part[c] : part[c + nval];
+                            const float keep = upper ? part[c + nval] : part[c];
+                            part[c] = keep + __shfl_xor(send, off);
+                        }
+                    }
+                } else {
+                    part[0] += __shfl_xor(part[0], off);
+                }
+            }
+            if (j < T && (!kPairs || (sub & 1) == 0))
+                sc[qown * max_seq + j] = j <= cur + t0 + qown ? part[0] : -INFINITY;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur_r[u] = nxt_r[u];
+    }
+    __syncthreads();
+    {   // soft-max of query 2*wave + (lane / 32) over its 32 lanes
+        const int qi = 2 * wave + (lane >> 5), l32 = lane & 31;
+        float* row = sc + qi * max_seq;
+        float mx = -INFINITY;
+        for (int j = l32; j < T; j += 32) mx = fmaxf(mx, row[j]);
+        for (int o2 = 16; o2 > 0; o2 >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o2));
+        float sum = 0.f;
+        for (int j = l32; j < T; j += 32) {
+            const float pj = expf(row[j] - mx);
+            row[j] = pj;
+            sum += pj;
+        }
+        for (int o2 = 16; o2 > 0; o2 >>= 1) sum += __shfl_xor(sum, o2);
+        if (l32 == 0) inv_sum[qi] = 1.0f / sum;
+    }
+    __syncthreads();
+    float acc[QB][8] = {};
+    for (int base = 0; base < T; base += STEP) {
+        if (base + STEP < T) load_rows(nxt_r, Vp, base + STEP);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * KR + jw;
+            if (j < T) {
+                const float v0 = __uint_as_float(cur_r[u].x << 16), v1 = __uint_as_float(cur_r[u].x & 0xFFFF0000u);
+                const float v2 = __uint_as_float(cur_r[u].y << 16), v3 = __uint_as_float(cur_r[u].y & 0xFFFF0000u);
+                const float v4 = __uint_as_float(cur_r[u].z << 16), v5 = __uint_as_float(cur_r[u].z & 0xFFFF0000u);
+                const float v6 = __uint_as_float(cur_r[u].w << 16), v7 = __uint_as_float(cur_r[u].w & 0xFFFF0000u);
+#pragma unroll
+                for (int i = 0; i < QB; ++i) {
+                    const float pj = sc[i * max_seq + j];
+                    acc[i][0] = fmaf(pj, v0, acc[i][0]); acc[i][1] = fmaf(pj, v1, acc[i][1]);
+                    acc[i][2] = fmaf(pj, v2, acc[i][2]); acc[i][3] = fmaf(pj, v3, acc[i][3]);
+                    acc[i][4] = fmaf(pj, v4, acc[i][4]); acc[i][5] = fmaf(pj, v5, acc[i][5]);
+                    acc[i][6] = fmaf(pj, v6, acc[i][6]); acc[i][7] = fmaf(pj, v7, acc[i][7]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur_r[u] = nxt_r[u];
+    }
+#pragma unroll
+    for (int i = 0; i < QB; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+#pragma unroll
+            for (int o2 = LPK; o2 < 64; o2 <<= 1) acc[i][e] += __shfl_xor(acc[i][e], o2);
+        }
+    if (grp == 0) {
+#pragma unroll
+        for (int i = 0; i < QB; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ored[wave][i][sub * 8 + e] = acc[i][e];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < QB * LPK; idx += 256) {
+        const int i = idx / LPK, c = idx % LPK;
+        if (i >= nq) continue;
+        float ov[8];
+        const float inv = inv_sum[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int d0 = c * 8 + e;
+            ov[e] = ((ored[0][i][d0] + ored[1][i][d0]) + (ored[2][i][d0] + ored[3][i][d0])) * inv;
+        }
+        uint32_t oh[4], ol[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split2(ov[2 * e], ov[2 * e + 1], oh[e], ol[e]);
+        const size_t slot = block_slot(b * S + t0 + i, h * D + c * 8, H >> 4);
+        o[slot] = u32x4{oh[0], oh[1], oh[2], oh[3]};
+        if (o_lo) o_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+    }
+}
+
 static int g_num_cus = 0;
 
 int num_cus() {
@@ -704,7 +911,12 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
                       int m_tiles, int ksplit, const Epi& p) {
     constexpr int U = NT <= 4 ? 4 : 2;
     dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
-    gemm_skinny_kernel<MODE, NT, U><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
+    // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
+    // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
+    constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
+    constexpr size_t kWant = 84 * 1024;
+    const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+    gemm_skinny_kernel<MODE, NT, U><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
                                                          n_tiles, ksplit, p);
 }
 
@@ -738,7 +950,7 @@ void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
     const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
     const int nblk = tiles_n * tiles_m;
     const int grid = ((nblk + 7) / 8) * 8;
-    gemm_tiled_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32, MT32,
+    gemm_tiled_kernel<MODE><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32, MT32,
                                                  tiles_n, tiles_m, p);
 }
 
@@ -824,6 +1036,19 @@ void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part
 
 void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
                const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq) {
+    const size_t prompt_shm = (size_t)QB * max_seq * sizeof(float);
+    if (S >= QB && prompt_shm <= 96 * 1024) {  // prompt rows: blocks of QB queries per workgroup
+        dim3 pgrid((S + QB - 1) / QB, n_heads, M / S);
+        if (H / n_heads == 128)
+            attn_prompt_kernel<128><<<pgrid, 256, prompt_shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
+                                                                   (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+                                                                   max_batch, max_seq);
+        else
+            attn_prompt_kernel<64><<<pgrid, 256, prompt_shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
+                                                                  (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+                                                                  max_batch, max_seq);
+        return;
+    }
     dim3 grid(M, n_heads);
     const size_t shm = (size_t)max_seq * sizeof(float);
     if (H / n_heads == 128)

@@ -252,6 +252,12 @@ __global__ void rng_words_kernel(uint32_t* out, int count, uint32_t v0, uint32_t
     if (i < count) out[i] = philox_word0(v0 + (uint32_t)i, n, b, k0, k1);
 }
 
+// plain 16-byte-per-thread copy: the known-size reference that profiler byte counters are scaled by
+__global__ void calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 __global__ void copy_out_kernel(const int32_t* __restrict__ ids, const float* __restrict__ lp,
                                 int32_t* __restrict__ out_ids, float* __restrict__ out_lp, int count) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -331,6 +337,10 @@ void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out) {
     rng_words_kernel<<<(count + 255) / 256, 256, 0, s>>>(out, count, v0, n, b, (uint32_t)(seed & 0xFFFFFFFFu),
                                                          (uint32_t)(seed >> 32));
+}
+
+void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+    calibration_copy_kernel<<<4096, 256, 0, s>>>((const uint4*)src, (uint4*)dst, bytes / 16);
 }
 
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count) {
