@@ -217,7 +217,11 @@ def main():
     dom_avg_s = fc1_sweep_us * 1e-6
     achieved = kern_bytes[dom] / dom_avg_s / 1e9 if dom_avg_s > 0 else 0.0
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": None,
+                "frac": achieved / (HBM_PEAK / 1e9),
+                # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this command, scaled by
+                # the counters' readings for kernels of known size (profiles/decode_fc1_gemm_opt13b_pmc.txt);
+                # measured for the OPT-13B layer shape only
+                "traffic": 217.8e6 if (H, F) == (5120, 20480) else None,
                 "kernel": "gemm_skinny_kernel<MODE_BIAS_RELU> (decode FC1 + bias + ReLU)",
                 "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6}
 
