@@ -893,6 +893,142 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
     }
 }
 
+// ----------------------------------------------------------------- attention, prompt rows, on the matrix cores
+//
+// Flash-style causal attention for the prompt pass.  One wavefront owns 32 queries of one
+// (sequence, head); the four wavefronts of a workgroup share each 32-key tile of K and V through
+// LDS.  Everything is computed transposed so that a lane owns ONE query: S^T = K Q^T puts the
+// scores of query lane%32 in that lane's 16 accumulators (online soft-max needs one exchange
+// with lane^32), and O^T = V^T P^T accumulates that query's output column, so the soft-max
+// rescaling is a per-lane scalar.  Q and P enter the MFMA as two bf16 terms (hi + lo).  The
+// keys of a PV step are taken in the order the score accumulators already hold them; V is
+// transposed into that order while it is staged in LDS.
+template <int D>
+__global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __restrict__ q,
+                                                               const bf16_t* __restrict__ kv, u32x4* __restrict__ o,
+                                                               u32x4* __restrict__ o_lo,
+                                                               const he_dev_state* __restrict__ st, int S, int layer,
+                                                               int H, int n_heads, int max_batch, int max_seq) {
+    constexpr int KBD = D / 16;      // k-blocks over the head dimension
+    constexpr int DB = D / 32;       // 32-wide blocks of output dimensions
+    constexpr int KPITCH = D + 8;    // bf16 per K row in LDS (16 bytes of padding)
+    __shared__ __align__(16) bf16_t ks[32 * KPITCH];
+    __shared__ __align__(16) bf16_t vt[DB * 2 * 2 * 32 * 8];  // [dim block][k-step][lane half][dim][8 keys]
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = lane & 31, hh = lane >> 5;
+    const int cur = st->cur_len;
+    const int T = cur + S;                          // keys in the cache once this pass is stored
+    const int t0 = (blockIdx.x * 4 + wave) * 32;    // this wavefront's first query
+    const bool live = t0 < S;
+    const int qpos = cur + t0 + j;                  // last key this lane's query may see
+    const int wg_last = min(T - 1, cur + min(S, (int)(blockIdx.x * 4 + 4) * 32) - 1);
+    const int n_tiles = wg_last / 32 + 1;
+    const int my_last_tile = live ? min(T - 1, cur + t0 + 31) / 32 : -1;
+
+    u32x4 qhi[KBD], qlo[KBD];
+    {
+        const bool ok = t0 + j < S;
+        const float* qp = q + (size_t)(b * S + (ok ? t0 + j : 0)) * H + h * D + hh * 8;
+#pragma unroll
+        for (int kb = 0; kb < KBD; ++kb) {
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+            if (ok) {
+                a = *reinterpret_cast<const float4*>(qp + kb * 16);
+                c = *reinterpret_cast<const float4*>(qp + kb * 16 + 4);
+            }
+            uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+            split2(a.x, a.y, h0, l0); split2(a.z, a.w, h1, l1); split2(c.x, c.y, h2, l2); split2(c.z, c.w, h3, l3);
+            qhi[kb] = u32x4{h0, h1, h2, h3};
+            qlo[kb] = u32x4{l0, l1, l2, l3};
+        }
+    }
+    const bf16_t* Kg = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D);
+    const bf16_t* Vg = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D);
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i) oacc[i] = f32x16{};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        __syncthreads();  // the previous tile has been consumed
+        // stage K rows as they are, V transposed into the PV operand order
+        for (int c = threadIdx.x; c < 32 * (D / 8); c += 256) {
+            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8, kabs = kt * 32 + key;
+            u32x4 kk = u32x4{0u, 0u, 0u, 0u}, vv = kk;
+            if (kabs < T) {
+                kk = *reinterpret_cast<const u32x4*>(Kg + (size_t)kabs * D + d0);
+                vv = *reinterpret_cast<const u32x4*>(Vg + (size_t)kabs * D + d0);
+            }
+            *reinterpret_cast<u32x4*>(&ks[key * KPITCH + d0]) = kk;
+            const int s2 = key >> 4, k16 = key & 15, vh = (k16 >> 2) & 1, e = 4 * (k16 >> 3) + (k16 & 3);
+            const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int d = d0 + x;
+                vt[((((d >> 5) * 2 + s2) * 2 + vh) * 32 + (d & 31)) * 8 + e] = (bf16_t)(w[x >> 1] >> ((x & 1) * 16));
+            }
+        }
+        __syncthreads();
+        if (kt > my_last_tile) continue;  // wholly above the diagonal for this wavefront (uniform per wavefront)
+        f32x16 sacc = f32x16{};
+#pragma unroll
+        for (int kb = 0; kb < KBD; ++kb) {
+            const u32x4 kblk = *reinterpret_cast<const u32x4*>(&ks[j * KPITCH + kb * 16 + hh * 8]);
+            sacc = mfma_bf16(kblk, qhi[kb], sacc);
+            sacc = mfma_bf16(kblk, qlo[kb], sacc);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kabs = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            if (kabs > qpos) sacc[r] = -INFINITY;
+            mx = fmaxf(mx, sacc[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible to every query
+        const float alpha = expf(m_run - m_new);
+        float psum = 0.f;
+        float pr[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { pr[r] = expf(sacc[r] - m_new); psum += pr[r]; }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t ph[4], pl[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) split2(pr[8 * s2 + 2 * x], pr[8 * s2 + 2 * x + 1], ph[x], pl[x]);
+            const u32x4 phi = u32x4{ph[0], ph[1], ph[2], ph[3]}, plo = u32x4{pl[0], pl[1], pl[2], pl[3]};
+#pragma unroll
+            for (int i = 0; i < DB; ++i) {
+                const u32x4 vblk = *reinterpret_cast<const u32x4*>(&vt[(((i * 2 + s2) * 2 + hh) * 32 + j) * 8]);
+                oacc[i] = mfma_bf16(vblk, phi, oacc[i]);
+                oacc[i] = mfma_bf16(vblk, plo, oacc[i]);
+            }
+        }
+    }
+    if (!live || t0 + j >= S) return;
+    const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+    const int m = b * S + t0 + j;
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int dim = h * D + i * 32 + 8 * qd + 4 * hh;  // four consecutive output dimensions
+            uint32_t h0, h1, l0, l1;
+            split2(oacc[i][qd * 4 + 0] * inv, oacc[i][qd * 4 + 1] * inv, h0, l0);
+            split2(oacc[i][qd * 4 + 2] * inv, oacc[i][qd * 4 + 3] * inv, h1, l1);
+            const size_t slot = block_slot(m, dim & ~7, H >> 4);
+            reinterpret_cast<uint2*>(o + slot)[(dim >> 2) & 1] = make_uint2(h0, h1);
+            if (o_lo) reinterpret_cast<uint2*>(o_lo + slot)[(dim >> 2) & 1] = make_uint2(l0, l1);
+        }
+}
+
 static int g_num_cus = 0;
 
 int num_cus() {
@@ -965,14 +1101,32 @@ void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K) {
     tile_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total);
 }
 
-// k-splits of a decode-shaped STORE GEMM with 4 tiles per workgroup: as many as put one
-// workgroup on (nearly) every CU, while each wavefront keeps a few unrolled rounds
+// Shape of a decode-shaped STORE GEMM: nt tiles per workgroup and ks k-splits such that about one
+// workgroup lands on every CU.  Four tiles per workgroup (activation blocks reused four times)
+// as long as each wavefront keeps 8 k-blocks, else two tiles and half the splits.  (Two tiles and
+// three splits for the 5120x5120 out-projection measured 2 us slower than four and six, more
+// than the LayerNorm that adds up the partial sums gained.)
+static void store_shape(int N, int K, int* nt, int* ks) {
+    const int tiles = (N + 31) / 32, kb = K / 16, cus = num_cus();
+    int n = 4, groups = (tiles + 3) / 4;
+    int k = cus / groups;
+    if (k < 1) k = 1;
+    if (kb / (k * 4) < 8) {
+        n = 2;
+        groups = (tiles + 1) / 2;
+        k = cus / groups;
+        if (k < 1) k = 1;
+        while (k > 1 && kb / (k * 4) < 8) --k;
+    }
+    if (k > 8) k = 8;
+    *nt = n;
+    *ks = k;
+}
+
 int bf16_gemm_ksplit(int N, int K) {
-    const int groups = ((N + 31) / 32 + 3) / 4;
-    int ks = num_cus() / groups;
-    const int by_k = (K / 16) / (4 * 8);
-    if (ks > by_k) ks = by_k;
-    return ks < 1 ? 1 : (ks > 8 ? 8 : ks);
+    int nt, ks;
+    store_shape(N, K, &nt, &ks);
+    return ks;
 }
 
 static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
@@ -989,7 +1143,12 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
     const int nt = skinny_nt_fused(n_tiles, m_tiles);
-    if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit > 1 ? 4 : nt, ksplit, p);
+    if (mode == EPI_STORE) {
+        int snt, sks;
+        store_shape(N, K, &snt, &sks);
+        if (sks != ksplit || m_tiles > 1) snt = ksplit > 1 ? 2 : nt;  // caller's split wins; keep it balanced
+        launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
+    }
     else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
     else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
 }
@@ -1036,8 +1195,20 @@ void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part
 
 void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
                const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq) {
+    if (S >= 32) {  // prompt rows: 32 queries per wavefront on the matrix cores
+        dim3 fgrid((S + 127) / 128, n_heads, M / S);
+        if (H / n_heads == 128)
+            attn_prompt_mfma_kernel<128><<<fgrid, 256, 0, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
+                                                               (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+                                                               max_batch, max_seq);
+        else
+            attn_prompt_mfma_kernel<64><<<fgrid, 256, 0, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
+                                                              (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+                                                              max_batch, max_seq);
+        return;
+    }
     const size_t prompt_shm = (size_t)QB * max_seq * sizeof(float);
-    if (S >= QB && prompt_shm <= 96 * 1024) {  // prompt rows: blocks of QB queries per workgroup
+    if (S >= QB && prompt_shm <= 96 * 1024) {  // short prompts: blocks of QB queries per workgroup
         dim3 pgrid((S + QB - 1) / QB, n_heads, M / S);
         if (H / n_heads == 128)
             attn_prompt_kernel<128><<<pgrid, 256, prompt_shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
