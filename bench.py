@@ -132,6 +132,7 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()  # default priority; the engine captures its decode step on it
     weights = device_weights(d, torch)
+    torch.cuda.synchronize()
     cfg = binding.make_config(d, stream=stream.cuda_stream)
     eng = binding.Engine(cfg, weights)
     prompts = torch.from_numpy(synth.make_prompts(d, seed=1234 + 3)).cuda()
@@ -153,6 +154,10 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         dev_ms = ev0.elapsed_time(ev1)
+        # the timed work produced real tokens: ids in range, finite negative log-probs
+        assert int(out_ids.min()) >= 0 and int(out_ids.max()) < d.vocab, "generated ids out of range"
+        assert bool(torch.isfinite(out_lp).all()) and float(out_lp.max()) <= 0.0, "log-probs not finite"
+
         ms_per_step = wall * 1e3 / args.steps
 
         # split of one job: prompt pass (he_prefill) and the decode loop, HIP events on the same stream

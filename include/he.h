@@ -104,11 +104,13 @@ typedef struct {
 size_t he_workspace_bytes(const he_config* cfg);
 
 /* Validates cfg, allocates arena and workspace, prepares weights.  *out is
- * set only on HE_OK.  Synchronises cfg.stream. */
+ * set only on HE_OK.  Synchronises the whole device first (the weights may have
+ * been written on any stream), then cfg.stream. */
 he_status he_create(const he_config* cfg, const he_weights* weights, he_engine** out);
 
 /* Re-reads the borrowed weight pointers after the caller changed the values
- * in place (re-tiles the GEMM matrices on the bf16 path).  Synchronises. */
+ * in place (re-tiles the GEMM matrices on the bf16 path).  Synchronises the
+ * device before and cfg.stream after. */
 he_status he_refresh_weights(he_engine* e);
 
 /* Prompt pass (Section 5.3 (I): "initial prompt").  d_prompt_ids is [B, S]

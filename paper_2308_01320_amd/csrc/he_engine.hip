@@ -443,6 +443,8 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         delete e;
         return r == hipErrorOutOfMemory ? HE_ERR_OOM : HE_ERR_DEVICE;
     }
+    // the caller's weights may still be in the making on another stream: wait for the whole device
+    r = hipDeviceSynchronize();
     launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
     if (e->fast) {
         // rows of the last 32-row tile beyond the batch are read by the matrix cores (their
@@ -471,6 +473,8 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
 
 he_status he_refresh_weights(he_engine* e) {
     if (!e) return HE_ERR_INVALID_ARG;
+    he_status rc = check_hip(e, hipDeviceSynchronize(), "he_refresh_weights");  // the update may be on any stream
+    if (rc != HE_OK) return rc;
     if (e->fast) tile_weights(e);
     return check_hip(e, hipStreamSynchronize(e->stream), "he_refresh_weights");
 }
