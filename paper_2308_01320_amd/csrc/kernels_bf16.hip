@@ -331,10 +331,13 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
 // ----------------------------------------------------------------- tiled GEMM (prompt pass)
 //
 // 256 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
-// 128x64 sub-tiles (4x2 MFMA tiles each: 12 LDS operand reads feed 16 MFMAs per
+// 128x64 sub-tiles (4x2 MFMA tiles each: 8 LDS operand reads feed 16 MFMAs per
 // k-block).  Operands arrive as 1 KiB blocks: global -> registers -> LDS
 // unchanged (conflict-free 16-byte accesses), two k-blocks per stage, double
-// buffered with one barrier per stage.  Activations are the two-term form here
+// buffered with one barrier per stage.  (Fetching either operand straight from
+// global memory into registers instead, to relieve LDS, measured 6-12 % slower:
+// the duplicate requests of the two wavefronts that share a block overload the
+// global-load path.)  Activations are the two-term form here
 // as well (hi and lo blocks against the same weight registers), which keeps keys
 // and values of the prompt within a rounding of the exact ones before they are
 // stored as bf16.
