@@ -224,3 +224,75 @@ def test_timing_hook_counts_launches():
     assert t["fc1"][1] == 12 and t["qkv"][1] == 12 and t["lm_head"][1] == 4 and t["layernorm"][1] == 4 * 7
     assert all(ms > 0 for ms, n in t.values() if n)
     eng.he_destroy()
+
+
+@pytest.mark.parametrize("B,S,G", [(1, 2, 1), (2, 1, 1), (3, 33, 2), (64, 4, 2)])
+def test_bf16_edge_batches_and_lengths(B, S, G):
+    """G = 1 (prompt pass only), a prompt of exactly one 32-query tile plus one, a decode batch of two
+    full 32-row slices."""
+    d = synth.ModelDims("x", 2, 128, 2, 256, 500, 64, B, S, G, "bf16", "greedy")
+    rep = _bf16_case(d, True, G, "greedy", 1.0, 0)
+    print(rep)
+
+
+def test_bf16_long_cache_and_generate_to_capacity():
+    """A cache of 2048 positions filled to the last slot: he_generate up to S + G - 1 == max_seq_len,
+    checked against the oracle on one sequence at the last steps."""
+    import torch
+    d = synth.ModelDims("x", 1, 128, 2, 256, 300, 2048, 2, 2000, 49, "bf16", "greedy")
+    w = synth.make_weights(d, seed=5)
+    prompts = synth.make_prompts(d, seed=6)
+    eng = util.make_engine(d, w, max_batch=2, max_seq_len=2048)
+    ids, lp = eng.he_generate(torch.from_numpy(prompts).cuda(), d.gen_len, binding.sampling("greedy"))
+    torch.cuda.synchronize()
+    assert eng.cache_len() == 2048
+    with pytest.raises(binding.HeError) as ei:
+        eng.he_decode_step(ids[:, -1].contiguous(), binding.sampling("greedy"))
+    assert ei.value.status == 3
+    w64 = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
+           for k, v in w.items()}
+    w64["lm_head"] = w64["tok_emb"]
+    want = O.generate(w64, prompts, d.gen_len, d.n_heads, forced_ids=ids.cpu().numpy(), kv_dtype="bf16")
+    sure = want["margins"] > 0.02
+    got = ids.cpu().numpy()
+    assert np.array_equal(got[sure], want["ids"][sure])
+    same = got == want["ids"]
+    assert np.abs(lp.cpu().numpy()[same] - want["logprobs"][same]).max() <= BF16_TOL
+    eng.he_destroy()
+
+
+def test_refresh_weights_picks_up_in_place_update():
+    """The training half overwrites the actor's weights in place between generation phases; after
+    he_refresh_weights the engine must generate from the new values."""
+    import torch
+    d = synth.ModelDims("x", 2, 128, 2, 256, 300, 64, 3, 6, 4, "bf16", "greedy")
+    w1 = synth.make_weights(d, seed=1)
+    w2 = synth.make_weights(d, seed=2)
+    p = torch.from_numpy(synth.make_prompts(d, seed=3)).cuda()
+    s = binding.sampling("greedy")
+    e1 = util.make_engine(d, w1)
+    e2 = util.make_engine(d, w2)
+    a1, l1 = e1.he_generate(p, 4, s)
+    a2, l2 = e2.he_generate(p, 4, s)
+    torch.cuda.synchronize()
+    assert not torch.equal(l1, l2)
+    # overwrite engine 1's borrowed tensors with model 2's values, in place
+    dev2 = binding.upload_weights(w2, "bf16")
+    for k in ("tok_emb", "pos_emb", "lnf_g", "lnf_b"):
+        e1.weights[k].copy_(dev2[k])
+    for lw, lw2 in zip(e1.weights["layers"], dev2["layers"]):
+        for k in lw:
+            lw[k].copy_(lw2[k])
+    e1.he_refresh_weights()
+    b1, m1 = e1.he_generate(p, 4, s)
+    torch.cuda.synchronize()
+    assert torch.equal(b1, a2) and torch.equal(m1, l2)
+    e1.he_destroy(); e2.he_destroy()
+
+
+def test_bf16_opt66b_layer_shape():
+    """The largest configuration's layer shape (hidden 9216, 72 heads, ffn 36864), one layer."""
+    base = synth.CONFIGS["opt-66b"]
+    d = base.sliced(n_layers=1, batch=8, prompt_len=40, gen_len=3, max_positions=64)
+    rep = _bf16_case(d, True, 3, "greedy", 1.0, 0, seed=1)
+    print(rep)
