@@ -332,29 +332,37 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
 //
 // 256 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
 // 128x64 sub-tiles (4x2 MFMA tiles each: 8 LDS operand reads feed 16 MFMAs per
-// k-block).  Operands arrive as 1 KiB blocks: global -> registers -> LDS
-// unchanged (conflict-free 16-byte accesses), two k-blocks per stage, double
-// buffered with one barrier per stage.  (Fetching either operand straight from
-// global memory into registers instead, to relieve LDS, measured 6-12 % slower:
-// the duplicate requests of the two wavefronts that share a block overload the
-// global-load path.)  Activations are the two-term form here
-// as well (hi and lo blocks against the same weight registers), which keeps keys
-// and values of the prompt within a rounding of the exact ones before they are
-// stored as bf16.
+// k-block).  Operands arrive as 1 KiB blocks whose layout is the lane order, so
+// they are moved global -> LDS directly (global_load_lds, 16 bytes per lane, no
+// staging registers) into a ring of four stages of two k-blocks each: loads run
+// three stages (about 3000 MFMA cycles) ahead of the arithmetic, which is what
+// it takes to cover an L2 / infinity-cache round trip; one barrier per stage.
+// Activations are the two-term form here as well (hi and lo blocks against the
+// same weight registers), which keeps keys and values of the prompt within a
+// rounding of the exact ones before they are stored as bf16.
 
 constexpr int TN = 256, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of k) per stage
 constexpr int TNB = TN / 32, TMB = TM / 32;   // 32-row operand blocks per tile side
+constexpr int NSTG = 4;                       // ring depth
+constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;  // 32 blocks = 32 KiB per stage
+
+__device__ __forceinline__ void load_block_to_lds(const u32x4* gsrc_lane, u32x4* lds_block) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc_lane,
+                                     (void __attribute__((address_space(3)))*)lds_block, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
 
 template <int MODE>
-__global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, Epi p) {
-    // per stage: W [8 row-tiles][2 k-blocks], X hi [4][2], X lo [4][2], 64 lanes of 16 bytes each
-    extern __shared__ __align__(16) unsigned char tiled_smem[];
-    typedef u32x4 (*WStage)[TNB][KSTAGE][64];
-    typedef u32x4 (*XStage)[2][TMB][KSTAGE][64];
-    WStage ldw = reinterpret_cast<WStage>(tiled_smem);                                          // [2 stages]
-    XStage ldx = reinterpret_cast<XStage>(tiled_smem + 2 * sizeof(u32x4) * TNB * KSTAGE * 64);  // [2 stages][hi|lo]
+    // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
+    __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
     // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.
@@ -376,55 +384,77 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const u32x4* __restr
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{};
 
-    // staging: wavefront w copies W row-tiles 2w, 2w+1 and row-tile w of X hi and X lo
+    // this wavefront brings in W row-tiles 2w, 2w+1 and row-tile w of X hi and X lo: 8 blocks per stage
     const u32x4* wsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) wsrc[i] = Wp + (size_t)min(tn * TNB + wave * 2 + i, NT32 - 1) * KB * 64 + lane;
     const int xrt = min(tm * TMB + wave, MT32 - 1);
     const u32x4* hsrc = Xhi + (size_t)xrt * KB * 64 + lane;
     const u32x4* lsrc = Xlo + (size_t)xrt * KB * 64 + lane;
-    u32x4 wreg[2][KSTAGE], hreg[KSTAGE], lreg[KSTAGE];
     const int nstage = KB / KSTAGE;  // KB is even (K % 32 == 0)
-    auto fetch = [&](int st) {
+    auto issue = [&](int st) {
+        u32x4 (*slot)[64] = ring[st % NSTG];
 #pragma unroll
         for (int j = 0; j < KSTAGE; ++j) {
             const size_t off = ((size_t)st * KSTAGE + j) * 64;
-            wreg[0][j] = wsrc[0][off]; wreg[1][j] = wsrc[1][off];
-            hreg[j] = hsrc[off]; lreg[j] = lsrc[off];
+            load_block_to_lds(wsrc[0] + off, &slot[(wave * 2 + 0) * KSTAGE + j][0]);
+            load_block_to_lds(wsrc[1] + off, &slot[(wave * 2 + 1) * KSTAGE + j][0]);
+            load_block_to_lds(hsrc + off, &slot[TNB * KSTAGE + wave * KSTAGE + j][0]);
+            load_block_to_lds(lsrc + off, &slot[(TNB + TMB) * KSTAGE + wave * KSTAGE + j][0]);
         }
     };
-    auto stash = [&](int buf) {
+    constexpr int kLoadsPerStage = 4 * KSTAGE;  // per wavefront
+    // operand registers of one k-block: 4 weight blocks, 2 activation tiles x (hi, lo)
+    struct Ops { u32x4 a[4], b[2][2]; };
+    auto read_ops = [&](Ops& o, int st, int j) {
+        u32x4 (*slot)[64] = ring[st % NSTG];
 #pragma unroll
-        for (int j = 0; j < KSTAGE; ++j) {
-            ldw[buf][wave * 2 + 0][j][lane] = wreg[0][j];
-            ldw[buf][wave * 2 + 1][j][lane] = wreg[1][j];
-            ldx[buf][0][wave][j][lane] = hreg[j];
-            ldx[buf][1][wave][j][lane] = lreg[j];
-        }
+        for (int i = 0; i < 4; ++i) o.a[i] = slot[(wn * 4 + i) * KSTAGE + j][lane];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) o.b[t][i] = slot[(TNB + t * TMB + wm * 2 + i) * KSTAGE + j][lane];
     };
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int s = 0; s < nstage; ++s) {
-        const int cur = s & 1;
-        if (s + 1 < nstage) fetch(s + 1);
+    auto mma_ops = [&](const Ops& o) {
 #pragma unroll
-        for (int j = 0; j < KSTAGE; ++j) {
-            u32x4 a[4];
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = ldw[cur][wn * 4 + i][j][lane];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const u32x4 b0 = ldx[cur][t][wm * 2 + 0][j][lane], b1 = ldx[cur][t][wm * 2 + 1][j][lane];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[i][0] = mfma_bf16(a[i], b0, acc[i][0]);
-                    acc[i][1] = mfma_bf16(a[i], b1, acc[i][1]);
-                }
+            for (int i = 0; i < 4; ++i) {
+                acc[i][0] = mfma_bf16(o.a[i], o.b[t][0], acc[i][0]);
+                acc[i][1] = mfma_bf16(o.a[i], o.b[t][1], acc[i][1]);
             }
-        }
-        if (s + 1 < nstage) stash(cur ^ 1);
+    };
+    // Stage st is usable once this wavefront's own loads of it have landed (at most the loads of the
+    // stages issued after it may still be outstanding) and every other wavefront says the same.
+    auto stage_ready = [&](int st, int last_issued) {
+        const int later = min(last_issued, nstage - 1) - st;
+        if (later >= 2) wait_vmcnt<2 * kLoadsPerStage>();
+        else if (later == 1) wait_vmcnt<kLoadsPerStage>();
+        else wait_vmcnt<0>();
         __syncthreads();
+    };
+#pragma unroll
+    for (int st = 0; st < NSTG - 1; ++st)
+        if (st < nstage) issue(st);
+    stage_ready(0, NSTG - 2);
+    Ops cur, nxt;
+    read_ops(cur, 0, 0);
+    // LDS reads run one k-block ahead of the MFMAs.  The barrier that opens stage s+1 sits before
+    // the last k-block of stage s; every wavefront that passes it has finished the MFMAs of stage
+    // s-1, so that stage's slot is refilled right there (three stages ahead of its use).
+    for (int s = 0; s < nstage; ++s) {
+#pragma unroll
+        for (int j = 0; j < KSTAGE; ++j) {
+            if (j + 1 < KSTAGE) {
+                read_ops(nxt, s, j + 1);
+            } else if (s + 1 < nstage) {
+                stage_ready(s + 1, s + NSTG - 2);
+                if (s + NSTG - 1 < nstage) issue(s + NSTG - 1);
+                read_ops(nxt, s + 1, 0);
+            }
+            mma_ops(cur);
+            cur = nxt;
+        }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -439,7 +469,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const u32x4* __restr
         }
 }
 
-constexpr size_t kTiledSmem = 2 * sizeof(u32x4) * (TNB + 2 * TMB) * KSTAGE * 64;  // 64 KiB
+constexpr size_t kTiledSmem = 0;
 
 // ----------------------------------------------------------------- LayerNorm (+ residual update)
 //
