@@ -182,15 +182,16 @@ __device__ __forceinline__ void skinny_mma(const SkinnyRegs<NT, U>& r, f32x16 (&
     }
 }
 
-template <int MODE, int NT, int U>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
-                                                          const u32x4* __restrict__ Xlo, int KB, int n_tiles,
-                                                          int ksplit, Epi p) {
-    __shared__ float red[4][NT][16][64];
+template <int MODE, int NT, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __restrict__ Wp,
+                                                                 const u32x4* __restrict__ Xhi,
+                                                                 const u32x4* __restrict__ Xlo, int KB, int n_tiles,
+                                                                 int ksplit, Epi p) {
+    __shared__ float red[WAVES][NT][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
-    const int parts = ksplit * 4, part = ks * 4 + wave;
+    const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
     const u32x4* w[NT];
 #pragma unroll
@@ -198,12 +199,17 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
         w[t] = Wp + ((size_t)min(grp * NT + t, n_tiles - 1) * KB + kb0) * 64 + lane;
     const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
     const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
+    // After the k loop the NT*4 (tile, row-quad) items of the workgroup are shared out over its
+    // wavefronts: item = wave + i*WAVES -> tile item/4, rows 8*(item%4) + 4*(lane/32) + 0..3.
+    constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
     // epilogue operands are requested now, long before they are used
-    const int nl = 8 * wave + 4 * (lane >> 5);  // first of this lane's four rows inside a tile
-    uint2 bias_w[NT];
+    uint2 bias_w[ITEMS];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-        bias_w[t] = grp * NT + t < n_tiles ? epilogue_bias<MODE>(p, (grp * NT + t) * 32 + nl) : make_uint2(0, 0);
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+        bias_w[i] = (item < NT * 4 && tile < n_tiles)
+                        ? epilogue_bias<MODE>(p, tile * 32 + 8 * (item & 3) + 4 * (lane >> 5)) : make_uint2(0, 0);
+    }
     const int cur_len = epilogue_len<MODE>(p);
     f32x16 acc[NT];
 #pragma unroll
@@ -233,29 +239,38 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4* __restric
         for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
     __syncthreads();
     const int m = mt * 32 + (lane & 31);
-    float v[NT][4];
+    float v[ITEMS][4];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, t = item >> 2, q = item & 3;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            v[t][r] = (red[0][t][wave * 4 + r][lane] + red[1][t][wave * 4 + r][lane]) +
-                      (red[2][t][wave * 4 + r][lane] + red[3][t][wave * 4 + r][lane]);
+        for (int r = 0; r < 4; ++r) {
+            float sum = 0.f;
+            if (item < NT * 4) {
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ww += 2) sum += red[ww][t][q * 4 + r][lane] + red[ww + 1][t][q * 4 + r][lane];
+            }
+            v[i][r] = sum;
+        }
+    }
     float (*zt)[32][33] = reinterpret_cast<float (*)[32][33]>(&red[0][0][0][0]);  // logits tiles reuse the LDS
     if (MODE == MODE_LMHEAD) __syncthreads();                                      // once every partial is read
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int tile = grp * NT + t;
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, t = item >> 2, tile = grp * NT + t;
+        const int nl = 8 * (item & 3) + 4 * (lane >> 5);  // first of this lane's four rows inside the tile
+        if (item >= NT * 4) continue;
         if (MODE != MODE_LMHEAD) {
-            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[t][0], v[t][1], v[t][2], v[t][3], bias_w[t], cur_len);
+            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[i][0], v[i][1], v[i][2], v[i][3], bias_w[i], cur_len);
         } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) zt[t][nl + r][lane & 31] = v[t][r];
+            for (int r = 0; r < 4; ++r) zt[t][nl + r][lane & 31] = v[i][r];
         }
     }
     if (MODE == MODE_LMHEAD) {
         // logits tiles -> per-(row, tile) softmax and arg-max partials
         __syncthreads();
-        for (int i0 = threadIdx.x; i0 < NT * 32; i0 += 256) {
+        for (int i0 = threadIdx.x; i0 < NT * 32; i0 += WAVES * 64) {
             const int t = i0 >> 5, mm = mt * 32 + (i0 & 31), tile = grp * NT + t;
             if (mm >= p.M || tile >= n_tiles) continue;
             const int mode = p.st->mode, step = p.st->step;
@@ -1075,18 +1090,35 @@ int num_cus() {
     return g_num_cus;
 }
 
+#ifndef HE_SKINNY_U
+#define HE_SKINNY_U(NT) ((NT) <= 4 ? 4 : 2)
+#endif
+#ifndef HE_SKINNY_W8_MAXNT
+#define HE_SKINNY_W8_MAXNT 2
+#endif
 template <int MODE, int NT>
 void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles,
                       int m_tiles, int ksplit, const Epi& p) {
-    constexpr int U = NT <= 4 ? 4 : 2;
+    constexpr int U = HE_SKINNY_U(NT);
     dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
+    // What bounds a wavefront is its serial chain of load rounds (K/16 blocks / wavefronts / U
+    // rounds, about 1.7 us each under load): eight wavefronts halve the chain when K leaves each
+    // of them two rounds (and their accumulators still fit in LDS for the final reduction).
+    const bool eight = NT <= HE_SKINNY_W8_MAXNT && KB / (ksplit * 8) >= 2 * U;
     // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
     // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
-    constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
     constexpr size_t kWant = 84 * 1024;
-    const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
-    gemm_skinny_kernel<MODE, NT, U><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
-                                                         n_tiles, ksplit, p);
+    if (eight) {
+        constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+        gemm_skinny_kernel<MODE, NT <= HE_SKINNY_W8_MAXNT ? NT : 1, U, 8><<<grid, 512, pad, s>>>(
+            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+    } else {
+        constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+        gemm_skinny_kernel<MODE, NT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
+                                                                  (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+    }
 }
 
 // nt weight tiles per workgroup (1..8)
