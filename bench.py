@@ -26,8 +26,11 @@ HBM_PEAK = 8.0e12        # B/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 
 
-def device_weights(d, torch, seed=0, std=0.02):
-    """Random-init bf16 weights generated on the device, tensor by tensor."""
+def device_weights(d, torch, seed=0, std=0.02, tiled=False):
+    """Random-init bf16 weights generated on the device, tensor by tensor.  tiled=True: every GEMM
+    matrix is converted to the engine's MFMA-tiled form as soon as it is drawn and the row-major
+    original dropped (he_config.weights_tiled = 1: no second copy, for models that fill HBM)."""
+    from paper_2308_01320_amd import binding
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
     dt = torch.bfloat16
@@ -36,15 +39,23 @@ def device_weights(d, torch, seed=0, std=0.02):
         t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
         return (t * std + mean).to(dt).contiguous()
 
+    def mat(shape):
+        m = draw(shape)
+        if not tiled:
+            return m
+        t = binding.he_tile_matrix(m)
+        torch.cuda.synchronize()
+        return t
+
     H, F = d.hidden, d.ffn
     w = {"tok_emb": draw((d.vocab, H)), "pos_emb": draw((d.max_positions + d.pos_offset, H)), "layers": []}
     for _ in range(d.n_layers):
         w["layers"].append({
-            "ln1_g": draw((H,), 1.0), "ln1_b": draw((H,)), "wqkv": draw((3 * H, H)), "bqkv": draw((3 * H,)),
-            "wo": draw((H, H)), "bo": draw((H,)), "ln2_g": draw((H,), 1.0), "ln2_b": draw((H,)),
-            "w1": draw((F, H)), "b1": draw((F,)), "w2": draw((H, F)), "b2": draw((H,))})
+            "ln1_g": draw((H,), 1.0), "ln1_b": draw((H,)), "wqkv": mat((3 * H, H)), "bqkv": draw((3 * H,)),
+            "wo": mat((H, H)), "bo": draw((H,)), "ln2_g": draw((H,), 1.0), "ln2_b": draw((H,)),
+            "w1": mat((F, H)), "b1": draw((F,)), "w2": mat((H, F)), "b2": draw((H,))})
     w["lnf_g"], w["lnf_b"] = draw((H,), 1.0), draw((H,))
-    w["lm_head"] = w["tok_emb"]
+    w["lm_head"] = binding.he_tile_matrix(w["tok_emb"]) if tiled else w["tok_emb"]
     return w
 
 
@@ -113,6 +124,8 @@ def main():
     ap.add_argument("--workload", default="opt-13b", help="tiny | opt-1.3b | opt-6.7b | opt-13b | opt-66b")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (a reduced model: not the headline number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--weights-tiled", action="store_true",
+                    help="hand the engine pre-tiled matrices (no second copy); implied by opt-66b")
     ap.add_argument("--timing-steps", type=int, default=24, help="decode steps run with per-kernel HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -131,9 +144,10 @@ def main():
     B, S, G = d.batch, d.prompt_len, d.gen_len
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()  # default priority; the engine captures its decode step on it
-    weights = device_weights(d, torch)
+    tiled = args.weights_tiled or d.name == "opt-66b"
+    weights = device_weights(d, torch, tiled=tiled)
     torch.cuda.synchronize()
-    cfg = binding.make_config(d, stream=stream.cuda_stream)
+    cfg = binding.make_config(d, stream=stream.cuda_stream, weights_tiled=1 if tiled else 0)
     eng = binding.Engine(cfg, weights)
     prompts = torch.from_numpy(synth.make_prompts(d, seed=1234 + 3)).cuda()
     samp = binding.sampling(d.sampling, 1.0, 42)

@@ -73,6 +73,12 @@ typedef struct {
     void* stream;      /* hipStream_t or NULL */
     int impl;          /* 0 = default kernels for the dtype; 1 = the plain (f32-path) kernels
                           instantiated for this dtype -- a slow comparator for tests */
+    int weights_tiled; /* bf16, impl 0 only.  0: wqkv, wo, w1, w2 and lm_head are row-major and the engine
+                          keeps MFMA-tiled copies of them (twice the memory).  1: the caller passes those
+                          five kinds of matrices already tiled by he_tile_matrix and the engine uses them
+                          in place, no copies -- for models whose weights fill more than half of HBM.
+                          tok_emb is row-major in both cases (with a tied head and weights_tiled = 1,
+                          lm_head is the tiled copy of tok_emb). */
 } he_config;
 
 typedef struct {
@@ -98,6 +104,14 @@ typedef struct {
     float temperature; /* > 0, used in mode 1 only */
     uint64_t seed;     /* g = -log(-log u), u from Philox4x32-10 keyed by seed at counter (v, step, b, 0) */
 } he_sampling;
+
+/* Bytes of the MFMA-tiled form of a bf16 [rows, cols] matrix (rows padded to a multiple of 32;
+ * cols must be a multiple of 16), and the conversion itself: d_src row-major bf16 [rows, cols],
+ * d_dst the tiled form, distinct buffers, on `stream`.  The tiled form is [rows/32][cols/16]
+ * blocks of 64 lanes x 8 values: lane 32*((c%16)/8) + r%32 holds columns 16*(c/16) + 8*(lane/32)
+ * + 0..7 of row r -- one MFMA 32x32x16 operand per block. */
+size_t he_tiled_bytes(int rows, int cols);
+he_status he_tile_matrix(const void* d_src, void* d_dst, int rows, int cols, void* stream);
 
 /* Bytes of device memory he_create will allocate for cfg (KV arena, workspace,
  * tiled weight copies).  Pure host computation; 0 if cfg is invalid. */

@@ -23,7 +23,7 @@ class he_config(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("hidden", C.c_int), ("n_heads", C.c_int), ("ffn", C.c_int),
                 ("vocab", C.c_int), ("max_positions", C.c_int), ("pos_offset", C.c_int), ("ln_eps", C.c_float),
                 ("dtype", C.c_int), ("max_batch", C.c_int), ("max_seq_len", C.c_int), ("device", C.c_int),
-                ("stream", C.c_void_p), ("impl", C.c_int)]
+                ("stream", C.c_void_p), ("impl", C.c_int), ("weights_tiled", C.c_int)]
 
 
 LAYER_FIELDS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -85,6 +85,10 @@ def lib() -> C.CDLL:
     L.he_timing_enable.argtypes = [vp, C.c_int]
     L.he_timing_read.restype = C.c_int
     L.he_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_long), C.c_int]
+    L.he_tiled_bytes.restype = C.c_size_t
+    L.he_tiled_bytes.argtypes = [C.c_int, C.c_int]
+    L.he_tile_matrix.restype = C.c_int
+    L.he_tile_matrix.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -97,7 +101,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
-           "he_timing_read", "he_calibration_copy", "he_kernel_sweep")
+           "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
+           "he_tile_matrix")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -110,12 +115,12 @@ def sampling(mode: str = "greedy", temperature: float = 1.0, seed: int = 0) -> h
     return he_sampling({"greedy": 0, "gumbel": 1}[mode], float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF)
 
 
-def make_config(dims, max_batch=None, max_seq_len=None, device=0, stream=None, impl=0) -> he_config:
+def make_config(dims, max_batch=None, max_seq_len=None, device=0, stream=None, impl=0, weights_tiled=0) -> he_config:
     """he_config from a synth.ModelDims (or anything with the same fields)."""
     return he_config(dims.n_layers, dims.hidden, dims.n_heads, dims.ffn, dims.vocab, dims.max_positions,
                      dims.pos_offset, dims.ln_eps, HE_BF16 if dims.dtype == "bf16" else HE_F32,
                      max_batch or dims.batch, max_seq_len or (dims.prompt_len + dims.gen_len), device,
-                     stream, impl)
+                     stream, impl, weights_tiled)
 
 
 def upload_weights(w: dict, dtype: str, device="cuda:0") -> dict:
@@ -245,3 +250,38 @@ def he_calibration_copy(src, dst, stream=None):
     if rc != HE_OK:
         raise HeError(rc, "he_calibration_copy")
     return nbytes
+
+
+def he_tile_matrix(src, stream=None):
+    """Tiled copy (uint8 tensor of he_tiled_bytes) of a row-major bf16 [rows, cols] device tensor."""
+    import torch
+    rows, cols = src.shape
+    n = lib().he_tiled_bytes(rows, cols)
+    if n == 0:
+        raise HeError(1, "he_tiled_bytes: bad shape")
+    dst = torch.empty(n, dtype=torch.uint8, device=src.device)
+    rc = lib().he_tile_matrix(src.data_ptr(), dst.data_ptr(), rows, cols, stream)
+    if rc != HE_OK:
+        raise HeError(rc, "he_tile_matrix")
+    return dst
+
+
+TILED_KINDS = ("wqkv", "wo", "w1", "w2")
+
+
+def tile_weights_in_place(weights: dict) -> dict:
+    """Replaces the GEMM matrices of a device weight dict by their tiled forms, one at a time, so that
+    at most one matrix exists twice (for he_config.weights_tiled = 1)."""
+    import torch
+    out = dict(weights)
+    out["layers"] = []
+    for lw in weights["layers"]:
+        nl = dict(lw)
+        for k in TILED_KINDS:
+            nl[k] = he_tile_matrix(lw[k])
+            torch.cuda.synchronize()
+            lw[k] = None
+        out["layers"].append(nl)
+    out["lm_head"] = he_tile_matrix(weights["lm_head"])
+    torch.cuda.synchronize()
+    return out

@@ -69,6 +69,8 @@ const char* check_config(const he_config* c) {
     if (c->max_positions <= 0 || c->pos_offset < 0 || c->max_batch <= 0 || c->max_seq_len <= 0) return "non-positive capacity";
     if (c->dtype != HE_F32 && c->dtype != HE_BF16) return "unknown dtype";
     if (c->impl != 0 && c->impl != 1) return "unknown impl";
+    if (c->weights_tiled != 0 && c->weights_tiled != 1) return "weights_tiled must be 0 or 1";
+    if (c->weights_tiled && !(c->dtype == HE_BF16 && c->impl == 0)) return "weights_tiled needs dtype bf16 and impl 0";
     if (!(c->ln_eps > 0.f)) return "ln_eps must be positive";
     return nullptr;
 }
@@ -110,7 +112,8 @@ Sizes sizes_of(const he_config& c) {
     const size_t ntile = (size_t)(c.vocab + 31) / 32;
     s.stats = (size_t)c.max_batch * ntile * 4 * sizeof(float);
     s.stats_idx = (size_t)c.max_batch * ntile * sizeof(int);
-    s.total += 2 * s.rowsH /* resid, q */ + (size_t)c.n_layers * s.tiled_layer + s.tiled_lm + 4 * s.ablk + 2 * s.hblk +
+    s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
+               4 * s.ablk + 2 * s.hblk +
                2 * s.xfblk + s.part + s.stats + s.stats_idx;
     return s;
 }
@@ -278,6 +281,7 @@ he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int
 // (Re)builds the MFMA-tiled copies from the caller's row-major matrices.
 void tile_weights(he_engine* e) {
     const he_config& c = e->cfg;
+    if (c.weights_tiled) return;  // nothing of the engine's own to rebuild
     const int H = c.hidden, F = c.ffn;
     for (int l = 0; l < c.n_layers; ++l) {
         bf16_tile_rows(e->stream, e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H);
@@ -425,11 +429,20 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     } else {
         const int H = cfg->hidden, F = cfg->ffn;
         e->tiled.resize(cfg->n_layers);
-        for (auto& t : e->tiled) {
-            A(&t.wqkv, bf16_tiled_bytes(3 * H, H)); A(&t.wo, bf16_tiled_bytes(H, H));
-            A(&t.w1, bf16_tiled_bytes(F, H)); A(&t.w2, bf16_tiled_bytes(H, F));
+        if (cfg->weights_tiled) {  // the caller's matrices are tiled already: used in place
+            for (int l = 0; l < cfg->n_layers; ++l) {
+                const he_layer_weights& lw = e->layers[l];
+                e->tiled[l] = {const_cast<void*>(lw.wqkv), const_cast<void*>(lw.wo), const_cast<void*>(lw.w1),
+                               const_cast<void*>(lw.w2)};
+            }
+            e->lm_tiled = const_cast<void*>(e->w.lm_head);
+        } else {
+            for (auto& t : e->tiled) {
+                A(&t.wqkv, bf16_tiled_bytes(3 * H, H)); A(&t.wo, bf16_tiled_bytes(H, H));
+                A(&t.w1, bf16_tiled_bytes(F, H)); A(&t.w2, bf16_tiled_bytes(H, F));
+            }
+            A(&e->lm_tiled, z.tiled_lm);
         }
-        A(&e->lm_tiled, z.tiled_lm);
         A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
         A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
         A(&e->part, z.part); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
@@ -589,6 +602,17 @@ he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_
 const char* he_last_error(const he_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
 
 int he_cache_len(const he_engine* e) { return e ? e->cur_len : -1; }
+
+size_t he_tiled_bytes(int rows, int cols) {
+    if (rows <= 0 || cols <= 0 || cols % 16) return 0;
+    return bf16_tiled_bytes(rows, cols);
+}
+
+he_status he_tile_matrix(const void* d_src, void* d_dst, int rows, int cols, void* stream) {
+    if (!d_src || !d_dst || d_src == d_dst || rows <= 0 || cols <= 0 || cols % 16) return HE_ERR_INVALID_ARG;
+    bf16_tile_rows((hipStream_t)stream, d_src, d_dst, rows, cols);
+    return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
+}
 
 he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
     if (!e) return HE_ERR_INVALID_ARG;

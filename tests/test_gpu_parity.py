@@ -6,6 +6,7 @@ path the oracle runs on the configuration's storage formats: bf16-valued
 weights and a bf16 KV cache, float64 everywhere else."""
 import numpy as np
 import pytest
+from ctypes import byref as C_byref
 
 from oracle import opt_oracle as O
 from paper_2308_01320_amd import binding, synth
@@ -296,3 +297,23 @@ def test_bf16_opt66b_layer_shape():
     d = base.sliced(n_layers=1, batch=8, prompt_len=40, gen_len=3, max_positions=64)
     rep = _bf16_case(d, True, 3, "greedy", 1.0, 0, seed=1)
     print(rep)
+
+
+def test_pretiled_weights_give_identical_results():
+    """he_config.weights_tiled = 1: the caller tiles the GEMM matrices with he_tile_matrix and the engine
+    keeps no copies; ids and log-probs must be bit-identical to the default mode."""
+    import torch
+    d = synth.ModelDims("x", 2, 256, 2, 576, 1111, 64, 5, 40, 6, "bf16", "gumbel")
+    w = synth.make_weights(d, seed=5, tied=True)
+    p = torch.from_numpy(synth.make_prompts(d, seed=6)).cuda()
+    s = binding.sampling("gumbel", 1.0, 3)
+    e0 = util.make_engine(d, w)
+    a, al = e0.he_generate(p, d.gen_len, s)
+    dev = binding.tile_weights_in_place(binding.upload_weights(w, "bf16"))
+    cfg = binding.make_config(d, weights_tiled=1)
+    assert binding.lib().he_workspace_bytes(C_byref(cfg)) < binding.lib().he_workspace_bytes(C_byref(e0.cfg))
+    e1 = binding.Engine(cfg, dev)
+    b, bl = e1.he_generate(p, d.gen_len, s)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(al, bl)
+    e0.he_destroy(); e1.he_destroy()
