@@ -32,6 +32,10 @@ struct he_engine {
     void *ablk_lo = nullptr, *oblk_lo = nullptr, *hblk_lo = nullptr, *xfblk_lo = nullptr;  // second bf16 term
     float *part = nullptr, *stats = nullptr;
     int* stats_idx = nullptr;
+    // decode rows: LayerNorms folded into the GEMMs around them
+    float *cvec = nullptr;     // per layer W gamma, W beta for wqkv (2 x 3H) and w1 (2 x F), then the LM head's (2 x V), padded to 32
+    float *ln_stats = nullptr; // per-column-group mean / squared deviations of the residual rows
+    int* ln_counters = nullptr;
 
     // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
     hipGraphExec_t step_graph = nullptr;
@@ -55,7 +59,7 @@ namespace {
 struct Sizes {
     size_t kv, rowsH, rowsF, xf, logits, gen, total;
     // bf16 path
-    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx;
+    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx, cvec, ln_stats, ln_counters;
 };
 
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
@@ -107,11 +111,19 @@ Sizes sizes_of(const he_config& c) {
     s.ablk = bf16_tiled_bytes((int)rows, H);
     s.hblk = bf16_tiled_bytes((int)rows, F);
     s.xfblk = bf16_tiled_bytes(c.max_batch, H);
-    const size_t prow = rows > (size_t)kMaxKSplit * c.max_batch ? rows : (size_t)kMaxKSplit * c.max_batch;
+    // prompt rows, or the decode step's k-split scratch: splits x rows padded to 32, twice (a
+    // workgroup of eight wavefronts on a single tile leaves half of its slots unused)
+    const size_t drow = (size_t)2 * kMaxKSplit * (((size_t)c.max_batch + 31) / 32 * 32);
+    const size_t prow = rows > drow ? rows : drow;
     s.part = prow * H * sizeof(float);
     const size_t ntile = (size_t)(c.vocab + 31) / 32;
     s.stats = (size_t)c.max_batch * ntile * 4 * sizeof(float);
     s.stats_idx = (size_t)c.max_batch * ntile * sizeof(int);
+    const size_t vpad = ((size_t)c.vocab + 31) / 32 * 32, mtiles = ((size_t)c.max_batch + 31) / 32;
+    s.cvec = ((size_t)c.n_layers * 2 * (3 * H + F) + 2 * vpad) * sizeof(float);
+    s.ln_stats = mtiles * (H / 32) * 32 * 2 * sizeof(float) + 1024;  // at most one group per 32 columns
+    s.ln_counters = mtiles * (H / 32) * sizeof(int);
+    s.total += s.cvec + s.ln_stats + s.ln_counters;
     s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
                4 * s.ablk + 2 * s.hblk +
                2 * s.xfblk + s.part + s.stats + s.stats_idx;
@@ -201,6 +213,24 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     e->cur_len += Sp;
 }
 
+// Where the vectors W gamma (c1) and W beta (c2) of the GEMMs that follow a LayerNorm live.
+struct CVec { float *c1, *c2; };
+CVec cvec_qkv(const he_engine* e, int l) {
+    const size_t H = e->cfg.hidden, F = e->cfg.ffn;
+    float* p = e->cvec + (size_t)l * 2 * (3 * H + F);
+    return {p, p + 3 * H};
+}
+CVec cvec_fc1(const he_engine* e, int l) {
+    const size_t H = e->cfg.hidden, F = e->cfg.ffn;
+    float* p = e->cvec + (size_t)l * 2 * (3 * H + F) + 6 * H;
+    return {p, p + F};
+}
+CVec cvec_lm(const he_engine* e) {
+    const size_t H = e->cfg.hidden, F = e->cfg.ffn, vpad = ((size_t)e->cfg.vocab + 31) / 32 * 32;
+    float* p = e->cvec + (size_t)e->cfg.n_layers * 2 * (3 * H + F);
+    return {p, p + vpad};
+}
+
 // bf16 path, one new token per sequence (a decode step, or the last prompt token):
 // weight-streaming GEMMs with two-term activations, attention over the cache, LM head
 // fused with log-softmax and sampling.
@@ -208,25 +238,39 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
                       int out_stride, int out_at_step, float* d_logits_opt) {
     const he_config& c = e->cfg;
     hipStream_t s = e->stream;
-    const int H = c.hidden, F = c.ffn;
+    const int H = c.hidden, F = c.ffn, L = c.n_layers;
     bf16_gemm_args base;
     base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
     base.max_seq = c.max_seq_len;
-    plain_embed(s, 1, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, B, 1, H, c.vocab, c.pos_offset);
-    const float* pend = nullptr;  // k-split partial sums not yet added to the residual stream
-    int pend_ks = 0;
-    const void* pend_b = nullptr;
+    // No LayerNorm kernels here: each one is folded into the GEMM after it.  Whoever produces a
+    // residual row (the embedding, the out-projection, FC2) leaves gamma * x as two-term blocks
+    // and statistics per group of columns; the column groups are the producer's workgroups.
+    int nt1, ks1, nt2, ks2;
+    bf16_store_shape(B, H, H, &nt1, &ks1);
+    bf16_store_shape(B, H, F, &nt2, &ks2);
+    const int gw1 = nt1 * 32, gw2 = L ? nt2 * 32 : 128;  // column-group widths after the out-projection / after FC2 and the embedding
     const size_t split = (size_t)B * H;
-    const int ks1 = bf16_gemm_ksplit(H, H), ks2 = bf16_gemm_ksplit(H, F);
-    for (int l = 0; l < c.n_layers; ++l) {
+    auto fold = [&](bf16_gemm_args& a, int gw, const CVec& cv) {
+        a.ln_stats = e->ln_stats; a.ln_gw = gw; a.ln_groups = (H + gw - 1) / gw; a.ln_cols = H; a.ln_eps = c.ln_eps;
+        a.c1 = cv.c1; a.c2 = cv.c2;
+    };
+    auto store_ln = [&](bf16_gemm_args& a, const void* bias, const void* gamma, void* blk, void* blk_lo) {
+        a.out = e->part; a.out_split = split; a.bias = bias; a.resid = e->resid; a.gamma = gamma;
+        a.out_blocks = blk; a.out_blocks_lo = blk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
+    };
+    {
+        LaunchTimer t(e, HE_K_LAYERNORM);
+        const bool last = L == 0;
+        bf16_embed_ln(s, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->st, B, H, c.vocab, c.pos_offset, gw2,
+                      last ? e->w.lnf_g : e->layers[0].ln1_g, e->resid, last ? e->xfblk : e->ablk,
+                      last ? e->xfblk_lo : e->ablk_lo, e->ln_stats);
+    }
+    for (int l = 0; l < L; ++l) {
         const he_layer_weights& lw = e->layers[l];
         const he_engine::Tiled& tw = e->tiled[l];
-        {
-            LaunchTimer t(e, HE_K_LAYERNORM);
-            bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
-        }
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
+        fold(a, gw2, cvec_qkv(e, l));
         {
             LaunchTimer t(e, HE_K_QKV);
             bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
@@ -235,35 +279,33 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
             LaunchTimer t(e, HE_K_ATTENTION);
             bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
         }
-        a = base; a.out = e->part; a.out_split = split;
+        a = base;
+        store_ln(a, lw.bo, lw.ln2_g, e->ablk, e->ablk_lo);
         {
             LaunchTimer t(e, HE_K_OUT_PROJ);
-            bf16_gemm_skinny(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
-        }
-        {
-            LaunchTimer t(e, HE_K_LAYERNORM);
-            bf16_ln(s, e->resid, e->part, ks1, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+            bf16_gemm_skinny(s, EPI_STORE_LN, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
         }
         a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        fold(a, gw1, cvec_fc1(e, l));
         {
             LaunchTimer t(e, HE_K_FC1);
             bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
         }
-        a = base; a.out = e->part; a.out_split = split;
+        a = base;
+        const bool last = l == L - 1;
+        store_ln(a, lw.b2, last ? e->w.lnf_g : e->layers[l + 1].ln1_g, last ? e->xfblk : e->ablk,
+                 last ? e->xfblk_lo : e->ablk_lo);
         {
             LaunchTimer t(e, HE_K_FC2);
-            bf16_gemm_skinny(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
+            bf16_gemm_skinny(s, EPI_STORE_LN, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
         }
-        pend = e->part; pend_ks = ks2; pend_b = lw.b2;
-    }
-    {
-        LaunchTimer t(e, HE_K_LAYERNORM);
-        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
     }
     {
         LaunchTimer t(e, HE_K_LM_HEAD);
+        bf16_gemm_args a = base;
+        fold(a, gw2, cvec_lm(e));
         bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
-                     ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+                     ids_out, lp_out, out_stride, out_at_step, e->cur_ids, &a);
     }
     { LaunchTimer t(e, HE_K_EMPTY); }
     launch_advance_state(s, e->st, 1, 1);
@@ -278,18 +320,28 @@ he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int
     return check_hip(e, hipGetLastError(), "kernel launch");
 }
 
-// (Re)builds the MFMA-tiled copies from the caller's row-major matrices.
+// (Re)builds the MFMA-tiled copies from the caller's row-major matrices
+// and the vectors W gamma, W beta of every GEMM that follows a LayerNorm.
 void tile_weights(he_engine* e) {
     const he_config& c = e->cfg;
-    if (c.weights_tiled) return;  // nothing of the engine's own to rebuild
     const int H = c.hidden, F = c.ffn;
-    for (int l = 0; l < c.n_layers; ++l) {
-        bf16_tile_rows(e->stream, e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H);
-        bf16_tile_rows(e->stream, e->layers[l].wo, e->tiled[l].wo, H, H);
-        bf16_tile_rows(e->stream, e->layers[l].w1, e->tiled[l].w1, F, H);
-        bf16_tile_rows(e->stream, e->layers[l].w2, e->tiled[l].w2, H, F);
+    if (!c.weights_tiled) {  // else the caller's matrices are used in place
+        for (int l = 0; l < c.n_layers; ++l) {
+            bf16_tile_rows(e->stream, e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H);
+            bf16_tile_rows(e->stream, e->layers[l].wo, e->tiled[l].wo, H, H);
+            bf16_tile_rows(e->stream, e->layers[l].w1, e->tiled[l].w1, F, H);
+            bf16_tile_rows(e->stream, e->layers[l].w2, e->tiled[l].w2, H, F);
+        }
+        bf16_tile_rows(e->stream, e->w.lm_head, e->lm_tiled, c.vocab, H);
     }
-    bf16_tile_rows(e->stream, e->w.lm_head, e->lm_tiled, c.vocab, H);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const he_layer_weights& lw = e->layers[l];
+        const CVec q = cvec_qkv(e, l), f = cvec_fc1(e, l);
+        bf16_wvec(e->stream, e->tiled[l].wqkv, 3 * H, H, lw.ln1_g, lw.ln1_b, q.c1, q.c2);
+        bf16_wvec(e->stream, e->tiled[l].w1, F, H, lw.ln2_g, lw.ln2_b, f.c1, f.c2);
+    }
+    const CVec v = cvec_lm(e);
+    bf16_wvec(e->stream, e->lm_tiled, c.vocab, H, e->w.lnf_g, e->w.lnf_b, v.c1, v.c2);
 }
 
 // One pass of the decoder over M = B*S new rows (S = prompt length, or 1 for a
@@ -446,6 +498,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
         A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
         A(&e->part, z.part); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
+        A(&e->cvec, z.cvec); A(&e->ln_stats, z.ln_stats); A(&e->ln_counters, z.ln_counters);
     }
     A(&e->gen_lp, z.gen); A(&e->gen_ids, z.gen);
     A(&e->cur_ids, cfg->max_batch * sizeof(int32_t));
@@ -470,6 +523,8 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         (void)hipMemsetAsync(e->oblk_lo, 0, z.ablk, e->stream);
         (void)hipMemsetAsync(e->xfblk_lo, 0, z.xfblk, e->stream);
         (void)hipMemsetAsync(e->hblk_lo, 0, z.hblk, e->stream);
+        (void)hipMemsetAsync(e->ln_stats, 0, z.ln_stats, e->stream);
+        (void)hipMemsetAsync(e->ln_counters, 0, z.ln_counters, e->stream);
         tile_weights(e);
     }
     r = hipStreamSynchronize(e->stream);
@@ -631,15 +686,23 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
             bf16_gemm_args a = base;
             if (kernel_class == HE_K_FC1) {
                 a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+                int nt1, ks1;
+                bf16_store_shape(B, H, H, &nt1, &ks1);
+                a.ln_stats = e->ln_stats; a.ln_gw = nt1 * 32; a.ln_groups = (H + a.ln_gw - 1) / a.ln_gw; a.ln_cols = H;
+                a.ln_eps = c.ln_eps; a.c1 = cvec_fc1(e, l).c1; a.c2 = cvec_fc1(e, l).c2;
                 bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
-            } else if (kernel_class == HE_K_FC2) {
-                a.out = e->part; a.out_split = split;
-                bf16_gemm_skinny(e->stream, EPI_STORE, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F,
-                                 bf16_gemm_ksplit(H, F), a);
             } else {
-                a.out = e->part; a.out_split = split;
-                bf16_gemm_skinny(e->stream, EPI_STORE, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H,
-                                 bf16_gemm_ksplit(H, H), a);
+                // as in a decode step: the last workgroup of each column group folds the partial sums
+                // into the residual rows and rewrites the blocks and statistics the next GEMM reads
+                const bool fc2 = kernel_class == HE_K_FC2;
+                int nt, ks;
+                bf16_store_shape(B, H, fc2 ? F : H, &nt, &ks);
+                a.out = e->part; a.out_split = split; a.resid = e->resid;
+                a.bias = fc2 ? e->layers[l].b2 : e->layers[l].bo;
+                a.gamma = fc2 ? e->layers[l].ln1_g : e->layers[l].ln2_g;
+                a.out_blocks = e->ablk; a.out_blocks_lo = e->ablk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
+                if (fc2) bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F, ks, a);
+                else bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H, ks, a);
             }
         }
     return check_hip(e, hipGetLastError(), "he_kernel_sweep");

@@ -5,7 +5,7 @@
 
 struct he_dev_state;
 
-enum { EPI_STORE = 0, EPI_BIAS_RELU = 1, EPI_QKV = 2 };
+enum { EPI_STORE = 0, EPI_BIAS_RELU = 1, EPI_QKV = 2, EPI_STORE_LN = 3 };
 
 // ---- plain kernels (kernels_plain.hip): float activations, row-major; bf16 != 0 selects bf16 storage
 void plain_embed(hipStream_t s, int bf16, const int32_t* ids, int id_stride, const void* tok, const void* pos, float* x,
@@ -40,10 +40,28 @@ struct bf16_gemm_args {
     const he_dev_state* st = nullptr;
     int S = 1, layer = 0, H = 0, n_heads = 0, max_batch = 0, max_seq = 0;
     float qscale = 1.f;
+    // LayerNorm folded into the GEMM that consumes it (EPI_BIAS_RELU, EPI_QKV, LM head; decode rows):
+    // the activations are gamma * x and ln_stats holds per-column-group statistics of x
+    const float* ln_stats = nullptr;  // [m_tiles][ln_groups][32][2] (+ 1 KiB of padding); null = not folded
+    int ln_groups = 0, ln_gw = 0, ln_cols = 0;
+    float ln_eps = 0.f;
+    const float* c1 = nullptr;        // [N padded to 32] W gamma
+    const float* c2 = nullptr;        // [N padded to 32] W beta
+    // EPI_STORE_LN: k-split sum + bias + residual, gamma * x blocks (out_blocks, out_blocks_lo) and statistics
+    float* resid = nullptr;           // [M][N]
+    const void* gamma = nullptr;      // bf16 [N]
+    float* stats_out = nullptr;       // [m_tiles][groups][32][2]
+    int* counters = nullptr;          // [groups * m_tiles] zeros
 };
 size_t bf16_tiled_bytes(int rows, int K);
 void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K);
 int bf16_gemm_ksplit(int N, int K);
+// decode-shaped STORE GEMM of M rows: weight tiles per workgroup (its column group is 32*nt wide) and k-splits
+void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
+void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
+                   const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
+                   void* x_blocks, void* x_blocks_lo, float* stats);
+void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2);
 // rows in slices of 32 (decode, LM head): activations as hi + lo bf16 terms
 void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                       int ksplit, const bf16_gemm_args& a);
@@ -52,7 +70,8 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
                      const bf16_gemm_args& a);
 void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
-                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids);
+                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids,
+                  const bf16_gemm_args* fold = nullptr);
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
              int in_mul, int in_add, int writeback);

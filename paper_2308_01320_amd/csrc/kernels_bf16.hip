@@ -20,6 +20,8 @@
 // takes the activation rounding error from 2^-9 to 2^-17.  Decode-shaped GEMMs
 // are bound by the weight stream, so there it costs no time; the prompt pass
 // pays twice the matrix-core work for it.
+#include <algorithm>
+
 #include "he_common.h"
 #include "kernels.h"
 
@@ -48,6 +50,18 @@ __device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t&
 // index (in 16-byte units) of the slot holding R[r][k0..k0+7], k0 % 8 == 0
 __device__ __forceinline__ size_t block_slot(int r, int k0, int KB) {
     return ((size_t)(r >> 5) * KB + (k0 >> 4)) * 64 + (((k0 >> 3) & 1) << 5) + (r & 31);
+}
+
+// 16 bytes per lane, global memory -> LDS with no staging registers: lane i's bytes land at lds_block + 16*i
+__device__ __forceinline__ void load_block_to_lds(const u32x4* gsrc_lane, u32x4* lds_block) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc_lane,
+                                     (void __attribute__((address_space(3)))*)lds_block, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
 // ----------------------------------------------------------------- weight tiling
@@ -83,9 +97,23 @@ struct Epi {
     float* stats;           // [M][n_tiles][4]: max z, sum exp(z - max), best score, z at best
     int* stats_idx;         // [M][n_tiles]: id of best score
     int n_tiles;
+    // LayerNorm folded into this GEMM (BIAS_RELU, QKV, LMHEAD on decode rows): X is gamma * x, not
+    // normalised; ln_stats[(mt*ln_groups + g)*32 + m%32] = (mean, sum of squared deviations) of x[m]
+    // over column group g (ln_gw columns, the last group may be short); c1 = W gamma, c2 = W beta.
+    const float2* ln_stats;  // null: X is already normalised
+    int ln_groups, ln_gw, ln_cols;
+    float ln_eps;
+    const float *c1, *c2;   // [N]
+    // STORE_LN: the workgroup that finishes a column group last adds the k-split partial sums,
+    // bias and residual, and hands the next GEMM gamma * x (out_blocks, out_blocks_lo) and the
+    // group's statistics
+    float* resid;           // [M][N] residual stream, updated in place
+    const bf16_t* gamma;    // [N] gain of the LayerNorm that follows
+    float2* stats_out;      // [m_tiles][groups][32]
+    int* counters;          // [groups][m_tiles], zero between launches
 };
 
-enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3 };
+enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3, MODE_STORE_LN = 4 };
 
 // bias words for outputs n0..n0+3 and the cache length, fetched ahead of the epilogue
 template <int MODE>
@@ -188,11 +216,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
                                                                  const u32x4* __restrict__ Xlo, int KB, int n_tiles,
                                                                  int ksplit, Epi p) {
     __shared__ float red[WAVES][NT][16][64];
+    extern __shared__ float dyn_lds[];  // LayerNorm statistics of this slice of rows, when folded
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
+    constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV || MODE == MODE_LMHEAD;
+    const bool fold = FOLDABLE && p.ln_stats != nullptr;
+    if (fold) {  // statistics go straight to LDS, 1 KiB per instruction; they are read after the k loop
+        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;  // the buffer is padded to this
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
+        for (int c = wave; c < chunks; c += WAVES)
+            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
+    }
     const u32x4* w[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
@@ -204,11 +241,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
     // epilogue operands are requested now, long before they are used
     uint2 bias_w[ITEMS];
+    float4 c1w[ITEMS], c2w[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
-        bias_w[i] = (item < NT * 4 && tile < n_tiles)
-                        ? epilogue_bias<MODE>(p, tile * 32 + 8 * (item & 3) + 4 * (lane >> 5)) : make_uint2(0, 0);
+        const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+        const bool live = item < NT * 4 && tile < n_tiles;
+        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+        if (FOLDABLE) {
+            c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (fold && live) {  // c1 and c2 are padded to whole tiles
+                c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+                c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+            }
+        }
     }
     const int cur_len = epilogue_len<MODE>(p);
     f32x16 acc[NT];
@@ -237,6 +283,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
+    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
     __syncthreads();
     const int m = mt * 32 + (lane & 31);
     float v[ITEMS][4];
@@ -252,6 +299,137 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
             }
             v[i][r] = sum;
         }
+    }
+    if (fold) {
+        // Row statistics from the group statistics (pairwise-update form, pivoted on the first
+        // group's mean), then  W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta.
+        const float2* gs = reinterpret_cast<const float2*>(dyn_lds) + (lane & 31);
+        const float pivot = gs[0].x;
+        float s1 = 0.f, s2 = 0.f, sm = 0.f;
+        for (int g = 0; g < p.ln_groups; ++g) {
+            const float2 e = gs[g * 32];
+            const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
+            s1 += cnt * dlt;
+            s2 += cnt * dlt * dlt;
+            sm += e.y;
+        }
+        const float inv = 1.0f / (float)p.ln_cols;
+        const float mean = pivot + s1 * inv;
+        const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
+        const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
+            v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
+            v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
+            v[i][3] = rstd * (v[i][3] - mean * c1w[i].w) + c2w[i].w;
+        }
+    }
+    if (MODE == MODE_STORE_LN) {
+        __shared__ int s_last;
+        __shared__ float sred[2][WAVES][32];
+        const size_t cell = (size_t)grp * gridDim.y + mt;
+        // The k-split partial sums cross workgroups (and XCDs, each with an L2 of its own) inside
+        // one launch.  They travel as agent-scope atomic words -- written through to, and read
+        // from, the level every XCD shares -- so no cache has to be flushed or invalidated.  The
+        // words of one (split, item, r) are laid out thread after thread: every access is a
+        // contiguous 256 bytes per wavefront.
+        constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
+        float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
+        if (ksplit > 1) {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+                if (item < NT * 4 && tile < n_tiles && m < p.M) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            // Once the stores are acknowledged, count this workgroup in; whoever counts last for
+            // the column group sees all of the partial sums.  Nobody waits: the others are done.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (threadIdx.x == 0)
+                s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                         ksplit - 1;
+            __syncthreads();
+            if (!s_last) return;
+        }
+        float x[ITEMS][4];
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+            const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+            const bool live = item < NT * 4 && tile < n_tiles && m < p.M;
+            x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
+            if (!live) continue;
+            const size_t at = (size_t)m * p.N + n0;
+            const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
+            const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
+            const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0);
+            float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+            if (ksplit > 1) {
+                // every split is read back, this workgroup's own included, and added in split
+                // order: the sum does not depend on which workgroup came last
+                float y[8][4];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+#pragma unroll
+                for (int k = 1; k < 8; ++k)
+                    if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
+            }
+            x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
+            x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
+            x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
+            x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
+            *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            uint32_t h0, h1, l0, l1;
+            split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+            split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+            const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
+            reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
+            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
+            s += (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+        }
+        // mean and sum of squared deviations of each row over this group's columns, fixed order
+        const float cnt = 32.f * (float)min(NT, n_tiles - grp * NT);
+        s += __shfl_xor(s, 32);
+        if (lane < 32) sred[0][wave][lane] = s;
+        __syncthreads();
+        float tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][lane & 31];
+        const float mean = tot / cnt;
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+            if (item < NT * 4 && tile < n_tiles && m < p.M) {
+                const float d0 = x[i][0] - mean, d1 = x[i][1] - mean, d2 = x[i][2] - mean, d3 = x[i][3] - mean;
+                q += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+        }
+        q += __shfl_xor(q, 32);
+        if (lane < 32) sred[1][wave][lane] = q;
+        __syncthreads();
+        if (threadIdx.x < 32) {
+            float m2 = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) m2 += sred[1][ww][lane];
+            const int groups = (n_tiles + NT - 1) / NT;
+            p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(mean, m2);
+        }
+        if (threadIdx.x == 0 && ksplit > 1)  // ready for the next launch
+            __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
     }
     float (*zt)[32][33] = reinterpret_cast<float (*)[32][33]>(&red[0][0][0][0]);  // logits tiles reuse the LDS
     if (MODE == MODE_LMHEAD) __syncthreads();                                      // once every partial is read
@@ -360,17 +538,6 @@ constexpr int TN = 256, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of 
 constexpr int TNB = TN / 32, TMB = TM / 32;   // 32-row operand blocks per tile side
 constexpr int NSTG = 4;                       // ring depth
 constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;  // 32 blocks = 32 KiB per stage
-
-__device__ __forceinline__ void load_block_to_lds(const u32x4* gsrc_lane, u32x4* lds_block) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc_lane,
-                                     (void __attribute__((address_space(3)))*)lds_block, 16, 0, 0);
-}
-
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left at their maxima)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
 
 template <int MODE>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
@@ -639,6 +806,91 @@ __global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, con
         const size_t slot = block_slot(m, k0 & ~7, KB);
         reinterpret_cast<uint2*>(a + slot)[(k0 >> 2) & 1] = make_uint2(h0, h1);
         if (a_lo) reinterpret_cast<uint2*>(a_lo + slot)[(k0 >> 2) & 1] = make_uint2(l0, l1);
+    }
+}
+
+// ----------------------------------------------------------------- LayerNorm folded into the next GEMM (decode rows)
+//
+// For the few rows of a decode step a LayerNorm kernel of its own is all latency.  Instead
+//   W LN(x) + b = rstd * (W (gamma . x) - mean * (W gamma)) + W beta + b,
+// so the kernel that produces x (the embedding below, or the out-projection / FC2 GEMM
+// through its last-arriving workgroup) writes gamma . x as two-term blocks plus per-column-
+// group statistics of x, the consuming GEMM multiplies those blocks by the unchanged bf16
+// weights and applies mean and rstd in its epilogue, and W gamma, W beta are vectors computed
+// once per weight update.
+
+// Row m of a decode step: x = tok_emb[id] + pos_emb[cur_len + pos_offset]; one wavefront per
+// (column group, row), four columns per lane (gw <= 256).
+__global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict__ ids, int id_stride,
+                                                      const bf16_t* __restrict__ tok, const bf16_t* __restrict__ pos,
+                                                      const he_dev_state* __restrict__ st, int V, int pos_offset,
+                                                      int H, int gw, int groups, const bf16_t* __restrict__ gamma,
+                                                      float* __restrict__ r, u32x4* __restrict__ xb,
+                                                      u32x4* __restrict__ xb_lo, float2* __restrict__ stats) {
+    const int g = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
+    int id = ids[(size_t)m * id_stride];
+    id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+    const size_t prow = (size_t)(st->cur_len + pos_offset);
+    const int cols = min(gw, H - g * gw), c0 = g * gw + 4 * lane;
+    const bool live = 4 * lane < cols;
+    float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f;
+    if (live) {
+        const uint2 t = *reinterpret_cast<const uint2*>(tok + (size_t)id * H + c0);
+        const uint2 q = *reinterpret_cast<const uint2*>(pos + prow * H + c0);
+        const uint2 gg = *reinterpret_cast<const uint2*>(gamma + c0);
+        x0 = __uint_as_float(t.x << 16) + __uint_as_float(q.x << 16);
+        x1 = __uint_as_float(t.x & 0xFFFF0000u) + __uint_as_float(q.x & 0xFFFF0000u);
+        x2 = __uint_as_float(t.y << 16) + __uint_as_float(q.y << 16);
+        x3 = __uint_as_float(t.y & 0xFFFF0000u) + __uint_as_float(q.y & 0xFFFF0000u);
+        *reinterpret_cast<float4*>(r + (size_t)m * H + c0) = make_float4(x0, x1, x2, x3);
+        uint32_t h0, h1, l0, l1;
+        split2(x0 * __uint_as_float(gg.x << 16), x1 * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+        split2(x2 * __uint_as_float(gg.y << 16), x3 * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+        const size_t slot = block_slot(m, c0 & ~7, H >> 4);
+        reinterpret_cast<uint2*>(xb + slot)[(c0 >> 2) & 1] = make_uint2(h0, h1);
+        reinterpret_cast<uint2*>(xb_lo + slot)[(c0 >> 2) & 1] = make_uint2(l0, l1);
+    }
+    float s = (x0 + x1) + (x2 + x3);
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mean = s / (float)cols;
+    float q2 = 0.f;
+    if (live) {
+        const float d0 = x0 - mean, d1 = x1 - mean, d2 = x2 - mean, d3 = x3 - mean;
+        q2 = (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+    }
+    for (int o = 32; o > 0; o >>= 1) q2 += __shfl_xor(q2, o);
+    if (lane == 0) stats[((size_t)(m >> 5) * groups + g) * 32 + (m & 31)] = make_float2(mean, q2);
+}
+
+// c1[n] = sum_k W[n][k] gamma[k], c2[n] = sum_k W[n][k] beta[k] from the tiled weights: one
+// wavefront per 32-row tile (lane = row and k half), float accumulation in k order.
+__global__ __launch_bounds__(256) void wvec_kernel(const u32x4* __restrict__ Wp, int KB, int n_tiles,
+                                                   const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta,
+                                                   float* __restrict__ c1, float* __restrict__ c2) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile >= n_tiles) return;
+    const u32x4* w = Wp + (size_t)tile * KB * 64 + lane;
+    float a1 = 0.f, a2 = 0.f;
+    for (int kb = 0; kb < KB; ++kb) {
+        const u32x4 wv = w[(size_t)kb * 64];
+        const int k0 = kb * 16 + (lane >> 5) * 8;
+        const u32x4 gv = *reinterpret_cast<const u32x4*>(gamma + k0), bv = *reinterpret_cast<const u32x4*>(beta + k0);
+        const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w}, gg[4] = {gv.x, gv.y, gv.z, gv.w}, bb[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float w0 = __uint_as_float(ww[j] << 16), w1 = __uint_as_float(ww[j] & 0xFFFF0000u);
+            a1 = fmaf(w0, __uint_as_float(gg[j] << 16), a1);
+            a1 = fmaf(w1, __uint_as_float(gg[j] & 0xFFFF0000u), a1);
+            a2 = fmaf(w0, __uint_as_float(bb[j] << 16), a2);
+            a2 = fmaf(w1, __uint_as_float(bb[j] & 0xFFFF0000u), a2);
+        }
+    }
+    a1 += __shfl_xor(a1, 32);
+    a2 += __shfl_xor(a2, 32);
+    if (lane < 32) {  // rows past the matrix are zero blocks: their entries come out zero
+        c1[tile * 32 + lane] = a1;
+        c2[tile * 32 + lane] = a2;
     }
 }
 
@@ -1108,14 +1360,15 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
     // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
     // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
     constexpr size_t kWant = 84 * 1024;
+    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
-        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
         gemm_skinny_kernel<MODE, NT <= HE_SKINNY_W8_MAXNT ? NT : 1, U, 8><<<grid, 512, pad, s>>>(
             (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
-        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
         gemm_skinny_kernel<MODE, NT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
                                                                   (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
     }
@@ -1194,12 +1447,21 @@ int bf16_gemm_ksplit(int N, int K) {
     return ks;
 }
 
+void bf16_store_shape(int M, int N, int K, int* nt, int* ks) {
+    store_shape(N, K, nt, ks);
+    const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
+    if (m_tiles > 1) *nt = *ks > 1 ? 2 : skinny_nt_fused(n_tiles, m_tiles);  // several row slices: keep the launch balanced
+}
+
 static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
     Epi p{};
     p.M = M; p.N = N; p.bias = (const bf16_t*)a.bias; p.out = a.out; p.out_split = a.out_split;
     p.out_blocks = (u32x4*)a.out_blocks; p.out_blocks_lo = (u32x4*)a.out_blocks_lo; p.kv = (bf16_t*)a.kv; p.st = a.st;
     p.S = a.S; p.layer = a.layer; p.H = a.H; p.n_heads = a.n_heads; p.d = a.n_heads ? a.H / a.n_heads : 0;
     p.max_batch = a.max_batch; p.max_seq = a.max_seq; p.qscale = a.qscale;
+    p.ln_stats = (const float2*)a.ln_stats; p.ln_groups = a.ln_groups; p.ln_gw = a.ln_gw; p.ln_cols = a.ln_cols;
+    p.ln_eps = a.ln_eps; p.c1 = a.c1; p.c2 = a.c2;
+    p.resid = a.resid; p.gamma = (const bf16_t*)a.gamma; p.stats_out = (float2*)a.stats_out; p.counters = a.counters;
     return p;
 }
 
@@ -1208,11 +1470,12 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
     const int nt = skinny_nt_fused(n_tiles, m_tiles);
-    if (mode == EPI_STORE) {
+    if (mode == EPI_STORE || mode == EPI_STORE_LN) {  // ksplit is what bf16_store_shape returns for this shape
         int snt, sks;
-        store_shape(N, K, &snt, &sks);
-        if (sks != ksplit || m_tiles > 1) snt = ksplit > 1 ? 2 : nt;  // caller's split wins; keep it balanced
-        launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
+        bf16_store_shape(M, N, K, &snt, &sks);
+        if (sks != ksplit) snt = ksplit > 1 ? 2 : nt;
+        if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
+        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
     }
     else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
     else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
@@ -1226,10 +1489,26 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
     else launch_tiled<MODE_QKV>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
 }
 
+void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
+                   const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
+                   void* x_blocks, void* x_blocks_lo, float* stats) {
+    const int groups = (H + gw - 1) / gw;
+    embed_ln_kernel<<<dim3(groups, B), 64, 0, s>>>(ids, id_stride, (const bf16_t*)tok, (const bf16_t*)pos, st, V,
+                                                   pos_offset, H, gw, groups, (const bf16_t*)gamma, r,
+                                                   (u32x4*)x_blocks, (u32x4*)x_blocks_lo, (float2*)stats);
+}
+
+void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2) {
+    const int n_tiles = (N + 31) / 32;
+    wvec_kernel<<<(n_tiles + 3) / 4, 256, 0, s>>>((const u32x4*)Wp, K / 16, n_tiles, (const bf16_t*)gamma,
+                                                  (const bf16_t*)beta, c1, c2);
+}
+
 void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
-                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids) {
+                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids, const bf16_gemm_args* fold) {
     Epi p{};
+    if (fold) p = make_epi(B, V, *fold);
     p.M = B; p.N = V; p.st = st; p.logits = logits_opt; p.stats = stats; p.stats_idx = stats_idx;
     p.n_tiles = (V + 31) / 32;
     const int m_tiles = (B + 31) / 32;

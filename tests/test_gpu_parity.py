@@ -222,7 +222,7 @@ def test_timing_hook_counts_launches():
     eng.he_timing_enable(False)
     assert torch.equal(ids0, ids1) and torch.equal(lp0, lp1)
     # 4 decode-shaped passes (last prompt token + 3 steps) x 3 layers
-    assert t["fc1"][1] == 12 and t["qkv"][1] == 12 and t["lm_head"][1] == 4 and t["layernorm"][1] == 4 * 7
+    assert t["fc1"][1] == 12 and t["qkv"][1] == 12 and t["lm_head"][1] == 4 and t["layernorm"][1] == 4  # decode rows: the embedding kernel only, LayerNorms are folded into the GEMMs
     assert all(ms > 0 for ms, n in t.values() if n)
     eng.he_destroy()
 
