@@ -24,7 +24,9 @@ causal exactness; closed forms for degenerate weights; every primitive against
 torch's float64 CPU routine; whole model against an independently written
 OPT implementation (transformers, random init); Philox known-answer vectors;
 Gumbel-max token frequencies against softmax; bfloat16 rounding against
-torch's conversion.  The bf16 tolerance (2e-2) is fixed by the benchmark
+torch's conversion; the scoring pass against that same independent
+implementation's cross-entropy, a uniform-logits closed form, normalisation
+over every possible next token, and the log-probabilities `generate` reports.  The bf16 tolerance (2e-2) is fixed by the benchmark
 definition, not by the paper: parity unpinned for that number only.
 """
 from __future__ import annotations
@@ -145,6 +147,21 @@ def forward_full(w, ids, n_heads, eps=1e-5, pos_offset=0, kv_dtype="f64"):
     for lw in w["layers"]:
         x, _, _ = _layer(x, lw, n_heads, eps, None, None, 0, kv_dtype)
     return lm_logits(w, x, eps)
+
+
+def score(w, ids, n_heads, eps=1e-5, pos_offset=0, kv_dtype="f64"):
+    """Log-probability the model gives each token of ids [B,T] after its prefix:
+    out[b,t] = log_softmax(logits[b,t,:])[ids[b,t+1]], t = 0..T-2 -> [B,T-1].
+
+    This is the pass that follows generation in the inference phase of an RLHF
+    iteration (Section 4: that phase produces the inputs of the training phase;
+    Section 5.3 (I) counts it with the generation phase): the prompt-plus-answer
+    sequence goes once through the model and the log-probabilities of the tokens
+    that are actually there are read off.  No cache, no sampling: the cache-free
+    forward, log-softmax, gather."""
+    ids = np.asarray(ids)
+    lp = log_softmax(forward_full(w, ids, n_heads, eps, pos_offset, kv_dtype))
+    return np.take_along_axis(lp[:, :-1, :], ids[:, 1:, None].astype(np.int64), axis=2)[:, :, 0]
 
 
 class CachedDecoder:

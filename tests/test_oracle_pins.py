@@ -375,3 +375,91 @@ def test_bf16_cache_cached_equals_cache_free_and_differs_from_f64():
     exact = O.forward_full(w, seq[:, :-1], d.n_heads)
     diff = np.abs(full - exact).max()
     assert 1e-5 < diff < 0.1  # the cache format matters, by about bf16's precision
+
+
+# ---------------------------------------------------------------- scoring pass
+
+def _hf_opt(d, w, pos_offset):
+    tr = pytest.importorskip("transformers")
+    cfg = tr.OPTConfig(vocab_size=d.vocab, hidden_size=d.hidden, num_hidden_layers=d.n_layers, ffn_dim=d.ffn,
+                       num_attention_heads=d.n_heads, max_position_embeddings=d.max_positions,
+                       word_embed_proj_dim=d.hidden, do_layer_norm_before=True, activation_function="relu",
+                       dropout=0.0, attention_dropout=0.0, layerdrop=0.0, tie_word_embeddings=True)
+    cfg._attn_implementation = "eager"
+    model = tr.OPTForCausalLM(cfg).double().eval()
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    H = d.hidden
+    sd = {"model.decoder.embed_tokens.weight": t(w["tok_emb"]), "model.decoder.embed_positions.weight": t(w["pos_emb"]),
+          "model.decoder.final_layer_norm.weight": t(w["lnf_g"]), "model.decoder.final_layer_norm.bias": t(w["lnf_b"]),
+          "lm_head.weight": t(w["lm_head"])}
+    for i, lw in enumerate(w["layers"]):
+        p = f"model.decoder.layers.{i}."
+        for j, nm in enumerate(("q_proj", "k_proj", "v_proj")):
+            sd[p + f"self_attn.{nm}.weight"] = t(lw["wqkv"][j * H:(j + 1) * H])
+            sd[p + f"self_attn.{nm}.bias"] = t(lw["bqkv"][j * H:(j + 1) * H])
+        sd[p + "self_attn.out_proj.weight"], sd[p + "self_attn.out_proj.bias"] = t(lw["wo"]), t(lw["bo"])
+        sd[p + "self_attn_layer_norm.weight"], sd[p + "self_attn_layer_norm.bias"] = t(lw["ln1_g"]), t(lw["ln1_b"])
+        sd[p + "fc1.weight"], sd[p + "fc1.bias"] = t(lw["w1"]), t(lw["b1"])
+        sd[p + "fc2.weight"], sd[p + "fc2.bias"] = t(lw["w2"]), t(lw["b2"])
+        sd[p + "final_layer_norm.weight"], sd[p + "final_layer_norm.bias"] = t(lw["ln2_g"]), t(lw["ln2_b"])
+    model.load_state_dict(sd, strict=False)
+    return model
+
+
+def test_score_against_transformers_cross_entropy():
+    # the other implementation's own loss: mean over positions of -log p(next token)
+    d = tiny_dims(n_layers=2, hidden=32, n_heads=4, ffn=64, vocab=50, max_positions=24, pos_offset=2)
+    w = synth.make_weights(d, seed=21, tied=True, std=0.2)
+    model = _hf_opt(d, w, 2)
+    ids = synth.make_prompts(d, seed=4, batch=3, prompt_len=11)
+    got = O.score(w, ids, d.n_heads, eps=1e-5, pos_offset=2)
+    assert got.shape == (3, 10)
+    with torch.no_grad():
+        for b in range(3):
+            row = torch.from_numpy(ids[b:b + 1]).long()
+            loss = model(input_ids=row, labels=row).loss.item()
+            assert abs(-got[b].mean() - loss) < 2e-6
+        # and position by position through torch's cross entropy on that model's logits
+        z = model(input_ids=torch.from_numpy(ids).long()).logits
+        ce = torch.nn.functional.cross_entropy(z[:, :-1].reshape(-1, d.vocab), torch.from_numpy(ids[:, 1:]).long().reshape(-1),
+                                               reduction="none").reshape(3, 10).numpy()
+    np.testing.assert_allclose(got, -ce, atol=2e-6)
+
+
+def test_score_closed_forms_and_normalisation():
+    d = tiny_dims(n_layers=1, vocab=17)
+    w = synth.make_weights(d, seed=22, tied=False, std=0.3)
+    ids = synth.make_prompts(d, seed=5, batch=2, prompt_len=6)
+    # a zero LM head gives uniform logits: every token scores -log V whatever the model does
+    w0 = dict(w)
+    w0["lm_head"] = np.zeros_like(w["lm_head"])
+    np.testing.assert_allclose(O.score(w0, ids, d.n_heads), -math.log(d.vocab), atol=1e-12)
+    # over all possible next tokens at one position the probabilities add up to one, and the
+    # token that is really there gets the value score() reports (causality: earlier positions
+    # do not move when the last token is exchanged)
+    base = O.score(w, ids, d.n_heads)
+    tot = np.zeros(2)
+    for v in range(d.vocab):
+        alt = ids.copy()
+        alt[:, -1] = v
+        s = O.score(w, alt, d.n_heads)
+        assert np.array_equal(s[:, :-1], base[:, :-1])
+        tot += np.exp(s[:, -1])
+    np.testing.assert_allclose(tot, 1.0, atol=1e-12)
+    # shifting a sequence's logits by a constant changes nothing: score is shift-invariant in z
+    z = O.forward_full(w, ids, d.n_heads)
+    lp = O.log_softmax(z + 3.7)
+    np.testing.assert_allclose(np.take_along_axis(lp[:, :-1], ids[:, 1:, None].astype(np.int64), 2)[:, :, 0], base, atol=1e-12)
+
+
+def test_score_reproduces_the_logprobs_generate_reports():
+    # generate() goes through the cached decoder and the sampler; score() through the cache-free
+    # forward: the answer tokens' log-probabilities must agree
+    d = tiny_dims(n_layers=2, hidden=48, n_heads=6, ffn=96, vocab=40)
+    w = synth.make_weights(d, seed=23, tied=True, std=0.25)
+    prompts = synth.make_prompts(d, seed=6, batch=3, prompt_len=5)
+    for mode in ("greedy", "gumbel"):
+        out = O.generate(w, prompts, 6, d.n_heads, mode=mode, seed=9)
+        seq = np.concatenate([prompts, out["ids"]], axis=1)
+        s = O.score(w, seq, d.n_heads)
+        np.testing.assert_allclose(s[:, prompts.shape[1] - 1:], out["logprobs"], atol=1e-10)
