@@ -124,6 +124,7 @@ def main():
     ap.add_argument("--workload", default="opt-13b", help="tiny | opt-1.3b | opt-6.7b | opt-13b | opt-66b")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (a reduced model: not the headline number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-score", action="store_true", help="skip the scoring pass measured after the timed region")
     ap.add_argument("--weights-tiled", action="store_true",
                     help="hand the engine pre-tiled matrices (no second copy); implied by opt-66b")
     ap.add_argument("--timing-steps", type=int, default=24, help="decode steps run with per-kernel HIP events")
@@ -142,6 +143,7 @@ def main():
     if d.dtype != "bf16":
         raise SystemExit("bench.py times the bf16 workloads; the tiny f32 configuration is a parity case")
     B, S, G = d.batch, d.prompt_len, d.gen_len
+    H, F = d.hidden, d.ffn
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()  # default priority; the engine captures its decode step on it
     tiled = args.weights_tiled or d.name == "opt-66b"
@@ -201,6 +203,25 @@ def main():
         s1.record(stream)
         torch.cuda.synchronize()
         fc1_sweep_us = s0.elapsed_time(s1) * 1e3 / (sweep_reps * d.n_layers)
+        # the scoring pass that follows generation: prompt + answer, all positions at once
+        score = None
+        if not args.no_score and S + G <= cfg.max_seq_len and S + G <= d.max_positions:
+            seq = torch.cat([prompts, out_ids], dim=1).contiguous()
+            sc_out = torch.empty(B, S + G - 1, dtype=torch.float32, device="cuda")
+            eng.he_score(seq, sc_out)  # warm
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record(stream)
+            eng.he_score(seq, sc_out)
+            c1.record(stream)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(sc_out).all()) and float(sc_out.max()) <= 0.0, "scores not finite"
+            # the answer's scores are the log-probs generation reported (other kernels, same model)
+            score_dev = float((sc_out[:, S - 1:] - out_lp).abs().max())
+            T = S + G
+            sf = 2 * B * T * d.n_layers * (4 * H * H + 2 * H * F) + d.n_layers * B * 2 * T * T * H + 2 * B * T * d.vocab * H
+            sms = c0.elapsed_time(c1)
+            score = {"ms": sms, "positions": B * T, "TFLOP/s": sf / (sms * 1e-3) / 1e12,
+                     "mfma_frac": sf / (sms * 1e-3) / MFMA_BF16_PEAK, "max_abs_vs_generation_logprobs": score_dev}
         # a plain copy of known size (256 MiB read + 256 MiB written): the reference that
         # rocprofv3's FETCH_SIZE / WRITE_SIZE readings of this same command are scaled by
         cal_src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
@@ -259,6 +280,8 @@ def main():
                     "mfma_frac": pf / (prefill_ms * 1e-3) / MFMA_BF16_PEAK},
         "kernels": kernels,
     }
+    if score is not None:
+        result["score"] = score
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(d)
     eng.he_destroy()

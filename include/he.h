@@ -152,6 +152,18 @@ he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_samplin
 he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
                       int32_t* d_out_ids, float* d_out_logprobs);
 
+/* Scoring pass: the log-probability the model gives every token of a sequence after its prefix
+ * (Section 4: the inference phase of an RLHF iteration produces the inputs of the training phase --
+ * after the answer is generated, prompt plus answer goes through the model once more and the
+ * log-probabilities of the tokens that are there are kept; Section 5.3 (I) counts this with the
+ * generation phase).  d_ids is [B, T] int32 row-major, 1 <= B <= max_batch, 2 <= T <= max_seq_len and
+ * within max_positions.  d_out_logprobs is [B, T-1] float:
+ *   out[b][t] = log_softmax(logits at position t of sequence b)[d_ids[b][t+1]],  t = 0 .. T-2.
+ * All T positions go through the prompt-pass kernels at once; the LM head is fused with the
+ * log-softmax and the gather, so the [B*T, V] logits are never stored.  Uses the KV arena as
+ * scratch: the cache is emptied before and after (as by he_reset). */
+he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_out_logprobs);
+
 /* Empties the KV cache (lengths to zero; memory is kept). */
 he_status he_reset(he_engine* e);
 

@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libhe.so")
 
 HE_OK = 0
+HE_ERR_INVALID_ARG, HE_ERR_SHAPE, HE_ERR_CAPACITY, HE_ERR_OOM, HE_ERR_DEVICE, HE_ERR_STATE = 1, 2, 3, 4, 5, 6
 STATUS_NAMES = {0: "HE_OK", 1: "HE_ERR_INVALID_ARG", 2: "HE_ERR_SHAPE", 3: "HE_ERR_CAPACITY", 4: "HE_ERR_OOM",
                 5: "HE_ERR_DEVICE", 6: "HE_ERR_STATE"}
 HE_F32, HE_BF16 = 0, 1
@@ -73,6 +74,8 @@ def lib() -> C.CDLL:
     L.he_decode_step.argtypes = [vp, ip, C.POINTER(he_sampling), ip, fp, fp]
     L.he_generate.restype = C.c_int
     L.he_generate.argtypes = [vp, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp]
+    L.he_score.restype = C.c_int
+    L.he_score.argtypes = [vp, ip, C.c_int, C.c_int, fp]
     L.he_reset.restype = C.c_int
     L.he_reset.argtypes = [vp]
     L.he_destroy.restype = C.c_int
@@ -102,7 +105,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
-           "he_tile_matrix")
+           "he_tile_matrix", "he_score")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -201,6 +204,14 @@ class Engine:
         self._check(lib().he_generate(self.handle, prompt_ids.data_ptr(), B, S, G, C.byref(samp),
                                       out_ids.data_ptr(), out_lp.data_ptr()))
         return out_ids, out_lp
+
+    def he_score(self, ids, out_lp=None):
+        t = self._torch
+        B, T = ids.shape
+        if out_lp is None:
+            out_lp = t.empty(B, T - 1, dtype=t.float32, device=self.device)
+        self._check(lib().he_score(self.handle, ids.data_ptr(), B, T, out_lp.data_ptr()))
+        return out_lp
 
     def he_reset(self):
         self._check(lib().he_reset(self.handle))

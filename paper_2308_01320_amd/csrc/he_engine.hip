@@ -36,6 +36,7 @@ struct he_engine {
     float *cvec = nullptr;     // per layer W gamma, W beta for wqkv (2 x 3H) and w1 (2 x F), then the LM head's (2 x V), padded to 32
     float *ln_stats = nullptr; // per-column-group mean / squared deviations of the residual rows
     int* ln_counters = nullptr;
+    float *score_stats = nullptr, *score_tgt = nullptr;  // scoring pass: soft-max partials per row and vocabulary slice
 
     // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
     hipGraphExec_t step_graph = nullptr;
@@ -59,7 +60,7 @@ namespace {
 struct Sizes {
     size_t kv, rowsH, rowsF, xf, logits, gen, total;
     // bf16 path
-    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx, cvec, ln_stats, ln_counters;
+    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx, cvec, ln_stats, ln_counters, score_stats;
 };
 
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
@@ -123,7 +124,8 @@ Sizes sizes_of(const he_config& c) {
     s.cvec = ((size_t)c.n_layers * 2 * (3 * H + F) + 2 * vpad) * sizeof(float);
     s.ln_stats = mtiles * (H / 32) * 32 * 2 * sizeof(float) + 1024;  // at most one group per 32 columns
     s.ln_counters = mtiles * (H / 32) * sizeof(int);
-    s.total += s.cvec + s.ln_stats + s.ln_counters;
+    s.score_stats = rows * bf16_score_parts(c.vocab) * 2 * sizeof(float);
+    s.total += s.cvec + s.ln_stats + s.ln_counters + s.score_stats + s.gen;
     s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
                4 * s.ablk + 2 * s.hblk +
                2 * s.xfblk + s.part + s.stats + s.stats_idx;
@@ -180,7 +182,10 @@ struct LaunchTimer {
 // bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  Only the
 // K/V cache is wanted from these rows (the last prompt token takes the decode-shaped pass
 // below), so the final layer stops once its keys and values are stored.
-void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int Sp) {
+// With `full` (the scoring pass) every layer is completed and the last FC2's output is left
+// pending, as k-split partial sums plus *pend_bias, for the final LayerNorm.
+void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int Sp, bool full = false,
+                     const void** pend_bias = nullptr) {
     const he_config& c = e->cfg;
     hipStream_t s = e->stream;
     const int M = B * Sp, H = c.hidden, F = c.ffn;
@@ -198,7 +203,7 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
         bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, M, 3 * H, H, a);
-        if (l == c.n_layers - 1) break;
+        if (l == c.n_layers - 1 && !full) break;
         bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
         a = base; a.out = e->part; a.out_split = split;
         bf16_gemm_tiled(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, M, H, H, a);
@@ -209,6 +214,7 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
         bf16_gemm_tiled(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, M, H, F, a);
         pend = e->part; pend_b = lw.b2;
     }
+    if (pend_bias) *pend_bias = pend_b;
     launch_advance_state(s, e->st, Sp, 0);
     e->cur_len += Sp;
 }
@@ -499,6 +505,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
         A(&e->part, z.part); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
         A(&e->cvec, z.cvec); A(&e->ln_stats, z.ln_stats); A(&e->ln_counters, z.ln_counters);
+        A(&e->score_stats, z.score_stats); A(&e->score_tgt, z.gen);
     }
     A(&e->gen_lp, z.gen); A(&e->gen_ids, z.gen);
     A(&e->cur_ids, cfg->max_batch * sizeof(int32_t));
@@ -618,6 +625,60 @@ he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, i
     }
     launch_copy_out(e->stream, e->gen_ids, e->gen_lp, d_out_ids, d_out_logprobs, B * G);
     return check_hip(e, hipGetLastError(), "he_generate");
+}
+
+he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_out_logprobs) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!d_ids || !d_out_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_score: NULL buffer");
+    if (B < 1 || T < 2) return fail(e, HE_ERR_INVALID_ARG, "he_score: B must be positive and T at least 2");
+    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_score: B exceeds max_batch");
+    if (T > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_score: T exceeds max_seq_len");
+    if (T > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_score: T exceeds max_positions");
+    he_status rc = he_reset(e);
+    if (rc != HE_OK) return rc;
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int M = B * T, H = c.hidden, F = c.ffn, V = c.vocab;
+    if (e->fast) {
+        const void* pend_b = nullptr;
+        pass_tiled_bf16(e, d_ids, T, B, T, true, &pend_b);
+        bf16_ln(s, e->resid, c.n_layers ? e->part : nullptr, 1, (size_t)M * H, pend_b, e->w.lnf_g, e->w.lnf_b, e->ablk,
+                e->ablk_lo, M, H, c.ln_eps, 1, 0, 0);
+        bf16_score_head(s, e->lm_tiled, e->ablk, e->ablk_lo, M, T, V, H, d_ids, e->score_stats, e->score_tgt,
+                        d_out_logprobs);
+    } else {
+        const int bf = e->bf16;
+        const float qscale = 1.0f / sqrtf((float)e->d);
+        plain_embed(s, bf, d_ids, T, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, M, T, H, V, c.pos_offset);
+        const float* pend_y = nullptr;
+        const void* pend_b = nullptr;
+        for (int l = 0; l < c.n_layers; ++l) {
+            const he_layer_weights& lw = e->layers[l];
+            plain_ln(s, bf, e->resid, pend_y, pend_b, lw.ln1_g, lw.ln1_b, e->abuf, M, H, c.ln_eps, 1, 0, 1);
+            plain_gemm(s, bf, e->abuf, lw.wqkv, lw.bqkv, M, 3 * H, H, EPI_QKV, e->qbuf, e->kv, e->st, T, l, H, c.n_heads,
+                       c.max_batch, c.max_seq_len, qscale);
+            plain_attn(s, bf, e->qbuf, e->kv, e->obuf, e->st, M, T, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+            plain_gemm(s, bf, e->obuf, lw.wo, nullptr, M, H, H, EPI_STORE, e->ybuf, nullptr, e->st, T, l, H, c.n_heads,
+                       c.max_batch, c.max_seq_len, 1.f);
+            plain_ln(s, bf, e->resid, e->ybuf, lw.bo, lw.ln2_g, lw.ln2_b, e->abuf, M, H, c.ln_eps, 1, 0, 1);
+            plain_gemm(s, bf, e->abuf, lw.w1, lw.b1, M, F, H, EPI_BIAS_RELU, e->hbuf, nullptr, e->st, T, l, H, c.n_heads,
+                       c.max_batch, c.max_seq_len, 1.f);
+            plain_gemm(s, bf, e->hbuf, lw.w2, nullptr, M, H, F, EPI_STORE, e->ybuf, nullptr, e->st, T, l, H, c.n_heads,
+                       c.max_batch, c.max_seq_len, 1.f);
+            pend_y = e->ybuf;
+            pend_b = lw.b2;
+        }
+        // final LayerNorm of every row into abuf, then the LM head max_batch rows at a time
+        plain_ln(s, bf, e->resid, pend_y, pend_b, e->w.lnf_g, e->w.lnf_b, e->abuf, M, H, c.ln_eps, 1, 0, 0);
+        for (int r0 = 0; r0 < M; r0 += c.max_batch) {
+            const int n = M - r0 < c.max_batch ? M - r0 : c.max_batch;
+            plain_lm_head(s, bf, e->abuf + (size_t)r0 * H, e->w.lm_head, e->logits, n, H, V);
+            plain_score_rows(s, e->logits, d_ids, r0, n, T, V, d_out_logprobs);
+        }
+    }
+    rc = check_hip(e, hipGetLastError(), "he_score");
+    const he_status rc2 = he_reset(e);  // the arena held this sequence's keys and values only as scratch
+    return rc != HE_OK ? rc : rc2;
 }
 
 he_status he_destroy(he_engine* e) {

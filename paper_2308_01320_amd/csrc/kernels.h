@@ -18,6 +18,8 @@ void plain_gemm(hipStream_t s, int bf16, const float* A, const void* W, const vo
 void plain_attn(hipStream_t s, int bf16, const float* q, const void* kv, float* o, const he_dev_state* st, int M, int S,
                 int layer, int H, int n_heads, int max_batch, int max_seq);
 void plain_lm_head(hipStream_t s, int bf16, const float* xf, const void* W, float* logits, int B, int H, int V);
+// rows row0 .. row0+n-1 of the M = B*S positions, given their logits [n][V]: out[b][t] = log_softmax(z)[ids[m+1]]
+void plain_score_rows(hipStream_t s, const float* logits, const int32_t* ids, int row0, int n, int S, int V, float* out);
 
 // ---- shared small kernels
 void launch_sample(hipStream_t s, const float* logits, int B, int V, const he_dev_state* st, int32_t* ids_out,
@@ -72,6 +74,11 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
                   float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids,
                   const bf16_gemm_args* fold = nullptr);
+// LM head over all M = B*S positions fused with log-softmax and the gather of each position's next
+// token: out [B][S-1]; stats [M][bf16_score_parts(V)][2] and tgt [M] are scratch
+int bf16_score_parts(int V);
+void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int M, int S, int V, int K,
+                     const int32_t* ids, float* stats, float* tgt, float* out);
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
              int in_mul, int in_add, int writeback);

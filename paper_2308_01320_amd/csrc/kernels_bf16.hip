@@ -111,9 +111,16 @@ struct Epi {
     const bf16_t* gamma;    // [N] gain of the LayerNorm that follows
     float2* stats_out;      // [m_tiles][groups][32]
     int* counters;          // [groups][m_tiles], zero between launches
+    // SCORE (tiled LM head over every position): row m = b*S + t is scored on the token that
+    // follows it, ids[m + 1]; sc_stats[m][part] = (max z, sum exp(z - max)) over a 128-wide slice
+    // of the vocabulary, sc_tgt[m] = z at that token
+    const int32_t* ids;
+    float2* sc_stats;
+    float* sc_tgt;
+    int sc_parts;
 };
 
-enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3, MODE_STORE_LN = 4 };
+enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3, MODE_STORE_LN = 4, MODE_SCORE = 5 };
 
 // bias words for outputs n0..n0+3 and the cache length, fetched ahead of the epilogue
 template <int MODE>
@@ -638,6 +645,41 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
             cur = nxt;
         }
     }
+    if (MODE == MODE_SCORE) {
+        // The logits never leave the registers: per row, the soft-max partials of this wavefront's
+        // 128 vocabulary entries and, if the row's next token is among them, its logit.
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int m = tm * TM + (wm * 2 + j) * 32 + (lane & 31);
+            int tgt = -1;
+            if (m < p.M && m % p.S != p.S - 1) {
+                tgt = p.ids[m + 1];
+                tgt = tgt < 0 ? 0 : (tgt >= p.N ? p.N - 1 : tgt);  // clamped like the embedding's ids
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = tn * TN + (wn * 4 + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float z = n < p.N ? acc[i][j][r] : -INFINITY;
+                    acc[i][j][r] = z;
+                    mx = fmaxf(mx, z);
+                    if (n == tgt) p.sc_tgt[m] = z;
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            float sum = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sum += expf(acc[i][j][r] - mx);
+            }
+            sum += __shfl_xor(sum, 32);
+            if (lane < 32 && m < p.M) p.sc_stats[(size_t)m * p.sc_parts + tn * 2 + wn] = make_float2(mx, sum);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -649,6 +691,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
                 epilogue4<MODE>(p, m, nb + 8 * q, 0, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
                                 acc[i][j][q * 4 + 3], epilogue_bias<MODE>(p, nb + 8 * q), cur_len);
         }
+}
+
+// One wavefront per scored row: log-sum-exp over the vocabulary slices in slice order, then
+// out[b][t] = z[next token] - lse  (out is [B][S-1]; the last position of a sequence scores nothing).
+__global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restrict__ stats, const float* __restrict__ tgt,
+                                                           int parts, int M, int S, float* __restrict__ out) {
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (m >= M || m % S == S - 1) return;
+    const float2* sp = stats + (size_t)m * parts;
+    float mx = -INFINITY;
+    for (int i = lane; i < parts; i += 64) mx = fmaxf(mx, sp[i].x);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+    for (int i = lane; i < parts; i += 64) {
+        const float2 e = sp[i];
+        if (e.x > -INFINITY) sum += e.y * expf(e.x - mx);
+    }
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) out[(size_t)(m / S) * (S - 1) + m % S] = tgt[m] - (mx + logf(sum));
 }
 
 constexpr size_t kTiledSmem = 0;
@@ -1502,6 +1563,16 @@ void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, c
     const int n_tiles = (N + 31) / 32;
     wvec_kernel<<<(n_tiles + 3) / 4, 256, 0, s>>>((const u32x4*)Wp, K / 16, n_tiles, (const bf16_t*)gamma,
                                                   (const bf16_t*)beta, c1, c2);
+}
+
+int bf16_score_parts(int V) { return 2 * ((V + TN - 1) / TN); }
+
+void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int M, int S, int V, int K,
+                     const int32_t* ids, float* stats, float* tgt, float* out) {
+    Epi p{};
+    p.M = M; p.N = V; p.S = S; p.ids = ids; p.sc_stats = (float2*)stats; p.sc_tgt = tgt; p.sc_parts = bf16_score_parts(V);
+    launch_tiled<MODE_SCORE>(s, Wp, Xhi, Xlo, K / 16, V, M, p);
+    score_reduce_kernel<<<(M + 3) / 4, 256, 0, s>>>((const float2*)stats, tgt, p.sc_parts, M, S, out);
 }
 
 void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,

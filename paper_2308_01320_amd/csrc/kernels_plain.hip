@@ -319,6 +319,42 @@ void plain_lm_head(hipStream_t s, int bf16, const float* xf, const void* W, floa
     else lm_head_kernel<float><<<grid, kThreads, 0, s>>>(xf, (const float*)W, logits, B, H, V);
 }
 
+// one workgroup per row: log-sum-exp of the row's logits, then the next token's log-probability
+__global__ void score_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ ids, int row0, int S,
+                                  int V, float* __restrict__ out) {
+    __shared__ float red[kThreads];
+    const int m = row0 + blockIdx.x;
+    if (m % S == S - 1) return;
+    const float* z = logits + (size_t)blockIdx.x * V;
+    float mx = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += blockDim.x) mx = fmaxf(mx, z[i]);
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    for (int o = blockDim.x / 2; o > 0; o >>= 1) {
+        if (threadIdx.x < o) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + o]);
+        __syncthreads();
+    }
+    mx = red[0];
+    __syncthreads();
+    float sum = 0.f;
+    for (int i = threadIdx.x; i < V; i += blockDim.x) sum += expf(z[i] - mx);
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    for (int o = blockDim.x / 2; o > 0; o >>= 1) {
+        if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        int t = ids[m + 1];
+        t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+        out[(size_t)(m / S) * (S - 1) + m % S] = z[t] - (mx + logf(red[0]));
+    }
+}
+
+void plain_score_rows(hipStream_t s, const float* logits, const int32_t* ids, int row0, int n, int S, int V, float* out) {
+    score_rows_kernel<<<n, kThreads, 0, s>>>(logits, ids, row0, S, V, out);
+}
+
 void launch_sample(hipStream_t s, const float* logits, int B, int V, const he_dev_state* st, int32_t* ids_out,
                    float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids) {
     sample_kernel<<<B, kThreads, 0, s>>>(logits, V, st, ids_out, lp_out, out_stride, out_at_step, cur_ids);
