@@ -241,8 +241,9 @@ def gumbel_noise(seed, b, n, V):
     return -np.log(-np.log(u))
 
 
-def sample(z, mode, temperature, seed, n):
-    """z [B,V] logits of generation step n.  Returns (tok int32 [B],
+def sample(z, mode, temperature, seed, n, rows=None):
+    """z [B,V] logits of generation step n; row i is sequence rows[i] of the
+    batch (default i) -- the noise is keyed by that number.  Returns (tok int32 [B],
     logprob [B], margin [B]): greedy takes argmax z; 'gumbel' takes
     argmax(z/temperature + g).  Ties go to the lowest index.  logprob is the
     untempered log-softmax of z at tok; margin is the gap between the best and
@@ -256,7 +257,7 @@ def sample(z, mode, temperature, seed, n):
         if mode == "greedy":
             score = z[b]
         elif mode == "gumbel":
-            score = z[b] / temperature + gumbel_noise(seed, b, n, V)
+            score = z[b] / temperature + gumbel_noise(seed, b if rows is None else rows[b], n, V)
         else:
             raise ValueError(mode)
         t = int(np.argmax(score))  # first maximum = lowest index
@@ -292,3 +293,48 @@ def generate(w, prompt_ids, G, n_heads, mode="greedy", temperature=1.0, seed=0,
             feed = ids[:, n] if forced_ids is None else np.asarray(forced_ids)[:, n]
             z = dec.step(feed)
     return {"ids": ids, "logprobs": lps, "margins": mar, "logits": np.stack(logits)}
+
+
+def generate_ragged(w, prompts, G, n_heads, mode="greedy", temperature=1.0, seed=0, eos_id=-1, pad_id=0,
+                    eps=1e-5, pos_offset=0, forced_ids=None, kv_dtype="f64"):
+    """Prompts of different lengths and answers that may end early.
+
+    The benchmark setting pads or cuts every prompt to one length and lets every
+    answer run to the cap (Section 5.3 (I): 256 and 256 tokens); real prompts are
+    shorter than the cap and sit right-aligned behind padding, and an answer is
+    over once the end-of-sequence token has been produced.  Padding is not part of
+    a sequence: what the model computes for sequence b is, by definition, what it
+    computes for that sequence's own tokens alone, at positions 0, 1, 2, ...  So
+    each sequence is run by itself here, on its unpadded prompt; only its row
+    number b enters, through the sampling noise.
+
+    prompts: list of B one-dimensional id arrays (length >= 1).  After the step
+    that samples eos_id (eos_id < 0: never) a sequence produces nothing more: its
+    remaining ids are pad_id and their log-probabilities 0.  forced_ids [B,G]
+    feeds those ids forward instead of the sampled ones (the stop still follows
+    the fed id).
+
+    Returns dict(ids [B,G], logprobs [B,G], margins [B,G] (inf where nothing was
+    sampled), lens [B] = tokens produced including the end token, logits = list
+    over b of [lens[b], V])."""
+    B = len(prompts)
+    ids = np.full((B, G), pad_id, np.int32)
+    lps = np.zeros((B, G), F64)
+    mar = np.full((B, G), np.inf, F64)
+    lens = np.zeros(B, np.int32)
+    logits = []
+    for b, prompt in enumerate(prompts):
+        dec = CachedDecoder(w, n_heads, eps, pos_offset, kv_dtype)
+        z = dec.prefill(np.asarray(prompt).reshape(1, -1))
+        zs = []
+        for n in range(G):
+            zs.append(z[0])
+            tok, lp, m = sample(z, mode, temperature, seed, n, rows=[b])
+            ids[b, n], lps[b, n], mar[b, n] = tok[0], lp[0], m[0]
+            lens[b] = n + 1
+            feed = tok[0] if forced_ids is None else int(np.asarray(forced_ids)[b, n])
+            if feed == eos_id or n + 1 == G:
+                break
+            z = dec.step(np.array([feed]))
+        logits.append(np.stack(zs))
+    return {"ids": ids, "logprobs": lps, "margins": mar, "lens": lens, "logits": logits}

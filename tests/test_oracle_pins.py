@@ -463,3 +463,68 @@ def test_score_reproduces_the_logprobs_generate_reports():
         seq = np.concatenate([prompts, out["ids"]], axis=1)
         s = O.score(w, seq, d.n_heads)
         np.testing.assert_allclose(s[:, prompts.shape[1] - 1:], out["logprobs"], atol=1e-10)
+
+
+# ---------------------------------------------------------------- ragged prompts, early stop
+
+def test_ragged_prompts_against_transformers_left_padding():
+    # the other implementation takes a left-padded batch plus an attention mask (positions
+    # counted from the first real token, padded keys masked): its logits at the last position
+    # must be those of each sequence run alone on its own tokens
+    d = tiny_dims(n_layers=2, hidden=32, n_heads=4, ffn=64, vocab=50, max_positions=24, pos_offset=2)
+    w = synth.make_weights(d, seed=31, tied=True, std=0.2)
+    model = _hf_opt(d, w, 2)
+    rng = np.random.default_rng(5)
+    lens = [3, 9, 1, 6]
+    S = max(lens)
+    prompts = [rng.integers(0, d.vocab, n).astype(np.int32) for n in lens]
+    out = O.generate_ragged(w, prompts, 3, d.n_heads, mode="greedy", eps=1e-5, pos_offset=2)
+    batch = np.zeros((len(lens), S + 2), np.int64)
+    mask = np.zeros_like(batch)
+    for b, p in enumerate(prompts):
+        seq = np.concatenate([p, out["ids"][b, :2]])  # prompt and the first two answer tokens
+        batch[b, -len(seq):] = seq
+        mask[b, -len(seq):] = 1
+    # in float32: that implementation builds its mask from the most negative finite number, which
+    # in float64 overflows on padded rows; logits are O(1), a wrong position or mask moves them by 0.1
+    with torch.no_grad():
+        z = model.float()(input_ids=torch.from_numpy(batch), attention_mask=torch.from_numpy(mask)).logits.numpy()
+    for b in range(len(lens)):
+        for n in range(3):  # logits that produced answer token n sit 2 - n places before the end
+            np.testing.assert_allclose(out["logits"][b][n], z[b, S + 1 - (2 - n)], atol=3e-5)
+
+
+def test_ragged_equal_lengths_is_plain_generation_and_end_token_stops():
+    d = tiny_dims(n_layers=2, hidden=48, n_heads=6, ffn=96, vocab=40)
+    w = synth.make_weights(d, seed=32, tied=True, std=0.25)
+    prompts = synth.make_prompts(d, seed=7, batch=4, prompt_len=5)
+    for mode in ("greedy", "gumbel"):
+        plain = O.generate(w, prompts, 6, d.n_heads, mode=mode, seed=3)
+        rag = O.generate_ragged(w, list(prompts), 6, d.n_heads, mode=mode, seed=3)
+        assert np.array_equal(rag["ids"], plain["ids"]) and np.array_equal(rag["lens"], [6] * 4)
+        np.testing.assert_allclose(rag["logprobs"], plain["logprobs"], atol=1e-12)
+        # make the token row 1 produced at step 2 the end token
+        eos = int(plain["ids"][1, 2])
+        rag = O.generate_ragged(w, list(prompts), 6, d.n_heads, mode=mode, seed=3, eos_id=eos, pad_id=39)
+        for b in range(4):
+            hits = np.nonzero(plain["ids"][b] == eos)[0]
+            n = int(hits[0]) + 1 if len(hits) else 6
+            assert rag["lens"][b] == n
+            assert np.array_equal(rag["ids"][b, :n], plain["ids"][b, :n]) and (rag["ids"][b, n:] == 39).all()
+            np.testing.assert_allclose(rag["logprobs"][b, :n], plain["logprobs"][b, :n], atol=1e-12)
+            assert (rag["logprobs"][b, n:] == 0).all()
+        assert rag["lens"][1] <= 3
+
+
+def test_ragged_sequence_does_not_depend_on_its_neighbours():
+    d = tiny_dims(n_layers=1, vocab=30)
+    w = synth.make_weights(d, seed=33, tied=True, std=0.3)
+    rng = np.random.default_rng(6)
+    prompts = [rng.integers(0, d.vocab, n).astype(np.int32) for n in (2, 7, 4)]
+    full = O.generate_ragged(w, prompts, 4, d.n_heads, mode="gumbel", seed=11)
+    # the same sequence in another batch keeps its result only if it keeps its row number
+    # (the noise is keyed by it): put other prompts around row 1
+    other = [prompts[2], prompts[1], prompts[0]]
+    again = O.generate_ragged(w, other, 4, d.n_heads, mode="gumbel", seed=11)
+    assert np.array_equal(full["ids"][1], again["ids"][1])
+    np.testing.assert_array_equal(full["logprobs"][1], again["logprobs"][1])
