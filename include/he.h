@@ -30,8 +30,9 @@
  *  - Every call validates its arguments and returns a status; nothing throws
  *    across the boundary.  After an error the engine is reusable once
  *    he_reset has been called.  An engine is not thread-safe.
- *  - All sequences of a batch have the same prompt length; exactly G tokens
- *    are generated per sequence (no stop token).
+ *  - he_prefill / he_generate: all sequences of a batch have the same prompt
+ *    length and exactly G tokens are generated per sequence (no stop token);
+ *    the _ragged variants lift both restrictions.
  */
 #ifndef HE_H
 #define HE_H
@@ -151,6 +152,31 @@ he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_samplin
  * Requires S + G - 1 <= max_seq_len and within max_positions. */
 he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
                       int32_t* d_out_ids, float* d_out_logprobs);
+
+/* Prompts of different lengths and answers that end early (Section 5.3 (I) pads or cuts every
+ * prompt to one length and lets every answer run to the cap; real prompts are shorter and sit
+ * right-aligned behind padding, and an answer is over once the end-of-sequence token has come).
+ * d_prompt_ids is [B, S] int32 row-major, LEFT-padded: row b's tokens are its last d_prompt_lens[b]
+ * entries (1 <= len <= S; values outside are clamped), whatever stands before them is ignored.
+ * Padding is not part of a sequence: sequence b is computed exactly as if it were run alone on its own
+ * tokens at positions 0, 1, 2, ... (only its row number b enters, through the sampling noise), and its
+ * cache holds len[b] positions after the prompt.  Capacity is checked as for S tokens per sequence.
+ *
+ * he_prefill_ragged is he_prefill for such a batch; he_decode_step then continues every sequence at
+ * its own position.
+ *
+ * he_generate_ragged is he_generate for such a batch with an end token: once a sequence has produced
+ * eos_id (eos_id < 0: never) it produces nothing more -- its remaining d_out_ids are pad_id and their
+ * d_out_logprobs 0 -- and d_out_lens [B] int32 receives the number of tokens each sequence produced,
+ * the end token included.  When every sequence has ended, the remaining steps are skipped (the count
+ * of running sequences is read back every 16 steps, which synchronises cfg.stream).  Rows of a
+ * batch of at most 32 share one matrix-core tile, so ended sequences are not compacted away: their
+ * attention is skipped and their rows ride along in the GEMMs at no cost. */
+he_status he_prefill_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S,
+                            const he_sampling* sampling, int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt);
+he_status he_generate_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S, int G,
+                             const he_sampling* sampling, int eos_id, int pad_id, int32_t* d_out_ids,
+                             float* d_out_logprobs, int32_t* d_out_lens);
 
 /* Scoring pass: the log-probability the model gives every token of a sequence after its prefix
  * (Section 4: the inference phase of an RLHF iteration produces the inputs of the training phase --

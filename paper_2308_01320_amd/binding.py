@@ -74,6 +74,10 @@ def lib() -> C.CDLL:
     L.he_decode_step.argtypes = [vp, ip, C.POINTER(he_sampling), ip, fp, fp]
     L.he_generate.restype = C.c_int
     L.he_generate.argtypes = [vp, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp]
+    L.he_prefill_ragged.restype = C.c_int
+    L.he_prefill_ragged.argtypes = [vp, ip, ip, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp, fp]
+    L.he_generate_ragged.restype = C.c_int
+    L.he_generate_ragged.argtypes = [vp, ip, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), C.c_int, C.c_int, ip, fp, ip]
     L.he_score.restype = C.c_int
     L.he_score.argtypes = [vp, ip, C.c_int, C.c_int, fp]
     L.he_reset.restype = C.c_int
@@ -105,7 +109,8 @@ def lib() -> C.CDLL:
 EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill", "he_decode_step", "he_generate",
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
-           "he_tile_matrix", "he_score")
+           "he_tile_matrix", "he_score", "he_prefill_ragged",
+           "he_generate_ragged")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -183,6 +188,27 @@ class Engine:
         self._check(lib().he_prefill(self.handle, prompt_ids.data_ptr(), B, S, C.byref(samp), ids.data_ptr(),
                                      lp.data_ptr(), _ptr(lg)))
         return ids, lp, lg
+
+    def he_prefill_ragged(self, prompt_ids, prompt_lens, samp: he_sampling, want_logits=False):
+        t = self._torch
+        B, S = prompt_ids.shape
+        ids = t.empty(B, dtype=t.int32, device=self.device)
+        lp = t.empty(B, dtype=t.float32, device=self.device)
+        lg = t.empty(B, self.cfg.vocab, dtype=t.float32, device=self.device) if want_logits else None
+        self._check(lib().he_prefill_ragged(self.handle, prompt_ids.data_ptr(), prompt_lens.data_ptr(), B, S,
+                                            C.byref(samp), ids.data_ptr(), lp.data_ptr(), _ptr(lg)))
+        return ids, lp, lg
+
+    def he_generate_ragged(self, prompt_ids, prompt_lens, G: int, samp: he_sampling, eos_id: int, pad_id: int):
+        t = self._torch
+        B, S = prompt_ids.shape
+        out_ids = t.empty(B, G, dtype=t.int32, device=self.device)
+        out_lp = t.empty(B, G, dtype=t.float32, device=self.device)
+        out_lens = t.empty(B, dtype=t.int32, device=self.device)
+        self._check(lib().he_generate_ragged(self.handle, prompt_ids.data_ptr(), prompt_lens.data_ptr(), B, S, G,
+                                             C.byref(samp), eos_id, pad_id, out_ids.data_ptr(), out_lp.data_ptr(),
+                                             out_lens.data_ptr()))
+        return out_ids, out_lp, out_lens
 
     def he_decode_step(self, in_ids, samp: he_sampling, want_logits=False):
         t = self._torch

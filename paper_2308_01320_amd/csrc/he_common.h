@@ -9,13 +9,32 @@ typedef uint16_t bf16_t;  // raw bfloat16: the upper 16 bits of an IEEE float
 // numbers and sampling parameters from here rather than from launch
 // arguments, so a captured decode step can be replayed unchanged.
 struct he_dev_state {
-    int cur_len;       // positions already in the KV cache, per sequence
+    int cur_len;       // positions already in the KV cache, per sequence (uniform batches)
     int step;          // generation step n of the token about to be sampled
     int mode;          // 0 greedy, 1 Gumbel-max
     float temperature;
     uint32_t seed_lo, seed_hi;
-    int pad[2];
+    int ragged;        // 1: sequences differ in length -- per-sequence numbers live in seq[]
+    int max_batch;
+    int eos_id, pad_id;  // end-of-sequence stop (eos_id < 0: none) and the filler written after it
+    int n_active;      // sequences that have not produced eos_id yet
+    int reserved[5];
+    // [0 .. max_batch): cached positions of sequence b;  [max_batch .. 2 max_batch): left padding of
+    // the rows now going through the model (0 outside a prompt pass);  [2 .. 3 max_batch): 1 once the
+    // sequence has produced eos_id;  [3 .. 4 max_batch): tokens produced so far
+    int seq[1];
 };
+
+__host__ __device__ inline size_t he_dev_state_bytes(int max_batch) {
+    return sizeof(he_dev_state) + (size_t)4 * max_batch * sizeof(int);
+}
+// positions of sequence b already in the cache
+__device__ __forceinline__ int seq_len(const he_dev_state* st, int b) { return st->ragged ? st->seq[b] : st->cur_len; }
+// leading rows of sequence b in this pass that are padding, not tokens
+__device__ __forceinline__ int row_pad(const he_dev_state* st, int b) { return st->ragged ? st->seq[st->max_batch + b] : 0; }
+__device__ __forceinline__ bool seq_done(const he_dev_state* st, int b) {
+    return st->ragged && st->seq[2 * st->max_batch + b] != 0;
+}
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 

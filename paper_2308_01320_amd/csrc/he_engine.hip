@@ -41,6 +41,7 @@ struct he_engine {
     // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
     hipGraphExec_t step_graph = nullptr;
     int graph_B = 0, graph_G = 0;
+    bool graph_ragged = false;
 
     // measurement hook: HIP events around every launch of a kernel class of the decode step
     bool timing = false;
@@ -49,7 +50,9 @@ struct he_engine {
     size_t ev_next = 0;
 
     // host mirror of the device state
-    int cur_len = 0, step = 0, batch = 0;
+    int cur_len = 0, step = 0, batch = 0;  // cur_len: the longest sequence's, when they differ
+    bool ragged_gen = false;   // he_generate_ragged is running: sampling is followed by the end-token bookkeeping
+    int* host_active = nullptr;  // pinned: sequences still generating, read back every few steps
     std::string err;
 };
 
@@ -101,7 +104,7 @@ Sizes sizes_of(const he_config& c) {
     s.xf = (size_t)c.max_batch * c.hidden * sizeof(float);
     s.logits = (size_t)c.max_batch * c.vocab * sizeof(float);
     s.gen = rows * sizeof(float);
-    s.total = s.kv + s.logits + 2 * s.gen + c.max_batch * sizeof(int32_t) + 256;
+    s.total = s.kv + s.logits + 2 * s.gen + c.max_batch * sizeof(int32_t) + he_dev_state_bytes(c.max_batch);
     if (!is_fast(c)) {
         s.total += 5 * s.rowsH + s.rowsF + s.xf;
         return s;
@@ -314,6 +317,7 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
                      ids_out, lp_out, out_stride, out_at_step, e->cur_ids, &a);
     }
     { LaunchTimer t(e, HE_K_EMPTY); }
+    if (e->ragged_gen) launch_ragged_post(s, e->st, ids_out, lp_out, e->cur_ids, out_stride, B);
     launch_advance_state(s, e->st, 1, 1);
     e->cur_len += 1;
     e->step += 1;
@@ -384,6 +388,7 @@ he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t*
     float* logits = d_logits_opt ? d_logits_opt : e->logits;
     plain_lm_head(s, bf, e->xf, e->w.lm_head, logits, B, H, c.vocab);
     launch_sample(s, logits, B, c.vocab, e->st, ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    if (e->ragged_gen) launch_ragged_post(s, e->st, ids_out, lp_out, e->cur_ids, out_stride, B);
     launch_advance_state(s, e->st, S, 1);
     e->cur_len += S;
     e->step += 1;
@@ -394,12 +399,13 @@ void drop_step_graph(he_engine* e) {
     if (e->step_graph) (void)hipGraphExecDestroy(e->step_graph);
     e->step_graph = nullptr;
     e->graph_B = e->graph_G = 0;
+    e->graph_ragged = false;
 }
 
 // Captures one decode step of he_generate (input ids from cur_ids, outputs into the
 // engine's [B, G] generation buffers at the device-side step index).
 he_status ensure_step_graph(he_engine* e, int B, int G) {
-    if (e->step_graph && e->graph_B == B && e->graph_G == G) return HE_OK;
+    if (e->step_graph && e->graph_B == B && e->graph_G == G && e->graph_ragged == e->ragged_gen) return HE_OK;
     drop_step_graph(e);
     const int len = e->cur_len, step = e->step;
     hipError_t r = hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal);
@@ -421,6 +427,7 @@ he_status ensure_step_graph(he_engine* e, int B, int G) {
         return check_hip(e, r, "hipGraphInstantiate");
     }
     e->graph_B = B;
+    e->graph_ragged = e->ragged_gen;
     e->graph_G = G;
     return HE_OK;
 }
@@ -477,7 +484,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     auto A = [&](auto** p, size_t bytes) { if (r == hipSuccess) r = dev_alloc(e, p, bytes); };
     e->fast = is_fast(*cfg);
     A(&e->kv, z.kv);
-    A(&e->st, 256);
+    A(&e->st, he_dev_state_bytes(cfg->max_batch));
     A(&e->resid, z.rowsH); A(&e->qbuf, z.rowsH);
     A(&e->logits, z.logits);
     if (!e->fast) {
@@ -518,7 +525,8 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     }
     // the caller's weights may still be in the making on another stream: wait for the whole device
     r = hipDeviceSynchronize();
-    launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
+    if (r == hipSuccess) r = hipHostMalloc((void**)&e->host_active, sizeof(int), hipHostMallocDefault);
+    launch_init_state(e->stream, e->st, cfg->max_batch);
     if (e->fast) {
         // rows of the last 32-row tile beyond the batch are read by the matrix cores (their
         // products are never stored): give them defined contents once
@@ -557,24 +565,40 @@ he_status he_refresh_weights(he_engine* e) {
 he_status he_reset(he_engine* e) {
     if (!e) return HE_ERR_INVALID_ARG;
     e->cur_len = 0; e->step = 0; e->batch = 0;
+    e->ragged_gen = false;
     launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
     return check_hip(e, hipGetLastError(), "he_reset");
 }
 
-he_status he_prefill(he_engine* e, const int32_t* d_prompt_ids, int B, int S, const he_sampling* sampling,
-                     int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt) {
+static he_status prefill_impl(he_engine* e, const char* who, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens,
+                              bool ragged, int B, int S, const he_sampling* sampling, int32_t* d_next_ids,
+                              float* d_logprobs, float* d_logits_opt) {
     if (!e) return HE_ERR_INVALID_ARG;
-    if (!d_prompt_ids || !d_next_ids || !d_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_prefill: NULL buffer");
+    const std::string w(who);
+    if (!d_prompt_ids || !d_next_ids || !d_logprobs || (ragged && !d_prompt_lens))
+        return fail(e, HE_ERR_INVALID_ARG, w + ": NULL buffer");
     if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
-    if (B < 1 || S < 1) return fail(e, HE_ERR_INVALID_ARG, "he_prefill: B and S must be positive");
-    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_prefill: B exceeds max_batch");
-    if (S > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_prefill: S exceeds max_seq_len");
-    if (S > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_prefill: S exceeds max_positions");
-    if (e->cur_len != 0) return fail(e, HE_ERR_STATE, "he_prefill: cache is not empty (call he_reset)");
+    if (B < 1 || S < 1) return fail(e, HE_ERR_INVALID_ARG, w + ": B and S must be positive");
+    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, w + ": B exceeds max_batch");
+    if (S > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, w + ": S exceeds max_seq_len");
+    if (S > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, w + ": S exceeds max_positions");
+    if (e->cur_len != 0) return fail(e, HE_ERR_STATE, w + ": cache is not empty (call he_reset)");
     e->batch = B;
     e->step = 0;
     launch_set_state(e->stream, e->st, 0, 0, 1, sampling->mode, sampling->temperature, sampling->seed);
+    if (ragged) launch_set_ragged(e->stream, e->st, d_prompt_lens, B, S, -1, 0);
     return run_forward(e, d_prompt_ids, B, S, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
+}
+
+he_status he_prefill(he_engine* e, const int32_t* d_prompt_ids, int B, int S, const he_sampling* sampling,
+                     int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt) {
+    return prefill_impl(e, "he_prefill", d_prompt_ids, nullptr, false, B, S, sampling, d_next_ids, d_logprobs, d_logits_opt);
+}
+
+he_status he_prefill_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S,
+                            const he_sampling* sampling, int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt) {
+    return prefill_impl(e, "he_prefill_ragged", d_prompt_ids, d_prompt_lens, true, B, S, sampling, d_next_ids, d_logprobs,
+                        d_logits_opt);
 }
 
 he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
@@ -589,19 +613,29 @@ he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_samplin
     return run_forward(e, d_in_ids, e->batch, 1, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
 }
 
-he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
-                      int32_t* d_out_ids, float* d_out_logprobs) {
+static he_status generate_impl(he_engine* e, const char* who, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens,
+                               bool ragged, int B, int S, int G, const he_sampling* sampling, int eos_id, int pad_id,
+                               int32_t* d_out_ids, float* d_out_logprobs, int32_t* d_out_lens) {
     if (!e) return HE_ERR_INVALID_ARG;
-    if (!d_prompt_ids || !d_out_ids || !d_out_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_generate: NULL buffer");
+    const std::string w(who);
+    if (!d_prompt_ids || !d_out_ids || !d_out_logprobs || (ragged && (!d_prompt_lens || !d_out_lens)))
+        return fail(e, HE_ERR_INVALID_ARG, w + ": NULL buffer");
     if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
-    if (B < 1 || S < 1 || G < 1) return fail(e, HE_ERR_INVALID_ARG, "he_generate: B, S and G must be positive");
-    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_generate: B exceeds max_batch");
-    if ((long)S + G - 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_generate: S + G - 1 exceeds max_seq_len");
-    if ((long)S + G - 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_generate: S + G - 1 exceeds max_positions");
+    if (B < 1 || S < 1 || G < 1) return fail(e, HE_ERR_INVALID_ARG, w + ": B, S and G must be positive");
+    if (ragged && (pad_id < 0 || pad_id >= e->cfg.vocab || eos_id >= e->cfg.vocab))
+        return fail(e, HE_ERR_INVALID_ARG, w + ": pad_id must be a vocabulary id, eos_id a vocabulary id or negative");
+    if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, w + ": B exceeds max_batch");
+    if ((long)S + G - 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, w + ": S + G - 1 exceeds max_seq_len");
+    if ((long)S + G - 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, w + ": S + G - 1 exceeds max_positions");
     he_status rc = he_reset(e);
     if (rc != HE_OK) return rc;
     e->batch = B;
     launch_set_state(e->stream, e->st, 0, 0, 1, sampling->mode, sampling->temperature, sampling->seed);
+    if (ragged) {
+        launch_set_ragged(e->stream, e->st, d_prompt_lens, B, S, eos_id, pad_id);
+        launch_fill_gen(e->stream, e->gen_ids, e->gen_lp, B * G, e->st);  // steps never run stay filler
+        e->ragged_gen = true;
+    }
     rc = run_forward(e, d_prompt_ids, B, S, e->gen_ids, e->gen_lp, G, 1, nullptr);
     if (rc != HE_OK) return rc;
     // Every later step is the same launch sequence (positions, step number and sampling
@@ -609,22 +643,43 @@ he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, i
     // stream of its own: on the NULL stream, and while per-kernel timing is on, the steps are
     // launched one by one instead -- same kernels, same results.
     const bool use_graph = e->stream != nullptr && !e->timing && G > 2;
-    if (use_graph) {
-        rc = ensure_step_graph(e, B, G);
-        if (rc != HE_OK) return rc;
-        for (int n = 1; n < G; ++n) {
-            const hipError_t r = hipGraphLaunch(e->step_graph, e->stream);
-            if (r != hipSuccess) return check_hip(e, r, "hipGraphLaunch");
+    if (use_graph) rc = ensure_step_graph(e, B, G);
+    // With an end token, the number of sequences still running is read back every kCheck steps
+    // (one small copy and a stream synchronisation): once it is zero the remaining steps are skipped.
+    constexpr int kCheck = 16;
+    for (int n = 1; n < G && rc == HE_OK; ++n) {
+        if (use_graph) {
+            rc = check_hip(e, hipGraphLaunch(e->step_graph, e->stream), "hipGraphLaunch");
             e->cur_len += 1;
             e->step += 1;
-        }
-    } else {
-        for (int n = 1; n < G && rc == HE_OK; ++n)
+        } else {
             rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
-        if (rc != HE_OK) return rc;
+        }
+        if (rc == HE_OK && ragged && eos_id >= 0 && n % kCheck == 0 && n + 1 < G) {
+            hipError_t r = hipMemcpyAsync(e->host_active, &e->st->n_active, sizeof(int), hipMemcpyDeviceToHost, e->stream);
+            if (r == hipSuccess) r = hipStreamSynchronize(e->stream);
+            rc = check_hip(e, r, "reading the active count");
+            if (rc == HE_OK && *e->host_active == 0) break;
+        }
     }
+    if (rc != HE_OK) return rc;
     launch_copy_out(e->stream, e->gen_ids, e->gen_lp, d_out_ids, d_out_logprobs, B * G);
-    return check_hip(e, hipGetLastError(), "he_generate");
+    if (ragged) launch_copy_lens(e->stream, e->st, d_out_lens, B);
+    e->ragged_gen = false;
+    return check_hip(e, hipGetLastError(), who);
+}
+
+he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
+                      int32_t* d_out_ids, float* d_out_logprobs) {
+    return generate_impl(e, "he_generate", d_prompt_ids, nullptr, false, B, S, G, sampling, -1, 0, d_out_ids,
+                         d_out_logprobs, nullptr);
+}
+
+he_status he_generate_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S, int G,
+                             const he_sampling* sampling, int eos_id, int pad_id, int32_t* d_out_ids,
+                             float* d_out_logprobs, int32_t* d_out_lens) {
+    return generate_impl(e, "he_generate_ragged", d_prompt_ids, d_prompt_lens, true, B, S, G, sampling, eos_id, pad_id,
+                         d_out_ids, d_out_logprobs, d_out_lens);
 }
 
 he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_out_logprobs) {
@@ -686,6 +741,7 @@ he_status he_destroy(he_engine* e) {
     (void)hipStreamSynchronize(e->stream);
     drop_step_graph(e);
     for (hipEvent_t ev : e->ev_pool) (void)hipEventDestroy(ev);
+    if (e->host_active) (void)hipHostFree(e->host_active);
     free_all(e);
     delete e;
     return HE_OK;

@@ -27,6 +27,12 @@ void launch_sample(hipStream_t s, const float* logits, int B, int V, const he_de
 void launch_set_state(hipStream_t s, he_dev_state* st, int cur_len, int step, int set_pos, int mode, float temperature,
                       uint64_t seed);
 void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps);
+void launch_init_state(hipStream_t s, he_dev_state* st, int max_batch);
+// sequences of different lengths: B left-padded rows of S entries, lens[b] of them tokens
+void launch_set_ragged(hipStream_t s, he_dev_state* st, const int32_t* lens, int B, int S, int eos_id, int pad_id);
+void launch_ragged_post(hipStream_t s, he_dev_state* st, int32_t* gen_ids, float* gen_lp, int32_t* cur_ids, int G, int B);
+void launch_fill_gen(hipStream_t s, int32_t* ids, float* lp, int count, const he_dev_state* st);
+void launch_copy_lens(hipStream_t s, const he_dev_state* st, int32_t* out, int B);
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out);
 void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count);

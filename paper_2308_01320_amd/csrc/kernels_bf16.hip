@@ -130,7 +130,7 @@ __device__ __forceinline__ uint2 epilogue_bias(const Epi& p, int n0) {
 }
 template <int MODE>
 __device__ __forceinline__ int epilogue_len(const Epi& p) {
-    return MODE == MODE_QKV ? p.st->cur_len : 0;
+    return MODE == MODE_QKV ? (p.st->ragged ? -1 : p.st->cur_len) : 0;  // -1: look the sequence up
 }
 
 // four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0); bb = their bias, cur_len = cached positions
@@ -162,7 +162,13 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
                 make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
         } else {
             const int which = n0 >= 2 * p.H, c = n0 - (which ? 2 * p.H : p.H);
-            const int b = m / p.S, t = cur_len + (m % p.S);
+            const int b = m / p.S;
+            int t = cur_len + (m % p.S);
+            if (cur_len < 0) {  // sequences of different lengths; padding rows append nothing
+                const int tr = m % p.S - row_pad(p.st, b);
+                if (tr < 0) return;
+                t = seq_len(p.st, b) + tr;
+            }
             bf16_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
             *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
         }
@@ -891,7 +897,7 @@ __global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict_
     const int g = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
     int id = ids[(size_t)m * id_stride];
     id = id < 0 ? 0 : (id >= V ? V - 1 : id);
-    const size_t prow = (size_t)(st->cur_len + pos_offset);
+    const size_t prow = (size_t)(seq_len(st, m) + pos_offset);  // one row per sequence here
     const int cols = min(gw, H - g * gw), c0 = g * gw + 4 * lane;
     const bool live = 4 * lane < cols;
     float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f;
@@ -975,9 +981,18 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     __shared__ float red[8];
     __shared__ float ored[4][LPK * 8];
     const int m = blockIdx.x, h = blockIdx.y;
-    const int b = m / S, T = st->cur_len + (m % S) + 1;
+    const int b = m / S, T = seq_len(st, b) + (m % S) - row_pad(st, b) + 1;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane % LPK, grp = lane / LPK;
+    if (seq_done(st, b)) return;  // the sequence has ended: its row's output is not used any more
+    if (T <= 0) {                 // a padding row: nothing to attend to, nothing reads the output; keep it finite
+        if (wave == 0 && grp == 0) {
+            const size_t slot = block_slot(m, h * D + sub * 8, H >> 4);
+            o[slot] = u32x4{0u, 0u, 0u, 0u};
+            if (o_lo) o_lo[slot] = u32x4{0u, 0u, 0u, 0u};
+        }
+        return;
+    }
     const float4 qa = *reinterpret_cast<const float4*>(q + (size_t)m * H + h * D + sub * 8);
     const float4 qb = *reinterpret_cast<const float4*>(q + (size_t)m * H + h * D + sub * 8 + 4);
     const u32x4* Kp = reinterpret_cast<const u32x4*>(kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D));
@@ -1101,7 +1116,7 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
     __shared__ float inv_sum[QB];
     const int t0 = blockIdx.x * QB, h = blockIdx.y, b = blockIdx.z;
     const int nq = min(QB, S - t0);
-    const int cur = st->cur_len;
+    const int cur = seq_len(st, b) - row_pad(st, b);  // cache position of row 0: negative while rows are padding
     const int T = cur + t0 + nq;  // keys any query of the block may see
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane % LPK, grp = lane / LPK;
@@ -1175,7 +1190,7 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
                 }
             }
             if (j < T && (!kPairs || (sub & 1) == 0))
-                sc[qown * max_seq + j] = j <= cur + t0 + qown ? part[0] : -INFINITY;
+                sc[qown * max_seq + j] = j <= max(cur + t0 + qown, 0) ? part[0] : -INFINITY;  // a padding row looks at key 0
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) cur_r[u] = nxt_r[u];
@@ -1194,7 +1209,7 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
             sum += pj;
         }
         for (int o2 = 16; o2 > 0; o2 >>= 1) sum += __shfl_xor(sum, o2);
-        if (l32 == 0) inv_sum[qi] = 1.0f / sum;
+        if (l32 == 0) inv_sum[qi] = sum > 0.f ? 1.0f / sum : 0.f;  // no keys at all: a block of padding rows
     }
     __syncthreads();
     float acc[QB][8] = {};
@@ -1278,11 +1293,11 @@ __global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __re
     const int h = blockIdx.y, b = blockIdx.z;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int j = lane & 31, hh = lane >> 5;
-    const int cur = st->cur_len;
+    const int cur = seq_len(st, b) - row_pad(st, b);  // cache position of row 0: negative while rows are padding
     const int T = cur + S;                          // keys in the cache once this pass is stored
     const int t0 = (blockIdx.x * 4 + wave) * 32;    // this wavefront's first query
     const bool live = t0 < S;
-    const int qpos = cur + t0 + j;                  // last key this lane's query may see
+    const int qpos = max(cur + t0 + j, 0);          // last key this lane's query may see (a padding row looks at key 0)
     const int wg_last = min(T - 1, cur + min(S, (int)(blockIdx.x * 4 + 4) * 32) - 1);
     const int n_tiles = wg_last / 32 + 1;
     const int my_last_tile = live ? min(T - 1, cur + t0 + 31) / 32 : -1;
@@ -1374,7 +1389,8 @@ __global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __re
         }
     }
     if (!live || t0 + j >= S) return;
-    const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // 0: a wavefront of padding rows saw no tile
     const int m = b * S + t0 + j;
 #pragma unroll
     for (int i = 0; i < DB; ++i)

@@ -35,10 +35,14 @@ template <typename ST>
 __global__ void embed_kernel(const int32_t* __restrict__ ids, int id_stride, const ST* __restrict__ tok,
                              const ST* __restrict__ pos, float* __restrict__ x, const he_dev_state* __restrict__ st,
                              int S, int H, int V, int pos_offset) {
-    const int m = blockIdx.x;
-    int id = ids[(size_t)(m / S) * id_stride + (m % S)];
+    const int m = blockIdx.x, b = m / S, t = m % S - row_pad(st, b);
+    if (t < 0) {  // a padding row: not a token, nothing downstream uses it
+        for (int i = threadIdx.x; i < H; i += blockDim.x) x[(size_t)m * H + i] = 0.f;
+        return;
+    }
+    int id = ids[(size_t)b * id_stride + (m % S)];
     id = id < 0 ? 0 : (id >= V ? V - 1 : id);  // out-of-range ids are clamped, never read out of bounds
-    const size_t p = (size_t)(st->cur_len + (m % S) + pos_offset);
+    const size_t p = (size_t)(seq_len(st, b) + t + pos_offset);
     for (int i = threadIdx.x; i < H; i += blockDim.x)
         x[(size_t)m * H + i] = ld_f32(tok, (size_t)id * H + i) + ld_f32(pos, p * H + i);
 }
@@ -123,8 +127,9 @@ __global__ void gemm_kernel(const float* __restrict__ A, const ST* __restrict__ 
                     out[(size_t)m * H + n] = v * qscale;
                 } else {
                     const int which = (n >= 2 * H), c = n - (which ? 2 * H : H);
-                    const int b = m / S, t = st->cur_len + (m % S);
-                    st_val(kv, kv_index(layer, which, b, c / d, t, max_batch, n_heads, max_seq, d) + (c % d), v);
+                    const int b = m / S, tr = m % S - row_pad(st, b);  // padding rows append nothing
+                    if (tr >= 0)
+                        st_val(kv, kv_index(layer, which, b, c / d, seq_len(st, b) + tr, max_batch, n_heads, max_seq, d) + (c % d), v);
                 }
             }
         }
@@ -142,7 +147,11 @@ __global__ void attn_kernel(const float* __restrict__ q, const ST* __restrict__ 
     float* qs = smem;      // [d]
     float* sc = smem + d;  // [max_seq]
     const int m = blockIdx.x, h = blockIdx.y;
-    const int b = m / S, nkeys = st->cur_len + (m % S) + 1;
+    const int b = m / S, nkeys = seq_len(st, b) + (m % S) - row_pad(st, b) + 1;
+    if (nkeys <= 0 || seq_done(st, b)) {  // a padding row, or a sequence that has ended: nothing reads this output
+        for (int e = threadIdx.x; e < d; e += blockDim.x) o[(size_t)m * H + h * d + e] = 0.f;
+        return;
+    }
     const ST* Kp = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, d);
     const ST* Vp = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, d);
     for (int e = threadIdx.x; e < d; e += blockDim.x) qs[e] = q[(size_t)m * H + h * d + e];
@@ -237,13 +246,80 @@ __global__ void sample_kernel(const float* __restrict__ logits, int V, const he_
 
 __global__ void set_state_kernel(he_dev_state* st, int cur_len, int step, int set_pos, int mode, float temperature,
                                  uint32_t seed_lo, uint32_t seed_hi) {
-    if (set_pos) { st->cur_len = cur_len; st->step = step; }
+    if (set_pos) { st->cur_len = cur_len; st->step = step; st->ragged = 0; }
     st->mode = mode; st->temperature = temperature; st->seed_lo = seed_lo; st->seed_hi = seed_hi;
 }
 
+__global__ void init_state_kernel(he_dev_state* st, int max_batch) {
+    for (int i = threadIdx.x; i < 4 * max_batch; i += blockDim.x) st->seq[i] = 0;
+    if (threadIdx.x == 0) {
+        st->cur_len = 0; st->step = 0; st->mode = 0; st->temperature = 1.f; st->seed_lo = st->seed_hi = 0u;
+        st->ragged = 0; st->max_batch = max_batch; st->eos_id = -1; st->pad_id = 0; st->n_active = 0;
+    }
+}
+
+// Start of a ragged batch: B left-padded prompt rows of S entries, lens[b] of them tokens.
+__global__ void set_ragged_kernel(he_dev_state* st, const int32_t* __restrict__ lens, int B, int S, int eos_id,
+                                  int pad_id) {
+    const int mb = st->max_batch;
+    for (int b = threadIdx.x; b < mb; b += blockDim.x) {
+        int n = b < B ? lens[b] : S;
+        n = n < 1 ? 1 : (n > S ? S : n);  // lengths are clamped to what the rows can hold
+        st->seq[b] = 0;
+        st->seq[mb + b] = S - n;
+        st->seq[2 * mb + b] = 0;
+        st->seq[3 * mb + b] = 0;
+    }
+    if (threadIdx.x == 0) { st->ragged = 1; st->eos_id = eos_id; st->pad_id = pad_id; st->n_active = B; }
+}
+
+// End of a pass that fed `tokens` rows per sequence (padding included) and sampled `steps` tokens.
 __global__ void advance_state_kernel(he_dev_state* st, int tokens, int steps) {
-    st->cur_len += tokens;
-    st->step += steps;
+    if (st->ragged) {
+        const int mb = st->max_batch;
+        for (int b = threadIdx.x; b < mb; b += blockDim.x) {
+            if (!st->seq[2 * mb + b]) st->seq[b] += tokens - st->seq[mb + b];
+            st->seq[mb + b] = 0;
+        }
+    }
+    if (threadIdx.x == 0) {
+        st->cur_len += tokens;
+        st->step += steps;
+    }
+}
+
+// he_generate_ragged, after a step's sampling: a sequence that has ended keeps producing the
+// filler (log-probability 0); one that has just produced eos_id ends here.
+__global__ void ragged_post_kernel(he_dev_state* st, int32_t* __restrict__ gen_ids, float* __restrict__ gen_lp,
+                                   int32_t* __restrict__ cur_ids, int G, int B) {
+    __shared__ int active;
+    if (threadIdx.x == 0) active = 0;
+    __syncthreads();
+    const int mb = st->max_batch, n = st->step;
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const size_t at = (size_t)b * G + n;
+        if (st->seq[2 * mb + b]) {
+            gen_ids[at] = st->pad_id;
+            gen_lp[at] = 0.f;
+            cur_ids[b] = st->pad_id;
+        } else {
+            st->seq[3 * mb + b] = n + 1;
+            if (gen_ids[at] == st->eos_id) st->seq[2 * mb + b] = 1;
+            else atomicAdd(&active, 1);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) st->n_active = active;
+}
+
+__global__ void fill_gen_kernel(int32_t* ids, float* lp, int count, const he_dev_state* st) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) { ids[i] = st->pad_id; lp[i] = 0.f; }
+}
+
+__global__ void copy_lens_kernel(const he_dev_state* st, int32_t* out, int B) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) out[b] = st->seq[3 * st->max_batch + b];
 }
 
 __global__ void rng_words_kernel(uint32_t* out, int count, uint32_t v0, uint32_t n, uint32_t b, uint32_t k0,
@@ -366,8 +442,21 @@ void launch_set_state(hipStream_t s, he_dev_state* st, int cur_len, int step, in
                                      (uint32_t)(seed >> 32));
 }
 
+void launch_init_state(hipStream_t s, he_dev_state* st, int max_batch) { init_state_kernel<<<1, 256, 0, s>>>(st, max_batch); }
+void launch_set_ragged(hipStream_t s, he_dev_state* st, const int32_t* lens, int B, int S, int eos_id, int pad_id) {
+    set_ragged_kernel<<<1, 256, 0, s>>>(st, lens, B, S, eos_id, pad_id);
+}
+void launch_ragged_post(hipStream_t s, he_dev_state* st, int32_t* gen_ids, float* gen_lp, int32_t* cur_ids, int G, int B) {
+    ragged_post_kernel<<<1, 256, 0, s>>>(st, gen_ids, gen_lp, cur_ids, G, B);
+}
+void launch_fill_gen(hipStream_t s, int32_t* ids, float* lp, int count, const he_dev_state* st) {
+    fill_gen_kernel<<<(count + 255) / 256, 256, 0, s>>>(ids, lp, count, st);
+}
+void launch_copy_lens(hipStream_t s, const he_dev_state* st, int32_t* out, int B) {
+    copy_lens_kernel<<<(B + 255) / 256, 256, 0, s>>>(st, out, B);
+}
 void launch_advance_state(hipStream_t s, he_dev_state* st, int tokens, int steps) {
-    advance_state_kernel<<<1, 1, 0, s>>>(st, tokens, steps);
+    advance_state_kernel<<<1, 64, 0, s>>>(st, tokens, steps);
 }
 
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out) {
