@@ -86,6 +86,24 @@ def round_bf16(x):
     return r.view(F64)
 
 
+def merge_lora(W, A, B, scale):
+    """Weights with a low-rank adapter folded in, as stored for generation:
+    bf16(W + scale * B A), W [out,in], A [rank,in], B [out,rank] (Section 4: the
+    actor is trained with LoRA and generates with the inference kernels, which
+    see one dense matrix per linear layer).
+
+    The sum decides a bf16 rounding, so it is taken in the precision the engine
+    takes it in, float32, in this order: t = sum over j = 0..rank-1 of B[:,j] A[j,:]
+    (each product exact for bf16 inputs, added one by one), then W + scale * t, each
+    operation rounded to float32; the result is rounded to nearest-even bf16.
+    Returns float64 holding the bf16 values."""
+    W32, A32, B32 = (np.asarray(x, np.float32) for x in (W, A, B))
+    t = np.zeros_like(W32)
+    for j in range(A32.shape[0]):
+        t = t + B32[:, j:j + 1] * A32[j:j + 1, :]
+    return round_bf16((W32 + np.float32(scale) * t).astype(F64))
+
+
 def log_softmax(z):
     m = z.max(axis=-1, keepdims=True)
     return z - (m + np.log(np.exp(z - m).sum(axis=-1, keepdims=True)))

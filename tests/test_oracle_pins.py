@@ -528,3 +528,29 @@ def test_ragged_sequence_does_not_depend_on_its_neighbours():
     again = O.generate_ragged(w, other, 4, d.n_heads, mode="gumbel", seed=11)
     assert np.array_equal(full["ids"][1], again["ids"][1])
     np.testing.assert_array_equal(full["logprobs"][1], again["logprobs"][1])
+
+
+# ---------------------------------------------------------------- low-rank adapters folded into the weights
+
+def test_merge_lora_against_float64_and_the_two_branch_form():
+    rng = np.random.default_rng(9)
+    out_f, in_f, r = 24, 40, 4
+    bf = synth.round_to_bf16
+    W, A, B = bf(rng.normal(0, 0.05, (out_f, in_f))), bf(rng.normal(0, 0.05, (r, in_f))), bf(rng.normal(0, 0.05, (out_f, r)))
+    s = 0.5
+    exact = W.astype(np.float64) + s * (B.astype(np.float64) @ A.astype(np.float64))
+    got = O.merge_lora(W, A, B, s)
+    # a bf16 value within half a bf16 step (at most 2^-8 of the value) plus float32 noise of the exact sum
+    assert np.all(np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-7)
+    np.testing.assert_array_equal(got, O.round_bf16(got))  # bf16-representable
+    # equal to rounding the exact sum wherever that sum is not within float32 noise of a rounding boundary
+    direct = O.round_bf16(exact)
+    assert (got == direct).mean() > 0.99
+    # no adapter, or a zero scale, leaves the weights as they are
+    np.testing.assert_array_equal(O.merge_lora(W, A[:0], B[:, :0], s), W.astype(np.float64))
+    np.testing.assert_array_equal(O.merge_lora(W, A, B, 0.0), W.astype(np.float64))
+    # orientation: x (W + s B A)^T is the dense branch plus the low-rank branch x A^T B^T
+    x = rng.normal(0, 1, (5, in_f))
+    two_branch = O.linear(x, W.astype(np.float64)) + s * O.linear(O.linear(x, A.astype(np.float64)), B.astype(np.float64))
+    np.testing.assert_allclose(O.linear(x, exact), two_branch, atol=1e-12)
+    assert np.abs(O.linear(x, got) - two_branch).max() < 0.02  # and the stored form is that, rounded
