@@ -113,6 +113,11 @@ typedef struct {
  * + 0..7 of row r -- one MFMA 32x32x16 operand per block. */
 size_t he_tiled_bytes(int rows, int cols);
 he_status he_tile_matrix(const void* d_src, void* d_dst, int rows, int cols, void* stream);
+/* The same with a low-rank adapter folded in: d_dst = tiled bf16(src + scale * B A), d_a bf16 [rank, cols],
+ * d_b bf16 [rows, rank], summed as he_refresh_weights_lora states (for callers that keep the tiled
+ * matrices themselves, weights_tiled = 1). */
+he_status he_tile_matrix_lora(const void* d_src, void* d_dst, int rows, int cols, const void* d_a, const void* d_b,
+                              int rank, float scale, void* stream);
 
 /* Bytes of device memory he_create will allocate for cfg (KV arena, workspace,
  * tiled weight copies).  Pure host computation; 0 if cfg is invalid. */
@@ -152,6 +157,29 @@ he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_samplin
  * Requires S + G - 1 <= max_seq_len and within max_positions. */
 he_status he_generate(he_engine* e, const int32_t* d_prompt_ids, int B, int S, int G, const he_sampling* sampling,
                       int32_t* d_out_ids, float* d_out_logprobs);
+
+/* Hand-over from the training phase (Section 4: the Hybrid Engine switches one actor between a
+ * training mode, where memory-saving techniques such as LoRA are in use, and an inference mode that
+ * runs the generation kernels, and reconfigures memory between the two modes).
+ *
+ * he_refresh_weights_lora is he_refresh_weights with low-rank adapters folded in on the way: the
+ * engine's tiled copy of a matrix W [out, in] becomes bf16(W + scale * B A), A bf16 [rank, in] and
+ * B bf16 [out, rank] row-major device pointers (a == b == NULL: no adapter on that matrix).  The sum is
+ * taken in float: the products B[o][j] A[j][i] added one by one for j = 0 .. rank-1, then
+ * W + scale * that, each operation rounded separately, then rounded to nearest-even bf16.  The
+ * caller's W is not written, so a later plain he_refresh_weights undoes the merge.  `adapters` is a
+ * host array of n_layers entries (copied); the factors are read during the call only.  Needs dtype
+ * bf16, impl 0, weights_tiled 0.
+ *
+ * he_release_arena frees the KV arena (the cache is emptied first) so that the training phase can
+ * have the memory; he_acquire_arena allocates it again (HE_ERR_OOM if that fails; the engine then
+ * stays released).  While released, prefill / decode / generate / score return HE_ERR_STATE.  These
+ * two calls are the only ones after he_create that allocate or free device memory. */
+typedef struct { const void* a; const void* b; } he_lora;
+typedef struct { he_lora wqkv, wo, w1, w2; } he_lora_layer;
+he_status he_refresh_weights_lora(he_engine* e, const he_lora_layer* adapters, int rank, float scale);
+he_status he_release_arena(he_engine* e);
+he_status he_acquire_arena(he_engine* e);
 
 /* Prompts of different lengths and answers that end early (Section 5.3 (I) pads or cuts every
  * prompt to one length and lets every answer run to the cap; real prompts are shorter and sit

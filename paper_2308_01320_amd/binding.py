@@ -27,6 +27,14 @@ class he_config(C.Structure):
                 ("stream", C.c_void_p), ("impl", C.c_int), ("weights_tiled", C.c_int)]
 
 
+class he_lora(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("b", C.c_void_p)]
+
+
+class he_lora_layer(C.Structure):
+    _fields_ = [("wqkv", he_lora), ("wo", he_lora), ("w1", he_lora), ("w2", he_lora)]
+
+
 LAYER_FIELDS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 
 
@@ -78,6 +86,12 @@ def lib() -> C.CDLL:
     L.he_prefill_ragged.argtypes = [vp, ip, ip, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp, fp]
     L.he_generate_ragged.restype = C.c_int
     L.he_generate_ragged.argtypes = [vp, ip, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), C.c_int, C.c_int, ip, fp, ip]
+    L.he_refresh_weights_lora.restype = C.c_int
+    L.he_refresh_weights_lora.argtypes = [vp, C.POINTER(he_lora_layer), C.c_int, C.c_float]
+    L.he_release_arena.restype = C.c_int
+    L.he_release_arena.argtypes = [vp]
+    L.he_acquire_arena.restype = C.c_int
+    L.he_acquire_arena.argtypes = [vp]
     L.he_score.restype = C.c_int
     L.he_score.argtypes = [vp, ip, C.c_int, C.c_int, fp]
     L.he_reset.restype = C.c_int
@@ -96,6 +110,8 @@ def lib() -> C.CDLL:
     L.he_tiled_bytes.argtypes = [C.c_int, C.c_int]
     L.he_tile_matrix.restype = C.c_int
     L.he_tile_matrix.argtypes = [vp, vp, C.c_int, C.c_int, vp]
+    L.he_tile_matrix_lora.restype = C.c_int
+    L.he_tile_matrix_lora.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_float, vp]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -110,7 +126,7 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
            "he_tile_matrix", "he_score", "he_prefill_ragged",
-           "he_generate_ragged")
+           "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena", "he_tile_matrix_lora")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -245,6 +261,21 @@ class Engine:
     def he_refresh_weights(self):
         self._check(lib().he_refresh_weights(self.handle))
 
+    def he_refresh_weights_lora(self, adapters, rank: int, scale: float):
+        """adapters: per layer a dict {"wqkv"|"wo"|"w1"|"w2": (A, B)} of bf16 device tensors A [rank,in], B [out,rank]."""
+        arr = (he_lora_layer * len(adapters))()
+        for l, ad in enumerate(adapters):
+            for name, (a, b) in ad.items():
+                getattr(arr[l], name).a = a.data_ptr()
+                getattr(arr[l], name).b = b.data_ptr()
+        self._check(lib().he_refresh_weights_lora(self.handle, arr, rank, scale))
+
+    def he_release_arena(self):
+        self._check(lib().he_release_arena(self.handle))
+
+    def he_acquire_arena(self):
+        self._check(lib().he_acquire_arena(self.handle))
+
     def he_timing_enable(self, on: bool):
         self._check(lib().he_timing_enable(self.handle, 1 if on else 0))
 
@@ -300,6 +331,18 @@ def he_tile_matrix(src, stream=None):
     rc = lib().he_tile_matrix(src.data_ptr(), dst.data_ptr(), rows, cols, stream)
     if rc != HE_OK:
         raise HeError(rc, "he_tile_matrix")
+    return dst
+
+
+def he_tile_matrix_lora(src, a, b, scale, stream=None):
+    """Tiled copy of bf16(src + scale * b @ a): src [rows, cols], a [rank, cols], b [rows, rank], bf16 device tensors."""
+    import torch
+    rows, cols = src.shape
+    dst = torch.empty(lib().he_tiled_bytes(rows, cols), dtype=torch.uint8, device=src.device)
+    rc = lib().he_tile_matrix_lora(src.data_ptr(), dst.data_ptr(), rows, cols, a.data_ptr(), b.data_ptr(), a.shape[0],
+                                   scale, stream)
+    if rc != HE_OK:
+        raise HeError(rc, "he_tile_matrix_lora")
     return dst
 
 

@@ -51,6 +51,11 @@ struct he_engine {
 
     // host mirror of the device state
     int cur_len = 0, step = 0, batch = 0;  // cur_len: the longest sequence's, when they differ
+    std::vector<he_lora_layer> lora;  // adapters folded into the tiled copies by the last refresh (empty: none)
+    int lora_rank = 0;
+    float lora_scale = 0.f;
+    bool arena_released = false;
+    size_t kv_bytes = 0;
     bool ragged_gen = false;   // he_generate_ragged is running: sampling is followed by the end-token bookkeeping
     int* host_active = nullptr;  // pinned: sequences still generating, read back every few steps
     std::string err;
@@ -336,11 +341,18 @@ void tile_weights(he_engine* e) {
     const he_config& c = e->cfg;
     const int H = c.hidden, F = c.ffn;
     if (!c.weights_tiled) {  // else the caller's matrices are used in place
+        auto tile = [&](const void* src, void* dst, int R, int K, const he_lora* ad) {
+            if (ad && ad->a && ad->b && e->lora_rank > 0)
+                bf16_tile_rows_lora(e->stream, src, dst, R, K, ad->a, ad->b, e->lora_rank, e->lora_scale);
+            else
+                bf16_tile_rows(e->stream, src, dst, R, K);
+        };
         for (int l = 0; l < c.n_layers; ++l) {
-            bf16_tile_rows(e->stream, e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H);
-            bf16_tile_rows(e->stream, e->layers[l].wo, e->tiled[l].wo, H, H);
-            bf16_tile_rows(e->stream, e->layers[l].w1, e->tiled[l].w1, F, H);
-            bf16_tile_rows(e->stream, e->layers[l].w2, e->tiled[l].w2, H, F);
+            const he_lora_layer* ad = e->lora.empty() ? nullptr : &e->lora[l];
+            tile(e->layers[l].wqkv, e->tiled[l].wqkv, 3 * H, H, ad ? &ad->wqkv : nullptr);
+            tile(e->layers[l].wo, e->tiled[l].wo, H, H, ad ? &ad->wo : nullptr);
+            tile(e->layers[l].w1, e->tiled[l].w1, F, H, ad ? &ad->w1 : nullptr);
+            tile(e->layers[l].w2, e->tiled[l].w2, H, F, ad ? &ad->w2 : nullptr);
         }
         bf16_tile_rows(e->stream, e->w.lm_head, e->lm_tiled, c.vocab, H);
     }
@@ -484,6 +496,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     auto A = [&](auto** p, size_t bytes) { if (r == hipSuccess) r = dev_alloc(e, p, bytes); };
     e->fast = is_fast(*cfg);
     A(&e->kv, z.kv);
+    e->kv_bytes = z.kv;
     A(&e->st, he_dev_state_bytes(cfg->max_batch));
     A(&e->resid, z.rowsH); A(&e->qbuf, z.rowsH);
     A(&e->logits, z.logits);
@@ -556,10 +569,61 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
 
 he_status he_refresh_weights(he_engine* e) {
     if (!e) return HE_ERR_INVALID_ARG;
+    e->lora.clear();
+    e->lora_rank = 0;
     he_status rc = check_hip(e, hipDeviceSynchronize(), "he_refresh_weights");  // the update may be on any stream
     if (rc != HE_OK) return rc;
     if (e->fast) tile_weights(e);
     return check_hip(e, hipStreamSynchronize(e->stream), "he_refresh_weights");
+}
+
+he_status he_refresh_weights_lora(he_engine* e, const he_lora_layer* adapters, int rank, float scale) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!adapters || rank < 1) return fail(e, HE_ERR_INVALID_ARG, "he_refresh_weights_lora: adapters NULL or rank < 1");
+    if (!e->fast || e->cfg.weights_tiled)
+        return fail(e, HE_ERR_STATE, "he_refresh_weights_lora: needs dtype bf16, impl 0 and engine-owned tiled copies (weights_tiled = 0)");
+    for (int l = 0; l < e->cfg.n_layers; ++l) {
+        const he_lora* ps[] = {&adapters[l].wqkv, &adapters[l].wo, &adapters[l].w1, &adapters[l].w2};
+        for (const he_lora* p : ps)
+            if ((p->a == nullptr) != (p->b == nullptr))
+                return fail(e, HE_ERR_INVALID_ARG, "he_refresh_weights_lora: an adapter needs both factors");
+    }
+    e->lora.assign(adapters, adapters + e->cfg.n_layers);
+    e->lora_rank = rank;
+    e->lora_scale = scale;
+    he_status rc = check_hip(e, hipDeviceSynchronize(), "he_refresh_weights_lora");
+    if (rc != HE_OK) return rc;
+    tile_weights(e);
+    return check_hip(e, hipStreamSynchronize(e->stream), "he_refresh_weights_lora");
+}
+
+he_status he_release_arena(he_engine* e) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (e->arena_released) return HE_OK;
+    he_status rc = he_reset(e);
+    if (rc != HE_OK) return rc;
+    rc = check_hip(e, hipStreamSynchronize(e->stream), "he_release_arena");
+    if (rc != HE_OK) return rc;
+    drop_step_graph(e);  // the captured step holds the arena's address
+    for (auto it = e->allocs.begin(); it != e->allocs.end(); ++it)
+        if (*it == e->kv) { e->allocs.erase(it); break; }
+    rc = check_hip(e, hipFree(e->kv), "he_release_arena");
+    e->kv = nullptr;
+    e->arena_released = true;
+    return rc;
+}
+
+he_status he_acquire_arena(he_engine* e) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!e->arena_released) return HE_OK;
+    const hipError_t r = dev_alloc(e, &e->kv, e->kv_bytes);
+    if (r != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(e, r == hipErrorOutOfMemory ? HE_ERR_OOM : HE_ERR_DEVICE,
+                    std::string("he_acquire_arena: ") + hipGetErrorString(r));
+    }
+    e->arena_released = false;
+    return HE_OK;
 }
 
 he_status he_reset(he_engine* e) {
@@ -582,6 +646,7 @@ static he_status prefill_impl(he_engine* e, const char* who, const int32_t* d_pr
     if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, w + ": B exceeds max_batch");
     if (S > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, w + ": S exceeds max_seq_len");
     if (S > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, w + ": S exceeds max_positions");
+    if (e->arena_released) return fail(e, HE_ERR_STATE, w + ": the KV arena is released (call he_acquire_arena)");
     if (e->cur_len != 0) return fail(e, HE_ERR_STATE, w + ": cache is not empty (call he_reset)");
     e->batch = B;
     e->step = 0;
@@ -627,6 +692,7 @@ static he_status generate_impl(he_engine* e, const char* who, const int32_t* d_p
     if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, w + ": B exceeds max_batch");
     if ((long)S + G - 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, w + ": S + G - 1 exceeds max_seq_len");
     if ((long)S + G - 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, w + ": S + G - 1 exceeds max_positions");
+    if (e->arena_released) return fail(e, HE_ERR_STATE, w + ": the KV arena is released (call he_acquire_arena)");
     he_status rc = he_reset(e);
     if (rc != HE_OK) return rc;
     e->batch = B;
@@ -689,6 +755,7 @@ he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_ou
     if (B > e->cfg.max_batch) return fail(e, HE_ERR_CAPACITY, "he_score: B exceeds max_batch");
     if (T > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_score: T exceeds max_seq_len");
     if (T > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_score: T exceeds max_positions");
+    if (e->arena_released) return fail(e, HE_ERR_STATE, "he_score: the KV arena is released (call he_acquire_arena)");
     he_status rc = he_reset(e);
     if (rc != HE_OK) return rc;
     const he_config& c = e->cfg;
@@ -783,6 +850,14 @@ size_t he_tiled_bytes(int rows, int cols) {
 he_status he_tile_matrix(const void* d_src, void* d_dst, int rows, int cols, void* stream) {
     if (!d_src || !d_dst || d_src == d_dst || rows <= 0 || cols <= 0 || cols % 16) return HE_ERR_INVALID_ARG;
     bf16_tile_rows((hipStream_t)stream, d_src, d_dst, rows, cols);
+    return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
+}
+
+he_status he_tile_matrix_lora(const void* d_src, void* d_dst, int rows, int cols, const void* d_a, const void* d_b,
+                              int rank, float scale, void* stream) {
+    if (!d_src || !d_dst || d_src == d_dst || rows <= 0 || cols <= 0 || cols % 16 || !d_a || !d_b || rank < 1)
+        return HE_ERR_INVALID_ARG;
+    bf16_tile_rows_lora((hipStream_t)stream, d_src, d_dst, rows, cols, d_a, d_b, rank, scale);
     return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
 }
 

@@ -63,6 +63,9 @@ struct bf16_gemm_args {
 };
 size_t bf16_tiled_bytes(int rows, int K);
 void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K);
+// dst = tiled bf16(src + scale * B A): A bf16 [rank, K], B bf16 [R, rank]
+void bf16_tile_rows_lora(hipStream_t s, const void* src, void* dst, int R, int K, const void* A, const void* B, int rank,
+                         float scale);
 int bf16_gemm_ksplit(int N, int K);
 // decode-shaped STORE GEMM of M rows: weight tiles per workgroup (its column group is 32*nt wide) and k-splits
 void bf16_store_shape(int M, int N, int K, int* nt, int* ks);

@@ -79,6 +79,49 @@ __global__ void tile_rows_kernel(const bf16_t* __restrict__ src, u32x4* __restri
     dst[idx] = v;
 }
 
+// The same with a low-rank adapter folded in: dst = tiled bf16(W + scale * B A), A [rank, K], B [R, rank].
+// The sum fixes a bf16 rounding, so its order is part of the definition: products B[r][j] A[j][k]
+// (exact in float for bf16 inputs) are added one by one for j = 0..rank-1, then W + scale * that, every
+// operation a separate float rounding (no fused multiply-add).
+__global__ void tile_rows_lora_kernel(const bf16_t* __restrict__ src, u32x4* __restrict__ dst, int R, int K, size_t total,
+                                      const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, int rank, float scale) {
+#pragma clang fp contract(off)  // scale * t and the addition to W round separately, as stated
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int KB = K >> 4;
+    const int lane = (int)(idx & 63);
+    const int kb = (int)((idx >> 6) % KB);
+    const int rt = (int)((idx >> 6) / KB);
+    const int r = rt * 32 + (lane & 31), k = kb * 16 + (lane >> 5) * 8;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (r < R) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(src + (size_t)r * K + k);
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < rank; ++j) {
+            const float b = bf16_to_f32(B[(size_t)r * rank + j]);
+            const u32x4 a = *reinterpret_cast<const u32x4*>(A + (size_t)j * K + k);
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p0 = b * __uint_as_float(aw[i] << 16), p1 = b * __uint_as_float(aw[i] & 0xFFFF0000u);
+                t[2 * i] = t[2 * i] + p0;
+                t[2 * i + 1] = t[2 * i + 1] + p1;
+            }
+        }
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float s0 = scale * t[2 * i], s1 = scale * t[2 * i + 1];  // plain operators: the pragma above covers them
+            const float lo = __uint_as_float(ww[i] << 16) + s0;
+            const float hi = __uint_as_float(ww[i] & 0xFFFF0000u) + s1;
+            o[i] = pack2(lo, hi);
+        }
+        v = u32x4{o[0], o[1], o[2], o[3]};
+    }
+    dst[idx] = v;
+}
+
 // ----------------------------------------------------------------- epilogues
 
 struct Epi {
@@ -1494,6 +1537,13 @@ size_t bf16_tiled_bytes(int rows, int K) { return (size_t)((rows + 31) / 32) * (
 void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K) {
     const size_t total = (size_t)((R + 31) / 32) * (K / 16) * 64;
     tile_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total);
+}
+
+void bf16_tile_rows_lora(hipStream_t s, const void* src, void* dst, int R, int K, const void* A, const void* B, int rank,
+                         float scale) {
+    const size_t total = (size_t)((R + 31) / 32) * (K / 16) * 64;
+    tile_rows_lora_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total,
+                                                                          (const bf16_t*)A, (const bf16_t*)B, rank, scale);
 }
 
 // Shape of a decode-shaped STORE GEMM: nt tiles per workgroup and ks k-splits such that about one
