@@ -239,7 +239,7 @@ int he_cache_len(const he_engine* e);
  * created on demand while the hook is on (the one place the engine allocates after
  * he_create); results are unaffected. */
 enum {
-    HE_K_LAYERNORM = 0, /* residual update + LayerNorm */
+    HE_K_LAYERNORM = 0, /* decode rows: the embedding kernel (their LayerNorms are folded into the GEMMs) */
     HE_K_QKV = 1,       /* fused QKV projection, K/V appended to the cache */
     HE_K_ATTENTION = 2, /* attention over the cache */
     HE_K_OUT_PROJ = 3,
