@@ -123,6 +123,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="opt-13b", help="tiny | opt-1.3b | opt-6.7b | opt-13b | opt-66b")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (a reduced model: not the headline number)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch (a batch sweep: not the headline number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score", action="store_true", help="skip the scoring pass measured after the timed region")
     ap.add_argument("--weights-tiled", action="store_true",
@@ -140,6 +141,8 @@ def main():
     d = synth.CONFIGS[args.workload]
     if args.layers:
         d = d.sliced(n_layers=args.layers)
+    if args.batch:
+        d = d.sliced(batch=args.batch)
     if d.dtype != "bf16":
         raise SystemExit("bench.py times the bf16 workloads; the tiny f32 configuration is a parity case")
     B, S, G = d.batch, d.prompt_len, d.gen_len

@@ -2,6 +2,7 @@
 // and workspace (allocated once), and the stream-ordered kernel sequence of a
 // prompt pass / decode step of the actor's generation phase (paper Section 4
 // and Section 5.3 (I)).
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -123,7 +124,10 @@ Sizes sizes_of(const he_config& c) {
     // prompt rows, or the decode step's k-split scratch: splits x rows padded to 32, twice (a
     // workgroup of eight wavefronts on a single tile leaves half of its slots unused)
     const size_t drow = (size_t)2 * kMaxKSplit * (((size_t)c.max_batch + 31) / 32 * 32);
-    const size_t prow = rows > drow ? rows : drow;
+    // ... or, for decode steps of more than 32 rows, the k-split partial sums of the widest GEMM
+    const size_t wide = (size_t)(3 * c.hidden > c.ffn ? 3 * c.hidden : c.ffn);
+    const size_t mrow = c.max_batch > 32 ? ((size_t)kMaxKSplit * c.max_batch * wide + c.hidden - 1) / c.hidden : 0;
+    const size_t prow = std::max(std::max(rows, drow), mrow);
     s.part = prow * H * sizeof(float);
     const size_t ntile = (size_t)(c.vocab + 31) / 32;
     s.stats = (size_t)c.max_batch * ntile * 4 * sizeof(float);
@@ -328,10 +332,83 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     e->step += 1;
 }
 
+// The same pass for more than 32 sequences: rows no longer fit one matrix-core tile, so the GEMMs are
+// the prompt-pass tiles (weights shared through LDS by all rows), cut along k until they fill the
+// chip; LayerNorms are kernels of their own again and add the partial sums.
+void pass_decode_wide_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int32_t* ids_out, float* lp_out,
+                           int out_stride, int out_at_step, float* d_logits_opt) {
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int H = c.hidden, F = c.ffn;
+    bf16_gemm_args base;
+    base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
+    base.max_seq = c.max_seq_len;
+    plain_embed(s, 1, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->resid, e->st, B, 1, H, c.vocab, c.pos_offset);
+    const float* pend = nullptr;
+    int pend_ks = 0;
+    const void* pend_b = nullptr;
+    const size_t split = (size_t)B * H;
+    const int ksq = bf16_tiled_ksplit(B, 3 * H, H), kso = bf16_tiled_ksplit(B, H, H);
+    const int ks1 = bf16_tiled_ksplit(B, F, H), ks2 = bf16_tiled_ksplit(B, H, F);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const he_layer_weights& lw = e->layers[l];
+        const he_engine::Tiled& tw = e->tiled[l];
+        {
+            LaunchTimer t(e, HE_K_LAYERNORM);
+            bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        }
+        bf16_gemm_args a = base;
+        a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
+        {
+            LaunchTimer t(e, HE_K_QKV);
+            bf16_gemm_tiled_ksplit(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, ksq, e->part, (size_t)B * 3 * H, a);
+        }
+        {
+            LaunchTimer t(e, HE_K_ATTENTION);
+            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        }
+        a = base;
+        {
+            LaunchTimer t(e, HE_K_OUT_PROJ);
+            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, kso, e->part, split, a);
+        }
+        {
+            LaunchTimer t(e, HE_K_LAYERNORM);
+            bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+        }
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        {
+            LaunchTimer t(e, HE_K_FC1);
+            bf16_gemm_tiled_ksplit(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, ks1, e->part, (size_t)B * F, a);
+        }
+        a = base;
+        {
+            LaunchTimer t(e, HE_K_FC2);
+            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, e->part, split, a);
+        }
+        pend = e->part; pend_ks = ks2; pend_b = lw.b2;
+    }
+    {
+        LaunchTimer t(e, HE_K_LAYERNORM);
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
+    }
+    {
+        LaunchTimer t(e, HE_K_LM_HEAD);
+        bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
+                     ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
+    }
+    { LaunchTimer t(e, HE_K_EMPTY); }
+    if (e->ragged_gen) launch_ragged_post(s, e->st, ids_out, lp_out, e->cur_ids, out_stride, B);
+    launch_advance_state(s, e->st, 1, 1);
+    e->cur_len += 1;
+    e->step += 1;
+}
+
 he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
                            int out_stride, int out_at_step, float* d_logits_opt) {
     if (S > 1) pass_tiled_bf16(e, d_ids, S, B, S - 1);
-    pass_decode_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
+    if (B > 32) pass_decode_wide_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
+    else pass_decode_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
     return check_hip(e, hipGetLastError(), "kernel launch");
 }
 
@@ -876,6 +953,20 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
     for (int r = 0; r < reps; ++r)
         for (int l = 0; l < c.n_layers; ++l) {
             bf16_gemm_args a = base;
+            if (B > 32) {  // the GEMMs of the wide decode step
+                if (kernel_class == HE_K_FC1) {
+                    a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H,
+                                           bf16_tiled_ksplit(B, F, H), e->part, (size_t)B * F, a);
+                } else if (kernel_class == HE_K_FC2) {
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F,
+                                           bf16_tiled_ksplit(B, H, F), e->part, split, a);
+                } else {
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H,
+                                           bf16_tiled_ksplit(B, H, H), e->part, split, a);
+                }
+                continue;
+            }
             if (kernel_class == HE_K_FC1) {
                 a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
                 int nt1, ks1;

@@ -79,6 +79,12 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
 // many rows (prompt pass)
 void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                      const bf16_gemm_args& a);
+// a decode step of more than 32 rows: the same tiles, cut into k ranges so that they fill the chip.  The
+// partial sums go to part [ksplit][M][N]; for EPI_STORE the caller's LayerNorm adds them, for the other
+// modes a second kernel adds them and applies the epilogue.
+int bf16_tiled_ksplit(int M, int N, int K);
+void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                            int ksplit, float* part, size_t part_split, const bf16_gemm_args& a);
 void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
                   float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids,

@@ -598,16 +598,20 @@ constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;  // 32 blocks = 32 KiB pe
 template <int MODE>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
-                                                         int tiles_n, int tiles_m, Epi p) {
+                                                         int tiles_n, int tiles_m, int ksplit, Epi p) {
     // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
     __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
-    // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.
+    // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.  With few
+    // rows (a decode step of a large batch) the tiles alone do not fill the chip: each is then cut
+    // into ksplit k ranges (MODE_STORE only; the partial sums go to separate slots).
     const int nblk = tiles_n * tiles_m;
-    const int per_xcd = (nblk + 7) / 8;
-    const int lin = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (lin >= nblk) return;
+    const int nitem = nblk * ksplit;
+    const int per_xcd = (nitem + 7) / 8;
+    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (item >= nitem) return;
+    const int lin = item / ksplit, ks = item % ksplit;
     const int GROUP = 8;  // m-tiles per super-row
     const int gsize = GROUP * tiles_n;
     const int g = lin / gsize, first_m = g * GROUP;
@@ -629,7 +633,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int xrt = min(tm * TMB + wave, MT32 - 1);
     const u32x4* hsrc = Xhi + (size_t)xrt * KB * 64 + lane;
     const u32x4* lsrc = Xlo + (size_t)xrt * KB * 64 + lane;
-    const int nstage = KB / KSTAGE;  // KB is even (K % 32 == 0)
+    const int nst_all = KB / KSTAGE;  // KB is even (K % 32 == 0)
+    const int st0 = (int)((long)ks * nst_all / ksplit);
+    const int nstage = (int)((long)(ks + 1) * nst_all / ksplit) - st0;  // this workgroup's stages: st0 .. st0+nstage-1
+    {
+        const size_t skip = (size_t)st0 * KSTAGE * 64;
+        wsrc[0] += skip; wsrc[1] += skip; hsrc += skip; lsrc += skip;
+    }
     auto issue = [&](int st) {
         u32x4 (*slot)[64] = ring[st % NSTG];
 #pragma unroll
@@ -737,7 +747,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
             const int nb = tn * TN + (wn * 4 + i) * 32 + 4 * (lane >> 5);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                epilogue4<MODE>(p, m, nb + 8 * q, 0, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
+                epilogue4<MODE>(p, m, nb + 8 * q, ks, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
                                 acc[i][j][q * 4 + 3], epilogue_bias<MODE>(p, nb + 8 * q), cur_len);
         }
 }
@@ -1519,13 +1529,30 @@ int skinny_nt_fused(int n_tiles, int m_tiles) {
 }
 
 template <int MODE>
-void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p) {
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p,
+                  int ksplit = 1) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
     const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
-    const int nblk = tiles_n * tiles_m;
-    const int grid = ((nblk + 7) / 8) * 8;
+    const int nitem = tiles_n * tiles_m * ksplit;
+    const int grid = ((nitem + 7) / 8) * 8;
     gemm_tiled_kernel<MODE><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32, MT32,
-                                                 tiles_n, tiles_m, p);
+                                                 tiles_n, tiles_m, ksplit, p);
+}
+
+// After a k-split MODE_STORE GEMM whose epilogue needs the whole sum: adds the partial sums in split
+// order and applies the epilogue of MODE (bias + ReLU into blocks, or the QKV hand-out).
+template <int MODE>
+__global__ __launch_bounds__(256) void finish_kernel(const float* __restrict__ part, int ksplit, size_t split, Epi p) {
+    const int quads = p.N >> 2;  // N is a multiple of 4 here
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)p.M * quads) return;
+    const int m = (int)(idx / quads), n0 = (int)(idx % quads) * 4;
+    float4 v = *reinterpret_cast<const float4*>(part + (size_t)m * p.N + n0);
+    for (int k = 1; k < ksplit; ++k) {
+        const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * split + (size_t)m * p.N + n0);
+        v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+    }
+    epilogue4<MODE>(p, m, n0, 0, v.x, v.y, v.z, v.w, epilogue_bias<MODE>(p, n0), epilogue_len<MODE>(p));
 }
 
 }  // namespace
@@ -1614,6 +1641,31 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
     if (mode == EPI_STORE) launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
     else if (mode == EPI_BIAS_RELU) launch_tiled<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
     else launch_tiled<MODE_QKV>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+}
+
+int bf16_tiled_ksplit(int M, int N, int K) {
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / KSTAGE;
+    int ks = num_cus() / tiles;
+    if (ks > 8) ks = 8;
+    while (ks > 1 && stages / ks < 2 * NSTG) --ks;  // keep the ring worth filling
+    return ks < 1 ? 1 : ks;
+}
+
+void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                            int ksplit, float* part, size_t part_split, const bf16_gemm_args& a) {
+    if (ksplit == 1 && mode != EPI_STORE) {  // the tiles alone fill the chip: the epilogue runs in the GEMM
+        bf16_gemm_tiled(s, mode, Wp, Xhi, Xlo, M, N, K, a);
+        return;
+    }
+    bf16_gemm_args st = a;
+    st.out = part; st.out_split = part_split;
+    const Epi ps = make_epi(M, N, st);
+    launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, ps, ksplit);
+    if (mode == EPI_STORE) return;  // the consumer (a LayerNorm) adds the partial sums
+    const Epi p = make_epi(M, N, a);
+    const unsigned grid = (unsigned)(((size_t)M * (N / 4) + 255) / 256);
+    if (mode == EPI_BIAS_RELU) finish_kernel<MODE_BIAS_RELU><<<grid, 256, 0, s>>>(part, ksplit, part_split, p);
+    else finish_kernel<MODE_QKV><<<grid, 256, 0, s>>>(part, ksplit, part_split, p);
 }
 
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,

@@ -153,6 +153,7 @@ def test_bf16_shapes(impl, L, H, nh, F, V, B, S, G, tied):
     ("opt-13b", 2, 4, 131, 3),    # prompt rows span several 128-row tiles plus a ragged tail
     ("opt-13b", 1, 32, 9, 3),     # full decode batch of the headline workload
     ("opt-6.7b", 2, 16, 64, 3),
+    ("opt-13b", 1, 96, 5, 3),     # more than 32 sequences: the decode step on k-split prompt-pass tiles
 ])
 def test_bf16_real_layer_shapes(name, L, B, S, G):
     """Layer-truncated models at the real GEMM / head / vocabulary shapes of the benchmark configs."""
