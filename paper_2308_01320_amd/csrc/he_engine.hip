@@ -32,6 +32,7 @@ struct he_engine {
     void *lm_tiled = nullptr, *ablk = nullptr, *oblk = nullptr, *hblk = nullptr, *xfblk = nullptr;
     void *ablk_lo = nullptr, *oblk_lo = nullptr, *hblk_lo = nullptr, *xfblk_lo = nullptr;  // second bf16 term
     float *part = nullptr, *stats = nullptr;
+    size_t part_floats = 0;  // capacity of `part`
     int* stats_idx = nullptr;
     // decode rows: LayerNorms folded into the GEMMs around them
     float *cvec = nullptr;     // per layer W gamma, W beta for wqkv (2 x 3H) and w1 (2 x F), then the LM head's (2 x V), padded to 32
@@ -168,6 +169,8 @@ hipError_t dev_alloc(he_engine* e, T** p, size_t bytes) {
 void free_all(he_engine* e) {
     for (void* p : e->allocs) (void)hipFree(p);
     e->allocs.clear();
+    if (e->host_active) (void)hipHostFree(e->host_active);
+    e->host_active = nullptr;
 }
 
 // Brackets the launches made during its lifetime with a pair of events when timing is on.
@@ -263,17 +266,17 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     // No LayerNorm kernels here: each one is folded into the GEMM after it.  Whoever produces a
     // residual row (the embedding, the out-projection, FC2) leaves gamma * x as two-term blocks
     // and statistics per group of columns; the column groups are the producer's workgroups.
-    int nt1, ks1, nt2, ks2;
-    bf16_store_shape(B, H, H, &nt1, &ks1);
-    bf16_store_shape(B, H, F, &nt2, &ks2);
-    const int gw1 = nt1 * 32, gw2 = L ? nt2 * 32 : 128;  // column-group widths after the out-projection / after FC2 and the embedding
+    int gw1, ks1, gw2, ks2;  // column-group widths after the out-projection / after FC2 and the embedding
+    bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+    bf16_store_plan(B, H, F, e->part_floats, &gw2, &ks2);
+    if (!L) gw2 = 128;
     const size_t split = (size_t)B * H;
     auto fold = [&](bf16_gemm_args& a, int gw, const CVec& cv) {
         a.ln_stats = e->ln_stats; a.ln_gw = gw; a.ln_groups = (H + gw - 1) / gw; a.ln_cols = H; a.ln_eps = c.ln_eps;
         a.c1 = cv.c1; a.c2 = cv.c2;
     };
     auto store_ln = [&](bf16_gemm_args& a, const void* bias, const void* gamma, void* blk, void* blk_lo) {
-        a.out = e->part; a.out_split = split; a.bias = bias; a.resid = e->resid; a.gamma = gamma;
+        a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.bias = bias; a.resid = e->resid; a.gamma = gamma;
         a.out_blocks = blk; a.out_blocks_lo = blk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
     };
     {
@@ -600,7 +603,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         }
         A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
         A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
-        A(&e->part, z.part); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
+        A(&e->part, z.part); e->part_floats = z.part / sizeof(float); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
         A(&e->cvec, z.cvec); A(&e->ln_stats, z.ln_stats); A(&e->ln_counters, z.ln_counters);
         A(&e->score_stats, z.score_stats); A(&e->score_tgt, z.gen);
     }
@@ -616,6 +619,13 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
     // the caller's weights may still be in the making on another stream: wait for the whole device
     r = hipDeviceSynchronize();
     if (r == hipSuccess) r = hipHostMalloc((void**)&e->host_active, sizeof(int), hipHostMallocDefault);
+    if (r != hipSuccess) {
+        g_create_error = std::string("he_create: ") + hipGetErrorString(r);
+        (void)hipGetLastError();
+        free_all(e);
+        delete e;
+        return HE_ERR_DEVICE;
+    }
     launch_init_state(e->stream, e->st, cfg->max_batch);
     if (e->fast) {
         // rows of the last 32-row tile beyond the batch are read by the matrix cores (their
@@ -885,7 +895,6 @@ he_status he_destroy(he_engine* e) {
     (void)hipStreamSynchronize(e->stream);
     drop_step_graph(e);
     for (hipEvent_t ev : e->ev_pool) (void)hipEventDestroy(ev);
-    if (e->host_active) (void)hipHostFree(e->host_active);
     free_all(e);
     delete e;
     return HE_OK;
@@ -969,18 +978,18 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
             }
             if (kernel_class == HE_K_FC1) {
                 a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
-                int nt1, ks1;
-                bf16_store_shape(B, H, H, &nt1, &ks1);
-                a.ln_stats = e->ln_stats; a.ln_gw = nt1 * 32; a.ln_groups = (H + a.ln_gw - 1) / a.ln_gw; a.ln_cols = H;
+                int gw1, ks1;
+                bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+                a.ln_stats = e->ln_stats; a.ln_gw = gw1; a.ln_groups = (H + a.ln_gw - 1) / a.ln_gw; a.ln_cols = H;
                 a.ln_eps = c.ln_eps; a.c1 = cvec_fc1(e, l).c1; a.c2 = cvec_fc1(e, l).c2;
                 bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
             } else {
                 // as in a decode step: the last workgroup of each column group folds the partial sums
                 // into the residual rows and rewrites the blocks and statistics the next GEMM reads
                 const bool fc2 = kernel_class == HE_K_FC2;
-                int nt, ks;
-                bf16_store_shape(B, H, fc2 ? F : H, &nt, &ks);
-                a.out = e->part; a.out_split = split; a.resid = e->resid;
+                int gw, ks;
+                bf16_store_plan(B, H, fc2 ? F : H, e->part_floats, &gw, &ks);
+                a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.resid = e->resid;
                 a.bias = fc2 ? e->layers[l].b2 : e->layers[l].bo;
                 a.gamma = fc2 ? e->layers[l].ln1_g : e->layers[l].ln2_g;
                 a.out_blocks = e->ablk; a.out_blocks_lo = e->ablk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;

@@ -42,6 +42,7 @@ struct bf16_gemm_args {
     const void* bias = nullptr;      // bf16 [N]
     float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
     size_t out_split = 0;            // elements between k-splits
+    size_t out_capacity = 0;         // EPI_STORE_LN: floats `out` can hold (0 = not checked)
     void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled bf16 output (hi term)
     void* out_blocks_lo = nullptr;   // EPI_BIAS_RELU: lo term
     void* kv = nullptr;              // EPI_QKV
@@ -69,6 +70,9 @@ void bf16_tile_rows_lora(hipStream_t s, const void* src, void* dst, int R, int K
 int bf16_gemm_ksplit(int N, int K);
 // decode-shaped STORE GEMM of M rows: weight tiles per workgroup (its column group is 32*nt wide) and k-splits
 void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
+// EPI_STORE_LN GEMM of M <= 32 rows: columns per workgroup (= per group of LayerNorm statistics) and k-splits;
+// capacity = floats of k-split scratch available (the value passed as bf16_gemm_args.out_capacity)
+void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks);
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
                    void* x_blocks, void* x_blocks_lo, float* stats);

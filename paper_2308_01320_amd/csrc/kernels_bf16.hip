@@ -532,6 +532,302 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     }
 }
 
+// ----------------------------------------------------------------- skinny GEMM on 16-row units
+//
+// The kernel above hands out weight rows in units of 32, so a launch can only be balanced over
+// the CUs when the number of 32-row tiles happens to divide well: 640 tiles (FC1 of the 13B
+// shape) give 214 workgroups of three, and 42 CUs idle.  This variant hands out units of 16 rows
+// -- 1280 of them are five per CU on all 256 -- using the 16x16x32 matrix instruction: its A
+// operand is 16 rows x 32 k, i.e. one half (rows 0-15 or 16-31) of two consecutive 32x16 blocks,
+// which a wavefront gathers from the unchanged tiled layout as four 256-byte runs (lane l: k-block
+// l/32, k half (l/16)%2, row l%16).  The activations are gathered the same way, 16 of the 32 rows
+// per instruction.  Lane l ends up with D[n = 16 g + 4 (l/16) + 0..3][m = 16 mh + l%16]: four
+// consecutive outputs of one row, as the epilogues want them.  Everything else -- k split over the
+// wavefronts, double-buffered loads, reduction through LDS, folded LayerNorm, last-arriving
+// workgroup for the k-split modes -- is as above.
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16_bf16(const u32x4& a, const u32x4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+template <int HT, int U>
+struct HalfRegs {
+    u32x4 w[HT][U], xh[2][U], xl[2][U];
+};
+
+template <int HT, int U>
+__device__ __forceinline__ void half_load(HalfRegs<HT, U>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < HT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * 128);
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            r.xh[mh][u] = xh[u * 128 + mh * 16];
+            r.xl[mh][u] = xl[u * 128 + mh * 16];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < HT; ++t) w[t] += U * 128;
+    xh += U * 128;
+    xl += U * 128;
+}
+
+template <int HT, int U>
+__device__ __forceinline__ void half_mma(const HalfRegs<HT, U>& r, f32x4 (&acc)[HT][2]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < HT; ++t)
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+#pragma unroll
+        for (int t = 0; t < HT; ++t)
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+    }
+}
+
+// n_half = number of 16-row units of the weight matrix (N / 16); a workgroup owns HT of them.
+template <int MODE, int HT, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+                                                               const u32x4* __restrict__ Xlo, int KB, int n_half,
+                                                               int ksplit, Epi p) {
+    constexpr int NI = HT * 2;  // (unit, row half) items of a workgroup
+    __shared__ float red[WAVES][NI][4][64];
+    extern __shared__ float dyn_lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
+    const int mt = blockIdx.y;
+    const int KP = KB >> 1;  // pairs of k-blocks (32 values of k)
+    const int parts = ksplit * WAVES, part = ks * WAVES + wave;
+    const int kp0 = (int)(((long)part * KP) / parts), kp1 = (int)(((long)(part + 1) * KP) / parts);
+    constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV;
+    const bool fold = FOLDABLE && p.ln_stats != nullptr;
+    if (fold) {
+        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
+        for (int c = wave; c < chunks; c += WAVES)
+            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
+    }
+    // this lane's 16 bytes inside a pair of 32x16 blocks: k-block lane/32, slot 32*(k half) + row
+    const int in_pair = (lane >> 5) * 64 + 32 * ((lane >> 4) & 1) + (lane & 15);
+    const u32x4* w[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {  // units past the last one are computed from the last one, never stored
+        const int g = min(grp * HT + t, n_half - 1);
+        w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
+    }
+    const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * kp0) * 64 + in_pair;
+    const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * kp0) * 64 + in_pair;
+    constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/2, row half item%2
+    uint2 bias_w[ITEMS];
+    float4 c1w[ITEMS], c2w[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+        const int n0 = g * 16 + 4 * (lane >> 4);
+        const bool live = item < NI && g < n_half;
+        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+        c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (FOLDABLE && fold && live) {
+            c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+            c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+        }
+    }
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x4 acc[HT][2];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int n = kp1 - kp0;
+    if (n >= U) {
+        HalfRegs<HT, U> ra;
+        half_load<HT, U>(ra, w, xh, xl);
+        n -= U;
+        while (n >= U) {
+            HalfRegs<HT, U> rb;
+            half_load<HT, U>(rb, w, xh, xl);
+            n -= U;
+            half_mma<HT, U>(ra, acc);
+            ra = rb;
+        }
+        half_mma<HT, U>(ra, acc);
+    }
+    for (; n > 0; --n) {
+        HalfRegs<HT, 1> r1;
+        half_load<HT, 1>(r1, w, xh, xl);
+        half_mma<HT, 1>(r1, acc);
+    }
+#pragma unroll
+    for (int t = 0; t < HT; ++t)
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[wave][t * 2 + mh][r][lane] = acc[t][mh][r];
+    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
+    __syncthreads();
+    float v[ITEMS][4];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float sum = 0.f;
+            if (item < NI) {
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ww += 2) sum += red[ww][item][r][lane] + red[ww + 1][item][r][lane];
+            }
+            v[i][r] = sum;
+        }
+    }
+    if (fold) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES;
+            const float2* gs = reinterpret_cast<const float2*>(dyn_lds) + 16 * (item & 1) + (lane & 15);
+            const float pivot = gs[0].x;
+            float s1 = 0.f, s2 = 0.f, sm = 0.f;
+            for (int g = 0; g < p.ln_groups; ++g) {
+                const float2 e = gs[g * 32];
+                const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
+                s1 += cnt * dlt;
+                s2 += cnt * dlt * dlt;
+                sm += e.y;
+            }
+            const float inv = 1.0f / (float)p.ln_cols;
+            const float mean = pivot + s1 * inv;
+            const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
+            const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+            v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
+            v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
+            v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
+            v[i][3] = rstd * (v[i][3] - mean * c1w[i].w) + c2w[i].w;
+        }
+    }
+    if (MODE == MODE_STORE_LN) {
+        __shared__ int s_last;
+        __shared__ float sred[2][WAVES][32];
+        const size_t cell = (size_t)grp * gridDim.y + mt;
+        constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;
+        float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
+        if (ksplit > 1) {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+                const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
+                if (item < NI && g < n_half && m < p.M) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (threadIdx.x == 0)
+                s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                         ksplit - 1;
+            __syncthreads();
+            if (!s_last) return;
+        }
+        float x[ITEMS][4];
+        float srow[2] = {0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+            const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
+            const int n0 = g * 16 + 4 * (lane >> 4);
+            const bool live = item < NI && g < n_half && m < p.M;
+            x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
+            if (!live) continue;
+            const size_t at = (size_t)m * p.N + n0;
+            const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
+            const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
+            const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0);
+            float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+            if (ksplit > 1) {
+                float y[8][4];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+#pragma unroll
+                for (int k = 1; k < 8; ++k)
+                    if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
+            }
+            x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
+            x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
+            x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
+            x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
+            *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            uint32_t h0, h1, l0, l1;
+            split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+            split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+            const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
+            reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
+            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
+            srow[item & 1] += (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+        }
+        // per row (16 mh + lane%16) over this group's columns: the four lane groups hold different columns
+        const float cnt = 16.f * (float)min(HT, n_half - grp * HT);
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            srow[mh] += __shfl_xor(srow[mh], 16);
+            srow[mh] += __shfl_xor(srow[mh], 32);
+            if (lane < 16) sred[0][wave][16 * mh + lane] = srow[mh];
+        }
+        __syncthreads();
+        float mean[2], q[2] = {0.f, 0.f};
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            float tot = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][16 * mh + (lane & 15)];
+            mean[mh] = tot / cnt;
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+            const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
+            if (item < NI && g < n_half && m < p.M) {
+                const float mu = mean[item & 1];
+                const float d0 = x[i][0] - mu, d1 = x[i][1] - mu, d2 = x[i][2] - mu, d3 = x[i][3] - mu;
+                q[item & 1] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+        }
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            q[mh] += __shfl_xor(q[mh], 16);
+            q[mh] += __shfl_xor(q[mh], 32);
+            if (lane < 16) sred[1][wave][16 * mh + lane] = q[mh];
+        }
+        __syncthreads();
+        if (threadIdx.x < 32) {
+            float m2 = 0.f, tot = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) { m2 += sred[1][ww][lane]; tot += sred[0][ww][lane]; }
+            const int groups = (n_half + HT - 1) / HT;
+            p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(tot / cnt, m2);
+        }
+        if (threadIdx.x == 0 && ksplit > 1)
+            __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+        if (item >= NI || g >= n_half) continue;
+        epilogue4<MODE>(p, mt * 32 + 16 * (item & 1) + (lane & 15), g * 16 + 4 * (lane >> 4), ks, v[i][0], v[i][1], v[i][2],
+                        v[i][3], bias_w[i], cur_len);
+    }
+}
+
 // One block per sequence: combines the LM-head tile partials in tile order
 // (deterministic), writes token id and its untempered log-probability.
 __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __restrict__ stats_idx, int n_tiles,
@@ -1504,6 +1800,45 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
     }
 }
 
+template <int MODE, int HT>
+void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles,
+                    int ksplit, const Epi& p) {
+    constexpr int U = HT <= 3 ? 4 : 2;
+    dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
+    const bool eight = HT <= 4 && (KB / 2) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
+    constexpr size_t kWant = 84 * 1024;                              // one workgroup per CU
+    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
+    if (eight) {
+        constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8><<<grid, 512, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
+                                                                              (const u32x4*)Xlo, KB, n_half, ksplit, p);
+    } else {
+        constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_half_kernel<MODE, HT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
+                                                                n_half, ksplit, p);
+    }
+}
+
+constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the half-tile kernel is built for
+
+template <int MODE>
+void launch_half(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles, int ht,
+                 int ksplit, const Epi& p) {
+    switch (ht) {
+        case 2: launch_half_ht<MODE, 2>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 3: launch_half_ht<MODE, 3>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 4: launch_half_ht<MODE, 4>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 5: launch_half_ht<MODE, 5>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 6: launch_half_ht<MODE, 6>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 7: launch_half_ht<MODE, 7>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 8: launch_half_ht<MODE, 8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 9: launch_half_ht<MODE, 9>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        default: launch_half_ht<MODE, 10>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+    }
+}
+
 // nt weight tiles per workgroup (1..8)
 template <int MODE>
 void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles, int m_tiles,
@@ -1607,6 +1942,50 @@ void bf16_store_shape(int M, int N, int K, int* nt, int* ks) {
     if (m_tiles > 1) *nt = *ks > 1 ? 2 : skinny_nt_fused(n_tiles, m_tiles);  // several row slices: keep the launch balanced
 }
 
+// How a decode-shaped GEMM is cut up: weight rows in units of 32 (the skinny kernel) or 16 (the
+// half-tile kernel), `per_wg` units per workgroup, ks k-splits.  The launch waits for its most
+// loaded workgroup, so the plan with the fewest weight bytes per workgroup wins, as long as all of
+// its workgroups fit on the chip at once and every wavefront keeps at least 8 k-blocks.
+struct GemmPlan { bool half; int per_wg, ks; };
+
+static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no k-split
+    const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32, cus = num_cus();
+    GemmPlan g{false, skinny_nt_fused(n_tiles, m_tiles), 1};
+    if (m_tiles > 1 || N % 16) return g;
+    const int n_half = N / 16, ht = (n_half + cus - 1) / cus;
+    if (ht >= kHalfMin && ht <= kHalfMax && 16 * ht < 32 * g.per_wg) g = GemmPlan{true, ht, 1};
+    return g;
+}
+
+// capacity: floats the k-split scratch can hold (0 = not checked)
+static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
+    GemmPlan g{false, 0, 0};
+    bf16_store_shape(M, N, K, &g.per_wg, &g.ks);
+    if ((M + 31) / 32 > 1 || N % 16) return g;
+    const int n_half = N / 16, kb = K / 16, cus = num_cus();
+    double best = (double)g.per_wg * 32 / g.ks;  // rows x (k share) per workgroup
+    for (int ht = kHalfMax; ht >= kHalfMin; --ht) {
+        const int groups = (n_half + ht - 1) / ht;
+        int ks = cus / groups;
+        if (ks < 1) continue;
+        if (ks > 8) ks = 8;
+        while (ks > 1 && kb / (ks * 4) < 8) --ks;
+        // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
+        if (capacity && (size_t)groups * ks * (size_t)(2 * ht + 7) * 256 > capacity) continue;
+        const double load = (double)ht * 16 / ks;
+        // fewer, longer k ranges per wavefront cost a 16-row plan some of its balance back (measured on the
+        // 5120x5120 and 5120x20480 shapes: 6 % less load per workgroup ran no faster), so it has to win clearly
+        if (load < best * 0.9) { best = load; g = GemmPlan{true, ht, ks}; }
+    }
+    return g;
+}
+
+void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks) {
+    const GemmPlan g = plan_store(M, N, K, capacity);
+    *group_cols = g.per_wg * (g.half ? 16 : 32);
+    *ks = g.ks;
+}
+
 static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
     Epi p{};
     p.M = M; p.N = N; p.bias = (const bf16_t*)a.bias; p.out = a.out; p.out_split = a.out_split;
@@ -1624,15 +2003,27 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
     const int nt = skinny_nt_fused(n_tiles, m_tiles);
-    if (mode == EPI_STORE || mode == EPI_STORE_LN) {  // ksplit is what bf16_store_shape returns for this shape
+    if (mode == EPI_STORE_LN) {  // ksplit is what bf16_store_plan returns for this shape
+        const GemmPlan g = plan_store(M, N, K, a.out_capacity);
+        if (g.half) launch_half<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
+        return;
+    }
+    if (mode == EPI_STORE) {  // ksplit is what bf16_store_shape returns for this shape
         int snt, sks;
         bf16_store_shape(M, N, K, &snt, &sks);
         if (sks != ksplit) snt = ksplit > 1 ? 2 : nt;
-        if (mode == EPI_STORE) launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
-        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
+        launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
+        return;
     }
-    else if (mode == EPI_BIAS_RELU) launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
-    else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, nt, 1, p);
+    const GemmPlan g = plan_fused(M, N);
+    if (mode == EPI_BIAS_RELU) {
+        if (g.half) launch_half<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+    } else {
+        if (g.half) launch_half<MODE_QKV>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+    }
 }
 
 void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
