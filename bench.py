@@ -264,8 +264,8 @@ def main():
                 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this command, scaled by
                 # the counters' readings for kernels of known size (profiles/decode_fc1_gemm_opt13b_pmc.txt);
                 # measured for the OPT-13B layer shape only
-                "traffic": 218.0e6 if (H, F) == (5120, 20480) else None,
-                "kernel": "gemm_skinny_kernel<MODE_BIAS_RELU> (decode FC1 + bias + ReLU)",
+                "traffic": 218.1e6 if (H, F) == (5120, 20480) else None,
+                "kernel": "decode FC1 GEMM + bias + ReLU, LayerNorm folded in (gemm_half_kernel / gemm_skinny_kernel, mode 1)",
                 "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6}
 
     result = {
