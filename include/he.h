@@ -261,6 +261,14 @@ he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_
  * per-launch cost of an event pair. */
 he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps);
 
+/* Test hook, host logic only (no device work): how a decode-shaped GEMM of M <= 32 rows with an [N, K] weight
+ * matrix is shared out over `cus` compute units (0 = the current device's count, 256 if there is none): weight
+ * rows per unit (32, or 16 for the half-tile kernel), units per workgroup, and k-splits (always 1 unless
+ * ksplit_allowed, i.e. for the out-projection and FC2, whose partial sums go through scratch_floats floats of
+ * scratch; 0 = unlimited).  N and K multiples of 32. */
+he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t scratch_floats, int cus, int* unit_rows,
+                              int* units_per_workgroup, int* ksplit);
+
 /* Measurement hook: a plain copy kernel (reads `bytes`, writes `bytes`, a multiple of 16,
  * device pointers, on `stream`).  Hardware byte counters (rocprofv3 FETCH_SIZE /
  * WRITE_SIZE) are scaled by what they read for this kernel of known size. */

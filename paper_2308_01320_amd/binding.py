@@ -112,6 +112,9 @@ def lib() -> C.CDLL:
     L.he_tile_matrix.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     L.he_tile_matrix_lora.restype = C.c_int
     L.he_tile_matrix_lora.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_float, vp]
+    L.he_plan_decode_gemm.restype = C.c_int
+    L.he_plan_decode_gemm.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_int, C.POINTER(C.c_int),
+                                      C.POINTER(C.c_int), C.POINTER(C.c_int)]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -126,7 +129,7 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
            "he_tile_matrix", "he_score", "he_prefill_ragged",
-           "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena", "he_tile_matrix_lora")
+           "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena", "he_tile_matrix_lora", "he_plan_decode_gemm")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -334,6 +337,15 @@ def he_tile_matrix(src, stream=None):
     return dst
 
 
+def he_plan_decode_gemm(M, N, K, ksplit_allowed=False, scratch_floats=0, cus=256):
+    """(rows per unit, units per workgroup, k-splits) of a decode-shaped GEMM; host logic only."""
+    u, n, k = C.c_int(), C.c_int(), C.c_int()
+    rc = lib().he_plan_decode_gemm(M, N, K, 1 if ksplit_allowed else 0, scratch_floats, cus, C.byref(u), C.byref(n), C.byref(k))
+    if rc != HE_OK:
+        raise HeError(rc, "he_plan_decode_gemm")
+    return u.value, n.value, k.value
+
+
 def he_tile_matrix_lora(src, a, b, scale, stream=None):
     """Tiled copy of bf16(src + scale * b @ a): src [rows, cols], a [rank, cols], b [rows, rank], bf16 device tensors."""
     import torch
@@ -342,7 +354,7 @@ def he_tile_matrix_lora(src, a, b, scale, stream=None):
     rc = lib().he_tile_matrix_lora(src.data_ptr(), dst.data_ptr(), rows, cols, a.data_ptr(), b.data_ptr(), a.shape[0],
                                    scale, stream)
     if rc != HE_OK:
-        raise HeError(rc, "he_tile_matrix_lora")
+        raise HeError(rc, "he_tile_matrix_lora", "he_plan_decode_gemm")
     return dst
 
 

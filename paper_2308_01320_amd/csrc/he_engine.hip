@@ -947,6 +947,13 @@ he_status he_tile_matrix_lora(const void* d_src, void* d_dst, int rows, int cols
     return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
 }
 
+he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t scratch_floats, int cus, int* unit_rows,
+                              int* units_per_workgroup, int* ksplit) {
+    if (M < 1 || N < 1 || K < 1 || N % 32 || K % 32 || !unit_rows || !units_per_workgroup || !ksplit) return HE_ERR_INVALID_ARG;
+    bf16_plan_query(M, N, K, ksplit_allowed, scratch_floats, cus, unit_rows, units_per_workgroup, ksplit);
+    return HE_OK;
+}
+
 he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
     if (!e) return HE_ERR_INVALID_ARG;
     if (!e->fast) return fail(e, HE_ERR_STATE, "he_kernel_sweep: bf16 path only");

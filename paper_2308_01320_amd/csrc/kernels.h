@@ -73,6 +73,9 @@ void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
 // EPI_STORE_LN GEMM of M <= 32 rows: columns per workgroup (= per group of LayerNorm statistics) and k-splits;
 // capacity = floats of k-split scratch available (the value passed as bf16_gemm_args.out_capacity)
 void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks);
+// the launch plan itself (host logic only; cus > 0 overrides the device's CU count): rows per unit (32 or 16),
+// units per workgroup, k-splits; store != 0 for the k-split GEMMs
+void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks);
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
                    void* x_blocks, void* x_blocks_lo, float* stats);

@@ -1980,6 +1980,16 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
     return g;
 }
 
+void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks) {
+    const int saved = g_num_cus;
+    if (cus > 0) g_num_cus = cus;
+    const GemmPlan g = store ? plan_store(M, N, K, capacity) : plan_fused(M, N);
+    g_num_cus = saved;
+    *unit_rows = g.half ? 16 : 32;
+    *per_wg = g.per_wg;
+    *ks = g.ks;
+}
+
 void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks) {
     const GemmPlan g = plan_store(M, N, K, capacity);
     *group_cols = g.per_wg * (g.half ? 16 : 32);

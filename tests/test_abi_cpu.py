@@ -56,3 +56,35 @@ def test_host_side_argument_errors_need_no_gpu():
     assert L.he_reset(None) == 1
     assert L.he_cache_len(None) == -1
     assert L.he_rng_words(0, 0, 0, 0, 4, None, None) == 1
+
+
+def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
+    """Host logic of the launch planner: every plan puts at most one workgroup on a CU, leaves every
+    wavefront at least 8 k-blocks, stays inside the k-split scratch, and is never worse balanced than
+    32-row tiles alone."""
+    import math
+    cus = 256
+    for name in ("opt-1.3b", "opt-6.7b", "opt-13b", "opt-66b"):
+        d = synth.CONFIGS[name]
+        H, F = d.hidden, d.ffn
+        cap = 2 * 8 * 32 * H  # the engine's scratch for batches up to 32
+        for (N, K, store) in ((3 * H, H, False), (F, H, False), (H, H, True), (H, F, True)):
+            unit, per_wg, ks = binding.he_plan_decode_gemm(32, N, K, store, cap if store else 0, cus)
+            assert unit in (16, 32) and per_wg >= 1 and 1 <= ks <= 8
+            groups = math.ceil(N // unit / per_wg)
+            assert groups * ks <= cus, (name, N, K, unit, per_wg, ks)
+            assert (K // 16) // (ks * 4) >= 8 or ks == 1
+            if not store:
+                assert ks == 1
+                assert unit * per_wg <= 32 * math.ceil(N // 32 / cus)  # the most loaded workgroup
+            else:
+                assert groups * ks * (2 * per_wg + 7) * 256 <= cap or unit == 32
+    # the case the 16-row units exist for: 640 tiles do not divide over 256 CUs, 1280 units do
+    assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 256) == (16, 5, 1)
+    assert binding.he_plan_decode_gemm(32, 15360, 5120, False, 0, 256) == (32, 2, 1)
+    # fewer CUs, bigger shares: 640 tiles over 128 CUs are five each (nothing to gain from halves),
+    # over 200 CUs four tiles (128 rows) or seven halves (112 rows)
+    assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 128) == (32, 5, 1)
+    assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 200) == (16, 7, 1)
+    with pytest.raises(binding.HeError):
+        binding.he_plan_decode_gemm(32, 100, 64)
