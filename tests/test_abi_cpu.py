@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import pytest
+
 from paper_2308_01320_amd import binding, synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
