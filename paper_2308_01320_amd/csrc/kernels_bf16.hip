@@ -1135,18 +1135,19 @@ __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, 
     }
 }
 
-// The same operation for the few rows of a decode step: one 1024-thread workgroup per row,
-// every value held in registers (NV float4 per thread), all loads -- residual, k-split
-// partials, bias, gamma, beta -- issued before the first reduction, since with so little
-// work the kernel's time is the length of its dependent-load chain.
-template <int NV>
-__global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, const float* __restrict__ part, int ksplit,
+// The same operation with every value of the row held in registers (NV float4 per thread) and all
+// loads -- residual, k-split partials, bias, gamma, beta -- issued before the first reduction.
+// For the few rows of a decode step one 1024-thread workgroup per row (the kernel's time is then the
+// length of its dependent-load chain); for the many rows of a prompt pass 256 threads per row.
+template <int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, const float* __restrict__ part, int ksplit,
                                                       size_t part_split, const bf16_t* __restrict__ pbias,
                                                       const bf16_t* __restrict__ gamma,
                                                       const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
                                                       u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
                                                       int in_add, int writeback) {
-    __shared__ float red[2][16];
+    constexpr int NW = THREADS / 64;
+    __shared__ float red[2][NW];
     const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const size_t src = (size_t)m * in_mul + in_add;
     const int nq = H >> 2;  // float4 per row
@@ -1155,7 +1156,7 @@ __global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, con
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int i = threadIdx.x + j * 1024;
+        const int i = threadIdx.x + j * THREADS;
         v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         gg[j] = bb[j] = make_uint2(0, 0);
         if (i < nq) {
@@ -1167,7 +1168,7 @@ __global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, con
     if (part) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
-            const int i = threadIdx.x + j * 1024;
+            const int i = threadIdx.x + j * THREADS;
             if (i >= nq) continue;
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int k = 0; k < ksplit; ++k) {  // fixed order: the sum does not depend on scheduling
@@ -1189,12 +1190,12 @@ __global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, con
     __syncthreads();
     float tot = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) tot += red[0][i];
+    for (int i = 0; i < NW; ++i) tot += red[0][i];
     const float mean = tot / H;
     float q = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        if (threadIdx.x + j * 1024 < nq) {
+        if (threadIdx.x + j * THREADS < nq) {
             const float d0 = v[j].x - mean, d1 = v[j].y - mean, d2 = v[j].z - mean, d3 = v[j].w - mean;
             q += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
         }
@@ -1204,12 +1205,12 @@ __global__ __launch_bounds__(1024) void ln_row_kernel(float* __restrict__ r, con
     __syncthreads();
     tot = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) tot += red[1][i];
+    for (int i = 0; i < NW; ++i) tot += red[1][i];
     const float rstd = 1.0f / sqrtf(tot / H + eps);
     const int KB = H >> 4;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int i = threadIdx.x + j * 1024;
+        const int i = threadIdx.x + j * THREADS;
         if (i >= nq) continue;
         const float e0 = (v[j].x - mean) * rstd * __uint_as_float(gg[j].x << 16) + __uint_as_float(bb[j].x << 16);
         const float e1 = (v[j].y - mean) * rstd * __uint_as_float(gg[j].x & 0xFFFF0000u) + __uint_as_float(bb[j].x & 0xFFFF0000u);
@@ -2110,18 +2111,33 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
              int in_mul, int in_add, int writeback) {
-    const int nv = (H / 4 + 1023) / 1024;
+    const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
+#define HE_LN_ROW(NV, T)                                                                                                \
+    ln_row_kernel<NV, T><<<rows, T, 0, s>>>(r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma,    \
+                                            (const bf16_t*)beta, (u32x4*)a_blocks, (u32x4*)a_blocks_lo, H, eps, in_mul, \
+                                            in_add, writeback)
     if (rows <= 256 && nv <= 3) {  // a decode step
-#define HE_LN_ROW(NV)                                                                                             \
-    ln_row_kernel<NV><<<rows, 1024, 0, s>>>(r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, \
-                                            (const bf16_t*)beta, (u32x4*)a_blocks, (u32x4*)a_blocks_lo, H, eps,     \
-                                            in_mul, in_add, writeback)
-        if (nv == 1) HE_LN_ROW(1);
-        else if (nv == 2) HE_LN_ROW(2);
-        else HE_LN_ROW(3);
-#undef HE_LN_ROW
+        if (nv == 1) HE_LN_ROW(1, 1024);
+        else if (nv == 2) HE_LN_ROW(2, 1024);
+        else HE_LN_ROW(3, 1024);
         return;
     }
+    if (nv256 <= 10) {  // prompt rows, hidden sizes up to 10240
+        switch (nv256) {
+            case 1: HE_LN_ROW(1, 256); break;
+            case 2: HE_LN_ROW(2, 256); break;
+            case 3: HE_LN_ROW(3, 256); break;
+            case 4: HE_LN_ROW(4, 256); break;
+            case 5: HE_LN_ROW(5, 256); break;
+            case 6: HE_LN_ROW(6, 256); break;
+            case 7: HE_LN_ROW(7, 256); break;
+            case 8: HE_LN_ROW(8, 256); break;
+            case 9: HE_LN_ROW(9, 256); break;
+            default: HE_LN_ROW(10, 256); break;
+        }
+        return;
+    }
+#undef HE_LN_ROW
     ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
         (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback);
