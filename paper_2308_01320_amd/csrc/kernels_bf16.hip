@@ -886,16 +886,30 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
 // same weight registers), which keeps keys and values of the prompt within a
 // rounding of the exact ones before they are stored as bf16.
 
-constexpr int TN = 256, TM = 128, KSTAGE = 2;  // KSTAGE k-blocks (32 values of k) per stage
-constexpr int TNB = TN / 32, TMB = TM / 32;   // 32-row operand blocks per tile side
-constexpr int NSTG = 4;                       // ring depth
-constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;  // 32 blocks = 32 KiB per stage
+constexpr int TN = 256, TM = 128;  // TM: the smaller m tile
+constexpr int TNB = TN / 32;                   // 32-row operand blocks on the n side
+// The m side comes in two sizes: MW = 2 (128 rows per tile, 64 per wavefront) and MW = 4 (256 rows, 128 per
+// wavefront).  The larger tile moves a quarter less operand data per flop through L2, the vector cache
+// and LDS -- what the wavefronts of the smaller one spend 40 % of their time waiting for -- and is used
+// when there are enough rows to fill the chip with it.  The ring: four stages of two k-blocks (32 KiB each),
+// or six stages of one k-block (24 KiB each) -- the same barrier rate per MFMA, and loads that run
+// 4.5 stages = 4600 MFMA cycles ahead: a fifth of the operand blocks comes from HBM, not L2.
+template <int MW> struct TiledShape {
+    static constexpr int TMB = 2 * MW;                          // 32-row operand blocks on the m side
+    static constexpr int TMR = TMB * 32;                        // rows of the m tile
+    static constexpr int KSTAGE = MW == 2 ? 2 : 1;              // k-blocks (16 values of k each) per stage
+    static constexpr int NSTG = MW == 2 ? 4 : 6;                // ring depth
+    static constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;
+};
 
-template <int MODE>
+template <int MODE, int MW>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, int ksplit, Epi p) {
     // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
+    constexpr int TMB = TiledShape<MW>::TMB, TMR = TiledShape<MW>::TMR, NSTG = TiledShape<MW>::NSTG;
+    constexpr int KSTAGE = TiledShape<MW>::KSTAGE;
+    constexpr int STAGE_BLOCKS = TiledShape<MW>::STAGE_BLOCKS;
     __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
@@ -914,27 +928,34 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int gm = min(GROUP, tiles_m - first_m);
     const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
 
-    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 64 (m) sub-tile
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 32 MW (m) sub-tile
     const int cur_len = epilogue_len<MODE>(p);
-    f32x16 acc[4][2];
+    f32x16 acc[4][MW];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{};
+        for (int j = 0; j < MW; ++j) acc[i][j] = f32x16{};
 
-    // this wavefront brings in W row-tiles 2w, 2w+1 and row-tile w of X hi and X lo: 8 blocks per stage
+    // this wavefront brings in W row-tiles 2w, 2w+1 and XW row-tiles of X hi and X lo per k-block
+    constexpr int XW = TMB / 4;
     const u32x4* wsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) wsrc[i] = Wp + (size_t)min(tn * TNB + wave * 2 + i, NT32 - 1) * KB * 64 + lane;
-    const int xrt = min(tm * TMB + wave, MT32 - 1);
-    const u32x4* hsrc = Xhi + (size_t)xrt * KB * 64 + lane;
-    const u32x4* lsrc = Xlo + (size_t)xrt * KB * 64 + lane;
+    const u32x4 *hsrc[XW], *lsrc[XW];
+#pragma unroll
+    for (int x = 0; x < XW; ++x) {
+        const int xrt = min(tm * TMB + wave * XW + x, MT32 - 1);
+        hsrc[x] = Xhi + (size_t)xrt * KB * 64 + lane;
+        lsrc[x] = Xlo + (size_t)xrt * KB * 64 + lane;
+    }
     const int nst_all = KB / KSTAGE;  // KB is even (K % 32 == 0)
     const int st0 = (int)((long)ks * nst_all / ksplit);
     const int nstage = (int)((long)(ks + 1) * nst_all / ksplit) - st0;  // this workgroup's stages: st0 .. st0+nstage-1
     {
         const size_t skip = (size_t)st0 * KSTAGE * 64;
-        wsrc[0] += skip; wsrc[1] += skip; hsrc += skip; lsrc += skip;
+        wsrc[0] += skip; wsrc[1] += skip;
+#pragma unroll
+        for (int x = 0; x < XW; ++x) { hsrc[x] += skip; lsrc[x] += skip; }
     }
     auto issue = [&](int st) {
         u32x4 (*slot)[64] = ring[st % NSTG];
@@ -943,13 +964,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
             const size_t off = ((size_t)st * KSTAGE + j) * 64;
             load_block_to_lds(wsrc[0] + off, &slot[(wave * 2 + 0) * KSTAGE + j][0]);
             load_block_to_lds(wsrc[1] + off, &slot[(wave * 2 + 1) * KSTAGE + j][0]);
-            load_block_to_lds(hsrc + off, &slot[TNB * KSTAGE + wave * KSTAGE + j][0]);
-            load_block_to_lds(lsrc + off, &slot[(TNB + TMB) * KSTAGE + wave * KSTAGE + j][0]);
+#pragma unroll
+            for (int x = 0; x < XW; ++x) {
+                load_block_to_lds(hsrc[x] + off, &slot[(TNB + wave * XW + x) * KSTAGE + j][0]);
+                load_block_to_lds(lsrc[x] + off, &slot[(TNB + TMB + wave * XW + x) * KSTAGE + j][0]);
+            }
         }
     };
-    constexpr int kLoadsPerStage = 4 * KSTAGE;  // per wavefront
-    // operand registers of one k-block: 4 weight blocks, 2 activation tiles x (hi, lo)
-    struct Ops { u32x4 a[4], b[2][2]; };
+    constexpr int kLoadsPerStage = (2 + 2 * XW) * KSTAGE;  // per wavefront
+    // operand registers of one k-block: 4 weight blocks, MW activation tiles x (hi, lo)
+    struct Ops { u32x4 a[4], b[2][MW]; };
     auto read_ops = [&](Ops& o, int st, int j) {
         u32x4 (*slot)[64] = ring[st % NSTG];
 #pragma unroll
@@ -957,22 +981,24 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) o.b[t][i] = slot[(TNB + t * TMB + wm * 2 + i) * KSTAGE + j][lane];
+            for (int i = 0; i < MW; ++i) o.b[t][i] = slot[(TNB + t * TMB + wm * MW + i) * KSTAGE + j][lane];
     };
     auto mma_ops = [&](const Ops& o) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                acc[i][0] = mfma_bf16(o.a[i], o.b[t][0], acc[i][0]);
-                acc[i][1] = mfma_bf16(o.a[i], o.b[t][1], acc[i][1]);
+#pragma unroll
+                for (int jj = 0; jj < MW; ++jj) acc[i][jj] = mfma_bf16(o.a[i], o.b[t][jj], acc[i][jj]);
             }
     };
     // Stage st is usable once this wavefront's own loads of it have landed (at most the loads of the
     // stages issued after it may still be outstanding) and every other wavefront says the same.
     auto stage_ready = [&](int st, int last_issued) {
-        const int later = min(last_issued, nstage - 1) - st;
-        if (later >= 2) wait_vmcnt<2 * kLoadsPerStage>();
+        const int later = min(last_issued, nstage - 1) - st;  // 0 .. NSTG-2
+        if (later >= 4) wait_vmcnt<4 * kLoadsPerStage>();
+        else if (later == 3) wait_vmcnt<3 * kLoadsPerStage>();
+        else if (later == 2) wait_vmcnt<2 * kLoadsPerStage>();
         else if (later == 1) wait_vmcnt<kLoadsPerStage>();
         else wait_vmcnt<0>();
         __syncthreads();
@@ -980,32 +1006,68 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
 #pragma unroll
     for (int st = 0; st < NSTG - 1; ++st)
         if (st < nstage) issue(st);
-    stage_ready(0, NSTG - 2);
-    Ops cur, nxt;
-    read_ops(cur, 0, 0);
-    // LDS reads run one k-block ahead of the MFMAs.  The barrier that opens stage s+1 sits before
-    // the last k-block of stage s; every wavefront that passes it has finished the MFMAs of stage
-    // s-1, so that stage's slot is refilled right there (three stages ahead of its use).
-    for (int s = 0; s < nstage; ++s) {
-#pragma unroll
-        for (int j = 0; j < KSTAGE; ++j) {
-            if (j + 1 < KSTAGE) {
-                read_ops(nxt, s, j + 1);
-            } else if (s + 1 < nstage) {
+    // Two operand register sets, used in turn.  No set is ever copied into the other: a copy would
+    // have to wait for the LDS reads it copies, in the middle of the MFMAs.  A stage's slot is
+    // refilled behind the barrier that every wavefront passes only after its MFMAs of that stage.
+    Ops opa, opb;
+    if constexpr (KSTAGE == 2) {
+        // first k-block of a stage from A while B loads, second from B while A loads from the next
+        // stage; the barrier that opens stage s+1 sits before the last k-block of stage s
+        stage_ready(0, NSTG - 2);
+        read_ops(opa, 0, 0);
+        for (int s = 0; s < nstage; ++s) {
+            read_ops(opb, s, KSTAGE - 1);
+            mma_ops(opa);
+            if (s + 1 < nstage) {
                 stage_ready(s + 1, s + NSTG - 2);
                 if (s + NSTG - 1 < nstage) issue(s + NSTG - 1);
-                read_ops(nxt, s + 1, 0);
+                read_ops(opa, s + 1, 0);
             }
-            mma_ops(cur);
-            cur = nxt;
+            mma_ops(opb);
+        }
+    } else {
+        // One k-block per stage, an even number of stages (no k-split with this shape): even stages
+        // from A, odd ones from B.  In the steady state a stage is opened while the NSTG-3 stages
+        // issued after it are still in flight, and the slot just finished with is refilled.
+        constexpr int kAhead = (NSTG - 3) * kLoadsPerStage;
+        int s = 0;
+        if (nstage > NSTG) {  // then the prologue has issued NSTG-1 stages
+            wait_vmcnt<(NSTG - 2) * kLoadsPerStage>();
+            __syncthreads();
+            read_ops(opa, 0, 0);
+            for (; s + NSTG < nstage; s += 2) {
+                wait_vmcnt<kAhead>();
+                __syncthreads();
+                issue(s + NSTG - 1);
+                read_ops(opb, s + 1, 0);
+                mma_ops(opa);
+                wait_vmcnt<kAhead>();
+                __syncthreads();
+                issue(s + NSTG);
+                read_ops(opa, s + 2, 0);
+                mma_ops(opb);
+            }
+        }
+        // the last stages: issue the one that may still be missing (into the slot of stage s-1, which
+        // every wavefront has left once it is past the barrier), then one wait covers them all
+        __syncthreads();
+        if (s + NSTG - 1 < nstage) issue(s + NSTG - 1);
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (s == 0) read_ops(opa, 0, 0);
+        for (; s < nstage; s += 2) {
+            read_ops(opb, s + 1, 0);
+            mma_ops(opa);
+            if (s + 2 < nstage) read_ops(opa, s + 2, 0);
+            mma_ops(opb);
         }
     }
     if (MODE == MODE_SCORE) {
         // The logits never leave the registers: per row, the soft-max partials of this wavefront's
         // 128 vocabulary entries and, if the row's next token is among them, its logit.
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int m = tm * TM + (wm * 2 + j) * 32 + (lane & 31);
+        for (int j = 0; j < MW; ++j) {
+            const int m = tm * TMR + (wm * MW + j) * 32 + (lane & 31);
             int tgt = -1;
             if (m < p.M && m % p.S != p.S - 1) {
                 tgt = p.ids[m + 1];
@@ -1038,8 +1100,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int m = tm * TM + (wm * 2 + j) * 32 + (lane & 31);
+        for (int j = 0; j < MW; ++j) {
+            const int m = tm * TMR + (wm * MW + j) * 32 + (lane & 31);
             const int nb = tn * TN + (wn * 4 + i) * 32 + 4 * (lane >> 5);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
@@ -1868,11 +1930,19 @@ template <int MODE>
 void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p,
                   int ksplit = 1) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
-    const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
+    const int tiles_n = (N + TN - 1) / TN;
+    // 256-row m tiles once they give every CU at least two workgroups' worth of work; else 128-row tiles
+    const int big_m = (M + 255) / 256;
+    const bool big = ksplit == 1 && (long)tiles_n * big_m >= 2L * num_cus();
+    const int tiles_m = big ? big_m : (M + TM - 1) / TM;
     const int nitem = tiles_n * tiles_m * ksplit;
     const int grid = ((nitem + 7) / 8) * 8;
-    gemm_tiled_kernel<MODE><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32, MT32,
-                                                 tiles_n, tiles_m, ksplit, p);
+    if (big)
+        gemm_tiled_kernel<MODE, 4><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
+                                                                 NT32, MT32, tiles_n, tiles_m, ksplit, p);
+    else
+        gemm_tiled_kernel<MODE, 2><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
+                                                                 NT32, MT32, tiles_n, tiles_m, ksplit, p);
 }
 
 // After a k-split MODE_STORE GEMM whose epilogue needs the whole sum: adds the partial sums in split
@@ -2046,10 +2116,10 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
 }
 
 int bf16_tiled_ksplit(int M, int N, int K) {
-    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / KSTAGE;
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / TiledShape<2>::KSTAGE;
     int ks = num_cus() / tiles;
     if (ks > 8) ks = 8;
-    while (ks > 1 && stages / ks < 2 * NSTG) --ks;  // keep the ring worth filling
+    while (ks > 1 && stages / ks < 8) --ks;  // keep the ring worth filling
     return ks < 1 ? 1 : ks;
 }
 
