@@ -718,6 +718,9 @@ he_status he_reset(he_engine* e) {
     e->cur_len = 0; e->step = 0; e->batch = 0;
     e->ragged_gen = false;
     launch_set_state(e->stream, e->st, 0, 0, 1, 0, 1.f, 0);
+    // the arrival counters of the k-split GEMMs clear themselves; after a launch that failed half-way they
+    // may not have, so a reset clears them too (outside any captured graph)
+    if (e->ln_counters) (void)hipMemsetAsync(e->ln_counters, 0, sizes_of(e->cfg).ln_counters, e->stream);
     return check_hip(e, hipGetLastError(), "he_reset");
 }
 
