@@ -922,7 +922,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (item >= nitem) return;
     const int lin = item / ksplit, ks = item % ksplit;
-    const int GROUP = 8;  // m-tiles per super-row
+    const int GROUP = MW == 4 ? 4 : 8;  // m-tiles per super-row: the 32 tiles an XCD works on at once share their panels
+                                        // 4 x 8 (256-row tiles: X panels are twice as heavy as W panels) or 8 x 4
     const int gsize = GROUP * tiles_n;
     const int g = lin / gsize, first_m = g * GROUP;
     const int gm = min(GROUP, tiles_m - first_m);

@@ -88,6 +88,7 @@ def test_f32_ragged_teacher_forced(lens, S, G):
     (256, 2, [70, 64, 3, 33, 70, 1, 12], 70, 3),     # head_dim 128; rows past one 64-row stretch
     (128, 2, [9, 2, 5], 10, 3),                      # 9 prompt rows: the short-prompt attention kernel; all rows padded
     (128, 1, [3, 1, 2], 4, 4),                       # 3 prompt rows: attention row by row
+    (128, 2, [1 + (7 * i) % 12 for i in range(40)], 12, 3),  # 40 sequences: the decode step for more than 32 rows
 ])
 def test_bf16_ragged_teacher_forced(impl, H, nh, lens, S, G):
     d = synth.ModelDims("x", 2, H, nh, 2 * H, 1000, 128, len(lens), S, G, "bf16", "gumbel")
