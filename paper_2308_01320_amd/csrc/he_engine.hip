@@ -74,7 +74,7 @@ struct Sizes {
 };
 
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
-constexpr int kMaxKSplit = 8;  // bf16_gemm_ksplit never returns more
+constexpr int kMaxKSplit = 8;  // no GEMM plan splits k further
 
 size_t elt_bytes(const he_config& c) { return c.dtype == HE_BF16 ? 2 : 4; }
 

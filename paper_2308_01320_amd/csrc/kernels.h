@@ -67,7 +67,6 @@ void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K);
 // dst = tiled bf16(src + scale * B A): A bf16 [rank, K], B bf16 [R, rank]
 void bf16_tile_rows_lora(hipStream_t s, const void* src, void* dst, int R, int K, const void* A, const void* B, int rank,
                          float scale);
-int bf16_gemm_ksplit(int N, int K);
 // decode-shaped STORE GEMM of M rows: weight tiles per workgroup (its column group is 32*nt wide) and k-splits
 void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
 // EPI_STORE_LN GEMM of M <= 32 rows: columns per workgroup (= per group of LayerNorm statistics) and k-splits;
@@ -80,7 +79,8 @@ void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void*
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
                    void* x_blocks, void* x_blocks_lo, float* stats);
 void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2);
-// rows in slices of 32 (decode, LM head): activations as hi + lo bf16 terms
+// rows in slices of 32 (a decode step of up to 32 sequences): EPI_BIAS_RELU, EPI_QKV or EPI_STORE_LN;
+// activations as hi + lo bf16 terms; ksplit is ignored (the plan decides)
 void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                       int ksplit, const bf16_gemm_args& a);
 // many rows (prompt pass)

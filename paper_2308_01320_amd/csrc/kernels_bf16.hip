@@ -218,6 +218,139 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
     }
 }
 
+// ----------------------------------------------------------------- k-split GEMM -> residual rows + next LayerNorm's input
+//
+// Tail of the decode-shaped out-projection / FC2 GEMMs (MODE_STORE_LN), shared by the 32-row and the
+// 16-row kernel.  On entry every thread holds ITEMS quads v[i][0..3]: this workgroup's k-split partial
+// sums of outputs n0[i]..n0[i]+3 of row mrow[i] (live[i]: the quad exists).  rslot[i] says which of the
+// lane's 32/LG rows the quad belongs to: lanes with equal lane % LG hold different columns of the same
+// rows (LG = 32: one row per lane; LG = 16: two).
+//
+// The partial sums cross workgroups (and XCDs, each with an L2 of its own) inside one launch.  They
+// travel as agent-scope atomic words -- written through to, and read from, the level every XCD shares
+// -- so no cache has to be flushed or invalidated (an agent-scope fence does that to whole L2s and cost
+// 45 us per launch).  The words of one (split, item, r) are laid out thread after thread: every access
+// is a contiguous 256 bytes per wavefront.  Each workgroup publishes its partial sums, waits for the
+// stores to be acknowledged and counts itself in; whoever counts last for the column group reads all
+// splits back -- its own included -- and adds them in split order, so the sum does not depend on which
+// workgroup that was.  Nobody waits for anybody: the others are done.  The last one adds bias and
+// residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
+// (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
+// Returns to the caller, who returns.
+template <int ITEMS, int WAVES, int LG>
+__device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, int grp, int groups, int mt, float cnt,
+                                              const float (&v)[ITEMS][4], const int (&mrow)[ITEMS],
+                                              const int (&n0)[ITEMS], const bool (&live)[ITEMS],
+                                              const int (&rslot)[ITEMS]) {
+    constexpr int NSLOT = 32 / LG;
+    __shared__ int s_last;
+    __shared__ float sred[2][WAVES][32];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t cell = (size_t)grp * gridDim.y + mt;
+    constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
+    float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
+    if (ksplit > 1) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (!live[i]) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ksplit - 1;
+        __syncthreads();
+        if (!s_last) return;
+    }
+    float x[ITEMS][4];
+    float srow[NSLOT];
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) srow[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
+        if (!live[i]) continue;
+        const size_t at = (size_t)mrow[i] * p.N + n0[i];
+        const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0[i]);
+        const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0[i]);
+        float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+        if (ksplit > 1) {
+            float y[8][4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+#pragma unroll
+            for (int k = 1; k < 8; ++k)
+                if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
+        }
+        x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
+        x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
+        x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
+        x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
+        *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+        uint32_t h0, h1, l0, l1;
+        split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+        split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+        const size_t slot = block_slot(mrow[i], n0[i] & ~7, p.N >> 4);
+        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0[i] >> 2) & 1] = make_uint2(h0, h1);
+        reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0[i] >> 2) & 1] = make_uint2(l0, l1);
+        const float part = (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+#pragma unroll
+        for (int r = 0; r < NSLOT; ++r)
+            if (rslot[i] == r) srow[r] += part;
+    }
+    // row sums over the lanes that share a row, then over the wavefronts
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+#pragma unroll
+        for (int o = LG; o < 64; o <<= 1) srow[r] += __shfl_xor(srow[r], o);
+        if (lane < LG) sred[0][wave][LG * r + lane] = srow[r];
+    }
+    __syncthreads();
+    float mean[NSLOT], q[NSLOT];
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+        float tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][LG * r + (lane & (LG - 1))];
+        mean[r] = tot / cnt;
+        q[r] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        if (!live[i]) continue;
+#pragma unroll
+        for (int r = 0; r < NSLOT; ++r)
+            if (rslot[i] == r) {
+                const float d0 = x[i][0] - mean[r], d1 = x[i][1] - mean[r], d2 = x[i][2] - mean[r], d3 = x[i][3] - mean[r];
+                q[r] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+#pragma unroll
+        for (int o = LG; o < 64; o <<= 1) q[r] += __shfl_xor(q[r], o);
+        if (lane < LG) sred[1][wave][LG * r + lane] = q[r];
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        float m2 = 0.f, tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) { m2 += sred[1][ww][lane]; tot += sred[0][ww][lane]; }
+        p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(tot / cnt, m2);
+    }
+    if (threadIdx.x == 0 && ksplit > 1)  // ready for the next launch
+        __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ----------------------------------------------------------------- skinny GEMM (decode, LM head)
 //
 // At most 32 rows per grid.y slice: weights are streamed exactly once from HBM,
@@ -382,109 +515,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         }
     }
     if (MODE == MODE_STORE_LN) {
-        __shared__ int s_last;
-        __shared__ float sred[2][WAVES][32];
-        const size_t cell = (size_t)grp * gridDim.y + mt;
-        // The k-split partial sums cross workgroups (and XCDs, each with an L2 of its own) inside
-        // one launch.  They travel as agent-scope atomic words -- written through to, and read
-        // from, the level every XCD shares -- so no cache has to be flushed or invalidated.  The
-        // words of one (split, item, r) are laid out thread after thread: every access is a
-        // contiguous 256 bytes per wavefront.
-        constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
-        float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
-        if (ksplit > 1) {
-#pragma unroll
-            for (int i = 0; i < ITEMS; ++i) {
-                const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
-                if (item < NT * 4 && tile < n_tiles && m < p.M) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-            // Once the stores are acknowledged, count this workgroup in; whoever counts last for
-            // the column group sees all of the partial sums.  Nobody waits: the others are done.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (threadIdx.x == 0)
-                s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                         ksplit - 1;
-            __syncthreads();
-            if (!s_last) return;
-        }
-        float x[ITEMS][4];
-        float s = 0.f;
+        int mrow[ITEMS], n0[ITEMS], rslot[ITEMS];
+        bool live[ITEMS];
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
-            const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
-            const bool live = item < NT * 4 && tile < n_tiles && m < p.M;
-            x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
-            if (!live) continue;
-            const size_t at = (size_t)m * p.N + n0;
-            const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
-            const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
-            const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0);
-            float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
-            if (ksplit > 1) {
-                // every split is read back, this workgroup's own included, and added in split
-                // order: the sum does not depend on which workgroup came last
-                float y[8][4];
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
-#pragma unroll
-                for (int k = 1; k < 8; ++k)
-                    if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
-            }
-            x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
-            x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
-            x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
-            x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
-            *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
-            uint32_t h0, h1, l0, l1;
-            split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
-            split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
-            const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
-            reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
-            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
-            s += (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+            mrow[i] = m;
+            n0[i] = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+            live[i] = item < NT * 4 && tile < n_tiles && m < p.M;
+            rslot[i] = 0;
         }
-        // mean and sum of squared deviations of each row over this group's columns, fixed order
-        const float cnt = 32.f * (float)min(NT, n_tiles - grp * NT);
-        s += __shfl_xor(s, 32);
-        if (lane < 32) sred[0][wave][lane] = s;
-        __syncthreads();
-        float tot = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][lane & 31];
-        const float mean = tot / cnt;
-        float q = 0.f;
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
-            if (item < NT * 4 && tile < n_tiles && m < p.M) {
-                const float d0 = x[i][0] - mean, d1 = x[i][1] - mean, d2 = x[i][2] - mean, d3 = x[i][3] - mean;
-                q += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
-            }
-        }
-        q += __shfl_xor(q, 32);
-        if (lane < 32) sred[1][wave][lane] = q;
-        __syncthreads();
-        if (threadIdx.x < 32) {
-            float m2 = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) m2 += sred[1][ww][lane];
-            const int groups = (n_tiles + NT - 1) / NT;
-            p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(mean, m2);
-        }
-        if (threadIdx.x == 0 && ksplit > 1)  // ready for the next launch
-            __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_ln_tail<ITEMS, WAVES, 32>(p, ksplit, ks, grp, (n_tiles + NT - 1) / NT, mt,
+                                        32.f * (float)min(NT, n_tiles - grp * NT), v, mrow, n0, live, rslot);
         return;
     }
     float (*zt)[32][33] = reinterpret_cast<float (*)[32][33]>(&red[0][0][0][0]);  // logits tiles reuse the LDS
@@ -708,115 +750,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         }
     }
     if (MODE == MODE_STORE_LN) {
-        __shared__ int s_last;
-        __shared__ float sred[2][WAVES][32];
-        const size_t cell = (size_t)grp * gridDim.y + mt;
-        constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;
-        float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
-        if (ksplit > 1) {
-#pragma unroll
-            for (int i = 0; i < ITEMS; ++i) {
-                const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
-                const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
-                if (item < NI && g < n_half && m < p.M) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (threadIdx.x == 0)
-                s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                         ksplit - 1;
-            __syncthreads();
-            if (!s_last) return;
-        }
-        float x[ITEMS][4];
-        float srow[2] = {0.f, 0.f};
+        int mrow[ITEMS], n0[ITEMS], rslot[ITEMS];
+        bool live[ITEMS];
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
-            const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
-            const int n0 = g * 16 + 4 * (lane >> 4);
-            const bool live = item < NI && g < n_half && m < p.M;
-            x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
-            if (!live) continue;
-            const size_t at = (size_t)m * p.N + n0;
-            const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
-            const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0);
-            const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0);
-            float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
-            if (ksplit > 1) {
-                float y[8][4];
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
-#pragma unroll
-                for (int k = 1; k < 8; ++k)
-                    if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
-            }
-            x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
-            x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
-            x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
-            x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
-            *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
-            uint32_t h0, h1, l0, l1;
-            split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
-            split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
-            const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
-            reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
-            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
-            srow[item & 1] += (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+            mrow[i] = mt * 32 + 16 * (item & 1) + (lane & 15);
+            n0[i] = g * 16 + 4 * (lane >> 4);
+            live[i] = item < NI && g < n_half && mrow[i] < p.M;
+            rslot[i] = item & 1;
         }
-        // per row (16 mh + lane%16) over this group's columns: the four lane groups hold different columns
-        const float cnt = 16.f * (float)min(HT, n_half - grp * HT);
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            srow[mh] += __shfl_xor(srow[mh], 16);
-            srow[mh] += __shfl_xor(srow[mh], 32);
-            if (lane < 16) sred[0][wave][16 * mh + lane] = srow[mh];
-        }
-        __syncthreads();
-        float mean[2], q[2] = {0.f, 0.f};
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            float tot = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][16 * mh + (lane & 15)];
-            mean[mh] = tot / cnt;
-        }
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
-            const int m = mt * 32 + 16 * (item & 1) + (lane & 15);
-            if (item < NI && g < n_half && m < p.M) {
-                const float mu = mean[item & 1];
-                const float d0 = x[i][0] - mu, d1 = x[i][1] - mu, d2 = x[i][2] - mu, d3 = x[i][3] - mu;
-                q[item & 1] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
-            }
-        }
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            q[mh] += __shfl_xor(q[mh], 16);
-            q[mh] += __shfl_xor(q[mh], 32);
-            if (lane < 16) sred[1][wave][16 * mh + lane] = q[mh];
-        }
-        __syncthreads();
-        if (threadIdx.x < 32) {
-            float m2 = 0.f, tot = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) { m2 += sred[1][ww][lane]; tot += sred[0][ww][lane]; }
-            const int groups = (n_half + HT - 1) / HT;
-            p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(tot / cnt, m2);
-        }
-        if (threadIdx.x == 0 && ksplit > 1)
-            __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_ln_tail<ITEMS, WAVES, 16>(p, ksplit, ks, grp, (n_half + HT - 1) / HT, mt,
+                                        16.f * (float)min(HT, n_half - grp * HT), v, mrow, n0, live, rslot);
         return;
     }
 #pragma unroll
@@ -2002,12 +1947,6 @@ static void store_shape(int N, int K, int* nt, int* ks) {
     *ks = k;
 }
 
-int bf16_gemm_ksplit(int N, int K) {
-    int nt, ks;
-    store_shape(N, K, &nt, &ks);
-    return ks;
-}
-
 void bf16_store_shape(int M, int N, int K, int* nt, int* ks) {
     store_shape(N, K, nt, ks);
     const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
@@ -2082,20 +2021,13 @@ static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
 
 void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                       int ksplit, const bf16_gemm_args& a) {
+    (void)ksplit;
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
-    const int nt = skinny_nt_fused(n_tiles, m_tiles);
-    if (mode == EPI_STORE_LN) {  // ksplit is what bf16_store_plan returns for this shape
+    if (mode == EPI_STORE_LN) {  // the k-split is the one bf16_store_plan reports for this shape
         const GemmPlan g = plan_store(M, N, K, a.out_capacity);
         if (g.half) launch_half<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
         else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
-        return;
-    }
-    if (mode == EPI_STORE) {  // ksplit is what bf16_store_shape returns for this shape
-        int snt, sks;
-        bf16_store_shape(M, N, K, &snt, &sks);
-        if (sks != ksplit) snt = ksplit > 1 ? 2 : nt;
-        launch_skinny<MODE_STORE>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, snt, ksplit, p);
         return;
     }
     const GemmPlan g = plan_fused(M, N);
