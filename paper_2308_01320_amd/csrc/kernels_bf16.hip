@@ -218,6 +218,27 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
     }
 }
 
+// Folded LayerNorm, consumer side: mean and 1/sqrt(var + eps) of row `row` (0..31 of this slice of
+// rows) from the per-column-group statistics the producer left, staged in LDS as
+// [group][32 rows](mean, sum of squared deviations).  Pairwise-update form, pivoted on the first
+// group's mean so that the cross terms stay small.
+__device__ __forceinline__ float2 ln_row_from_groups(const float* lds_stats, int row, const Epi& p) {
+    const float2* gs = reinterpret_cast<const float2*>(lds_stats) + row;
+    const float pivot = gs[0].x;
+    float s1 = 0.f, s2 = 0.f, sm = 0.f;
+    for (int g = 0; g < p.ln_groups; ++g) {
+        const float2 e = gs[g * 32];
+        const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
+        s1 += cnt * dlt;
+        s2 += cnt * dlt * dlt;
+        sm += e.y;
+    }
+    const float inv = 1.0f / (float)p.ln_cols;
+    const float mean = pivot + s1 * inv;
+    const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
+    return make_float2(mean, 1.0f / sqrtf(var + p.ln_eps));
+}
+
 // ----------------------------------------------------------------- k-split GEMM -> residual rows + next LayerNorm's input
 //
 // Tail of the decode-shaped out-projection / FC2 GEMMs (MODE_STORE_LN), shared by the 32-row and the
@@ -489,23 +510,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
             v[i][r] = sum;
         }
     }
-    if (fold) {
-        // Row statistics from the group statistics (pairwise-update form, pivoted on the first
-        // group's mean), then  W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta.
-        const float2* gs = reinterpret_cast<const float2*>(dyn_lds) + (lane & 31);
-        const float pivot = gs[0].x;
-        float s1 = 0.f, s2 = 0.f, sm = 0.f;
-        for (int g = 0; g < p.ln_groups; ++g) {
-            const float2 e = gs[g * 32];
-            const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
-            s1 += cnt * dlt;
-            s2 += cnt * dlt * dlt;
-            sm += e.y;
-        }
-        const float inv = 1.0f / (float)p.ln_cols;
-        const float mean = pivot + s1 * inv;
-        const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
-        const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+    if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta
+        const float2 mr = ln_row_from_groups(dyn_lds, lane & 31, p);
+        const float mean = mr.x, rstd = mr.y;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
@@ -725,24 +732,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
             v[i][r] = sum;
         }
     }
-    if (fold) {
+    if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta; a lane's items sit in two rows
+        float2 mr[2];
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) mr[mh] = ln_row_from_groups(dyn_lds, 16 * mh + (lane & 15), p);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int item = wave + i * WAVES;
-            const float2* gs = reinterpret_cast<const float2*>(dyn_lds) + 16 * (item & 1) + (lane & 15);
-            const float pivot = gs[0].x;
-            float s1 = 0.f, s2 = 0.f, sm = 0.f;
-            for (int g = 0; g < p.ln_groups; ++g) {
-                const float2 e = gs[g * 32];
-                const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
-                s1 += cnt * dlt;
-                s2 += cnt * dlt * dlt;
-                sm += e.y;
-            }
-            const float inv = 1.0f / (float)p.ln_cols;
-            const float mean = pivot + s1 * inv;
-            const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
-            const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+            const int mh = (wave + i * WAVES) & 1;
+            const float mean = mr[mh].x, rstd = mr[mh].y;
             v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
             v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
             v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
