@@ -104,6 +104,46 @@ def merge_lora(W, A, B, scale):
     return round_bf16((W32 + np.float32(scale) * t).astype(F64))
 
 
+def e4m3_round(x):
+    """Nearest OCP FP8 E4M3 value (the published 8-bit format: 1 sign, 4 exponent bits with bias 7,
+    3 mantissa bits, subnormals, largest finite value 448, no infinities), ties to even, for
+    |x| <= 448.  Returns (values float64, codes uint8)."""
+    x = np.asarray(x, F64)
+    a = np.abs(x)
+    # exponent of the binade, clamped to the smallest normal one (below it the spacing stays 2^-9)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -20)))
+    e = np.clip(e, -6, 8)
+    step = 2.0 ** (e - 3)
+    q = np.rint(a / step)  # numpy rounds half to even
+    val = q * step         # q == 16 carries into the next binade by itself
+    assert np.all(val <= 448.0)
+    # encode
+    ee = np.floor(np.log2(np.maximum(val, 2.0 ** -20)))
+    normal = val >= 2.0 ** -6
+    ee = np.where(normal, ee, -6)
+    man = np.where(normal, val / 2.0 ** ee * 8 - 8, val / 2.0 ** -9)
+    code = (np.where(normal, ee + 7, 0).astype(np.int64) << 3) | man.astype(np.int64)
+    code = code | (np.signbit(x).astype(np.int64) << 7)
+    return np.where(np.signbit(x), -val, val), code.astype(np.uint8)
+
+
+def quantize_e4m3_rows(W):
+    """Weights as stored for 8-bit streaming: row n of W [out,in] becomes q[n,:] * 2^e[n] with q
+    in OCP FP8 E4M3 and e[n] the smallest integer for which the row's largest magnitude fits,
+    max|W[n,:]| * 2^-e[n] <= 448 (e = 0 for an all-zero row); q = nearest E4M3 value of W * 2^-e,
+    ties to even.  Scaling by a power of two is exact, so the only rounding is the one to E4M3,
+    and the dequantised weights q * 2^e are bf16 values again (four significant bits).
+    (An extension in the direction of Section 5.3 (I): generation is bound by the bytes read per
+    token; the paper itself streams 16-bit weights.)
+    Returns (dequantised weights float64 [out,in], codes uint8 [out,in], e int32 [out])."""
+    W = np.asarray(W, F64)
+    amax = np.abs(W).max(axis=1)
+    f, x = np.frexp(amax)  # amax = f * 2^x, f in [0.5, 1); 448 = 0.875 * 2^9
+    e = np.where(amax == 0, 0, np.where(f <= 0.875, x - 9, x - 8)).astype(np.int32)
+    vals, codes = e4m3_round(W * 2.0 ** (-e[:, None].astype(F64)))
+    return vals * 2.0 ** e[:, None].astype(F64), codes, e
+
+
 def log_softmax(z):
     m = z.max(axis=-1, keepdims=True)
     return z - (m + np.log(np.exp(z - m).sum(axis=-1, keepdims=True)))

@@ -554,3 +554,54 @@ def test_merge_lora_against_float64_and_the_two_branch_form():
     two_branch = O.linear(x, W.astype(np.float64)) + s * O.linear(O.linear(x, A.astype(np.float64)), B.astype(np.float64))
     np.testing.assert_allclose(O.linear(x, exact), two_branch, atol=1e-12)
     assert np.abs(O.linear(x, got) - two_branch).max() < 0.02  # and the stored form is that, rounded
+
+
+# ---------------------------------------------------------------- 8-bit weight storage
+
+def test_e4m3_rounding_against_torch_and_the_format_table():
+    if not hasattr(torch, "float8_e4m3fn"):
+        pytest.skip("this torch has no float8_e4m3fn")
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.normal(0, 50, 20000), rng.normal(0, 0.01, 20000), rng.uniform(-448, 448, 20000),
+                        [0.0, -0.0, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -6, 0.0009765625 * 1.0001,
+                         17.0, 18.0, 19.0, 20.0, 21.0, 22.0, 23.0, 24.0, 25.0, 26.0, 27.0, 28.0]])  # ties in the binade of 16
+    x = x.astype(np.float32).astype(np.float64)
+    vals, codes = O.e4m3_round(x)
+    t8 = torch.from_numpy(x.astype(np.float32)).to(torch.float8_e4m3fn)
+    np.testing.assert_array_equal(vals, t8.to(torch.float32).numpy().astype(np.float64))
+    np.testing.assert_array_equal(codes & 0x7F, t8.view(torch.uint8).numpy() & 0x7F)  # the sign of a zero may differ
+    # every code decodes by the format's definition, and encoding that value gives the code back
+    for c in range(256):
+        s_, e_, m_ = c >> 7, (c >> 3) & 15, c & 7
+        if e_ == 15 and m_ == 7:
+            continue  # NaN
+        v = (m_ * 2.0 ** -9) if e_ == 0 else (1 + m_ / 8) * 2.0 ** (e_ - 7)
+        v = -v if s_ else v
+        vv, cc = O.e4m3_round(np.array([v]))
+        assert vv[0] == v and (cc[0] == c or v == 0)
+
+
+def test_row_quantisation_scale_and_dequantised_values():
+    rng = np.random.default_rng(13)
+    W = synth.round_to_bf16(rng.normal(0, 0.02, (40, 96))).astype(np.float64)
+    W[3] = 0.0                 # an all-zero row
+    W[5] *= 2.0 ** 20          # rows of very different size
+    W[6] *= 2.0 ** -20
+    W[7, :] = 0.0
+    W[7, 11] = 448.0 * 2.0 ** -3  # largest magnitude exactly at the top of the range: fits with e = -3
+    Wq, codes, e = O.quantize_e4m3_rows(W)
+    for n in range(W.shape[0]):
+        amax = np.abs(W[n]).max()
+        if amax == 0:
+            assert e[n] == 0 and not Wq[n].any()
+            continue
+        assert amax * 2.0 ** -float(e[n]) <= 448 < amax * 2.0 ** -(float(e[n]) - 1)  # the smallest exponent that fits
+    assert e[7] == -3 and Wq[7, 11] == W[7, 11]
+    # relative error at most half a 4-bit step for values that stay normal, and bf16-representable results
+    big = np.abs(W) >= np.abs(W).max(axis=1, keepdims=True) * 2.0 ** -8
+    assert np.all(np.abs(Wq - W)[big] <= np.abs(W)[big] * 2.0 ** -4)
+    np.testing.assert_array_equal(Wq, O.round_bf16(Wq))
+    # codes and exponents reproduce the dequantised values through the format's definition
+    s_, e_, m_ = codes >> 7, (codes >> 3) & 15, codes & 7
+    dec = np.where(e_ == 0, m_ * 2.0 ** -9, (1 + m_ / 8) * 2.0 ** (e_.astype(np.float64) - 7)) * np.where(s_ == 1, -1.0, 1.0)
+    np.testing.assert_array_equal(dec * 2.0 ** e[:, None].astype(np.float64), Wq)
