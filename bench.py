@@ -59,11 +59,14 @@ def device_weights(d, torch, seed=0, std=0.02, tiled=False):
     return w
 
 
-def algorithmic_bytes(d):
+def algorithmic_bytes(d, fp8=False):
     """Bytes the method itself must move per decode step (weights once for the whole
-    batch; K/V of every cached position read, the new position written)."""
+    batch; K/V of every cached position read, the new position written).  With 8-bit layer
+    matrices: one byte per weight plus a float scale per row."""
     H, F, L, V = d.hidden, d.ffn, d.n_layers, d.vocab
     wbytes = 2 * (L * (4 * H * H + 2 * H * F + 9 * H + F) + 2 * H + V * H)
+    if fp8:
+        wbytes = L * (4 * H * H + 2 * H * F) + L * 4 * (5 * H + F) + 2 * (L * (9 * H + F) + 2 * H + V * H)
     kvtok = L * 2 * H * 2
     return wbytes, kvtok
 
@@ -128,6 +131,8 @@ def main():
     ap.add_argument("--no-score", action="store_true", help="skip the scoring pass measured after the timed region")
     ap.add_argument("--weights-tiled", action="store_true",
                     help="hand the engine pre-tiled matrices (no second copy); implied by opt-66b")
+    ap.add_argument("--weights-fp8", action="store_true",
+                    help="8-bit (E4M3) layer matrices: a second workload, not the headline number")
     ap.add_argument("--timing-steps", type=int, default=24, help="decode steps run with per-kernel HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -152,7 +157,8 @@ def main():
     tiled = args.weights_tiled or d.name == "opt-66b"
     weights = device_weights(d, torch, tiled=tiled)
     torch.cuda.synchronize()
-    cfg = binding.make_config(d, stream=stream.cuda_stream, weights_tiled=1 if tiled else 0)
+    cfg = binding.make_config(d, stream=stream.cuda_stream, weights_tiled=1 if tiled else 0,
+                              weights_fp8=1 if args.weights_fp8 else 0)
     eng = binding.Engine(cfg, weights)
     prompts = torch.from_numpy(synth.make_prompts(d, seed=1234 + 3)).cuda()
     samp = binding.sampling(d.sampling, 1.0, 42)
@@ -232,7 +238,7 @@ def main():
         binding.he_calibration_copy(cal_src, cal_dst, stream.cuda_stream)
         torch.cuda.synchronize()
 
-    wbytes, kvtok = algorithmic_bytes(d)
+    wbytes, kvtok = algorithmic_bytes(d, args.weights_fp8)
     # decode steps of a job see contexts S+1 .. S+G-1 (after appending the new position)
     step_bytes = [wbytes + B * T * kvtok + B * kvtok for T in range(S + 1, S + G)]
     decode_gbs = sum(step_bytes) / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 else 0.0
@@ -245,6 +251,8 @@ def main():
         # attention during the timed decode steps: contexts S+1 .. S+nt, K and V of one layer
         "attention": sum(2 * B * T * H * 2 for T in range(S + 1, S + nt + 1)) / nt,
     }
+    if args.weights_fp8:  # codes + row scales + bias
+        kern_bytes.update({"qkv": 3 * H * H + 3 * H * 6, "out_proj": H * H + H * 6, "fc1": F * H + F * 6, "fc2": H * F + H * 6})
     # an event pair brackets more than the kernel (the two timestamp packets); the same pair
     # around nothing measures that, and it is taken off every bracket
     pair_ms = timing["empty"][0] / max(1, timing["empty"][1])
@@ -264,7 +272,7 @@ def main():
                 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this command, scaled by
                 # the counters' readings for kernels of known size (profiles/decode_fc1_gemm_opt13b_pmc.txt);
                 # measured for the OPT-13B layer shape only
-                "traffic": 218.1e6 if (H, F) == (5120, 20480) else None,
+                "traffic": 218.1e6 if (H, F) == (5120, 20480) and not args.weights_fp8 else None,
                 "kernel": "decode FC1 GEMM + bias + ReLU, LayerNorm folded in (gemm_half_kernel / gemm_skinny_kernel, mode 1)",
                 "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6}
 
@@ -274,7 +282,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{d.name}-shaped actor, {d.n_layers} layers, hidden {H}, {d.n_heads} heads, ffn {F}, "
-                               f"vocab {d.vocab}; batch {B}, prompt {S}, generate {G}, {d.sampling} sampling",
+                               f"vocab {d.vocab}; batch {B}, prompt {S}, generate {G}, {d.sampling} sampling"
+                               + ("; layer matrices stored as 8-bit E4M3 codes" if args.weights_fp8 else ""),
                    "global_batch": B, "prompt_len": S, "gen_len": G},
         "roofline": roofline,
         "decode": {"ms_per_token_step": decode_ms / (G - 1), "hbm_GB/s": decode_gbs,

@@ -80,6 +80,17 @@ typedef struct {
                           in place, no copies -- for models whose weights fill more than half of HBM.
                           tok_emb is row-major in both cases (with a tied head and weights_tiled = 1,
                           lm_head is the tiled copy of tok_emb). */
+    int weights_fp8;   /* bf16, impl 0, weights_tiled 0 only.  1: the engine keeps the four matrices of every layer
+                          (wqkv, wo, w1, w2) as 8-bit codes instead of bf16 copies -- half the bytes a decode step
+                          streams, half the engine's weight memory.  Row n of a matrix is stored as OCP FP8 E4M3
+                          codes q[n][:] and a scale 2^e[n], e[n] the smallest integer with max|W[n][:]| 2^-e[n] <= 448,
+                          q the nearest E4M3 value of W 2^-e (ties to even); the model then computes with the
+                          dequantised weights q 2^e (bf16 values again, so everything else is unchanged:
+                          accumulation, activations, tolerances).  The LM head and the embeddings stay bf16.
+                          This goes beyond the paper, which streams 16-bit weights (Section 5.3 (I): generation is
+                          bound by the bytes read per token).  Decode steps of up to 32 sequences read the codes
+                          directly; prompt rows, scoring and larger batches dequantise a layer at a time into one
+                          layer of scratch.  Not combinable with he_refresh_weights_lora. */
 } he_config;
 
 typedef struct {
@@ -260,6 +271,12 @@ he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_
  * untouched.  One event pair around the call gives the kernel's launch duration without the
  * per-launch cost of an event pair. */
 he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps);
+
+/* Utility and test hook: the row quantisation weights_fp8 applies.  d_src bf16 [rows, cols] row-major (cols a
+ * multiple of 8); d_codes receives the E4M3 codes [rows, cols] uint8 row-major, d_exps [rows] int32 the
+ * exponents e[n], d_scales [rows] float the scales 2^e[n].  On `stream`. */
+he_status he_fp8_quantize_rows(const void* d_src, int rows, int cols, void* d_codes, int32_t* d_exps, float* d_scales,
+                               void* stream);
 
 /* Test hook, host logic only (no device work): how a decode-shaped GEMM of M <= 32 rows with an [N, K] weight
  * matrix is shared out over `cus` compute units (0 = the current device's count, 256 if there is none): weight

@@ -24,7 +24,7 @@ class he_config(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("hidden", C.c_int), ("n_heads", C.c_int), ("ffn", C.c_int),
                 ("vocab", C.c_int), ("max_positions", C.c_int), ("pos_offset", C.c_int), ("ln_eps", C.c_float),
                 ("dtype", C.c_int), ("max_batch", C.c_int), ("max_seq_len", C.c_int), ("device", C.c_int),
-                ("stream", C.c_void_p), ("impl", C.c_int), ("weights_tiled", C.c_int)]
+                ("stream", C.c_void_p), ("impl", C.c_int), ("weights_tiled", C.c_int), ("weights_fp8", C.c_int)]
 
 
 class he_lora(C.Structure):
@@ -112,6 +112,8 @@ def lib() -> C.CDLL:
     L.he_tile_matrix.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     L.he_tile_matrix_lora.restype = C.c_int
     L.he_tile_matrix_lora.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_float, vp]
+    L.he_fp8_quantize_rows.restype = C.c_int
+    L.he_fp8_quantize_rows.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp]
     L.he_plan_decode_gemm.restype = C.c_int
     L.he_plan_decode_gemm.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_int, C.POINTER(C.c_int),
                                       C.POINTER(C.c_int), C.POINTER(C.c_int)]
@@ -129,7 +131,8 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_reset", "he_destroy", "he_last_error", "he_cache_len", "he_rng_words", "he_timing_enable",
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
            "he_tile_matrix", "he_score", "he_prefill_ragged",
-           "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena", "he_tile_matrix_lora", "he_plan_decode_gemm")
+           "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena",
+           "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -142,12 +145,13 @@ def sampling(mode: str = "greedy", temperature: float = 1.0, seed: int = 0) -> h
     return he_sampling({"greedy": 0, "gumbel": 1}[mode], float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF)
 
 
-def make_config(dims, max_batch=None, max_seq_len=None, device=0, stream=None, impl=0, weights_tiled=0) -> he_config:
+def make_config(dims, max_batch=None, max_seq_len=None, device=0, stream=None, impl=0, weights_tiled=0,
+                weights_fp8=0) -> he_config:
     """he_config from a synth.ModelDims (or anything with the same fields)."""
     return he_config(dims.n_layers, dims.hidden, dims.n_heads, dims.ffn, dims.vocab, dims.max_positions,
                      dims.pos_offset, dims.ln_eps, HE_BF16 if dims.dtype == "bf16" else HE_F32,
                      max_batch or dims.batch, max_seq_len or (dims.prompt_len + dims.gen_len), device,
-                     stream, impl, weights_tiled)
+                     stream, impl, weights_tiled, weights_fp8)
 
 
 def upload_weights(w: dict, dtype: str, device="cuda:0") -> dict:
@@ -337,6 +341,19 @@ def he_tile_matrix(src, stream=None):
     return dst
 
 
+def he_fp8_quantize_rows(src, stream=None):
+    """(codes uint8 [rows, cols], exponents int32 [rows], scales float32 [rows]) of a bf16 [rows, cols] device tensor."""
+    import torch
+    rows, cols = src.shape
+    codes = torch.empty(rows, cols, dtype=torch.uint8, device=src.device)
+    exps = torch.empty(rows, dtype=torch.int32, device=src.device)
+    scales = torch.empty(rows, dtype=torch.float32, device=src.device)
+    rc = lib().he_fp8_quantize_rows(src.data_ptr(), rows, cols, codes.data_ptr(), exps.data_ptr(), scales.data_ptr(), stream)
+    if rc != HE_OK:
+        raise HeError(rc, "he_fp8_quantize_rows")
+    return codes, exps, scales
+
+
 def he_plan_decode_gemm(M, N, K, ksplit_allowed=False, scratch_floats=0, cus=256):
     """(rows per unit, units per workgroup, k-splits) of a decode-shaped GEMM; host logic only."""
     u, n, k = C.c_int(), C.c_int(), C.c_int()
@@ -354,7 +371,7 @@ def he_tile_matrix_lora(src, a, b, scale, stream=None):
     rc = lib().he_tile_matrix_lora(src.data_ptr(), dst.data_ptr(), rows, cols, a.data_ptr(), b.data_ptr(), a.shape[0],
                                    scale, stream)
     if rc != HE_OK:
-        raise HeError(rc, "he_tile_matrix_lora", "he_plan_decode_gemm")
+        raise HeError(rc, "he_tile_matrix_lora")
     return dst
 
 

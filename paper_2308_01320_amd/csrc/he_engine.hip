@@ -31,6 +31,12 @@ struct he_engine {
     std::vector<Tiled> tiled;
     void *lm_tiled = nullptr, *ablk = nullptr, *oblk = nullptr, *hblk = nullptr, *xfblk = nullptr;
     void *ablk_lo = nullptr, *oblk_lo = nullptr, *hblk_lo = nullptr, *xfblk_lo = nullptr;  // second bf16 term
+    // 8-bit weights: tiled[] then holds E4M3 units, wscale_buf the row scales (per layer 3H + H + F + H floats),
+    // scratch one layer's dequantised bf16 blocks for the GEMMs that read those
+    bool w8 = false;
+    float* wscale_buf = nullptr;
+    int* exps_tmp = nullptr;
+    Tiled scratch{nullptr, nullptr, nullptr, nullptr};
     float *part = nullptr, *stats = nullptr;
     size_t part_floats = 0;  // capacity of `part`
     int* stats_idx = nullptr;
@@ -86,6 +92,9 @@ const char* check_config(const he_config* c) {
     if (c->impl != 0 && c->impl != 1) return "unknown impl";
     if (c->weights_tiled != 0 && c->weights_tiled != 1) return "weights_tiled must be 0 or 1";
     if (c->weights_tiled && !(c->dtype == HE_BF16 && c->impl == 0)) return "weights_tiled needs dtype bf16 and impl 0";
+    if (c->weights_fp8 != 0 && c->weights_fp8 != 1) return "weights_fp8 must be 0 or 1";
+    if (c->weights_fp8 && !(c->dtype == HE_BF16 && c->impl == 0 && !c->weights_tiled))
+        return "weights_fp8 needs dtype bf16, impl 0 and weights_tiled 0";
     if (!(c->ln_eps > 0.f)) return "ln_eps must be positive";
     return nullptr;
 }
@@ -139,7 +148,12 @@ Sizes sizes_of(const he_config& c) {
     s.ln_counters = mtiles * (H / 32) * sizeof(int);
     s.score_stats = rows * bf16_score_parts(c.vocab) * 2 * sizeof(float);
     s.total += s.cvec + s.ln_stats + s.ln_counters + s.score_stats + s.gen;
-    s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
+    if (c.weights_fp8) {  // E4M3 units (half the bytes), row scales, one layer of bf16 scratch
+        const size_t q8_layer = fp8_units_bytes(3 * H, H) + fp8_units_bytes(H, H) + fp8_units_bytes(F, H) + fp8_units_bytes(H, F);
+        s.total += (size_t)c.n_layers * (q8_layer + (size_t)(5 * H + F) * sizeof(float)) + s.tiled_layer + s.tiled_lm +
+                   wide * sizeof(int);
+    }
+    s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled || c.weights_fp8 ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
                4 * s.ablk + 2 * s.hblk +
                2 * s.xfblk + s.part + s.stats + s.stats_idx;
     return s;
@@ -194,6 +208,26 @@ struct LaunchTimer {
     }
 };
 
+// 8-bit weights: where the row scales of layer l live, and the layer as bf16 blocks (dequantised into the
+// scratch layer, on the engine's stream, for the GEMMs that read 32x16 blocks: prompt rows, scoring,
+// decode steps of more than 32 rows).
+struct Scales { float *wqkv, *wo, *w1, *w2; };
+Scales scales_of(const he_engine* e, int l) {
+    const size_t H = e->cfg.hidden, F = e->cfg.ffn;
+    float* p = e->wscale_buf + (size_t)l * (5 * H + F);
+    return {p, p + 3 * H, p + 4 * H, p + 4 * H + F};
+}
+he_engine::Tiled layer_blocks(he_engine* e, int l) {
+    if (!e->w8) return e->tiled[l];
+    const int H = e->cfg.hidden, F = e->cfg.ffn;
+    const Scales sc = scales_of(e, l);
+    fp8_dequant_units(e->stream, e->tiled[l].wqkv, sc.wqkv, e->scratch.wqkv, 3 * H, H);
+    fp8_dequant_units(e->stream, e->tiled[l].wo, sc.wo, e->scratch.wo, H, H);
+    fp8_dequant_units(e->stream, e->tiled[l].w1, sc.w1, e->scratch.w1, F, H);
+    fp8_dequant_units(e->stream, e->tiled[l].w2, sc.w2, e->scratch.w2, H, F);
+    return e->scratch;
+}
+
 // bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  Only the
 // K/V cache is wanted from these rows (the last prompt token takes the decode-shaped pass
 // below), so the final layer stops once its keys and values are stored.
@@ -213,7 +247,7 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     const size_t split = (size_t)M * H;
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
-        const he_engine::Tiled& tw = e->tiled[l];
+        const he_engine::Tiled tw = layer_blocks(e, l);
         bf16_ln(s, e->resid, pend, 1, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, M, H, c.ln_eps, 1, 0, 1);
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
@@ -267,8 +301,13 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     // residual row (the embedding, the out-projection, FC2) leaves gamma * x as two-term blocks
     // and statistics per group of columns; the column groups are the producer's workgroups.
     int gw1, ks1, gw2, ks2;  // column-group widths after the out-projection / after FC2 and the embedding
-    bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
-    bf16_store_plan(B, H, F, e->part_floats, &gw2, &ks2);
+    if (e->w8) {
+        bf16_store_plan_w8(H, H, e->part_floats, &gw1, &ks1);
+        bf16_store_plan_w8(H, F, e->part_floats, &gw2, &ks2);
+    } else {
+        bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+        bf16_store_plan(B, H, F, e->part_floats, &gw2, &ks2);
+    }
     if (!L) gw2 = 128;
     const size_t split = (size_t)B * H;
     auto fold = [&](bf16_gemm_args& a, int gw, const CVec& cv) {
@@ -288,10 +327,12 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     }
     for (int l = 0; l < L; ++l) {
         const he_layer_weights& lw = e->layers[l];
-        const he_engine::Tiled& tw = e->tiled[l];
+        const he_engine::Tiled& tw = e->tiled[l];  // bf16 blocks, or E4M3 units with 8-bit weights
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
         fold(a, gw2, cvec_qkv(e, l));
+        const Scales sc = e->w8 ? scales_of(e, l) : Scales{nullptr, nullptr, nullptr, nullptr};
+        a.wscale = sc.wqkv;
         {
             LaunchTimer t(e, HE_K_QKV);
             bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
@@ -302,12 +343,14 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
         }
         a = base;
         store_ln(a, lw.bo, lw.ln2_g, e->ablk, e->ablk_lo);
+        a.wscale = sc.wo;
         {
             LaunchTimer t(e, HE_K_OUT_PROJ);
             bf16_gemm_skinny(s, EPI_STORE_LN, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
         }
         a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
         fold(a, gw1, cvec_fc1(e, l));
+        a.wscale = sc.w1;
         {
             LaunchTimer t(e, HE_K_FC1);
             bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
@@ -316,6 +359,7 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
         const bool last = l == L - 1;
         store_ln(a, lw.b2, last ? e->w.lnf_g : e->layers[l + 1].ln1_g, last ? e->xfblk : e->ablk,
                  last ? e->xfblk_lo : e->ablk_lo);
+        a.wscale = sc.w2;
         {
             LaunchTimer t(e, HE_K_FC2);
             bf16_gemm_skinny(s, EPI_STORE_LN, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
@@ -355,7 +399,7 @@ void pass_decode_wide_bf16(he_engine* e, const int32_t* d_ids, int id_stride, in
     const int ks1 = bf16_tiled_ksplit(B, F, H), ks2 = bf16_tiled_ksplit(B, H, F);
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
-        const he_engine::Tiled& tw = e->tiled[l];
+        const he_engine::Tiled tw = layer_blocks(e, l);
         {
             LaunchTimer t(e, HE_K_LAYERNORM);
             bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
@@ -420,6 +464,30 @@ he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int
 void tile_weights(he_engine* e) {
     const he_config& c = e->cfg;
     const int H = c.hidden, F = c.ffn;
+    if (e->w8) {
+        // E4M3 units and row scales of every layer matrix; the vectors W gamma, W beta from the dequantised
+        // layer (the weights the GEMMs really multiply by)
+        auto quant = [&](const void* src, void* units, float* scales, int R, int K) {
+            fp8_row_exponents(e->stream, src, R, K, e->exps_tmp, scales);
+            fp8_quant_units(e->stream, src, e->exps_tmp, units, R, K);
+        };
+        for (int l = 0; l < c.n_layers; ++l) {
+            const he_layer_weights& lw = e->layers[l];
+            const Scales sc = scales_of(e, l);
+            quant(lw.wqkv, e->tiled[l].wqkv, sc.wqkv, 3 * H, H);
+            quant(lw.wo, e->tiled[l].wo, sc.wo, H, H);
+            quant(lw.w1, e->tiled[l].w1, sc.w1, F, H);
+            quant(lw.w2, e->tiled[l].w2, sc.w2, H, F);
+            const he_engine::Tiled blk = layer_blocks(e, l);
+            const CVec q = cvec_qkv(e, l), f = cvec_fc1(e, l);
+            bf16_wvec(e->stream, blk.wqkv, 3 * H, H, lw.ln1_g, lw.ln1_b, q.c1, q.c2);
+            bf16_wvec(e->stream, blk.w1, F, H, lw.ln2_g, lw.ln2_b, f.c1, f.c2);
+        }
+        bf16_tile_rows(e->stream, e->w.lm_head, e->lm_tiled, c.vocab, H);
+        const CVec v = cvec_lm(e);
+        bf16_wvec(e->stream, e->lm_tiled, c.vocab, H, e->w.lnf_g, e->w.lnf_b, v.c1, v.c2);
+        return;
+    }
     if (!c.weights_tiled) {  // else the caller's matrices are used in place
         auto tile = [&](const void* src, void* dst, int R, int K, const he_lora* ad) {
             if (ad && ad->a && ad->b && e->lora_rank > 0)
@@ -594,6 +662,17 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
                                const_cast<void*>(lw.w2)};
             }
             e->lm_tiled = const_cast<void*>(e->w.lm_head);
+        } else if (cfg->weights_fp8) {
+            e->w8 = true;
+            for (auto& t : e->tiled) {
+                A(&t.wqkv, fp8_units_bytes(3 * H, H)); A(&t.wo, fp8_units_bytes(H, H));
+                A(&t.w1, fp8_units_bytes(F, H)); A(&t.w2, fp8_units_bytes(H, F));
+            }
+            A(&e->wscale_buf, (size_t)cfg->n_layers * (5 * H + F) * sizeof(float));
+            A(&e->exps_tmp, (size_t)(3 * H > F ? 3 * H : F) * sizeof(int));
+            A(&e->scratch.wqkv, bf16_tiled_bytes(3 * H, H)); A(&e->scratch.wo, bf16_tiled_bytes(H, H));
+            A(&e->scratch.w1, bf16_tiled_bytes(F, H)); A(&e->scratch.w2, bf16_tiled_bytes(H, F));
+            A(&e->lm_tiled, z.tiled_lm);
         } else {
             for (auto& t : e->tiled) {
                 A(&t.wqkv, bf16_tiled_bytes(3 * H, H)); A(&t.wo, bf16_tiled_bytes(H, H));
@@ -667,8 +746,8 @@ he_status he_refresh_weights(he_engine* e) {
 he_status he_refresh_weights_lora(he_engine* e, const he_lora_layer* adapters, int rank, float scale) {
     if (!e) return HE_ERR_INVALID_ARG;
     if (!adapters || rank < 1) return fail(e, HE_ERR_INVALID_ARG, "he_refresh_weights_lora: adapters NULL or rank < 1");
-    if (!e->fast || e->cfg.weights_tiled)
-        return fail(e, HE_ERR_STATE, "he_refresh_weights_lora: needs dtype bf16, impl 0 and engine-owned tiled copies (weights_tiled = 0)");
+    if (!e->fast || e->cfg.weights_tiled || e->w8)
+        return fail(e, HE_ERR_STATE, "he_refresh_weights_lora: needs dtype bf16, impl 0 and engine-owned bf16 tiled copies (weights_tiled = 0, weights_fp8 = 0)");
     for (int l = 0; l < e->cfg.n_layers; ++l) {
         const he_lora* ps[] = {&adapters[l].wqkv, &adapters[l].wo, &adapters[l].w1, &adapters[l].w2};
         for (const he_lora* p : ps)
@@ -950,6 +1029,14 @@ he_status he_tile_matrix_lora(const void* d_src, void* d_dst, int rows, int cols
     return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
 }
 
+he_status he_fp8_quantize_rows(const void* d_src, int rows, int cols, void* d_codes, int32_t* d_exps, float* d_scales,
+                               void* stream) {
+    if (!d_src || !d_codes || !d_exps || !d_scales || rows <= 0 || cols <= 0 || cols % 8) return HE_ERR_INVALID_ARG;
+    fp8_row_exponents((hipStream_t)stream, d_src, rows, cols, d_exps, d_scales);
+    fp8_quant_rows((hipStream_t)stream, d_src, d_exps, d_codes, rows, cols);
+    return hipGetLastError() == hipSuccess ? HE_OK : HE_ERR_DEVICE;
+}
+
 he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t scratch_floats, int cus, int* unit_rows,
                               int* units_per_workgroup, int* ksplit) {
     if (M < 1 || N < 1 || K < 1 || N % 32 || K % 32 || !unit_rows || !units_per_workgroup || !ksplit) return HE_ERR_INVALID_ARG;
@@ -973,6 +1060,7 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
         for (int l = 0; l < c.n_layers; ++l) {
             bf16_gemm_args a = base;
             if (B > 32) {  // the GEMMs of the wide decode step
+                if (e->w8) return fail(e, HE_ERR_STATE, "he_kernel_sweep: with 8-bit weights only for batches up to 32");
                 if (kernel_class == HE_K_FC1) {
                     a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
                     bf16_gemm_tiled_ksplit(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H,
@@ -989,7 +1077,9 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
             if (kernel_class == HE_K_FC1) {
                 a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
                 int gw1, ks1;
-                bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+                if (e->w8) bf16_store_plan_w8(H, H, e->part_floats, &gw1, &ks1);
+                else bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+                if (e->w8) a.wscale = scales_of(e, l).w1;
                 a.ln_stats = e->ln_stats; a.ln_gw = gw1; a.ln_groups = (H + a.ln_gw - 1) / a.ln_gw; a.ln_cols = H;
                 a.ln_eps = c.ln_eps; a.c1 = cvec_fc1(e, l).c1; a.c2 = cvec_fc1(e, l).c2;
                 bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
@@ -998,7 +1088,9 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
                 // into the residual rows and rewrites the blocks and statistics the next GEMM reads
                 const bool fc2 = kernel_class == HE_K_FC2;
                 int gw, ks;
-                bf16_store_plan(B, H, fc2 ? F : H, e->part_floats, &gw, &ks);
+                if (e->w8) bf16_store_plan_w8(H, fc2 ? F : H, e->part_floats, &gw, &ks);
+                else bf16_store_plan(B, H, fc2 ? F : H, e->part_floats, &gw, &ks);
+                if (e->w8) a.wscale = fc2 ? scales_of(e, l).w2 : scales_of(e, l).wo;
                 a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.resid = e->resid;
                 a.bias = fc2 ? e->layers[l].b2 : e->layers[l].bo;
                 a.gamma = fc2 ? e->layers[l].ln1_g : e->layers[l].ln2_g;

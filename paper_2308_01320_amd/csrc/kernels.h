@@ -61,6 +61,8 @@ struct bf16_gemm_args {
     const void* gamma = nullptr;      // bf16 [N]
     float* stats_out = nullptr;       // [m_tiles][groups][32][2]
     int* counters = nullptr;          // [groups * m_tiles] zeros
+    // 8-bit weights (bf16_gemm_skinny only): Wp holds E4M3 codes in 16-row units, wscale [N] the row scales 2^e
+    const float* wscale = nullptr;
 };
 size_t bf16_tiled_bytes(int rows, int K);
 void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K);
@@ -92,6 +94,14 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
 int bf16_tiled_ksplit(int M, int N, int K);
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                             int ksplit, float* part, size_t part_split, const bf16_gemm_args& a);
+// ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row
+size_t fp8_units_bytes(int rows, int K);  // codes in the half-tile kernel's units: [rows/16][K/64][64 lanes][16 bytes]
+void fp8_row_exponents(hipStream_t s, const void* src, int R, int K, int* exps, float* scales);  // e[n], 2^e[n]
+void fp8_quant_rows(hipStream_t s, const void* src, const int* exps, void* codes, int R, int K);  // row-major codes
+void fp8_quant_units(hipStream_t s, const void* src, const int* exps, void* units, int R, int K);
+// units -> bf16 32x16 blocks (what the tiled GEMMs read); exact
+void fp8_dequant_units(hipStream_t s, const void* units, const float* scales, void* dst_blocks, int R, int K);
+void bf16_store_plan_w8(int N, int K, size_t capacity, int* group_cols, int* ks);
 void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
                   float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids,

@@ -122,6 +122,108 @@ __global__ void tile_rows_lora_kernel(const bf16_t* __restrict__ src, u32x4* __r
     dst[idx] = v;
 }
 
+// ----------------------------------------------------------------- 8-bit weight storage
+//
+// Row n of a weight matrix is kept as E4M3 codes q[n][:] and a power-of-two scale 2^e[n], e[n] the
+// smallest integer with max|W[n][:]| 2^-e[n] <= 448; q = nearest E4M3 value of W 2^-e (ties to even).
+// Scaling by a power of two is exact, so the codes are a rounding decision on the weights' own values.
+
+// one wavefront per row: e[n] and 2^e[n]
+__global__ __launch_bounds__(256) void row_exp_kernel(const bf16_t* __restrict__ src, int R, int K, int* __restrict__ exps,
+                                                      float* __restrict__ scales) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= R) return;
+    float amax = 0.f;
+    for (int k = lane * 8; k < K; k += 512) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(src + (size_t)row * K + k);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[j] << 16)));
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[j] & 0xFFFF0000u)));
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    if (lane == 0) {
+        int x = 0, e = 0;
+        if (amax > 0.f) {
+            const float f = frexpf(amax, &x);  // amax = f 2^x, f in [0.5, 1); 448 = 0.875 2^9
+            e = f <= 0.875f ? x - 9 : x - 8;
+        }
+        exps[row] = e;
+        scales[row] = ldexpf(1.0f, e);
+    }
+}
+
+// eight bf16 values (one 16-byte load) -> eight E4M3 codes
+__device__ __forceinline__ uint2 quant8_e4m3(const u32x4& v, float inv_scale) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float f[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f[2 * j] = __uint_as_float(w[j] << 16) * inv_scale;
+        f[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u) * inv_scale;
+    }
+    int lo = 0, hi = 0;
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], lo, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], hi, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+    return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+// row-major codes (a utility, and what the tests compare bit for bit)
+__global__ void quant_rows_kernel(const bf16_t* __restrict__ src, const int* __restrict__ exps, uint2* __restrict__ codes,
+                                  int R, int K) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)R * (K / 8)) return;
+    const int row = (int)(idx / (K / 8));
+    codes[idx] = quant8_e4m3(reinterpret_cast<const u32x4*>(src)[idx], ldexpf(1.0f, -exps[row]));
+}
+
+// codes in the half-tile kernel's units: [R/16][K/64][64 lanes][16 bytes]
+__global__ void quant_units_kernel(const bf16_t* __restrict__ src, const int* __restrict__ exps, u32x4* __restrict__ dst,
+                                   int R, int K, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int KQ = K >> 6;
+    const int lane = (int)(idx & 63);
+    const int j = (int)((idx >> 6) % KQ), g = (int)((idx >> 6) / KQ);
+    const int row = g * 16 + (lane & 15), k0 = j * 64 + 8 * (lane >> 4);
+    u32x4 out = u32x4{0u, 0u, 0u, 0u};
+    if (row < R) {
+        const float inv = ldexpf(1.0f, -exps[row]);
+        const uint2 a = quant8_e4m3(*reinterpret_cast<const u32x4*>(src + (size_t)row * K + k0), inv);
+        const uint2 b = quant8_e4m3(*reinterpret_cast<const u32x4*>(src + (size_t)row * K + k0 + 32), inv);
+        out = u32x4{a.x, a.y, b.x, b.y};
+    }
+    dst[idx] = out;
+}
+
+// units -> the bf16 32x16 blocks the tiled GEMMs read (the dequantised weights are bf16 values exactly)
+__global__ void dequant_units_kernel(const u32x4* __restrict__ units, const float* __restrict__ scales,
+                                     u32x4* __restrict__ dst, int R, int K, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int KB = K >> 4, KQ = K >> 6;
+    const int lane = (int)(idx & 63);
+    const int kb = (int)((idx >> 6) % KB), rt = (int)((idx >> 6) / KB);
+    const int row = rt * 32 + (lane & 31), k0 = kb * 16 + 8 * (lane >> 5);
+    u32x4 out = u32x4{0u, 0u, 0u, 0u};
+    if (row < R) {
+        const int g = row >> 4, j = k0 >> 6, off = k0 & 63;
+        const u32x4 u = units[((size_t)g * KQ + j) * 64 + 16 * ((off & 31) >> 3) + (row & 15)];
+        const uint32_t c0 = off & 32 ? u.z : u.x, c1 = off & 32 ? u.w : u.y;
+        const float sc = scales[row];
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 f0 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, false), f1 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, true);
+        const f32x2 f2 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, false), f3 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, true);
+        out = u32x4{pack2(f0.x * sc, f0.y * sc), pack2(f1.x * sc, f1.y * sc), pack2(f2.x * sc, f2.y * sc),
+                    pack2(f3.x * sc, f3.y * sc)};
+    }
+    dst[idx] = out;
+}
+
 // ----------------------------------------------------------------- epilogues
 
 struct Epi {
@@ -161,6 +263,9 @@ struct Epi {
     float2* sc_stats;
     float* sc_tgt;
     int sc_parts;
+    // 8-bit weights (half-tile kernel): the accumulators are sums over E4M3 codes; row n of the result
+    // is scaled by wscale[n] = 2^e[n]
+    const float* wscale;
 };
 
 enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3, MODE_STORE_LN = 4, MODE_SCORE = 5 };
@@ -602,46 +707,84 @@ __device__ __forceinline__ f32x4 mfma16_bf16(const u32x4& a, const u32x4& b, f32
                                                    0, 0);
 }
 
-template <int HT, int U>
-struct HalfRegs {
-    u32x4 w[HT][U], xh[2][U], xl[2][U];
-};
-
-template <int HT, int U>
-__device__ __forceinline__ void half_load(HalfRegs<HT, U>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int t = 0; t < HT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * 128);
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            r.xh[mh][u] = xh[u * 128 + mh * 16];
-            r.xl[mh][u] = xl[u * 128 + mh * 16];
-        }
-    }
-#pragma unroll
-    for (int t = 0; t < HT; ++t) w[t] += U * 128;
-    xh += U * 128;
-    xl += U * 128;
+// 16 E4M3 codes -> two bf16 operand registers (exact: an E4M3 value has four significant bits).
+// Bytes 0-7 are the lane's eight k values of the first 32-wide k range, bytes 8-15 those of the second.
+__device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t word, bool upper) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true) : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
+    return (__float_as_uint(f.x) >> 16) | (__float_as_uint(f.y) & 0xFFFF0000u);
+}
+__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4& a1) {
+    a0 = u32x4{e4m3x2_to_bf16x2(w.x, false), e4m3x2_to_bf16x2(w.x, true), e4m3x2_to_bf16x2(w.y, false),
+               e4m3x2_to_bf16x2(w.y, true)};
+    a1 = u32x4{e4m3x2_to_bf16x2(w.z, false), e4m3x2_to_bf16x2(w.z, true), e4m3x2_to_bf16x2(w.w, false),
+               e4m3x2_to_bf16x2(w.w, true)};
 }
 
-template <int HT, int U>
-__device__ __forceinline__ void half_mma(const HalfRegs<HT, U>& r, f32x4 (&acc)[HT][2]) {
+// One loop step of a wavefront covers KU = 1 (bf16 weights) or 2 (8-bit weights: one 16-byte load holds
+// two) k ranges of 32, U steps per round of loads.
+template <int HT, int U, bool W8>
+struct HalfRegs {
+    static constexpr int KU = W8 ? 2 : 1;
+    u32x4 w[HT][U], xh[2][U * KU], xl[2][U * KU];
+};
+
+template <int HT, int U, bool W8>
+__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl) {
+    constexpr int KU = W8 ? 2 : 1, WSTEP = W8 ? 64 : 128;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int t = 0; t < HT; ++t)
+        for (int t = 0; t < HT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * WSTEP);
 #pragma unroll
-            for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+        for (int kp = 0; kp < KU; ++kp)
 #pragma unroll
-        for (int t = 0; t < HT; ++t)
+            for (int mh = 0; mh < 2; ++mh) {
+                r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + mh * 16];
+                r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + mh * 16];
+            }
+    }
 #pragma unroll
-            for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+    for (int t = 0; t < HT; ++t) w[t] += U * WSTEP;
+    xh += U * KU * 128;
+    xl += U * KU * 128;
+}
+
+template <int HT, int U, bool W8>
+__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&acc)[HT][2]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (W8) {
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                u32x4 a[2];
+                e4m3x16_to_bf16(r.w[t][u], a[0], a[1]);
+#pragma unroll
+                for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+                    for (int mh = 0; mh < 2; ++mh) {
+                        acc[t][mh] = mfma16_bf16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
+                        acc[t][mh] = mfma16_bf16(a[kp], r.xl[mh][u * 2 + kp], acc[t][mh]);
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < HT; ++t)
+#pragma unroll
+                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+#pragma unroll
+            for (int t = 0; t < HT; ++t)
+#pragma unroll
+                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+        }
     }
 }
 
 // n_half = number of 16-row units of the weight matrix (N / 16); a workgroup owns HT of them.
-template <int MODE, int HT, int U, int WAVES>
+// W8: the weights are E4M3 codes in units of [16 rows][64 k] -- lane l holds, for row l%16, the eight k
+// values 8 (l/16) + 0..7 of the unit's first 32 k in bytes 0-7 and those of its second 32 k in bytes
+// 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
+template <int MODE, int HT, int U, int WAVES, bool W8>
 __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                                const u32x4* __restrict__ Xlo, int KB, int n_half,
                                                                int ksplit, Epi p) {
@@ -651,7 +794,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
-    const int KP = KB >> 1;  // pairs of k-blocks (32 values of k)
+    constexpr int KU = W8 ? 2 : 1;       // 32-wide k ranges per loop step
+    const int KP = KB / (2 * KU);        // loop steps over the whole of k
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kp0 = (int)(((long)part * KP) / parts), kp1 = (int)(((long)(part + 1) * KP) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV;
@@ -668,19 +812,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
 #pragma unroll
     for (int t = 0; t < HT; ++t) {  // units past the last one are computed from the last one, never stored
         const int g = min(grp * HT + t, n_half - 1);
-        w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
+        if (W8) w[t] = Wp + ((size_t)g * KP + kp0) * 64 + lane;
+        else w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
     }
-    const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * kp0) * 64 + in_pair;
-    const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * kp0) * 64 + in_pair;
+    const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
+    const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
     constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/2, row half item%2
     uint2 bias_w[ITEMS];
-    float4 c1w[ITEMS], c2w[ITEMS];
+    float4 c1w[ITEMS], c2w[ITEMS], wsc[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
         const int n0 = g * 16 + 4 * (lane >> 4);
         const bool live = item < NI && g < n_half;
         bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+        wsc[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (W8 && live) wsc[i] = *reinterpret_cast<const float4*>(p.wscale + n0);
         c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (FOLDABLE && fold && live) {
             c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
@@ -693,22 +840,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     int n = kp1 - kp0;
     if (n >= U) {
-        HalfRegs<HT, U> ra;
-        half_load<HT, U>(ra, w, xh, xl);
+        HalfRegs<HT, U, W8> ra;
+        half_load<HT, U, W8>(ra, w, xh, xl);
         n -= U;
         while (n >= U) {
-            HalfRegs<HT, U> rb;
-            half_load<HT, U>(rb, w, xh, xl);
+            HalfRegs<HT, U, W8> rb;
+            half_load<HT, U, W8>(rb, w, xh, xl);
             n -= U;
-            half_mma<HT, U>(ra, acc);
+            half_mma<HT, U, W8>(ra, acc);
             ra = rb;
         }
-        half_mma<HT, U>(ra, acc);
+        half_mma<HT, U, W8>(ra, acc);
     }
     for (; n > 0; --n) {
-        HalfRegs<HT, 1> r1;
-        half_load<HT, 1>(r1, w, xh, xl);
-        half_mma<HT, 1>(r1, acc);
+        HalfRegs<HT, 1, W8> r1;
+        half_load<HT, 1, W8>(r1, w, xh, xl);
+        half_mma<HT, 1, W8>(r1, acc);
     }
 #pragma unroll
     for (int t = 0; t < HT; ++t)
@@ -730,6 +877,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
                 for (int ww = 0; ww < WAVES; ww += 2) sum += red[ww][item][r][lane] + red[ww + 1][item][r][lane];
             }
             v[i][r] = sum;
+        }
+    }
+    if (W8) {  // sums over codes -> sums over weights: exact, the scales are powers of two
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            v[i][0] *= wsc[i].x; v[i][1] *= wsc[i].y; v[i][2] *= wsc[i].z; v[i][3] *= wsc[i].w;
         }
     }
     if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta; a lane's items sit in two rows
@@ -1806,42 +1959,47 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
     }
 }
 
-template <int MODE, int HT>
+template <int MODE, int HT, bool W8>
 void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles,
                     int ksplit, const Epi& p) {
-    constexpr int U = HT <= 3 ? 4 : 2;
+    // loads per wavefront and round: (HT + 4) U 16-byte loads with bf16 weights, (HT + 8) U with 8-bit ones
+    constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
+    constexpr int KU = W8 ? 2 : 1;
     dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
-    const bool eight = HT <= 4 && (KB / 2) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
-    constexpr size_t kWant = 84 * 1024;                              // one workgroup per CU
+    const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
+    constexpr size_t kWant = 84 * 1024;                                     // one workgroup per CU
     const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
-        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8><<<grid, 512, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
-                                                                              (const u32x4*)Xlo, KB, n_half, ksplit, p);
+        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8, W8><<<grid, 512, pad, s>>>(
+            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
-        gemm_half_kernel<MODE, HT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
-                                                                n_half, ksplit, p);
+        gemm_half_kernel<MODE, HT, U, 4, W8><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo,
+                                                                    KB, n_half, ksplit, p);
     }
 }
 
-constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the half-tile kernel is built for
+constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the half-tile kernel is built for (8-bit: from 1)
 
-template <int MODE>
+template <int MODE, bool W8>
 void launch_half(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles, int ht,
                  int ksplit, const Epi& p) {
     switch (ht) {
-        case 2: launch_half_ht<MODE, 2>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 3: launch_half_ht<MODE, 3>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 4: launch_half_ht<MODE, 4>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 5: launch_half_ht<MODE, 5>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 6: launch_half_ht<MODE, 6>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 7: launch_half_ht<MODE, 7>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 8: launch_half_ht<MODE, 8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 9: launch_half_ht<MODE, 9>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        default: launch_half_ht<MODE, 10>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 1:
+            if constexpr (W8) { launch_half_ht<MODE, 1, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break; }
+            [[fallthrough]];
+        case 2: launch_half_ht<MODE, 2, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 3: launch_half_ht<MODE, 3, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 4: launch_half_ht<MODE, 4, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 5: launch_half_ht<MODE, 5, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 6: launch_half_ht<MODE, 6, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 7: launch_half_ht<MODE, 7, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 8: launch_half_ht<MODE, 8, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 9: launch_half_ht<MODE, 9, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        default: launch_half_ht<MODE, 10, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
     }
 }
 
@@ -1913,6 +2071,28 @@ size_t bf16_tiled_bytes(int rows, int K) { return (size_t)((rows + 31) / 32) * (
 void bf16_tile_rows(hipStream_t s, const void* src, void* dst, int R, int K) {
     const size_t total = (size_t)((R + 31) / 32) * (K / 16) * 64;
     tile_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (u32x4*)dst, R, K, total);
+}
+
+size_t fp8_units_bytes(int rows, int K) { return (size_t)((rows + 15) / 16) * (K / 64) * 1024; }
+
+void fp8_row_exponents(hipStream_t s, const void* src, int R, int K, int* exps, float* scales) {
+    row_exp_kernel<<<(R + 3) / 4, 256, 0, s>>>((const bf16_t*)src, R, K, exps, scales);
+}
+
+void fp8_quant_rows(hipStream_t s, const void* src, const int* exps, void* codes, int R, int K) {
+    const size_t total = (size_t)R * (K / 8);
+    quant_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, exps, (uint2*)codes, R, K);
+}
+
+void fp8_quant_units(hipStream_t s, const void* src, const int* exps, void* units, int R, int K) {
+    const size_t total = (size_t)((R + 15) / 16) * (K / 64) * 64;
+    quant_units_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)src, exps, (u32x4*)units, R, K, total);
+}
+
+void fp8_dequant_units(hipStream_t s, const void* units, const float* scales, void* dst_blocks, int R, int K) {
+    const size_t total = (size_t)((R + 31) / 32) * (K / 16) * 64;
+    dequant_units_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const u32x4*)units, scales, (u32x4*)dst_blocks, R, K,
+                                                                        total);
 }
 
 void bf16_tile_rows_lora(hipStream_t s, const void* src, void* dst, int R, int K, const void* A, const void* B, int rank,
@@ -1988,6 +2168,37 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
     return g;
 }
 
+// 8-bit weights: always the 16-row-unit kernel
+static GemmPlan plan_fused_w8(int N) {
+    const int n_half = N / 16, cus = num_cus();
+    int ht = (n_half + cus - 1) / cus;
+    if (ht > kHalfMax) ht = kHalfMax;
+    return GemmPlan{true, ht < 1 ? 1 : ht, 1};
+}
+
+static GemmPlan plan_store_w8(int N, int K, size_t capacity) {
+    const int n_half = N / 16, kq = K / 64, cus = num_cus();
+    GemmPlan g{true, kHalfMax, 1};
+    double best = 1e30;
+    for (int ht = kHalfMax; ht >= 1; --ht) {
+        const int groups = (n_half + ht - 1) / ht;
+        int ks = cus / groups;
+        if (ks < 1) ks = 1;
+        if (ks > 8) ks = 8;
+        while (ks > 1 && kq / (ks * 4) < 4) --ks;  // at least four 64-wide steps per wavefront
+        if (capacity && (size_t)groups * ks * (size_t)(2 * ht + 7) * 256 > capacity) continue;
+        const double load = (double)ht * 16 / ks * (groups * ks > cus ? (double)(groups * ks + cus - 1) / cus : 1.0);
+        if (load < best * 0.999) { best = load; g = GemmPlan{true, ht, ks}; }
+    }
+    return g;
+}
+
+void bf16_store_plan_w8(int N, int K, size_t capacity, int* group_cols, int* ks) {
+    const GemmPlan g = plan_store_w8(N, K, capacity);
+    *group_cols = g.per_wg * 16;
+    *ks = g.ks;
+}
+
 void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks) {
     const int saved = g_num_cus;
     if (cus > 0) g_num_cus = cus;
@@ -2013,6 +2224,7 @@ static Epi make_epi(int M, int N, const bf16_gemm_args& a) {
     p.ln_stats = (const float2*)a.ln_stats; p.ln_groups = a.ln_groups; p.ln_gw = a.ln_gw; p.ln_cols = a.ln_cols;
     p.ln_eps = a.ln_eps; p.c1 = a.c1; p.c2 = a.c2;
     p.resid = a.resid; p.gamma = (const bf16_t*)a.gamma; p.stats_out = (float2*)a.stats_out; p.counters = a.counters;
+    p.wscale = a.wscale;
     return p;
 }
 
@@ -2021,18 +2233,29 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
     (void)ksplit;
     const Epi p = make_epi(M, N, a);
     const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
+    if (a.wscale) {  // 8-bit weights: Wp holds E4M3 units; one row slice only
+        if (mode == EPI_STORE_LN) {
+            const GemmPlan g = plan_store_w8(N, K, a.out_capacity);
+            launch_half<MODE_STORE_LN, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        } else {
+            const GemmPlan g = plan_fused_w8(N);
+            if (mode == EPI_BIAS_RELU) launch_half<MODE_BIAS_RELU, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+            else launch_half<MODE_QKV, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        }
+        return;
+    }
     if (mode == EPI_STORE_LN) {  // the k-split is the one bf16_store_plan reports for this shape
         const GemmPlan g = plan_store(M, N, K, a.out_capacity);
-        if (g.half) launch_half<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        if (g.half) launch_half<MODE_STORE_LN, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
         else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
         return;
     }
     const GemmPlan g = plan_fused(M, N);
     if (mode == EPI_BIAS_RELU) {
-        if (g.half) launch_half<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        if (g.half) launch_half<MODE_BIAS_RELU, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
         else launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
     } else {
-        if (g.half) launch_half<MODE_QKV>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        if (g.half) launch_half<MODE_QKV, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
         else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
     }
 }
