@@ -92,6 +92,9 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
 // partial sums go to part [ksplit][M][N]; for EPI_STORE the caller's LayerNorm adds them, for the other
 // modes a second kernel adds them and applies the epilogue.
 int bf16_tiled_ksplit(int M, int N, int K);
+// k ranges per tile for a many-row MODE_STORE GEMM whose tiles do not come out in whole rounds of one per CU
+// (1 if they do, or if ks x M x N partial sums do not fit capacity_floats)
+int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats);
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                             int ksplit, float* part, size_t part_split, const bf16_gemm_args& a);
 // ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row

@@ -1016,7 +1016,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int per_xcd = (nitem + 7) / 8;
     const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (item >= nitem) return;
-    const int lin = item / ksplit, ks = item % ksplit;
+    // 256-row tiles: k range after k range, so that the tiles an XCD works on at once still share their panels;
+    // the few tiles of a wide decode step: all k ranges of a tile next to each other
+    const int lin = MW == 4 ? item % nblk : item / ksplit, ks = MW == 4 ? item / nblk : item % ksplit;
     const int GROUP = MW == 4 ? 4 : 8;  // m-tiles per super-row: the 32 tiles an XCD works on at once share their panels
                                         // 4 x 8 (256-row tiles: X panels are twice as heavy as W panels) or 8 x 4
     const int gsize = GROUP * tiles_n;
@@ -2034,7 +2036,8 @@ void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
     const int tiles_n = (N + TN - 1) / TN;
     // 256-row m tiles once they give every CU at least two workgroups' worth of work; else 128-row tiles
     const int big_m = (M + 255) / 256;
-    const bool big = ksplit == 1 && (long)tiles_n * big_m >= 2L * num_cus();
+    // (k ranges of a 256-row tile must hold an even number of k-blocks each: its ring alternates two register sets)
+    const bool big = (long)tiles_n * big_m >= 2L * num_cus() && (ksplit == 1 || KB % (2 * ksplit) == 0);
     const int tiles_m = big ? big_m : (M + TM - 1) / TM;
     const int nitem = tiles_n * tiles_m * ksplit;
     const int grid = ((nitem + 7) / 8) * 8;
@@ -2274,6 +2277,24 @@ int bf16_tiled_ksplit(int M, int N, int K) {
     if (ks > 8) ks = 8;
     while (ks > 1 && stages / ks < 8) --ks;  // keep the ring worth filling
     return ks < 1 ? 1 : ks;
+}
+
+// Many-row MODE_STORE GEMMs (out-projection and FC2 of a prompt pass): the 256x256 tiles come in rounds
+// of one per CU, and a last round that is partly empty costs as much as a full one (640 tiles on 256 CUs:
+// three rounds for the work of two and a half).  Cutting every tile into ks k ranges makes the rounds
+// shorter and the last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
+int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
+    const long cus = num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + 255) / 256);
+    const int KB = K / 16;
+    if (tiles < 2 * cus) return 1;
+    int best = 1;
+    double best_cost = (double)((tiles + cus - 1) / cus);  // in units of one full-K tile
+    for (int ks = 2; ks <= 4; ++ks) {
+        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<4>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
+        const double cost = (double)((tiles * ks + cus - 1) / cus) / ks * (1.0 + 0.02 * ks);
+        if (cost < 0.95 * best_cost) { best_cost = cost; best = ks; }
+    }
+    return best;
 }
 
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
