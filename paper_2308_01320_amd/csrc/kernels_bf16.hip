@@ -21,6 +21,7 @@
 // are bound by the weight stream, so there it costs no time; the prompt pass
 // pays twice the matrix-core work for it.
 #include <algorithm>
+#include <cstdlib>
 
 #include "he_common.h"
 #include "kernels.h"
@@ -974,37 +975,39 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
 // 128x64 sub-tiles (4x2 MFMA tiles each: 8 LDS operand reads feed 16 MFMAs per
 // k-block).  Operands arrive as 1 KiB blocks whose layout is the lane order, so
 // they are moved global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// staging registers) into a ring of four stages of two k-blocks each: loads run
-// three stages (about 3000 MFMA cycles) ahead of the arithmetic, which is what
-// it takes to cover an L2 / infinity-cache round trip; one barrier per stage.
+// staging registers) into a ring of stages; loads run several stages (about 3000
+// MFMA cycles) ahead of the arithmetic, which is what it takes to cover an L2 /
+// infinity-cache round trip; one barrier per stage.
 // Activations are the two-term form here as well (hi and lo blocks against the
 // same weight registers), which keeps keys and values of the prompt within a
 // rounding of the exact ones before they are stored as bf16.
+//
+// Two ring shapes.  PAIR = 0: four stages of two k-blocks (128 KiB), one workgroup per CU -- for launches
+// with fewer tiles than CUs (few rows; the k-split GEMMs of a wide decode step).  PAIR = 1: five stages of
+// one k-block (80 KiB) and at most 256 registers, so that TWO workgroups share a CU: while one of them
+// sits at its barrier, waits for operands or writes its results, the other one's MFMAs keep the matrix
+// cores busy (one workgroup per CU left them idle 40-50 % of the time, and a 256-row tile that moves a
+// quarter less operand data per flop, but fits only once, still 39 %).
 
-constexpr int TN = 256, TM = 128;  // TM: the smaller m tile
-constexpr int TNB = TN / 32;                   // 32-row operand blocks on the n side
-// The m side comes in two sizes: MW = 2 (128 rows per tile, 64 per wavefront) and MW = 4 (256 rows, 128 per
-// wavefront).  The larger tile moves a quarter less operand data per flop through L2, the vector cache
-// and LDS -- what the wavefronts of the smaller one spend 40 % of their time waiting for -- and is used
-// when there are enough rows to fill the chip with it.  The ring: four stages of two k-blocks (32 KiB each),
-// or six stages of one k-block (24 KiB each) -- the same barrier rate per MFMA, and loads that run
-// 4.5 stages = 4600 MFMA cycles ahead: a fifth of the operand blocks comes from HBM, not L2.
-template <int MW> struct TiledShape {
-    static constexpr int TMB = 2 * MW;                          // 32-row operand blocks on the m side
-    static constexpr int TMR = TMB * 32;                        // rows of the m tile
-    static constexpr int KSTAGE = MW == 2 ? 2 : 1;              // k-blocks (16 values of k each) per stage
-    static constexpr int NSTG = MW == 2 ? 4 : 6;                // ring depth
+constexpr int TN = 256, TM = 128;
+constexpr int TNB = TN / 32;   // 32-row operand blocks on the n side
+constexpr int MW = 2;          // 32-row m blocks per wavefront
+template <int PAIR> struct TiledShape {
+    static constexpr int TMB = 2 * MW;                 // 32-row operand blocks on the m side
+    static constexpr int TMR = TMB * 32;               // rows of the m tile
+    static constexpr int KSTAGE = PAIR ? 1 : 2;        // k-blocks (16 values of k each) per stage
+    static constexpr int NSTG = PAIR ? 5 : 4;          // ring depth
     static constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;
 };
 
-template <int MODE, int MW>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+template <int MODE, int PAIR>
+__global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, int ksplit, Epi p) {
     // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
-    constexpr int TMB = TiledShape<MW>::TMB, TMR = TiledShape<MW>::TMR, NSTG = TiledShape<MW>::NSTG;
-    constexpr int KSTAGE = TiledShape<MW>::KSTAGE;
-    constexpr int STAGE_BLOCKS = TiledShape<MW>::STAGE_BLOCKS;
+    constexpr int TMB = TiledShape<PAIR>::TMB, TMR = TiledShape<PAIR>::TMR, NSTG = TiledShape<PAIR>::NSTG;
+    constexpr int KSTAGE = TiledShape<PAIR>::KSTAGE;
+    constexpr int STAGE_BLOCKS = TiledShape<PAIR>::STAGE_BLOCKS;
     __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
@@ -1016,11 +1019,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
     const int per_xcd = (nitem + 7) / 8;
     const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (item >= nitem) return;
-    // 256-row tiles: k range after k range, so that the tiles an XCD works on at once still share their panels;
+    // PAIR: k range after k range, so that the tiles an XCD works on at once still share their panels;
     // the few tiles of a wide decode step: all k ranges of a tile next to each other
-    const int lin = MW == 4 ? item % nblk : item / ksplit, ks = MW == 4 ? item / nblk : item % ksplit;
-    const int GROUP = MW == 4 ? 4 : 8;  // m-tiles per super-row: the 32 tiles an XCD works on at once share their panels
-                                        // 4 x 8 (256-row tiles: X panels are twice as heavy as W panels) or 8 x 4
+    const int lin = PAIR ? item % nblk : item / ksplit, ks = PAIR ? item / nblk : item % ksplit;
+    const int GROUP = 8;  // m-tiles per super-row: the tiles an XCD works on at once (8 x 4, or 8 x 8 when two share
+                          // a CU) use the same few W and X panels
     const int gsize = GROUP * tiles_n;
     const int g = lin / gsize, first_m = g * GROUP;
     const int gm = min(GROUP, tiles_m - first_m);
@@ -1124,7 +1127,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const u32x4* __restrict
             mma_ops(opb);
         }
     } else {
-        // One k-block per stage, an even number of stages (no k-split with this shape): even stages
+        // One k-block per stage, an even number of stages (the launcher sees to that): even stages
         // from A, odd ones from B.  In the steady state a stage is opened while the NSTG-3 stages
         // issued after it are still in flight, and the slot just finished with is refilled.
         constexpr int kAhead = (NSTG - 3) * kLoadsPerStage;
@@ -1227,7 +1230,6 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restr
     if (lane == 0) out[(size_t)(m / S) * (S - 1) + m % S] = tgt[m] - (mx + logf(sum));
 }
 
-constexpr size_t kTiledSmem = 0;
 
 // ----------------------------------------------------------------- LayerNorm (+ residual update)
 //
@@ -2033,20 +2035,18 @@ template <int MODE>
 void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p,
                   int ksplit = 1) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
-    const int tiles_n = (N + TN - 1) / TN;
-    // 256-row m tiles once they give every CU at least two workgroups' worth of work; else 128-row tiles
-    const int big_m = (M + 255) / 256;
-    // (k ranges of a 256-row tile must hold an even number of k-blocks each: its ring alternates two register sets)
-    const bool big = (long)tiles_n * big_m >= 2L * num_cus() && (ksplit == 1 || KB % (2 * ksplit) == 0);
-    const int tiles_m = big ? big_m : (M + TM - 1) / TM;
+    const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
     const int nitem = tiles_n * tiles_m * ksplit;
     const int grid = ((nitem + 7) / 8) * 8;
-    if (big)
-        gemm_tiled_kernel<MODE, 4><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
-                                                                 NT32, MT32, tiles_n, tiles_m, ksplit, p);
+    // two workgroups per CU once there are that many (their k ranges must hold an even number of k-blocks
+    // each: that ring alternates two register sets)
+    const bool pair = nitem >= 2 * num_cus() && KB % (2 * ksplit) == 0;
+    if (pair)
+        gemm_tiled_kernel<MODE, 1><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+                                                        MT32, tiles_n, tiles_m, ksplit, p);
     else
-        gemm_tiled_kernel<MODE, 2><<<grid, 256, kTiledSmem, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB,
-                                                                 NT32, MT32, tiles_n, tiles_m, ksplit, p);
+        gemm_tiled_kernel<MODE, 0><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+                                                        MT32, tiles_n, tiles_m, ksplit, p);
 }
 
 // After a k-split MODE_STORE GEMM whose epilogue needs the whole sum: adds the partial sums in split
@@ -2272,26 +2272,26 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, c
 }
 
 int bf16_tiled_ksplit(int M, int N, int K) {
-    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / TiledShape<2>::KSTAGE;
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / TiledShape<0>::KSTAGE;
     int ks = num_cus() / tiles;
     if (ks > 8) ks = 8;
     while (ks > 1 && stages / ks < 8) --ks;  // keep the ring worth filling
     return ks < 1 ? 1 : ks;
 }
 
-// Many-row MODE_STORE GEMMs (out-projection and FC2 of a prompt pass): the 256x256 tiles come in rounds
-// of one per CU, and a last round that is partly empty costs as much as a full one (640 tiles on 256 CUs:
-// three rounds for the work of two and a half).  Cutting every tile into ks k ranges makes the rounds
-// shorter and the last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
+// Many-row MODE_STORE GEMMs (out-projection and FC2 of a prompt pass): the tiles come in rounds of two per
+// CU, and a last round that is partly empty costs as much as a full one (1280 tiles on 256 CUs: three rounds
+// for the work of two and a half).  Cutting every tile into ks k ranges makes the rounds shorter and the
+// last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
-    const long cus = num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + 255) / 256);
+    const long slots = 2L * num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + TM - 1) / TM);
     const int KB = K / 16;
-    if (tiles < 2 * cus) return 1;
+    if (tiles < slots || KB % 2) return 1;
     int best = 1;
-    double best_cost = (double)((tiles + cus - 1) / cus);  // in units of one full-K tile
+    double best_cost = (double)((tiles + slots - 1) / slots);  // in units of one full-K tile
     for (int ks = 2; ks <= 4; ++ks) {
-        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<4>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
-        const double cost = (double)((tiles * ks + cus - 1) / cus) / ks * (1.0 + 0.02 * ks);
+        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<1>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
+        const double cost = (double)((tiles * ks + slots - 1) / slots) / ks * (1.0 + 0.02 * ks);
         if (cost < 0.95 * best_cost) { best_cost = cost; best = ks; }
     }
     return best;

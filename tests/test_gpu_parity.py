@@ -152,6 +152,7 @@ def test_bf16_shapes(impl, L, H, nh, F, V, B, S, G, tied):
     ("opt-1.3b", 2, 32, 20, 4),   # full decode batch
     ("opt-13b", 2, 4, 131, 3),    # prompt rows span several 128-row tiles plus a ragged tail
     ("opt-13b", 1, 32, 9, 3),     # full decode batch of the headline workload
+    ("opt-13b", 1, 5, 221, 2),    # 1100 prompt rows: QKV and FC1 tiles two to a CU, ragged last tile
     ("opt-6.7b", 2, 16, 64, 3),
     ("opt-13b", 1, 96, 5, 3),     # more than 32 sequences: the decode step on k-split prompt-pass tiles
 ])
