@@ -1,0 +1,215 @@
+// Shared by the bf16-path kernel files for gfx950 (CDNA4, 64-wide wavefronts, MFMA 32x32x16 bf16).
+//
+// Tiled operand layout ("blocks"): a bf16 matrix R[rows, K] is stored as
+// [rows/32][K/16][64 lanes][8 values]; lane = 32*((k%16)/8) + r%32 holds
+// R[r][16*kb + 8*(lane/32) + 0..7].  One block is 1 KiB, contiguous, and is
+// exactly the per-lane register image of one MFMA operand, so a wavefront
+// fetches an operand with a single fully coalesced 16-byte-per-lane load and
+// feeds it to the matrix core with no shuffling.  Weights are tiled once at
+// engine creation; activations are written in this layout by the kernel that
+// produces them (LayerNorm, ReLU epilogue, attention).
+//
+// Every GEMM computes D[n][m] = sum_k W[n][k] X[m][k] with W blocks as the A
+// operand and X blocks as the B operand: lane l then holds, for column
+// m = l%32, rows n = 8*(r/4) + 4*(l/32) + r%4 (r = 0..15 accumulators),
+// i.e. runs of four consecutive n -- what the epilogues store.
+//
+// All
+// GEMM activations are carried as two bf16 terms, x = hi + lo with
+// lo = bf16(x - hi): a second MFMA per block against the same weight registers
+// takes the activation rounding error from 2^-9 to 2^-17.  Decode-shaped GEMMs
+// are bound by the weight stream, so there it costs no time; the prompt pass
+// pays twice the matrix-core work for it.
+#pragma once
+#include <algorithm>
+#include <cstdlib>
+
+#include "he_common.h"
+#include "kernels.h"
+
+namespace he_bf16 {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one lane's 16 bytes of a block
+
+__device__ __forceinline__ f32x16 mfma_bf16(const u32x4& a, const u32x4& b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// x = hi + lo in two bf16 terms
+__device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
+    const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);
+    hi = (uint32_t)ha | ((uint32_t)hb << 16);
+    lo = pack2(a - bf16_to_f32(ha), b - bf16_to_f32(hb));
+}
+
+// index (in 16-byte units) of the slot holding R[r][k0..k0+7], k0 % 8 == 0
+__device__ __forceinline__ size_t block_slot(int r, int k0, int KB) {
+    return ((size_t)(r >> 5) * KB + (k0 >> 4)) * 64 + (((k0 >> 3) & 1) << 5) + (r & 31);
+}
+
+// 16 bytes per lane, global memory -> LDS with no staging registers: lane i's bytes land at lds_block + 16*i
+__device__ __forceinline__ void load_block_to_lds(const u32x4* gsrc_lane, u32x4* lds_block) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc_lane,
+                                     (void __attribute__((address_space(3)))*)lds_block, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// ----------------------------------------------------------------- epilogues
+
+struct Epi {
+    int M, N;               // valid rows (m) and columns (n) of the product
+    const bf16_t* bias;     // [N] or null
+    float* out;             // STORE: partial sums [ksplit][M][N]; QKV: q [M][H]
+    size_t out_split;       // elements between two k-splits of `out`
+    u32x4* out_blocks;      // BIAS_RELU: tiled bf16 [M/32][N/16] blocks (hi term)
+    u32x4* out_blocks_lo;   // BIAS_RELU: lo term, or null
+    bf16_t* kv;             // QKV: the KV arena
+    const he_dev_state* st;
+    int S, layer, H, n_heads, d, max_batch, max_seq;
+    float qscale;
+    // LM head
+    float* logits;          // optional [M][N]
+    float* stats;           // [M][n_tiles][4]: max z, sum exp(z - max), best score, z at best
+    int* stats_idx;         // [M][n_tiles]: id of best score
+    int n_tiles;
+    // LayerNorm folded into this GEMM (BIAS_RELU, QKV, LMHEAD on decode rows): X is gamma * x, not
+    // normalised; ln_stats[(mt*ln_groups + g)*32 + m%32] = (mean, sum of squared deviations) of x[m]
+    // over column group g (ln_gw columns, the last group may be short); c1 = W gamma, c2 = W beta.
+    const float2* ln_stats;  // null: X is already normalised
+    int ln_groups, ln_gw, ln_cols;
+    float ln_eps;
+    const float *c1, *c2;   // [N]
+    // STORE_LN: the workgroup that finishes a column group last adds the k-split partial sums,
+    // bias and residual, and hands the next GEMM gamma * x (out_blocks, out_blocks_lo) and the
+    // group's statistics
+    float* resid;           // [M][N] residual stream, updated in place
+    const bf16_t* gamma;    // [N] gain of the LayerNorm that follows
+    float2* stats_out;      // [m_tiles][groups][32]
+    int* counters;          // [groups][m_tiles], zero between launches
+    // SCORE (tiled LM head over every position): row m = b*S + t is scored on the token that
+    // follows it, ids[m + 1]; sc_stats[m][part] = (max z, sum exp(z - max)) over a 128-wide slice
+    // of the vocabulary, sc_tgt[m] = z at that token
+    const int32_t* ids;
+    float2* sc_stats;
+    float* sc_tgt;
+    int sc_parts;
+    // 8-bit weights (half-tile kernel): the accumulators are sums over E4M3 codes; row n of the result
+    // is scaled by wscale[n] = 2^e[n]
+    const float* wscale;
+};
+
+enum { MODE_STORE = 0, MODE_BIAS_RELU = 1, MODE_QKV = 2, MODE_LMHEAD = 3, MODE_STORE_LN = 4, MODE_SCORE = 5 };
+
+// bias words for outputs n0..n0+3 and the cache length, fetched ahead of the epilogue
+template <int MODE>
+__device__ __forceinline__ uint2 epilogue_bias(const Epi& p, int n0) {
+    if ((MODE == MODE_BIAS_RELU || MODE == MODE_QKV) && n0 < p.N) return *reinterpret_cast<const uint2*>(p.bias + n0);
+    return make_uint2(0, 0);
+}
+template <int MODE>
+__device__ __forceinline__ int epilogue_len(const Epi& p) {
+    return MODE == MODE_QKV ? (p.st->ragged ? -1 : p.st->cur_len) : 0;  // -1: look the sequence up
+}
+
+// four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0); bb = their bias, cur_len = cached positions
+template <int MODE>
+__device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, float v0, float v1, float v2, float v3,
+                                          uint2 bb, int cur_len) {
+    if (m >= p.M || n0 >= p.N) return;  // N is a multiple of 4 wherever this is used
+    if (MODE == MODE_STORE) {
+        *reinterpret_cast<float4*>(p.out + (size_t)ks * p.out_split + (size_t)m * p.N + n0) =
+            make_float4(v0, v1, v2, v3);
+    } else if (MODE == MODE_BIAS_RELU) {
+        v0 = fmaxf(v0 + __uint_as_float(bb.x << 16), 0.f);
+        v1 = fmaxf(v1 + __uint_as_float(bb.x & 0xFFFF0000u), 0.f);
+        v2 = fmaxf(v2 + __uint_as_float(bb.y << 16), 0.f);
+        v3 = fmaxf(v3 + __uint_as_float(bb.y & 0xFFFF0000u), 0.f);
+        const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
+        uint32_t h0, h1, l0, l1;
+        split2(v0, v1, h0, l0);
+        split2(v2, v3, h1, l1);
+        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
+        if (p.out_blocks_lo) reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
+    } else if (MODE == MODE_QKV) {
+        v0 += __uint_as_float(bb.x << 16);
+        v1 += __uint_as_float(bb.x & 0xFFFF0000u);
+        v2 += __uint_as_float(bb.y << 16);
+        v3 += __uint_as_float(bb.y & 0xFFFF0000u);
+        if (n0 < p.H) {
+            *reinterpret_cast<float4*>(p.out + (size_t)m * p.H + n0) =
+                make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
+        } else {
+            const int which = n0 >= 2 * p.H, c = n0 - (which ? 2 * p.H : p.H);
+            const int b = m / p.S;
+            int t = cur_len + (m % p.S);
+            if (cur_len < 0) {  // sequences of different lengths; padding rows append nothing
+                const int tr = m % p.S - row_pad(p.st, b);
+                if (tr < 0) return;
+                t = seq_len(p.st, b) + tr;
+            }
+            bf16_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
+            *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+        }
+    }
+}
+
+// Folded LayerNorm, consumer side: mean and 1/sqrt(var + eps) of row `row` (0..31 of this slice of
+// rows) from the per-column-group statistics the producer left, staged in LDS as
+// [group][32 rows](mean, sum of squared deviations).  Pairwise-update form, pivoted on the first
+// group's mean so that the cross terms stay small.
+__device__ __forceinline__ float2 ln_row_from_groups(const float* lds_stats, int row, const Epi& p) {
+    const float2* gs = reinterpret_cast<const float2*>(lds_stats) + row;
+    const float pivot = gs[0].x;
+    float s1 = 0.f, s2 = 0.f, sm = 0.f;
+    for (int g = 0; g < p.ln_groups; ++g) {
+        const float2 e = gs[g * 32];
+        const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
+        s1 += cnt * dlt;
+        s2 += cnt * dlt * dlt;
+        sm += e.y;
+    }
+    const float inv = 1.0f / (float)p.ln_cols;
+    const float mean = pivot + s1 * inv;
+    const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);
+    return make_float2(mean, 1.0f / sqrtf(var + p.ln_eps));
+}
+
+// Compute units of the current device (256 on an MI355X; also the answer when there is no device).
+inline int num_cus() {
+    static int n_cus = 0;
+    if (n_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        n_cus = n;
+    }
+    return n_cus;
+}
+
+inline Epi make_epi(int M, int N, const bf16_gemm_args& a) {
+    Epi p{};
+    p.M = M; p.N = N; p.bias = (const bf16_t*)a.bias; p.out = a.out; p.out_split = a.out_split;
+    p.out_blocks = (u32x4*)a.out_blocks; p.out_blocks_lo = (u32x4*)a.out_blocks_lo; p.kv = (bf16_t*)a.kv; p.st = a.st;
+    p.S = a.S; p.layer = a.layer; p.H = a.H; p.n_heads = a.n_heads; p.d = a.n_heads ? a.H / a.n_heads : 0;
+    p.max_batch = a.max_batch; p.max_seq = a.max_seq; p.qscale = a.qscale;
+    p.ln_stats = (const float2*)a.ln_stats; p.ln_groups = a.ln_groups; p.ln_gw = a.ln_gw; p.ln_cols = a.ln_cols;
+    p.ln_eps = a.ln_eps; p.c1 = a.c1; p.c2 = a.c2;
+    p.resid = a.resid; p.gamma = (const bf16_t*)a.gamma; p.stats_out = (float2*)a.stats_out; p.counters = a.counters;
+    p.wscale = a.wscale;
+    return p;
+}
+
+}  // namespace he_bf16

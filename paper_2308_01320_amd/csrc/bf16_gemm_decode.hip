@@ -1,0 +1,897 @@
+// bf16 path: the weight-streaming GEMMs of a decode step (at most 32 rows per slice) and the LM head
+// fused with log-softmax and sampling.
+#include "bf16_common.h"
+
+using namespace he_bf16;
+
+namespace {
+
+// ----------------------------------------------------------------- k-split GEMM -> residual rows + next LayerNorm's input
+//
+// Tail of the decode-shaped out-projection / FC2 GEMMs (MODE_STORE_LN), shared by the 32-row and the
+// 16-row kernel.  On entry every thread holds ITEMS quads v[i][0..3]: this workgroup's k-split partial
+// sums of outputs n0[i]..n0[i]+3 of row mrow[i] (live[i]: the quad exists).  rslot[i] says which of the
+// lane's 32/LG rows the quad belongs to: lanes with equal lane % LG hold different columns of the same
+// rows (LG = 32: one row per lane; LG = 16: two).
+//
+// The partial sums cross workgroups (and XCDs, each with an L2 of its own) inside one launch.  They
+// travel as agent-scope atomic words -- written through to, and read from, the level every XCD shares
+// -- so no cache has to be flushed or invalidated (an agent-scope fence does that to whole L2s and cost
+// 45 us per launch).  The words of one (split, item, r) are laid out thread after thread: every access
+// is a contiguous 256 bytes per wavefront.  Each workgroup publishes its partial sums, waits for the
+// stores to be acknowledged and counts itself in; whoever counts last for the column group reads all
+// splits back -- its own included -- and adds them in split order, so the sum does not depend on which
+// workgroup that was.  Nobody waits for anybody: the others are done.  The last one adds bias and
+// residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
+// (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
+// Returns to the caller, who returns.
+template <int ITEMS, int WAVES, int LG>
+__device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, int grp, int groups, int mt, float cnt,
+                                              const float (&v)[ITEMS][4], const int (&mrow)[ITEMS],
+                                              const int (&n0)[ITEMS], const bool (&live)[ITEMS],
+                                              const int (&rslot)[ITEMS]) {
+    constexpr int NSLOT = 32 / LG;
+    __shared__ int s_last;
+    __shared__ float sred[2][WAVES][32];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t cell = (size_t)grp * gridDim.y + mt;
+    constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
+    float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
+    if (ksplit > 1) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (!live[i]) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            s_last = __hip_atomic_fetch_add(p.counters + cell, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ksplit - 1;
+        __syncthreads();
+        if (!s_last) return;
+    }
+    float x[ITEMS][4];
+    float srow[NSLOT];
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) srow[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
+        if (!live[i]) continue;
+        const size_t at = (size_t)mrow[i] * p.N + n0[i];
+        const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0[i]);
+        const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0[i]);
+        float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+        if (ksplit > 1) {
+            float y[8][4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+#pragma unroll
+            for (int k = 1; k < 8; ++k)
+                if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
+        }
+        x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
+        x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
+        x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
+        x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
+        *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+        uint32_t h0, h1, l0, l1;
+        split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+        split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+        const size_t slot = block_slot(mrow[i], n0[i] & ~7, p.N >> 4);
+        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0[i] >> 2) & 1] = make_uint2(h0, h1);
+        reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0[i] >> 2) & 1] = make_uint2(l0, l1);
+        const float part = (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+#pragma unroll
+        for (int r = 0; r < NSLOT; ++r)
+            if (rslot[i] == r) srow[r] += part;
+    }
+    // row sums over the lanes that share a row, then over the wavefronts
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+#pragma unroll
+        for (int o = LG; o < 64; o <<= 1) srow[r] += __shfl_xor(srow[r], o);
+        if (lane < LG) sred[0][wave][LG * r + lane] = srow[r];
+    }
+    __syncthreads();
+    float mean[NSLOT], q[NSLOT];
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+        float tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) tot += sred[0][ww][LG * r + (lane & (LG - 1))];
+        mean[r] = tot / cnt;
+        q[r] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        if (!live[i]) continue;
+#pragma unroll
+        for (int r = 0; r < NSLOT; ++r)
+            if (rslot[i] == r) {
+                const float d0 = x[i][0] - mean[r], d1 = x[i][1] - mean[r], d2 = x[i][2] - mean[r], d3 = x[i][3] - mean[r];
+                q[r] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < NSLOT; ++r) {
+#pragma unroll
+        for (int o = LG; o < 64; o <<= 1) q[r] += __shfl_xor(q[r], o);
+        if (lane < LG) sred[1][wave][LG * r + lane] = q[r];
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        float m2 = 0.f, tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) { m2 += sred[1][ww][lane]; tot += sred[0][ww][lane]; }
+        p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(tot / cnt, m2);
+    }
+    if (threadIdx.x == 0 && ksplit > 1)  // ready for the next launch
+        __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ----------------------------------------------------------------- skinny GEMM (decode, LM head)
+//
+// At most 32 rows per grid.y slice: weights are streamed exactly once from HBM,
+// straight from global memory into MFMA operand registers.  A workgroup of four
+// wavefronts owns NT consecutive 32-row weight tiles and one k-split; its
+// wavefronts divide the k range, keep U blocks per stream in flight (NT weight
+// streams plus the hi and lo activation streams out of L2, which every weight
+// tile reuses from registers), and combine their accumulators through LDS.  The
+// sum over k-splits (STORE mode) is taken, in a fixed order, by the LayerNorm
+// kernel that consumes it.
+//
+// What bounds this kernel is the number of bytes one CU can keep in flight, so
+// the launcher picks NT (and the k-split) to put one equally loaded workgroup on
+// as many of the CUs as the shape allows: more workgroups than CUs double up
+// on some CUs and the whole launch waits for those.
+
+template <int NT, int U>
+struct SkinnyRegs {
+    u32x4 w[NT][U], xh[U], xl[U];
+};
+
+template <int NT, int U>
+__device__ __forceinline__ void skinny_load(SkinnyRegs<NT, U>& r, const u32x4* (&w)[NT], const u32x4*& xh,
+                                            const u32x4*& xl) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * 64);
+        r.xh[u] = xh[u * 64];
+        r.xl[u] = xl[u * 64];
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) w[t] += U * 64;
+    xh += U * 64;
+    xl += U * 64;
+}
+
+template <int NT, int U>
+__device__ __forceinline__ void skinny_mma(const SkinnyRegs<NT, U>& r, f32x16 (&acc)[NT]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xh[u], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xl[u], acc[t]);
+    }
+}
+
+template <int MODE, int NT, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __restrict__ Wp,
+                                                                 const u32x4* __restrict__ Xhi,
+                                                                 const u32x4* __restrict__ Xlo, int KB, int n_tiles,
+                                                                 int ksplit, Epi p) {
+    __shared__ float red[WAVES][NT][16][64];
+    extern __shared__ float dyn_lds[];  // LayerNorm statistics of this slice of rows, when folded
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
+    const int mt = blockIdx.y;
+    const int parts = ksplit * WAVES, part = ks * WAVES + wave;
+    const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
+    constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV || MODE == MODE_LMHEAD;
+    const bool fold = FOLDABLE && p.ln_stats != nullptr;
+    if (fold) {  // statistics go straight to LDS, 1 KiB per instruction; they are read after the k loop
+        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;  // the buffer is padded to this
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
+        for (int c = wave; c < chunks; c += WAVES)
+            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
+    }
+    const u32x4* w[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
+        w[t] = Wp + ((size_t)min(grp * NT + t, n_tiles - 1) * KB + kb0) * 64 + lane;
+    const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
+    const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
+    // After the k loop the NT*4 (tile, row-quad) items of the workgroup are shared out over its
+    // wavefronts: item = wave + i*WAVES -> tile item/4, rows 8*(item%4) + 4*(lane/32) + 0..3.
+    constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
+    // epilogue operands are requested now, long before they are used
+    uint2 bias_w[ITEMS];
+    float4 c1w[ITEMS], c2w[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+        const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+        const bool live = item < NT * 4 && tile < n_tiles;
+        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+        if (FOLDABLE) {
+            c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (fold && live) {  // c1 and c2 are padded to whole tiles
+                c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+                c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+            }
+        }
+    }
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x16{};
+    int n = kb1 - kb0;
+    if (n >= U) {
+        SkinnyRegs<NT, U> ra;
+        skinny_load<NT, U>(ra, w, xh, xl);
+        n -= U;
+        while (n >= U) {
+            SkinnyRegs<NT, U> rb;
+            skinny_load<NT, U>(rb, w, xh, xl);
+            n -= U;
+            skinny_mma<NT, U>(ra, acc);
+            ra = rb;
+        }
+        skinny_mma<NT, U>(ra, acc);
+    }
+    for (; n > 0; --n) {
+        SkinnyRegs<NT, 1> r1;
+        skinny_load<NT, 1>(r1, w, xh, xl);
+        skinny_mma<NT, 1>(r1, acc);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
+    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
+    __syncthreads();
+    const int m = mt * 32 + (lane & 31);
+    float v[ITEMS][4];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, t = item >> 2, q = item & 3;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float sum = 0.f;
+            if (item < NT * 4) {
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ww += 2) sum += red[ww][t][q * 4 + r][lane] + red[ww + 1][t][q * 4 + r][lane];
+            }
+            v[i][r] = sum;
+        }
+    }
+    if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta
+        const float2 mr = ln_row_from_groups(dyn_lds, lane & 31, p);
+        const float mean = mr.x, rstd = mr.y;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
+            v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
+            v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
+            v[i][3] = rstd * (v[i][3] - mean * c1w[i].w) + c2w[i].w;
+        }
+    }
+    if (MODE == MODE_STORE_LN) {
+        int mrow[ITEMS], n0[ITEMS], rslot[ITEMS];
+        bool live[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+            mrow[i] = m;
+            n0[i] = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+            live[i] = item < NT * 4 && tile < n_tiles && m < p.M;
+            rslot[i] = 0;
+        }
+        store_ln_tail<ITEMS, WAVES, 32>(p, ksplit, ks, grp, (n_tiles + NT - 1) / NT, mt,
+                                        32.f * (float)min(NT, n_tiles - grp * NT), v, mrow, n0, live, rslot);
+        return;
+    }
+    float (*zt)[32][33] = reinterpret_cast<float (*)[32][33]>(&red[0][0][0][0]);  // logits tiles reuse the LDS
+    if (MODE == MODE_LMHEAD) __syncthreads();                                      // once every partial is read
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, t = item >> 2, tile = grp * NT + t;
+        const int nl = 8 * (item & 3) + 4 * (lane >> 5);  // first of this lane's four rows inside the tile
+        if (item >= NT * 4) continue;
+        if (MODE != MODE_LMHEAD) {
+            if (tile < n_tiles) epilogue4<MODE>(p, m, tile * 32 + nl, ks, v[i][0], v[i][1], v[i][2], v[i][3], bias_w[i], cur_len);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) zt[t][nl + r][lane & 31] = v[i][r];
+        }
+    }
+    if (MODE == MODE_LMHEAD) {
+        // logits tiles -> per-(row, tile) softmax and arg-max partials
+        __syncthreads();
+        for (int i0 = threadIdx.x; i0 < NT * 32; i0 += WAVES * 64) {
+            const int t = i0 >> 5, mm = mt * 32 + (i0 & 31), tile = grp * NT + t;
+            if (mm >= p.M || tile >= n_tiles) continue;
+            const int mode = p.st->mode, step = p.st->step;
+            const float temp = p.st->temperature;
+            const uint32_t k0 = p.st->seed_lo, k1 = p.st->seed_hi;
+            float mx = -INFINITY, best = -INFINITY, bestz = 0.f;
+            int besti = 0x7FFFFFFF;
+            const int nv = min(32, p.N - tile * 32);
+            for (int i = 0; i < nv; ++i) {
+                const float z = zt[t][i][i0 & 31];
+                const int vid = tile * 32 + i;
+                if (p.logits) p.logits[(size_t)mm * p.N + vid] = z;
+                mx = fmaxf(mx, z);
+                float s = z;
+                if (mode == 1)
+                    s = z / temp + gumbel_from_word(philox_word0((uint32_t)vid, (uint32_t)step, (uint32_t)mm, k0, k1));
+                if (s > best) { best = s; besti = vid; bestz = z; }  // ascending ids: strict > keeps the lowest
+            }
+            float sum = 0.f;
+            for (int i = 0; i < nv; ++i) sum += expf(zt[t][i][i0 & 31] - mx);
+            float* sp = p.stats + ((size_t)mm * p.n_tiles + tile) * 4;
+            sp[0] = mx; sp[1] = sum; sp[2] = best; sp[3] = bestz;
+            p.stats_idx[(size_t)mm * p.n_tiles + tile] = besti;
+        }
+    }
+}
+
+// ----------------------------------------------------------------- skinny GEMM on 16-row units
+//
+// The kernel above hands out weight rows in units of 32, so a launch can only be balanced over
+// the CUs when the number of 32-row tiles happens to divide well: 640 tiles (FC1 of the 13B
+// shape) give 214 workgroups of three, and 42 CUs idle.  This variant hands out units of 16 rows
+// -- 1280 of them are five per CU on all 256 -- using the 16x16x32 matrix instruction: its A
+// operand is 16 rows x 32 k, i.e. one half (rows 0-15 or 16-31) of two consecutive 32x16 blocks,
+// which a wavefront gathers from the unchanged tiled layout as four 256-byte runs (lane l: k-block
+// l/32, k half (l/16)%2, row l%16).  The activations are gathered the same way, 16 of the 32 rows
+// per instruction.  Lane l ends up with D[n = 16 g + 4 (l/16) + 0..3][m = 16 mh + l%16]: four
+// consecutive outputs of one row, as the epilogues want them.  Everything else -- k split over the
+// wavefronts, double-buffered loads, reduction through LDS, folded LayerNorm, last-arriving
+// workgroup for the k-split modes -- is as above.
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16_bf16(const u32x4& a, const u32x4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+// 16 E4M3 codes -> two bf16 operand registers (exact: an E4M3 value has four significant bits).
+// Bytes 0-7 are the lane's eight k values of the first 32-wide k range, bytes 8-15 those of the second.
+__device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t word, bool upper) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true) : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
+    return (__float_as_uint(f.x) >> 16) | (__float_as_uint(f.y) & 0xFFFF0000u);
+}
+__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4& a1) {
+    a0 = u32x4{e4m3x2_to_bf16x2(w.x, false), e4m3x2_to_bf16x2(w.x, true), e4m3x2_to_bf16x2(w.y, false),
+               e4m3x2_to_bf16x2(w.y, true)};
+    a1 = u32x4{e4m3x2_to_bf16x2(w.z, false), e4m3x2_to_bf16x2(w.z, true), e4m3x2_to_bf16x2(w.w, false),
+               e4m3x2_to_bf16x2(w.w, true)};
+}
+
+// One loop step of a wavefront covers KU = 1 (bf16 weights) or 2 (8-bit weights: one 16-byte load holds
+// two) k ranges of 32, U steps per round of loads.
+template <int HT, int U, bool W8>
+struct HalfRegs {
+    static constexpr int KU = W8 ? 2 : 1;
+    u32x4 w[HT][U], xh[2][U * KU], xl[2][U * KU];
+};
+
+template <int HT, int U, bool W8>
+__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl) {
+    constexpr int KU = W8 ? 2 : 1, WSTEP = W8 ? 64 : 128;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int t = 0; t < HT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * WSTEP);
+#pragma unroll
+        for (int kp = 0; kp < KU; ++kp)
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) {
+                r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + mh * 16];
+                r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + mh * 16];
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < HT; ++t) w[t] += U * WSTEP;
+    xh += U * KU * 128;
+    xl += U * KU * 128;
+}
+
+template <int HT, int U, bool W8>
+__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&acc)[HT][2]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (W8) {
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                u32x4 a[2];
+                e4m3x16_to_bf16(r.w[t][u], a[0], a[1]);
+#pragma unroll
+                for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+                    for (int mh = 0; mh < 2; ++mh) {
+                        acc[t][mh] = mfma16_bf16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
+                        acc[t][mh] = mfma16_bf16(a[kp], r.xl[mh][u * 2 + kp], acc[t][mh]);
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < HT; ++t)
+#pragma unroll
+                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+#pragma unroll
+            for (int t = 0; t < HT; ++t)
+#pragma unroll
+                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+        }
+    }
+}
+
+// n_half = number of 16-row units of the weight matrix (N / 16); a workgroup owns HT of them.
+// W8: the weights are E4M3 codes in units of [16 rows][64 k] -- lane l holds, for row l%16, the eight k
+// values 8 (l/16) + 0..7 of the unit's first 32 k in bytes 0-7 and those of its second 32 k in bytes
+// 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
+template <int MODE, int HT, int U, int WAVES, bool W8>
+__global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+                                                               const u32x4* __restrict__ Xlo, int KB, int n_half,
+                                                               int ksplit, Epi p) {
+    constexpr int NI = HT * 2;  // (unit, row half) items of a workgroup
+    __shared__ float red[WAVES][NI][4][64];
+    extern __shared__ float dyn_lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
+    const int mt = blockIdx.y;
+    constexpr int KU = W8 ? 2 : 1;       // 32-wide k ranges per loop step
+    const int KP = KB / (2 * KU);        // loop steps over the whole of k
+    const int parts = ksplit * WAVES, part = ks * WAVES + wave;
+    const int kp0 = (int)(((long)part * KP) / parts), kp1 = (int)(((long)(part + 1) * KP) / parts);
+    constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV;
+    const bool fold = FOLDABLE && p.ln_stats != nullptr;
+    if (fold) {
+        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
+        for (int c = wave; c < chunks; c += WAVES)
+            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
+    }
+    // this lane's 16 bytes inside a pair of 32x16 blocks: k-block lane/32, slot 32*(k half) + row
+    const int in_pair = (lane >> 5) * 64 + 32 * ((lane >> 4) & 1) + (lane & 15);
+    const u32x4* w[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {  // units past the last one are computed from the last one, never stored
+        const int g = min(grp * HT + t, n_half - 1);
+        if (W8) w[t] = Wp + ((size_t)g * KP + kp0) * 64 + lane;
+        else w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
+    }
+    const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
+    const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
+    constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/2, row half item%2
+    uint2 bias_w[ITEMS];
+    float4 c1w[ITEMS], c2w[ITEMS], wsc[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+        const int n0 = g * 16 + 4 * (lane >> 4);
+        const bool live = item < NI && g < n_half;
+        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+        wsc[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (W8 && live) wsc[i] = *reinterpret_cast<const float4*>(p.wscale + n0);
+        c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (FOLDABLE && fold && live) {
+            c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+            c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+        }
+    }
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x4 acc[HT][2];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int n = kp1 - kp0;
+    if (n >= U) {
+        HalfRegs<HT, U, W8> ra;
+        half_load<HT, U, W8>(ra, w, xh, xl);
+        n -= U;
+        while (n >= U) {
+            HalfRegs<HT, U, W8> rb;
+            half_load<HT, U, W8>(rb, w, xh, xl);
+            n -= U;
+            half_mma<HT, U, W8>(ra, acc);
+            ra = rb;
+        }
+        half_mma<HT, U, W8>(ra, acc);
+    }
+    for (; n > 0; --n) {
+        HalfRegs<HT, 1, W8> r1;
+        half_load<HT, 1, W8>(r1, w, xh, xl);
+        half_mma<HT, 1, W8>(r1, acc);
+    }
+#pragma unroll
+    for (int t = 0; t < HT; ++t)
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[wave][t * 2 + mh][r][lane] = acc[t][mh][r];
+    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
+    __syncthreads();
+    float v[ITEMS][4];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float sum = 0.f;
+            if (item < NI) {
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ww += 2) sum += red[ww][item][r][lane] + red[ww + 1][item][r][lane];
+            }
+            v[i][r] = sum;
+        }
+    }
+    if (W8) {  // sums over codes -> sums over weights: exact, the scales are powers of two
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            v[i][0] *= wsc[i].x; v[i][1] *= wsc[i].y; v[i][2] *= wsc[i].z; v[i][3] *= wsc[i].w;
+        }
+    }
+    if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta; a lane's items sit in two rows
+        float2 mr[2];
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) mr[mh] = ln_row_from_groups(dyn_lds, 16 * mh + (lane & 15), p);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int mh = (wave + i * WAVES) & 1;
+            const float mean = mr[mh].x, rstd = mr[mh].y;
+            v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
+            v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
+            v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
+            v[i][3] = rstd * (v[i][3] - mean * c1w[i].w) + c2w[i].w;
+        }
+    }
+    if (MODE == MODE_STORE_LN) {
+        int mrow[ITEMS], n0[ITEMS], rslot[ITEMS];
+        bool live[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+            mrow[i] = mt * 32 + 16 * (item & 1) + (lane & 15);
+            n0[i] = g * 16 + 4 * (lane >> 4);
+            live[i] = item < NI && g < n_half && mrow[i] < p.M;
+            rslot[i] = item & 1;
+        }
+        store_ln_tail<ITEMS, WAVES, 16>(p, ksplit, ks, grp, (n_half + HT - 1) / HT, mt,
+                                        16.f * (float)min(HT, n_half - grp * HT), v, mrow, n0, live, rslot);
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+        if (item >= NI || g >= n_half) continue;
+        epilogue4<MODE>(p, mt * 32 + 16 * (item & 1) + (lane & 15), g * 16 + 4 * (lane >> 4), ks, v[i][0], v[i][1], v[i][2],
+                        v[i][3], bias_w[i], cur_len);
+    }
+}
+
+// One block per sequence: combines the LM-head tile partials in tile order
+// (deterministic), writes token id and its untempered log-probability.
+__global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __restrict__ stats_idx, int n_tiles,
+                                 const he_dev_state* __restrict__ st, int32_t* __restrict__ ids_out,
+                                 float* __restrict__ lp_out, int out_stride, int out_at_step,
+                                 int32_t* __restrict__ cur_ids) {
+    __shared__ float smx[4], ssum[4], sbest[4], sz[4];
+    __shared__ int sidx[4];
+    const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float* sp = stats + (size_t)b * n_tiles * 4;
+    const int* ip = stats_idx + (size_t)b * n_tiles;
+    float mx = -INFINITY;
+    for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) mx = fmaxf(mx, sp[t * 4]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) smx[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
+    float sum = 0.f, best = -INFINITY, bz = 0.f;
+    int bi = 0x7FFFFFFF;
+    for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) {
+        sum += sp[t * 4 + 1] * expf(sp[t * 4] - mx);
+        const float s = sp[t * 4 + 2];
+        const int i = ip[t];
+        if (s > best || (s == best && i < bi)) { best = s; bi = i; bz = sp[t * 4 + 3]; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        sum += __shfl_xor(sum, o);
+        const float os = __shfl_xor(best, o), oz = __shfl_xor(bz, o);
+        const int oi = __shfl_xor(bi, o);
+        if (os > best || (os == best && oi < bi)) { best = os; bi = oi; bz = oz; }
+    }
+    if (lane == 0) { ssum[wave] = sum; sbest[wave] = best; sidx[wave] = bi; sz[wave] = bz; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sum = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+        best = sbest[0]; bi = sidx[0]; bz = sz[0];
+        for (int w = 1; w < 4; ++w)
+            if (sbest[w] > best || (sbest[w] == best && sidx[w] < bi)) { best = sbest[w]; bi = sidx[w]; bz = sz[w]; }
+        const size_t at = (size_t)b * out_stride + (out_at_step ? st->step : 0);
+        ids_out[at] = bi;
+        lp_out[at] = bz - (mx + logf(sum));
+        if (cur_ids) cur_ids[b] = bi;
+    }
+}
+
+// Launch shapes are sized for the current device's CU count, or for the count a planner query names.
+int g_cus_override = 0;
+int plan_cus() { return g_cus_override > 0 ? g_cus_override : num_cus(); }
+
+#ifndef HE_SKINNY_U
+#define HE_SKINNY_U(NT) ((NT) <= 4 ? 4 : 2)
+#endif
+#ifndef HE_SKINNY_W8_MAXNT
+#define HE_SKINNY_W8_MAXNT 2
+#endif
+template <int MODE, int NT>
+void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles,
+                      int m_tiles, int ksplit, const Epi& p) {
+    constexpr int U = HE_SKINNY_U(NT);
+    dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
+    // What bounds a wavefront is its serial chain of load rounds (K/16 blocks / wavefronts / U
+    // rounds, about 1.7 us each under load): eight wavefronts halve the chain when K leaves each
+    // of them two rounds (and their accumulators still fit in LDS for the final reduction).
+    const bool eight = NT <= HE_SKINNY_W8_MAXNT && KB / (ksplit * 8) >= 2 * U;
+    // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
+    // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
+    constexpr size_t kWant = 84 * 1024;
+    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
+    if (eight) {
+        constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_skinny_kernel<MODE, NT <= HE_SKINNY_W8_MAXNT ? NT : 1, U, 8><<<grid, 512, pad, s>>>(
+            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+    } else {
+        constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_skinny_kernel<MODE, NT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
+                                                                  (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+    }
+}
+
+template <int MODE, int HT, bool W8>
+void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles,
+                    int ksplit, const Epi& p) {
+    // loads per wavefront and round: (HT + 4) U 16-byte loads with bf16 weights, (HT + 8) U with 8-bit ones
+    constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
+    constexpr int KU = W8 ? 2 : 1;
+    dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
+    const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
+    constexpr size_t kWant = 84 * 1024;                                     // one workgroup per CU
+    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
+    if (eight) {
+        constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8, W8><<<grid, 512, pad, s>>>(
+            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+    } else {
+        constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
+        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        gemm_half_kernel<MODE, HT, U, 4, W8><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo,
+                                                                    KB, n_half, ksplit, p);
+    }
+}
+
+constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the half-tile kernel is built for (8-bit: from 1)
+
+template <int MODE, bool W8>
+void launch_half(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles, int ht,
+                 int ksplit, const Epi& p) {
+    switch (ht) {
+        case 1:
+            if constexpr (W8) { launch_half_ht<MODE, 1, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break; }
+            [[fallthrough]];
+        case 2: launch_half_ht<MODE, 2, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 3: launch_half_ht<MODE, 3, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 4: launch_half_ht<MODE, 4, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 5: launch_half_ht<MODE, 5, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 6: launch_half_ht<MODE, 6, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 7: launch_half_ht<MODE, 7, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 8: launch_half_ht<MODE, 8, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 9: launch_half_ht<MODE, 9, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        default: launch_half_ht<MODE, 10, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+    }
+}
+
+// nt weight tiles per workgroup (1..8)
+template <int MODE>
+void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles, int m_tiles,
+                   int nt, int ksplit, const Epi& p) {
+    switch (nt) {
+        case 1: launch_skinny_nt<MODE, 1>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 2: launch_skinny_nt<MODE, 2>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 3: launch_skinny_nt<MODE, 3>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 4: launch_skinny_nt<MODE, 4>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 5: launch_skinny_nt<MODE, 5>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 6: launch_skinny_nt<MODE, 6>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 7: launch_skinny_nt<MODE, 7>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        default: launch_skinny_nt<MODE, 8>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+    }
+}
+
+// Tiles per workgroup for a GEMM whose epilogue needs the whole sum in one workgroup: the
+// smallest count that fits all workgroups on the chip at once (one per CU), at most 8.
+int skinny_nt_fused(int n_tiles, int m_tiles) {
+    const int cus = plan_cus();
+    int nt = (n_tiles * m_tiles + cus - 1) / cus;
+    return nt < 1 ? 1 : (nt > 8 ? 8 : nt);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+// Shape of a decode-shaped STORE GEMM: nt tiles per workgroup and ks k-splits such that about one
+// workgroup lands on every CU.  Four tiles per workgroup (activation blocks reused four times)
+// as long as each wavefront keeps 8 k-blocks, else two tiles and half the splits.  (Two tiles and
+// three splits for the 5120x5120 out-projection measured 2 us slower than four and six, more
+// than the LayerNorm that adds up the partial sums gained.)
+static void store_shape(int N, int K, int* nt, int* ks) {
+    const int tiles = (N + 31) / 32, kb = K / 16, cus = plan_cus();
+    int n = 4, groups = (tiles + 3) / 4;
+    int k = cus / groups;
+    if (k < 1) k = 1;
+    if (kb / (k * 4) < 8) {
+        n = 2;
+        groups = (tiles + 1) / 2;
+        k = cus / groups;
+        if (k < 1) k = 1;
+        while (k > 1 && kb / (k * 4) < 8) --k;
+    }
+    if (k > 8) k = 8;
+    *nt = n;
+    *ks = k;
+}
+
+void bf16_store_shape(int M, int N, int K, int* nt, int* ks) {
+    store_shape(N, K, nt, ks);
+    const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
+    if (m_tiles > 1) *nt = *ks > 1 ? 2 : skinny_nt_fused(n_tiles, m_tiles);  // several row slices: keep the launch balanced
+}
+
+// How a decode-shaped GEMM is cut up: weight rows in units of 32 (the skinny kernel) or 16 (the
+// half-tile kernel), `per_wg` units per workgroup, ks k-splits.  The launch waits for its most
+// loaded workgroup, so the plan with the fewest weight bytes per workgroup wins, as long as all of
+// its workgroups fit on the chip at once and every wavefront keeps at least 8 k-blocks.
+struct GemmPlan { bool half; int per_wg, ks; };
+
+static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no k-split
+    const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32, cus = plan_cus();
+    GemmPlan g{false, skinny_nt_fused(n_tiles, m_tiles), 1};
+    if (m_tiles > 1 || N % 16) return g;
+    const int n_half = N / 16, ht = (n_half + cus - 1) / cus;
+    if (ht >= kHalfMin && ht <= kHalfMax && 16 * ht < 32 * g.per_wg) g = GemmPlan{true, ht, 1};
+    return g;
+}
+
+// capacity: floats the k-split scratch can hold (0 = not checked)
+static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
+    GemmPlan g{false, 0, 0};
+    bf16_store_shape(M, N, K, &g.per_wg, &g.ks);
+    if ((M + 31) / 32 > 1 || N % 16) return g;
+    const int n_half = N / 16, kb = K / 16, cus = plan_cus();
+    double best = (double)g.per_wg * 32 / g.ks;  // rows x (k share) per workgroup
+    for (int ht = kHalfMax; ht >= kHalfMin; --ht) {
+        const int groups = (n_half + ht - 1) / ht;
+        int ks = cus / groups;
+        if (ks < 1) continue;
+        if (ks > 8) ks = 8;
+        while (ks > 1 && kb / (ks * 4) < 8) --ks;
+        // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
+        if (capacity && (size_t)groups * ks * (size_t)(2 * ht + 7) * 256 > capacity) continue;
+        const double load = (double)ht * 16 / ks;
+        // fewer, longer k ranges per wavefront cost a 16-row plan some of its balance back (measured on the
+        // 5120x5120 and 5120x20480 shapes: 6 % less load per workgroup ran no faster), so it has to win clearly
+        if (load < best * 0.9) { best = load; g = GemmPlan{true, ht, ks}; }
+    }
+    return g;
+}
+
+// 8-bit weights: always the 16-row-unit kernel
+static GemmPlan plan_fused_w8(int N) {
+    const int n_half = N / 16, cus = plan_cus();
+    int ht = (n_half + cus - 1) / cus;
+    if (ht > kHalfMax) ht = kHalfMax;
+    return GemmPlan{true, ht < 1 ? 1 : ht, 1};
+}
+
+static GemmPlan plan_store_w8(int N, int K, size_t capacity) {
+    const int n_half = N / 16, kq = K / 64, cus = plan_cus();
+    GemmPlan g{true, kHalfMax, 1};
+    double best = 1e30;
+    for (int ht = kHalfMax; ht >= 1; --ht) {
+        const int groups = (n_half + ht - 1) / ht;
+        int ks = cus / groups;
+        if (ks < 1) ks = 1;
+        if (ks > 8) ks = 8;
+        while (ks > 1 && kq / (ks * 4) < 4) --ks;  // at least four 64-wide steps per wavefront
+        if (capacity && (size_t)groups * ks * (size_t)(2 * ht + 7) * 256 > capacity) continue;
+        const double load = (double)ht * 16 / ks * (groups * ks > cus ? (double)(groups * ks + cus - 1) / cus : 1.0);
+        if (load < best * 0.999) { best = load; g = GemmPlan{true, ht, ks}; }
+    }
+    return g;
+}
+
+void bf16_store_plan_w8(int N, int K, size_t capacity, int* group_cols, int* ks) {
+    const GemmPlan g = plan_store_w8(N, K, capacity);
+    *group_cols = g.per_wg * 16;
+    *ks = g.ks;
+}
+
+void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks) {
+    g_cus_override = cus;
+    const GemmPlan g = store ? plan_store(M, N, K, capacity) : plan_fused(M, N);
+    g_cus_override = 0;
+    *unit_rows = g.half ? 16 : 32;
+    *per_wg = g.per_wg;
+    *ks = g.ks;
+}
+
+void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks) {
+    const GemmPlan g = plan_store(M, N, K, capacity);
+    *group_cols = g.per_wg * (g.half ? 16 : 32);
+    *ks = g.ks;
+}
+
+void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                      int ksplit, const bf16_gemm_args& a) {
+    (void)ksplit;
+    const Epi p = make_epi(M, N, a);
+    const int KB = K / 16, n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32;
+    if (a.wscale) {  // 8-bit weights: Wp holds E4M3 units; one row slice only
+        if (mode == EPI_STORE_LN) {
+            const GemmPlan g = plan_store_w8(N, K, a.out_capacity);
+            launch_half<MODE_STORE_LN, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        } else {
+            const GemmPlan g = plan_fused_w8(N);
+            if (mode == EPI_BIAS_RELU) launch_half<MODE_BIAS_RELU, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+            else launch_half<MODE_QKV, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        }
+        return;
+    }
+    if (mode == EPI_STORE_LN) {  // the k-split is the one bf16_store_plan reports for this shape
+        const GemmPlan g = plan_store(M, N, K, a.out_capacity);
+        if (g.half) launch_half<MODE_STORE_LN, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
+        return;
+    }
+    const GemmPlan g = plan_fused(M, N);
+    if (mode == EPI_BIAS_RELU) {
+        if (g.half) launch_half<MODE_BIAS_RELU, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+    } else {
+        if (g.half) launch_half<MODE_QKV, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+    }
+}
+
+void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
+                  const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
+                  float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids, const bf16_gemm_args* fold) {
+    Epi p{};
+    if (fold) p = make_epi(B, V, *fold);
+    p.M = B; p.N = V; p.st = st; p.logits = logits_opt; p.stats = stats; p.stats_idx = stats_idx;
+    p.n_tiles = (V + 31) / 32;
+    const int m_tiles = (B + 31) / 32;
+    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, Xlo, K / 16, p.n_tiles, m_tiles, skinny_nt_fused(p.n_tiles, m_tiles), 1, p);
+    lm_reduce_kernel<<<B, 256, 0, s>>>(stats, stats_idx, p.n_tiles, st, ids_out, lp_out, out_stride, out_at_step,
+                                       cur_ids);
+}
+

@@ -1,0 +1,368 @@
+// bf16 path: the LDS-tiled MFMA GEMM of prompt rows, scoring passes and wide decode steps.
+#include "bf16_common.h"
+
+using namespace he_bf16;
+
+namespace {
+
+// ----------------------------------------------------------------- tiled GEMM (prompt pass)
+//
+// 256 (n) x 128 (m) output tile per workgroup, four wavefronts in a 2x2 grid of
+// 128x64 sub-tiles (4x2 MFMA tiles each: 8 LDS operand reads feed 16 MFMAs per
+// k-block).  Operands arrive as 1 KiB blocks whose layout is the lane order, so
+// they are moved global -> LDS directly (global_load_lds, 16 bytes per lane, no
+// staging registers) into a ring of stages; loads run several stages (about 3000
+// MFMA cycles) ahead of the arithmetic, which is what it takes to cover an L2 /
+// infinity-cache round trip; one barrier per stage.
+// Activations are the two-term form here as well (hi and lo blocks against the
+// same weight registers), which keeps keys and values of the prompt within a
+// rounding of the exact ones before they are stored as bf16.
+//
+// Two ring shapes.  PAIR = 0: four stages of two k-blocks (128 KiB), one workgroup per CU -- for launches
+// with fewer tiles than CUs (few rows; the k-split GEMMs of a wide decode step).  PAIR = 1: five stages of
+// one k-block (80 KiB) and at most 256 registers, so that TWO workgroups share a CU: while one of them
+// sits at its barrier, waits for operands or writes its results, the other one's MFMAs keep the matrix
+// cores busy (one workgroup per CU left them idle 40-50 % of the time, and a 256-row tile that moves a
+// quarter less operand data per flop, but fits only once, still 39 %).
+
+constexpr int TN = 256, TM = 128;
+constexpr int TNB = TN / 32;   // 32-row operand blocks on the n side
+constexpr int MW = 2;          // 32-row m blocks per wavefront
+template <int PAIR> struct TiledShape {
+    static constexpr int TMB = 2 * MW;                 // 32-row operand blocks on the m side
+    static constexpr int TMR = TMB * 32;               // rows of the m tile
+    static constexpr int KSTAGE = PAIR ? 1 : 2;        // k-blocks (16 values of k each) per stage
+    static constexpr int NSTG = PAIR ? 5 : 4;          // ring depth
+    static constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;
+};
+
+template <int MODE, int PAIR>
+__global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+                                                         const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
+                                                         int tiles_n, int tiles_m, int ksplit, Epi p) {
+    // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
+    constexpr int TMB = TiledShape<PAIR>::TMB, TMR = TiledShape<PAIR>::TMR, NSTG = TiledShape<PAIR>::NSTG;
+    constexpr int KSTAGE = TiledShape<PAIR>::KSTAGE;
+    constexpr int STAGE_BLOCKS = TiledShape<PAIR>::STAGE_BLOCKS;
+    __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
+    // contiguous run of tiles; within a run, tiles sharing an m panel are neighbours.  With few
+    // rows (a decode step of a large batch) the tiles alone do not fill the chip: each is then cut
+    // into ksplit k ranges (MODE_STORE only; the partial sums go to separate slots).
+    const int nblk = tiles_n * tiles_m;
+    const int nitem = nblk * ksplit;
+    const int per_xcd = (nitem + 7) / 8;
+    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (item >= nitem) return;
+    // PAIR: k range after k range, so that the tiles an XCD works on at once still share their panels;
+    // the few tiles of a wide decode step: all k ranges of a tile next to each other
+    const int lin = PAIR ? item % nblk : item / ksplit, ks = PAIR ? item / nblk : item % ksplit;
+    const int GROUP = 8;  // m-tiles per super-row: the tiles an XCD works on at once (8 x 4, or 8 x 8 when two share
+                          // a CU) use the same few W and X panels
+    const int gsize = GROUP * tiles_n;
+    const int g = lin / gsize, first_m = g * GROUP;
+    const int gm = min(GROUP, tiles_m - first_m);
+    const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
+
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 32 MW (m) sub-tile
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x16 acc[4][MW];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < MW; ++j) acc[i][j] = f32x16{};
+
+    // this wavefront brings in W row-tiles 2w, 2w+1 and XW row-tiles of X hi and X lo per k-block
+    constexpr int XW = TMB / 4;
+    const u32x4* wsrc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wsrc[i] = Wp + (size_t)min(tn * TNB + wave * 2 + i, NT32 - 1) * KB * 64 + lane;
+    const u32x4 *hsrc[XW], *lsrc[XW];
+#pragma unroll
+    for (int x = 0; x < XW; ++x) {
+        const int xrt = min(tm * TMB + wave * XW + x, MT32 - 1);
+        hsrc[x] = Xhi + (size_t)xrt * KB * 64 + lane;
+        lsrc[x] = Xlo + (size_t)xrt * KB * 64 + lane;
+    }
+    const int nst_all = KB / KSTAGE;  // KB is even (K % 32 == 0)
+    const int st0 = (int)((long)ks * nst_all / ksplit);
+    const int nstage = (int)((long)(ks + 1) * nst_all / ksplit) - st0;  // this workgroup's stages: st0 .. st0+nstage-1
+    {
+        const size_t skip = (size_t)st0 * KSTAGE * 64;
+        wsrc[0] += skip; wsrc[1] += skip;
+#pragma unroll
+        for (int x = 0; x < XW; ++x) { hsrc[x] += skip; lsrc[x] += skip; }
+    }
+    auto issue = [&](int st) {
+        u32x4 (*slot)[64] = ring[st % NSTG];
+#pragma unroll
+        for (int j = 0; j < KSTAGE; ++j) {
+            const size_t off = ((size_t)st * KSTAGE + j) * 64;
+            load_block_to_lds(wsrc[0] + off, &slot[(wave * 2 + 0) * KSTAGE + j][0]);
+            load_block_to_lds(wsrc[1] + off, &slot[(wave * 2 + 1) * KSTAGE + j][0]);
+#pragma unroll
+            for (int x = 0; x < XW; ++x) {
+                load_block_to_lds(hsrc[x] + off, &slot[(TNB + wave * XW + x) * KSTAGE + j][0]);
+                load_block_to_lds(lsrc[x] + off, &slot[(TNB + TMB + wave * XW + x) * KSTAGE + j][0]);
+            }
+        }
+    };
+    constexpr int kLoadsPerStage = (2 + 2 * XW) * KSTAGE;  // per wavefront
+    // operand registers of one k-block: 4 weight blocks, MW activation tiles x (hi, lo)
+    struct Ops { u32x4 a[4], b[2][MW]; };
+    auto read_ops = [&](Ops& o, int st, int j) {
+        u32x4 (*slot)[64] = ring[st % NSTG];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o.a[i] = slot[(wn * 4 + i) * KSTAGE + j][lane];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < MW; ++i) o.b[t][i] = slot[(TNB + t * TMB + wm * MW + i) * KSTAGE + j][lane];
+    };
+    auto mma_ops = [&](const Ops& o) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int jj = 0; jj < MW; ++jj) acc[i][jj] = mfma_bf16(o.a[i], o.b[t][jj], acc[i][jj]);
+            }
+    };
+    // Stage st is usable once this wavefront's own loads of it have landed (at most the loads of the
+    // stages issued after it may still be outstanding) and every other wavefront says the same.
+    auto stage_ready = [&](int st, int last_issued) {
+        const int later = min(last_issued, nstage - 1) - st;  // 0 .. NSTG-2
+        if (later >= 4) wait_vmcnt<4 * kLoadsPerStage>();
+        else if (later == 3) wait_vmcnt<3 * kLoadsPerStage>();
+        else if (later == 2) wait_vmcnt<2 * kLoadsPerStage>();
+        else if (later == 1) wait_vmcnt<kLoadsPerStage>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+    };
+#pragma unroll
+    for (int st = 0; st < NSTG - 1; ++st)
+        if (st < nstage) issue(st);
+    // Two operand register sets, used in turn.  No set is ever copied into the other: a copy would
+    // have to wait for the LDS reads it copies, in the middle of the MFMAs.  A stage's slot is
+    // refilled behind the barrier that every wavefront passes only after its MFMAs of that stage.
+    Ops opa, opb;
+    if constexpr (KSTAGE == 2) {
+        // first k-block of a stage from A while B loads, second from B while A loads from the next
+        // stage; the barrier that opens stage s+1 sits before the last k-block of stage s
+        stage_ready(0, NSTG - 2);
+        read_ops(opa, 0, 0);
+        for (int s = 0; s < nstage; ++s) {
+            read_ops(opb, s, KSTAGE - 1);
+            mma_ops(opa);
+            if (s + 1 < nstage) {
+                stage_ready(s + 1, s + NSTG - 2);
+                if (s + NSTG - 1 < nstage) issue(s + NSTG - 1);
+                read_ops(opa, s + 1, 0);
+            }
+            mma_ops(opb);
+        }
+    } else {
+        // One k-block per stage, an even number of stages (the launcher sees to that): even stages
+        // from A, odd ones from B.  In the steady state a stage is opened while the NSTG-3 stages
+        // issued after it are still in flight, and the slot just finished with is refilled.
+        constexpr int kAhead = (NSTG - 3) * kLoadsPerStage;
+        int s = 0;
+        if (nstage > NSTG) {  // then the prologue has issued NSTG-1 stages
+            wait_vmcnt<(NSTG - 2) * kLoadsPerStage>();
+            __syncthreads();
+            read_ops(opa, 0, 0);
+            for (; s + NSTG < nstage; s += 2) {
+                wait_vmcnt<kAhead>();
+                __syncthreads();
+                issue(s + NSTG - 1);
+                read_ops(opb, s + 1, 0);
+                mma_ops(opa);
+                wait_vmcnt<kAhead>();
+                __syncthreads();
+                issue(s + NSTG);
+                read_ops(opa, s + 2, 0);
+                mma_ops(opb);
+            }
+        }
+        // the last stages: issue the one that may still be missing (into the slot of stage s-1, which
+        // every wavefront has left once it is past the barrier), then one wait covers them all
+        __syncthreads();
+        if (s + NSTG - 1 < nstage) issue(s + NSTG - 1);
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (s == 0) read_ops(opa, 0, 0);
+        for (; s < nstage; s += 2) {
+            read_ops(opb, s + 1, 0);
+            mma_ops(opa);
+            if (s + 2 < nstage) read_ops(opa, s + 2, 0);
+            mma_ops(opb);
+        }
+    }
+    if (MODE == MODE_SCORE) {
+        // The logits never leave the registers: per row, the soft-max partials of this wavefront's
+        // 128 vocabulary entries and, if the row's next token is among them, its logit.
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int m = tm * TMR + (wm * MW + j) * 32 + (lane & 31);
+            int tgt = -1;
+            if (m < p.M && m % p.S != p.S - 1) {
+                tgt = p.ids[m + 1];
+                tgt = tgt < 0 ? 0 : (tgt >= p.N ? p.N - 1 : tgt);  // clamped like the embedding's ids
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = tn * TN + (wn * 4 + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float z = n < p.N ? acc[i][j][r] : -INFINITY;
+                    acc[i][j][r] = z;
+                    mx = fmaxf(mx, z);
+                    if (n == tgt) p.sc_tgt[m] = z;
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            float sum = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sum += expf(acc[i][j][r] - mx);
+            }
+            sum += __shfl_xor(sum, 32);
+            if (lane < 32 && m < p.M) p.sc_stats[(size_t)m * p.sc_parts + tn * 2 + wn] = make_float2(mx, sum);
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int m = tm * TMR + (wm * MW + j) * 32 + (lane & 31);
+            const int nb = tn * TN + (wn * 4 + i) * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                epilogue4<MODE>(p, m, nb + 8 * q, ks, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
+                                acc[i][j][q * 4 + 3], epilogue_bias<MODE>(p, nb + 8 * q), cur_len);
+        }
+}
+
+// One wavefront per scored row: log-sum-exp over the vocabulary slices in slice order, then
+// out[b][t] = z[next token] - lse  (out is [B][S-1]; the last position of a sequence scores nothing).
+__global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restrict__ stats, const float* __restrict__ tgt,
+                                                           int parts, int M, int S, float* __restrict__ out) {
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (m >= M || m % S == S - 1) return;
+    const float2* sp = stats + (size_t)m * parts;
+    float mx = -INFINITY;
+    for (int i = lane; i < parts; i += 64) mx = fmaxf(mx, sp[i].x);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+    for (int i = lane; i < parts; i += 64) {
+        const float2 e = sp[i];
+        if (e.x > -INFINITY) sum += e.y * expf(e.x - mx);
+    }
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) out[(size_t)(m / S) * (S - 1) + m % S] = tgt[m] - (mx + logf(sum));
+}
+
+
+template <int MODE>
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p,
+                  int ksplit = 1) {
+    const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
+    const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
+    const int nitem = tiles_n * tiles_m * ksplit;
+    const int grid = ((nitem + 7) / 8) * 8;
+    // two workgroups per CU once there are that many (their k ranges must hold an even number of k-blocks
+    // each: that ring alternates two register sets)
+    const bool pair = nitem >= 2 * num_cus() && KB % (2 * ksplit) == 0;
+    if (pair)
+        gemm_tiled_kernel<MODE, 1><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+                                                        MT32, tiles_n, tiles_m, ksplit, p);
+    else
+        gemm_tiled_kernel<MODE, 0><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+                                                        MT32, tiles_n, tiles_m, ksplit, p);
+}
+
+// After a k-split MODE_STORE GEMM whose epilogue needs the whole sum: adds the partial sums in split
+// order and applies the epilogue of MODE (bias + ReLU into blocks, or the QKV hand-out).
+template <int MODE>
+__global__ __launch_bounds__(256) void finish_kernel(const float* __restrict__ part, int ksplit, size_t split, Epi p) {
+    const int quads = p.N >> 2;  // N is a multiple of 4 here
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)p.M * quads) return;
+    const int m = (int)(idx / quads), n0 = (int)(idx % quads) * 4;
+    float4 v = *reinterpret_cast<const float4*>(part + (size_t)m * p.N + n0);
+    for (int k = 1; k < ksplit; ++k) {
+        const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * split + (size_t)m * p.N + n0);
+        v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+    }
+    epilogue4<MODE>(p, m, n0, 0, v.x, v.y, v.z, v.w, epilogue_bias<MODE>(p, n0), epilogue_len<MODE>(p));
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                     const bf16_gemm_args& a) {
+    const Epi p = make_epi(M, N, a);
+    if (mode == EPI_STORE) launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+    else if (mode == EPI_BIAS_RELU) launch_tiled<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+    else launch_tiled<MODE_QKV>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+}
+
+int bf16_tiled_ksplit(int M, int N, int K) {
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / TiledShape<0>::KSTAGE;
+    int ks = num_cus() / tiles;
+    if (ks > 8) ks = 8;
+    while (ks > 1 && stages / ks < 8) --ks;  // keep the ring worth filling
+    return ks < 1 ? 1 : ks;
+}
+
+// Many-row MODE_STORE GEMMs (out-projection and FC2 of a prompt pass): the tiles come in rounds of two per
+// CU, and a last round that is partly empty costs as much as a full one (1280 tiles on 256 CUs: three rounds
+// for the work of two and a half).  Cutting every tile into ks k ranges makes the rounds shorter and the
+// last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
+int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
+    const long slots = 2L * num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + TM - 1) / TM);
+    const int KB = K / 16;
+    if (tiles < slots || KB % 2) return 1;
+    int best = 1;
+    double best_cost = (double)((tiles + slots - 1) / slots);  // in units of one full-K tile
+    for (int ks = 2; ks <= 4; ++ks) {
+        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<1>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
+        const double cost = (double)((tiles * ks + slots - 1) / slots) / ks * (1.0 + 0.02 * ks);
+        if (cost < 0.95 * best_cost) { best_cost = cost; best = ks; }
+    }
+    return best;
+}
+
+void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+                            int ksplit, float* part, size_t part_split, const bf16_gemm_args& a) {
+    if (ksplit == 1 && mode != EPI_STORE) {  // the tiles alone fill the chip: the epilogue runs in the GEMM
+        bf16_gemm_tiled(s, mode, Wp, Xhi, Xlo, M, N, K, a);
+        return;
+    }
+    bf16_gemm_args st = a;
+    st.out = part; st.out_split = part_split;
+    const Epi ps = make_epi(M, N, st);
+    launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, ps, ksplit);
+    if (mode == EPI_STORE) return;  // the consumer (a LayerNorm) adds the partial sums
+    const Epi p = make_epi(M, N, a);
+    const unsigned grid = (unsigned)(((size_t)M * (N / 4) + 255) / 256);
+    if (mode == EPI_BIAS_RELU) finish_kernel<MODE_BIAS_RELU><<<grid, 256, 0, s>>>(part, ksplit, part_split, p);
+    else finish_kernel<MODE_QKV><<<grid, 256, 0, s>>>(part, ksplit, part_split, p);
+}
+
+int bf16_score_parts(int V) { return 2 * ((V + TN - 1) / TN); }
+
+void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int M, int S, int V, int K,
+                     const int32_t* ids, float* stats, float* tgt, float* out) {
+    Epi p{};
+    p.M = M; p.N = V; p.S = S; p.ids = ids; p.sc_stats = (float2*)stats; p.sc_tgt = tgt; p.sc_parts = bf16_score_parts(V);
+    launch_tiled<MODE_SCORE>(s, Wp, Xhi, Xlo, K / 16, V, M, p);
+    score_reduce_kernel<<<(M + 3) / 4, 256, 0, s>>>((const float2*)stats, tgt, p.sc_parts, M, S, out);
+}
+

@@ -1,0 +1,303 @@
+// bf16 path: LayerNorm kernels, and the producer side of LayerNorms folded into the next GEMM.
+#include "bf16_common.h"
+
+using namespace he_bf16;
+
+namespace {
+
+// ----------------------------------------------------------------- LayerNorm (+ residual update)
+//
+// Row `src = m*in_mul + in_add`: r += sum of k-split partials + bias (fixed order),
+// written back when asked; a = LayerNorm(r) is emitted as tiled bf16 blocks.
+__global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, const float* __restrict__ part,
+                                                        int ksplit, size_t part_split,
+                                                        const bf16_t* __restrict__ pbias,
+                                                        const bf16_t* __restrict__ gamma,
+                                                        const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
+                                                        u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
+                                                        int in_add, int writeback) {
+    extern __shared__ __align__(16) float row[];
+    __shared__ float red[16];
+    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwave = blockDim.x >> 6;
+    const size_t src = (size_t)m * in_mul + in_add;
+    float4* rr = reinterpret_cast<float4*>(r + src * H);
+    float s = 0.f;
+    for (int i = threadIdx.x; i < H / 4; i += blockDim.x) {
+        float4 v = rr[i];
+        if (part) {
+            for (int k = 0; k < ksplit; ++k) {
+                const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * part_split + src * H + 4 * i);
+                v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+            }
+            const uint2 bb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
+            v.x += __uint_as_float(bb.x << 16); v.y += __uint_as_float(bb.x & 0xFFFF0000u);
+            v.z += __uint_as_float(bb.y << 16); v.w += __uint_as_float(bb.y & 0xFFFF0000u);
+            if (writeback) rr[i] = v;
+        }
+        reinterpret_cast<float4*>(row)[i] = v;
+        s += (v.x + v.y) + (v.z + v.w);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    float tot = 0.f;
+    for (int i = 0; i < nwave; ++i) tot += red[i];
+    const float mean = tot / H;
+    float q = 0.f;
+    for (int i = threadIdx.x; i < H; i += blockDim.x) { const float dlt = row[i] - mean; q += dlt * dlt; }
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    __syncthreads();
+    if (lane == 0) red[wave] = q;
+    __syncthreads();
+    tot = 0.f;
+    for (int i = 0; i < nwave; ++i) tot += red[i];
+    const float rstd = 1.0f / sqrtf(tot / H + eps);
+    const int KB = H >> 4;
+    for (int c = threadIdx.x; c < H / 8; c += blockDim.x) {
+        const int k0 = c * 8;
+        const u32x4 gg = *reinterpret_cast<const u32x4*>(gamma + k0), bb = *reinterpret_cast<const u32x4*>(beta + k0);
+        const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w}, bw[4] = {bb.x, bb.y, bb.z, bb.w};
+        uint32_t o[4], ol[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float e0 = (row[k0 + 2 * j] - mean) * rstd * __uint_as_float(gw[j] << 16) + __uint_as_float(bw[j] << 16);
+            const float e1 = (row[k0 + 2 * j + 1] - mean) * rstd * __uint_as_float(gw[j] & 0xFFFF0000u) +
+                             __uint_as_float(bw[j] & 0xFFFF0000u);
+            split2(e0, e1, o[j], ol[j]);
+        }
+        const size_t slot = block_slot(m, k0, KB);
+        a[slot] = u32x4{o[0], o[1], o[2], o[3]};
+        if (a_lo) a_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+    }
+}
+
+// The same operation with every value of the row held in registers (NV float4 per thread) and all
+// loads -- residual, k-split partials, bias, gamma, beta -- issued before the first reduction.
+// For the few rows of a decode step one 1024-thread workgroup per row (the kernel's time is then the
+// length of its dependent-load chain); for the many rows of a prompt pass 256 threads per row.
+template <int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, const float* __restrict__ part, int ksplit,
+                                                      size_t part_split, const bf16_t* __restrict__ pbias,
+                                                      const bf16_t* __restrict__ gamma,
+                                                      const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
+                                                      u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
+                                                      int in_add, int writeback) {
+    constexpr int NW = THREADS / 64;
+    __shared__ float red[2][NW];
+    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t src = (size_t)m * in_mul + in_add;
+    const int nq = H >> 2;  // float4 per row
+    float4 v[NV];
+    uint2 gg[NV], bb[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * THREADS;
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        gg[j] = bb[j] = make_uint2(0, 0);
+        if (i < nq) {
+            v[j] = *reinterpret_cast<const float4*>(r + src * H + 4 * i);
+            gg[j] = *reinterpret_cast<const uint2*>(gamma + 4 * i);
+            bb[j] = *reinterpret_cast<const uint2*>(beta + 4 * i);
+        }
+    }
+    if (part) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + j * THREADS;
+            if (i >= nq) continue;
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < ksplit; ++k) {  // fixed order: the sum does not depend on scheduling
+                const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * part_split + src * H + 4 * i);
+                acc.x += y.x; acc.y += y.y; acc.z += y.z; acc.w += y.w;
+            }
+            const uint2 pb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
+            v[j].x += acc.x + __uint_as_float(pb.x << 16);
+            v[j].y += acc.y + __uint_as_float(pb.x & 0xFFFF0000u);
+            v[j].z += acc.z + __uint_as_float(pb.y << 16);
+            v[j].w += acc.w + __uint_as_float(pb.y & 0xFFFF0000u);
+            if (writeback) *reinterpret_cast<float4*>(r + src * H + 4 * i) = v[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) s += (v[j].x + v[j].y) + (v[j].z + v[j].w);  // lanes past the row hold zeros
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) red[0][wave] = s;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) tot += red[0][i];
+    const float mean = tot / H;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        if (threadIdx.x + j * THREADS < nq) {
+            const float d0 = v[j].x - mean, d1 = v[j].y - mean, d2 = v[j].z - mean, d3 = v[j].w - mean;
+            q += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    if (lane == 0) red[1][wave] = q;
+    __syncthreads();
+    tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) tot += red[1][i];
+    const float rstd = 1.0f / sqrtf(tot / H + eps);
+    const int KB = H >> 4;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * THREADS;
+        if (i >= nq) continue;
+        const float e0 = (v[j].x - mean) * rstd * __uint_as_float(gg[j].x << 16) + __uint_as_float(bb[j].x << 16);
+        const float e1 = (v[j].y - mean) * rstd * __uint_as_float(gg[j].x & 0xFFFF0000u) + __uint_as_float(bb[j].x & 0xFFFF0000u);
+        const float e2 = (v[j].z - mean) * rstd * __uint_as_float(gg[j].y << 16) + __uint_as_float(bb[j].y << 16);
+        const float e3 = (v[j].w - mean) * rstd * __uint_as_float(gg[j].y & 0xFFFF0000u) + __uint_as_float(bb[j].y & 0xFFFF0000u);
+        uint32_t h0, h1, l0, l1;
+        split2(e0, e1, h0, l0);
+        split2(e2, e3, h1, l1);
+        const int k0 = 4 * i;  // four values: half of a 16-byte slot
+        const size_t slot = block_slot(m, k0 & ~7, KB);
+        reinterpret_cast<uint2*>(a + slot)[(k0 >> 2) & 1] = make_uint2(h0, h1);
+        if (a_lo) reinterpret_cast<uint2*>(a_lo + slot)[(k0 >> 2) & 1] = make_uint2(l0, l1);
+    }
+}
+
+// ----------------------------------------------------------------- LayerNorm folded into the next GEMM (decode rows)
+//
+// For the few rows of a decode step a LayerNorm kernel of its own is all latency.  Instead
+//   W LN(x) + b = rstd * (W (gamma . x) - mean * (W gamma)) + W beta + b,
+// so the kernel that produces x (the embedding below, or the out-projection / FC2 GEMM
+// through its last-arriving workgroup) writes gamma . x as two-term blocks plus per-column-
+// group statistics of x, the consuming GEMM multiplies those blocks by the unchanged bf16
+// weights and applies mean and rstd in its epilogue, and W gamma, W beta are vectors computed
+// once per weight update.
+
+// Row m of a decode step: x = tok_emb[id] + pos_emb[cur_len + pos_offset]; one wavefront per
+// (column group, row), four columns per lane (gw <= 256).
+__global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict__ ids, int id_stride,
+                                                      const bf16_t* __restrict__ tok, const bf16_t* __restrict__ pos,
+                                                      const he_dev_state* __restrict__ st, int V, int pos_offset,
+                                                      int H, int gw, int groups, const bf16_t* __restrict__ gamma,
+                                                      float* __restrict__ r, u32x4* __restrict__ xb,
+                                                      u32x4* __restrict__ xb_lo, float2* __restrict__ stats) {
+    const int g = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
+    int id = ids[(size_t)m * id_stride];
+    id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+    const size_t prow = (size_t)(seq_len(st, m) + pos_offset);  // one row per sequence here
+    const int cols = min(gw, H - g * gw), c0 = g * gw + 4 * lane;
+    const bool live = 4 * lane < cols;
+    float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f;
+    if (live) {
+        const uint2 t = *reinterpret_cast<const uint2*>(tok + (size_t)id * H + c0);
+        const uint2 q = *reinterpret_cast<const uint2*>(pos + prow * H + c0);
+        const uint2 gg = *reinterpret_cast<const uint2*>(gamma + c0);
+        x0 = __uint_as_float(t.x << 16) + __uint_as_float(q.x << 16);
+        x1 = __uint_as_float(t.x & 0xFFFF0000u) + __uint_as_float(q.x & 0xFFFF0000u);
+        x2 = __uint_as_float(t.y << 16) + __uint_as_float(q.y << 16);
+        x3 = __uint_as_float(t.y & 0xFFFF0000u) + __uint_as_float(q.y & 0xFFFF0000u);
+        *reinterpret_cast<float4*>(r + (size_t)m * H + c0) = make_float4(x0, x1, x2, x3);
+        uint32_t h0, h1, l0, l1;
+        split2(x0 * __uint_as_float(gg.x << 16), x1 * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
+        split2(x2 * __uint_as_float(gg.y << 16), x3 * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
+        const size_t slot = block_slot(m, c0 & ~7, H >> 4);
+        reinterpret_cast<uint2*>(xb + slot)[(c0 >> 2) & 1] = make_uint2(h0, h1);
+        reinterpret_cast<uint2*>(xb_lo + slot)[(c0 >> 2) & 1] = make_uint2(l0, l1);
+    }
+    float s = (x0 + x1) + (x2 + x3);
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mean = s / (float)cols;
+    float q2 = 0.f;
+    if (live) {
+        const float d0 = x0 - mean, d1 = x1 - mean, d2 = x2 - mean, d3 = x3 - mean;
+        q2 = (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+    }
+    for (int o = 32; o > 0; o >>= 1) q2 += __shfl_xor(q2, o);
+    if (lane == 0) stats[((size_t)(m >> 5) * groups + g) * 32 + (m & 31)] = make_float2(mean, q2);
+}
+
+// c1[n] = sum_k W[n][k] gamma[k], c2[n] = sum_k W[n][k] beta[k] from the tiled weights: one
+// wavefront per 32-row tile (lane = row and k half), float accumulation in k order.
+__global__ __launch_bounds__(256) void wvec_kernel(const u32x4* __restrict__ Wp, int KB, int n_tiles,
+                                                   const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta,
+                                                   float* __restrict__ c1, float* __restrict__ c2) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile >= n_tiles) return;
+    const u32x4* w = Wp + (size_t)tile * KB * 64 + lane;
+    float a1 = 0.f, a2 = 0.f;
+    for (int kb = 0; kb < KB; ++kb) {
+        const u32x4 wv = w[(size_t)kb * 64];
+        const int k0 = kb * 16 + (lane >> 5) * 8;
+        const u32x4 gv = *reinterpret_cast<const u32x4*>(gamma + k0), bv = *reinterpret_cast<const u32x4*>(beta + k0);
+        const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w}, gg[4] = {gv.x, gv.y, gv.z, gv.w}, bb[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float w0 = __uint_as_float(ww[j] << 16), w1 = __uint_as_float(ww[j] & 0xFFFF0000u);
+            a1 = fmaf(w0, __uint_as_float(gg[j] << 16), a1);
+            a1 = fmaf(w1, __uint_as_float(gg[j] & 0xFFFF0000u), a1);
+            a2 = fmaf(w0, __uint_as_float(bb[j] << 16), a2);
+            a2 = fmaf(w1, __uint_as_float(bb[j] & 0xFFFF0000u), a2);
+        }
+    }
+    a1 += __shfl_xor(a1, 32);
+    a2 += __shfl_xor(a2, 32);
+    if (lane < 32) {  // rows past the matrix are zero blocks: their entries come out zero
+        c1[tile * 32 + lane] = a1;
+        c2[tile * 32 + lane] = a2;
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
+                   const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
+                   void* x_blocks, void* x_blocks_lo, float* stats) {
+    const int groups = (H + gw - 1) / gw;
+    embed_ln_kernel<<<dim3(groups, B), 64, 0, s>>>(ids, id_stride, (const bf16_t*)tok, (const bf16_t*)pos, st, V,
+                                                   pos_offset, H, gw, groups, (const bf16_t*)gamma, r,
+                                                   (u32x4*)x_blocks, (u32x4*)x_blocks_lo, (float2*)stats);
+}
+
+void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2) {
+    const int n_tiles = (N + 31) / 32;
+    wvec_kernel<<<(n_tiles + 3) / 4, 256, 0, s>>>((const u32x4*)Wp, K / 16, n_tiles, (const bf16_t*)gamma,
+                                                  (const bf16_t*)beta, c1, c2);
+}
+
+void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
+             const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
+             int in_mul, int in_add, int writeback) {
+    const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
+#define HE_LN_ROW(NV, T)                                                                                                \
+    ln_row_kernel<NV, T><<<rows, T, 0, s>>>(r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma,    \
+                                            (const bf16_t*)beta, (u32x4*)a_blocks, (u32x4*)a_blocks_lo, H, eps, in_mul, \
+                                            in_add, writeback)
+    if (rows <= 256 && nv <= 3) {  // a decode step
+        if (nv == 1) HE_LN_ROW(1, 1024);
+        else if (nv == 2) HE_LN_ROW(2, 1024);
+        else HE_LN_ROW(3, 1024);
+        return;
+    }
+    if (nv256 <= 10) {  // prompt rows, hidden sizes up to 10240
+        switch (nv256) {
+            case 1: HE_LN_ROW(1, 256); break;
+            case 2: HE_LN_ROW(2, 256); break;
+            case 3: HE_LN_ROW(3, 256); break;
+            case 4: HE_LN_ROW(4, 256); break;
+            case 5: HE_LN_ROW(5, 256); break;
+            case 6: HE_LN_ROW(6, 256); break;
+            case 7: HE_LN_ROW(7, 256); break;
+            case 8: HE_LN_ROW(8, 256); break;
+            case 9: HE_LN_ROW(9, 256); break;
+            default: HE_LN_ROW(10, 256); break;
+        }
+        return;
+    }
+#undef HE_LN_ROW
+    ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
+        r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
+        (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback);
+}
+

@@ -37,7 +37,7 @@ void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint
 void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count);
 
-// ---- bf16 path (kernels_bf16.hip): operands are tiled bf16 blocks, see that file
+// ---- bf16 path (bf16_*.hip): operands are tiled bf16 blocks, see bf16_common.h
 struct bf16_gemm_args {
     const void* bias = nullptr;      // bf16 [N]
     float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
