@@ -38,15 +38,12 @@ __device__ __forceinline__ f32x16 mfma_bf16(const u32x4& a, const u32x4& b, f32x
                                                    0, 0);
 }
 
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return f32x2_to_bf16x2(lo, hi); }
 
 // x = hi + lo in two bf16 terms
 __device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
-    const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);
-    hi = (uint32_t)ha | ((uint32_t)hb << 16);
-    lo = pack2(a - bf16_to_f32(ha), b - bf16_to_f32(hb));
+    hi = pack2(a, b);
+    lo = pack2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
 // index (in 16-byte units) of the slot holding R[r][k0..k0+7], k0 % 8 == 0
@@ -120,7 +117,10 @@ __device__ __forceinline__ uint2 epilogue_bias(const Epi& p, int n0) {
 }
 template <int MODE>
 __device__ __forceinline__ int epilogue_len(const Epi& p) {
-    return MODE == MODE_QKV ? (p.st->ragged ? -1 : p.st->cur_len) : 0;  // -1: look the sequence up
+    if (MODE != MODE_QKV) return 0;
+    // two independent loads and a select: a branch on the first would make the second wait for it
+    const int ragged = p.st->ragged, len = p.st->cur_len;
+    return ragged ? -1 : len;  // -1: look the sequence up
 }
 
 // four consecutive outputs D[n0..n0+3][m] (n0 % 4 == 0); bb = their bias, cur_len = cached positions
@@ -165,21 +165,65 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
     }
 }
 
-// Folded LayerNorm, consumer side: mean and 1/sqrt(var + eps) of row `row` (0..31 of this slice of
-// rows) from the per-column-group statistics the producer left, staged in LDS as
-// [group][32 rows](mean, sum of squared deviations).  Pairwise-update form, pivoted on the first
-// group's mean so that the cross terms stay small.
-__device__ __forceinline__ float2 ln_row_from_groups(const float* lds_stats, int row, const Epi& p) {
-    const float2* gs = reinterpret_cast<const float2*>(lds_stats) + row;
-    const float pivot = gs[0].x;
+// Folded LayerNorm, consumer side: mean and 1/sqrt(var + eps) of each of the 32 rows of a slice from the
+// per-column-group statistics the producer left ([group][32 rows](mean, sum of squared deviations)).
+// Pairwise-update form, pivoted on the first group's mean so that the cross terms stay small.  The work is
+// spread over a workgroup and taken off the tail of the kernel: wavefront w takes the groups
+// g = 2w + lane/32 (mod 2 WAVES), a lane one row of them; the loads are issued (ln_issue) before the first
+// weight loads, the partial sums formed (ln_partial) while those weights are in flight and left in LDS ahead
+// of the barrier that ends the k loop; after it every lane adds the WAVES partial sums of the rows it needs in
+// wavefront order (ln_finish).
+constexpr int kLnBatch = 6;  // statistics a lane keeps in flight; more groups than 2 WAVES kLnBatch are loaded late
+struct LnLoads { float2 e[kLnBatch]; float pivot; };
+
+template <int WAVES>
+__device__ __forceinline__ void ln_issue(LnLoads& L, const Epi& p, int mt, int wave, int lane) {
+    const float2* gs = p.ln_stats + (size_t)mt * p.ln_groups * 32 + (lane & 31);
+    L.pivot = gs[0].x;
+    const int g0 = 2 * wave + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < kLnBatch; ++i) {
+        const int g = g0 + i * 2 * WAVES;
+        L.e[i] = g < p.ln_groups ? gs[(size_t)g * 32] : make_float2(0.f, 0.f);
+    }
+}
+
+// lnp: [WAVES][4][32] floats of LDS
+template <int WAVES>
+__device__ __forceinline__ void ln_partial(const LnLoads& L, const Epi& p, int mt, int wave, int lane, float* lnp) {
+    const int g0 = 2 * wave + (lane >> 5);
     float s1 = 0.f, s2 = 0.f, sm = 0.f;
-    for (int g = 0; g < p.ln_groups; ++g) {
-        const float2 e = gs[g * 32];
-        const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - pivot;
+    auto add = [&](int g, float2 e) {
+        const float cnt = (float)min(p.ln_gw, p.ln_cols - g * p.ln_gw), dlt = e.x - L.pivot;
         s1 += cnt * dlt;
         s2 += cnt * dlt * dlt;
         sm += e.y;
+    };
+#pragma unroll
+    for (int i = 0; i < kLnBatch; ++i) {
+        const int g = g0 + i * 2 * WAVES;
+        if (g < p.ln_groups) add(g, L.e[i]);
     }
+    const float2* gs = p.ln_stats + (size_t)mt * p.ln_groups * 32 + (lane & 31);
+    for (int g = g0 + kLnBatch * 2 * WAVES; g < p.ln_groups; g += 2 * WAVES) add(g, gs[(size_t)g * 32]);
+    s1 += __shfl_xor(s1, 32);
+    s2 += __shfl_xor(s2, 32);
+    sm += __shfl_xor(sm, 32);
+    if (lane < 32) {
+        float* o = lnp + wave * 4 * 32 + lane;
+        o[0] = s1; o[32] = s2; o[64] = sm; o[96] = L.pivot;
+    }
+}
+
+template <int WAVES>
+__device__ __forceinline__ float2 ln_finish(const float* lnp, int row, const Epi& p) {
+    float s1 = 0.f, s2 = 0.f, sm = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        const float* o = lnp + w * 4 * 32 + row;
+        s1 += o[0]; s2 += o[32]; sm += o[64];
+    }
+    const float pivot = lnp[96 + row];
     const float inv = 1.0f / (float)p.ln_cols;
     const float mean = pivot + s1 * inv;
     const float var = fmaxf((sm + s2 - s1 * s1 * inv) * inv, 0.f);

@@ -17,10 +17,10 @@ namespace {
 // The partial sums cross workgroups (and XCDs, each with an L2 of its own) inside one launch.  They
 // travel as agent-scope atomic words -- written through to, and read from, the level every XCD shares
 // -- so no cache has to be flushed or invalidated (an agent-scope fence does that to whole L2s and cost
-// 45 us per launch).  The words of one (split, item, r) are laid out thread after thread: every access
-// is a contiguous 256 bytes per wavefront.  Each workgroup publishes its partial sums, waits for the
-// stores to be acknowledged and counts itself in; whoever counts last for the column group reads all
-// splits back -- its own included -- and adds them in split order, so the sum does not depend on which
+// 45 us per launch).  The 64-bit words of one (split, item, pair) are laid out thread after thread: every
+// access is a contiguous 512 bytes per wavefront.  Each workgroup publishes its partial sums, waits for the
+// stores to be acknowledged and counts itself in; whoever counts last for the column group reads the other
+// splits back and adds them, together with its own, in split order, so the sum does not depend on which
 // workgroup that was.  Nobody waits for anybody: the others are done.  The last one adds bias and
 // residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
 // (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
@@ -36,15 +36,19 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const size_t cell = (size_t)grp * gridDim.y + mt;
     constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
-    float* scratch = p.out + cell * ksplit * kPer + threadIdx.x;
+    // 64-bit words (two sums each): a wavefront can have 63 loads outstanding, and the wider they are, the more
+    // of the last workgroup's read-back is in flight at once
+    uint64_t* scratch = reinterpret_cast<uint64_t*>(p.out + cell * ksplit * kPer) + threadIdx.x;
+    constexpr size_t kPer2 = kPer / 2;
+    auto pair_bits = [](float a, float b) { return (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32); };
     if (ksplit > 1) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             if (!live[i]) continue;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                __hip_atomic_store(scratch + (ks * kPer + (size_t)(i * 4 + r) * WAVES * 64), v[i][r], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            for (int h = 0; h < 2; ++h)
+                __hip_atomic_store(scratch + (ks * kPer2 + (size_t)(i * 2 + h) * WAVES * 64), pair_bits(v[i][2 * h], v[i][2 * h + 1]),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -57,43 +61,75 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
     float srow[NSLOT];
 #pragma unroll
     for (int r = 0; r < NSLOT; ++r) srow[r] = 0.f;
+    // The splits' partial sums come from the level all XCDs share, a microsecond or two away.  All loads of
+    // a chunk of items are issued before anything is stored: with loads and stores outstanding together the
+    // hardware counter no longer tells which have returned, and every wait would drain them all.
+    constexpr int CH = ITEMS < 4 ? ITEMS : 4;
+    auto lo32 = [](uint64_t w) { return __uint_as_float((uint32_t)w); };
+    auto hi32 = [](uint64_t w) { return __uint_as_float((uint32_t)(w >> 32)); };
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
-        if (!live[i]) continue;
-        const size_t at = (size_t)mrow[i] * p.N + n0[i];
-        const float4 rr = *reinterpret_cast<const float4*>(p.resid + at);
-        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0[i]);
-        const uint2 gg = *reinterpret_cast<const uint2*>(p.gamma + n0[i]);
-        float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
-        if (ksplit > 1) {
-            float y[8][4];
+    for (int c0 = 0; c0 < ITEMS; c0 += CH) {
+        uint64_t y[CH][8][2];
+        float4 rr[CH];
+        uint2 bb[CH], gg[CH];
+        uint2 hh[CH], ll[CH];
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
+        for (int c = 0; c < CH; ++c) {
+            const int i = c0 + c;
+            if (i >= ITEMS || !live[i]) continue;
+            rr[c] = *reinterpret_cast<const float4*>(p.resid + (size_t)mrow[i] * p.N + n0[i]);
+            bb[c] = *reinterpret_cast<const uint2*>(p.bias + n0[i]);
+            gg[c] = *reinterpret_cast<const uint2*>(p.gamma + n0[i]);
+            if (ksplit > 1) {  // the other splits; this workgroup's own sums are still in its registers
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    y[k][r] = __hip_atomic_load(scratch + (min(k, ksplit - 1) * kPer + (size_t)(i * 4 + r) * WAVES * 64),
-                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            tot = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+                for (int k = 0; k < 8; ++k) {
+                    y[c][k][0] = pair_bits(v[i][0], v[i][1]);
+                    y[c][k][1] = pair_bits(v[i][2], v[i][3]);
+                    if (k < ksplit && k != ks) {
 #pragma unroll
-            for (int k = 1; k < 8; ++k)
-                if (k < ksplit) { tot.x += y[k][0]; tot.y += y[k][1]; tot.z += y[k][2]; tot.w += y[k][3]; }
+                        for (int h = 0; h < 2; ++h)
+                            y[c][k][h] = __hip_atomic_load(scratch + (k * kPer2 + (size_t)(i * 2 + h) * WAVES * 64),
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
         }
-        x[i][0] = rr.x + (tot.x + __uint_as_float(bb.x << 16));
-        x[i][1] = rr.y + (tot.y + __uint_as_float(bb.x & 0xFFFF0000u));
-        x[i][2] = rr.z + (tot.z + __uint_as_float(bb.y << 16));
-        x[i][3] = rr.w + (tot.w + __uint_as_float(bb.y & 0xFFFF0000u));
-        *reinterpret_cast<float4*>(p.resid + at) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
-        uint32_t h0, h1, l0, l1;
-        split2(x[i][0] * __uint_as_float(gg.x << 16), x[i][1] * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
-        split2(x[i][2] * __uint_as_float(gg.y << 16), x[i][3] * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
-        const size_t slot = block_slot(mrow[i], n0[i] & ~7, p.N >> 4);
-        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0[i] >> 2) & 1] = make_uint2(h0, h1);
-        reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0[i] >> 2) & 1] = make_uint2(l0, l1);
-        const float part = (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
 #pragma unroll
-        for (int r = 0; r < NSLOT; ++r)
-            if (rslot[i] == r) srow[r] += part;
+        for (int c = 0; c < CH; ++c) {
+            const int i = c0 + c;
+            if (i >= ITEMS) continue;
+            x[i][0] = x[i][1] = x[i][2] = x[i][3] = 0.f;
+            if (!live[i]) continue;
+            float4 tot = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+            if (ksplit > 1) {  // in split order, whichever split this workgroup was
+                tot = make_float4(lo32(y[c][0][0]), hi32(y[c][0][0]), lo32(y[c][0][1]), hi32(y[c][0][1]));
+#pragma unroll
+                for (int k = 1; k < 8; ++k)
+                    if (k < ksplit) {
+                        tot.x += lo32(y[c][k][0]); tot.y += hi32(y[c][k][0]);
+                        tot.z += lo32(y[c][k][1]); tot.w += hi32(y[c][k][1]);
+                    }
+            }
+            x[i][0] = rr[c].x + (tot.x + __uint_as_float(bb[c].x << 16));
+            x[i][1] = rr[c].y + (tot.y + __uint_as_float(bb[c].x & 0xFFFF0000u));
+            x[i][2] = rr[c].z + (tot.z + __uint_as_float(bb[c].y << 16));
+            x[i][3] = rr[c].w + (tot.w + __uint_as_float(bb[c].y & 0xFFFF0000u));
+            split2(x[i][0] * __uint_as_float(gg[c].x << 16), x[i][1] * __uint_as_float(gg[c].x & 0xFFFF0000u), hh[c].x, ll[c].x);
+            split2(x[i][2] * __uint_as_float(gg[c].y << 16), x[i][3] * __uint_as_float(gg[c].y & 0xFFFF0000u), hh[c].y, ll[c].y);
+            const float part = (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
+#pragma unroll
+            for (int r = 0; r < NSLOT; ++r)
+                if (rslot[i] == r) srow[r] += part;
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i = c0 + c;
+            if (i >= ITEMS || !live[i]) continue;
+            *reinterpret_cast<float4*>(p.resid + (size_t)mrow[i] * p.N + n0[i]) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            const size_t slot = block_slot(mrow[i], n0[i] & ~7, p.N >> 4);
+            reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0[i] >> 2) & 1] = hh[c];
+            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0[i] >> 2) & 1] = ll[c];
+        }
     }
     // row sums over the lanes that share a row, then over the wavefronts
 #pragma unroll
@@ -193,7 +229,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
                                                                  const u32x4* __restrict__ Xlo, int KB, int n_tiles,
                                                                  int ksplit, Epi p) {
     __shared__ float red[WAVES][NT][16][64];
-    extern __shared__ float dyn_lds[];  // LayerNorm statistics of this slice of rows, when folded
+    __shared__ float lnp[WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
@@ -201,12 +237,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV || MODE == MODE_LMHEAD;
     const bool fold = FOLDABLE && p.ln_stats != nullptr;
-    if (fold) {  // statistics go straight to LDS, 1 KiB per instruction; they are read after the k loop
-        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;  // the buffer is padded to this
-        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
-        for (int c = wave; c < chunks; c += WAVES)
-            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
-    }
+    LnLoads lnl;
+    if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);  // requested ahead of the weights, used once those are in flight
     const u32x4* w[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
@@ -233,7 +265,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
             }
         }
     }
-    const int cur_len = epilogue_len<MODE>(p);
+    int cur_len = 0;  // read from the device state once the first weights are on their way: nothing before them waits for it
     f32x16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x16{};
@@ -242,6 +274,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         SkinnyRegs<NT, U> ra;
         skinny_load<NT, U>(ra, w, xh, xl);
         n -= U;
+        cur_len = epilogue_len<MODE>(p);
+        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
         while (n >= U) {
             SkinnyRegs<NT, U> rb;
             skinny_load<NT, U>(rb, w, xh, xl);
@@ -250,6 +284,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
             ra = rb;
         }
         skinny_mma<NT, U>(ra, acc);
+    } else {
+        cur_len = epilogue_len<MODE>(p);
+        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
     }
     for (; n > 0; --n) {
         SkinnyRegs<NT, 1> r1;
@@ -260,7 +297,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
-    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
     __syncthreads();
     const int m = mt * 32 + (lane & 31);
     float v[ITEMS][4];
@@ -278,7 +314,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         }
     }
     if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta
-        const float2 mr = ln_row_from_groups(dyn_lds, lane & 31, p);
+        const float2 mr = ln_finish<WAVES>(lnp, lane & 31, p);
         const float mean = mr.x, rstd = mr.y;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
@@ -452,7 +488,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
                                                                int ksplit, Epi p) {
     constexpr int NI = HT * 2;  // (unit, row half) items of a workgroup
     __shared__ float red[WAVES][NI][4][64];
-    extern __shared__ float dyn_lds[];
+    __shared__ float lnp[WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
     const int mt = blockIdx.y;
@@ -462,12 +498,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     const int kp0 = (int)(((long)part * KP) / parts), kp1 = (int)(((long)(part + 1) * KP) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV;
     const bool fold = FOLDABLE && p.ln_stats != nullptr;
-    if (fold) {
-        const int chunks = (p.ln_groups * 32 * (int)sizeof(float2) + 1023) >> 10;
-        const u32x4* src = reinterpret_cast<const u32x4*>(p.ln_stats + (size_t)mt * p.ln_groups * 32);
-        for (int c = wave; c < chunks; c += WAVES)
-            load_block_to_lds(src + c * 64 + lane, reinterpret_cast<u32x4*>(dyn_lds) + c * 64);
-    }
+    LnLoads lnl;
+    if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);  // requested ahead of the weights, used once those are in flight
     // this lane's 16 bytes inside a pair of 32x16 blocks: k-block lane/32, slot 32*(k half) + row
     const int in_pair = (lane >> 5) * 64 + 32 * ((lane >> 4) & 1) + (lane & 15);
     const u32x4* w[HT];
@@ -496,7 +528,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
             c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
         }
     }
-    const int cur_len = epilogue_len<MODE>(p);
+    int cur_len = 0;  // read once the first weights are on their way
     f32x4 acc[HT][2];
 #pragma unroll
     for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -505,6 +537,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         HalfRegs<HT, U, W8> ra;
         half_load<HT, U, W8>(ra, w, xh, xl);
         n -= U;
+        cur_len = epilogue_len<MODE>(p);
+        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
         while (n >= U) {
             HalfRegs<HT, U, W8> rb;
             half_load<HT, U, W8>(rb, w, xh, xl);
@@ -513,6 +547,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
             ra = rb;
         }
         half_mma<HT, U, W8>(ra, acc);
+    } else {
+        cur_len = epilogue_len<MODE>(p);
+        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
     }
     for (; n > 0; --n) {
         HalfRegs<HT, 1, W8> r1;
@@ -525,7 +562,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
             for (int r = 0; r < 4; ++r) red[wave][t * 2 + mh][r][lane] = acc[t][mh][r];
-    if (FOLDABLE) wait_vmcnt<0>();  // the statistics have landed in LDS
     __syncthreads();
     float v[ITEMS][4];
 #pragma unroll
@@ -548,13 +584,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         }
     }
     if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta; a lane's items sit in two rows
-        float2 mr[2];
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) mr[mh] = ln_row_from_groups(dyn_lds, 16 * mh + (lane & 15), p);
+        // (selected, not indexed: an array indexed at run time would live in LDS, whose addressing
+        // reads the dispatch packet -- microseconds, here in the tail of the kernel)
+        const float2 mr0 = ln_finish<WAVES>(lnp, lane & 15, p), mr1 = ln_finish<WAVES>(lnp, 16 + (lane & 15), p);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int mh = (wave + i * WAVES) & 1;
-            const float mean = mr[mh].x, rstd = mr[mh].y;
+            const bool odd = (wave + i * WAVES) & 1;
+            const float mean = odd ? mr1.x : mr0.x, rstd = odd ? mr1.y : mr0.y;
             v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
             v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
             v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
@@ -652,15 +688,14 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
     // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
     // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
     constexpr size_t kWant = 84 * 1024;
-    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
-        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_skinny_kernel<MODE, NT <= HE_SKINNY_W8_MAXNT ? NT : 1, U, 8><<<grid, 512, pad, s>>>(
             (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
-        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_skinny_kernel<MODE, NT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
                                                                   (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
     }
@@ -675,15 +710,14 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
     dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
     const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
     constexpr size_t kWant = 84 * 1024;                                     // one workgroup per CU
-    const size_t ln_bytes = p.ln_stats ? (((size_t)p.ln_groups * 32 * sizeof(float2) + 1023) & ~(size_t)1023) : 0;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
-        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8, W8><<<grid, 512, pad, s>>>(
             (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
-        const size_t pad = std::max(kStatic >= kWant ? 0 : kWant - kStatic, ln_bytes);
+        const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_half_kernel<MODE, HT, U, 4, W8><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo,
                                                                     KB, n_half, ksplit, p);
     }

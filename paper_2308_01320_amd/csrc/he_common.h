@@ -38,13 +38,15 @@ __device__ __forceinline__ bool seq_done(const he_dev_state* st, int b) {
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x40);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// Two floats -> two bf16 in one word (first argument in the low half), round to nearest, ties to even:
+// the hardware's packed conversion, one instruction for the pair.
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+    typedef float he_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 he_bf16x2 __attribute__((ext_vector_type(2)));
+    const he_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, he_bf16x2));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(f32x2_to_bf16x2(f, 0.f) & 0xFFFFu); }
 
 __device__ __forceinline__ float ld_f32(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_f32(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
