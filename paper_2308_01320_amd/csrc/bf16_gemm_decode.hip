@@ -275,7 +275,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         skinny_load<NT, U>(ra, w, xh, xl);
         n -= U;
         cur_len = epilogue_len<MODE>(p);
-        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+        // the statistics are used once the second round is on its way as well (first trip peeled off
+        // the loop: a test inside it cost the loop its schedule)
+        if (n >= U) {
+            SkinnyRegs<NT, U> rb;
+            skinny_load<NT, U>(rb, w, xh, xl);
+            n -= U;
+            if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+            skinny_mma<NT, U>(ra, acc);
+            ra = rb;
+        } else if (fold) {
+            ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+        }
         while (n >= U) {
             SkinnyRegs<NT, U> rb;
             skinny_load<NT, U>(rb, w, xh, xl);
@@ -538,7 +549,17 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         half_load<HT, U, W8>(ra, w, xh, xl);
         n -= U;
         cur_len = epilogue_len<MODE>(p);
-        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+        // the statistics are used once the second round is on its way as well (first trip peeled off the loop)
+        if (n >= U) {
+            HalfRegs<HT, U, W8> rb;
+            half_load<HT, U, W8>(rb, w, xh, xl);
+            n -= U;
+            if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+            half_mma<HT, U, W8>(ra, acc);
+            ra = rb;
+        } else if (fold) {
+            ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+        }
         while (n >= U) {
             HalfRegs<HT, U, W8> rb;
             half_load<HT, U, W8>(rb, w, xh, xl);
