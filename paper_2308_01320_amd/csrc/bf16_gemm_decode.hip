@@ -236,9 +236,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV || MODE == MODE_LMHEAD;
-    const bool fold = FOLDABLE && p.ln_stats != nullptr;
-    LnLoads lnl;
-    if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);  // requested ahead of the weights, used once those are in flight
     const u32x4* w[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
@@ -248,24 +245,33 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     // After the k loop the NT*4 (tile, row-quad) items of the workgroup are shared out over its
     // wavefronts: item = wave + i*WAVES -> tile item/4, rows 8*(item%4) + 4*(lane/32) + 0..3.
     constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
-    // epilogue operands are requested now, long before they are used
+    // What the epilogue needs (bias, the folded LayerNorm's vectors and statistics, the cache length) is
+    // requested right behind the first round of weight loads: long before it is used, and without holding
+    // up the start of the weight stream, which then waits for three pointers and three sizes only.
     uint2 bias_w[ITEMS];
     float4 c1w[ITEMS], c2w[ITEMS];
+    LnLoads lnl;
+    bool fold = false;
+    int cur_len = 0;
+    auto request_epilogue_operands = [&]() {
+        fold = FOLDABLE && p.ln_stats != nullptr;
+        if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
-        const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
-        const bool live = item < NT * 4 && tile < n_tiles;
-        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
-        if (FOLDABLE) {
-            c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (fold && live) {  // c1 and c2 are padded to whole tiles
-                c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
-                c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, tile = grp * NT + (item >> 2);
+            const int n0 = tile * 32 + 8 * (item & 3) + 4 * (lane >> 5);
+            const bool live = item < NT * 4 && tile < n_tiles;
+            bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+            if (FOLDABLE) {
+                c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (fold && live) {  // c1 and c2 are padded to whole tiles
+                    c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+                    c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+                }
             }
         }
-    }
-    int cur_len = 0;  // read from the device state once the first weights are on their way: nothing before them waits for it
+        cur_len = epilogue_len<MODE>(p);
+    };
     f32x16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x16{};
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         SkinnyRegs<NT, U> ra;
         skinny_load<NT, U>(ra, w, xh, xl);
         n -= U;
-        cur_len = epilogue_len<MODE>(p);
+        request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off
         // the loop: a test inside it cost the loop its schedule)
         if (n >= U) {
@@ -296,7 +302,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         }
         skinny_mma<NT, U>(ra, acc);
     } else {
-        cur_len = epilogue_len<MODE>(p);
+        request_epilogue_operands();
         if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
     }
     for (; n > 0; --n) {
@@ -508,9 +514,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kp0 = (int)(((long)part * KP) / parts), kp1 = (int)(((long)(part + 1) * KP) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV;
-    const bool fold = FOLDABLE && p.ln_stats != nullptr;
-    LnLoads lnl;
-    if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);  // requested ahead of the weights, used once those are in flight
     // this lane's 16 bytes inside a pair of 32x16 blocks: k-block lane/32, slot 32*(k half) + row
     const int in_pair = (lane >> 5) * 64 + 32 * ((lane >> 4) & 1) + (lane & 15);
     const u32x4* w[HT];
@@ -523,23 +526,31 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
     const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
     constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/2, row half item%2
+    // epilogue operands: requested right behind the first round of weight loads (see gemm_skinny_kernel)
     uint2 bias_w[ITEMS];
     float4 c1w[ITEMS], c2w[ITEMS], wsc[ITEMS];
+    LnLoads lnl;
+    bool fold = false;
+    int cur_len = 0;
+    auto request_epilogue_operands = [&]() {
+        fold = FOLDABLE && p.ln_stats != nullptr;
+        if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
-        const int n0 = g * 16 + 4 * (lane >> 4);
-        const bool live = item < NI && g < n_half;
-        bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
-        wsc[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-        if (W8 && live) wsc[i] = *reinterpret_cast<const float4*>(p.wscale + n0);
-        c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (FOLDABLE && fold && live) {
-            c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
-            c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+        for (int i = 0; i < ITEMS; ++i) {
+            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+            const int n0 = g * 16 + 4 * (lane >> 4);
+            const bool live = item < NI && g < n_half;
+            bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
+            wsc[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (W8 && live) wsc[i] = *reinterpret_cast<const float4*>(p.wscale + n0);
+            c1w[i] = c2w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (FOLDABLE && fold && live) {
+                c1w[i] = *reinterpret_cast<const float4*>(p.c1 + n0);
+                c2w[i] = *reinterpret_cast<const float4*>(p.c2 + n0);
+            }
         }
-    }
-    int cur_len = 0;  // read once the first weights are on their way
+        cur_len = epilogue_len<MODE>(p);
+    };
     f32x4 acc[HT][2];
 #pragma unroll
     for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -548,7 +559,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         HalfRegs<HT, U, W8> ra;
         half_load<HT, U, W8>(ra, w, xh, xl);
         n -= U;
-        cur_len = epilogue_len<MODE>(p);
+        request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off the loop)
         if (n >= U) {
             HalfRegs<HT, U, W8> rb;
@@ -569,7 +580,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         }
         half_mma<HT, U, W8>(ra, acc);
     } else {
-        cur_len = epilogue_len<MODE>(p);
+        request_epilogue_operands();
         if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
     }
     for (; n > 0; --n) {
