@@ -14,6 +14,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed-fp32 instructions (v_pk_*_f32)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # per-kernel register / scratch report, scanned below: a kernel that spills registers to scratch
+    # memory is a performance bug here (it has happened silently to one launch shape)
+    "-Rpass-analysis=kernel-resource-usage",
 ]
 
 
@@ -56,12 +59,34 @@ def _wait(procs, verbose):
     while procs:
         src, p = procs.pop(0)
         out, _ = p.communicate()
-        # hipcc's host pass does not know the packed-fp32 feature name: harmless
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        lines = out.splitlines()
+        # the resource report: remember which kernels use scratch memory, drop the rest of it
+        spilled, name = [], "?"
+        for l in lines:
+            if "remark: Function Name:" in l:
+                name = l.split("Function Name:")[1].split("[")[0].strip()
+            elif "remark:     ScratchSize [bytes/lane]:" in l:
+                if int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0]) > 0:
+                    spilled.append(name)
+        keep, skip = [], 0
+        for l in lines:
+            # hipcc's host pass does not know the packed-fp32 feature name: harmless
+            if "packed-fp32-ops" in l:
+                continue
+            if "[-Rpass-analysis=kernel-resource-usage]" in l:
+                skip = 2  # the remark and the two source-context lines after it
+                continue
+            if skip:
+                skip -= 1
+                continue
+            keep.append(l)
+        out = "\n".join(keep)
         if out.strip() and (verbose or p.returncode):
             print(out)
         if p.returncode:
             raise RuntimeError(f"hipcc failed on {src}")
+        if spilled:
+            raise RuntimeError(f"{os.path.basename(src)}: kernels spilling registers to scratch memory: " + ", ".join(spilled))
 
 
 if __name__ == "__main__":

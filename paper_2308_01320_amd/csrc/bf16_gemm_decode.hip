@@ -740,12 +740,14 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
     constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
     constexpr int KU = W8 ? 2 : 1;
     dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
-    const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U;  // short chains per wavefront, as above
-    constexpr size_t kWant = 84 * 1024;                                     // one workgroup per CU
+    // eight wavefronts have 256 registers each: three units with four rounds of operands twice over do not fit
+    constexpr int U8 = (!W8 && HT == 3) ? 2 : U;
+    const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U8;  // short chains per wavefront, as above
+    constexpr size_t kWant = 84 * 1024;                                      // one workgroup per CU
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
-        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U, 8, W8><<<grid, 512, pad, s>>>(
+        gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, W8><<<grid, 512, pad, s>>>(
             (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
