@@ -101,7 +101,30 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
             bb[j] = *reinterpret_cast<const uint2*>(beta + 4 * i);
         }
     }
-    if (part) {
+    if (part && ksplit <= 2) {  // the usual cases, with every load of the row requested before the first is used
+        float4 y0[NV], y1[NV];
+        uint2 pb[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + j * THREADS;
+            y0[j] = y1[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            pb[j] = make_uint2(0, 0);
+            if (i >= nq) continue;
+            y0[j] = *reinterpret_cast<const float4*>(part + src * H + 4 * i);
+            if (ksplit == 2) y1[j] = *reinterpret_cast<const float4*>(part + part_split + src * H + 4 * i);
+            pb[j] = *reinterpret_cast<const uint2*>(pbias + 4 * i);
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + j * THREADS;
+            if (i >= nq) continue;
+            v[j].x += (y0[j].x + y1[j].x) + __uint_as_float(pb[j].x << 16);
+            v[j].y += (y0[j].y + y1[j].y) + __uint_as_float(pb[j].x & 0xFFFF0000u);
+            v[j].z += (y0[j].z + y1[j].z) + __uint_as_float(pb[j].y << 16);
+            v[j].w += (y0[j].w + y1[j].w) + __uint_as_float(pb[j].y & 0xFFFF0000u);
+            if (writeback) *reinterpret_cast<float4*>(r + src * H + 4 * i) = v[j];
+        }
+    } else if (part) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + j * THREADS;
