@@ -19,8 +19,8 @@ namespace {
 // -- so no cache has to be flushed or invalidated (an agent-scope fence does that to whole L2s and cost
 // 45 us per launch).  The 64-bit words of one (split, item, pair) are laid out thread after thread: every
 // access is a contiguous 512 bytes per wavefront.  Each workgroup publishes its partial sums, waits for the
-// stores to be acknowledged and counts itself in; whoever counts last for the column group reads the other
-// splits back and adds them, together with its own, in split order, so the sum does not depend on which
+// stores to be acknowledged and counts itself in; whoever counts last for the column group reads all splits
+// back -- its own included -- and adds them in split order, so the sum does not depend on which
 // workgroup that was.  Nobody waits for anybody: the others are done.  The last one adds bias and
 // residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
 // (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
@@ -76,21 +76,26 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             const int i = c0 + c;
-            if (i >= ITEMS || !live[i]) continue;
-            rr[c] = *reinterpret_cast<const float4*>(p.resid + (size_t)mrow[i] * p.N + n0[i]);
-            bb[c] = *reinterpret_cast<const uint2*>(p.bias + n0[i]);
-            gg[c] = *reinterpret_cast<const uint2*>(p.gamma + n0[i]);
-            if (ksplit > 1) {  // the other splits; this workgroup's own sums are still in its registers
+            if (i >= ITEMS) continue;
+            // every lane loads (rows and columns past the end are clamped, their results never stored):
+            // no per-lane branches around the loads
+            const int mc = min(mrow[i], p.M - 1), nc = min(n0[i], p.N - 4);
+            rr[c] = *reinterpret_cast<const float4*>(p.resid + (size_t)mc * p.N + nc);
+            bb[c] = *reinterpret_cast<const uint2*>(p.bias + nc);
+            gg[c] = *reinterpret_cast<const uint2*>(p.gamma + nc);
+        }
+        if (ksplit > 1) {  // every split's sums, this workgroup's own included: one uniform test per split
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    y[c][k][0] = pair_bits(v[i][0], v[i][1]);
-                    y[c][k][1] = pair_bits(v[i][2], v[i][3]);
-                    if (k < ksplit && k != ks) {
+            for (int k = 0; k < 8; ++k) {
+                if (k >= ksplit) break;
 #pragma unroll
-                        for (int h = 0; h < 2; ++h)
-                            y[c][k][h] = __hip_atomic_load(scratch + (k * kPer2 + (size_t)(i * 2 + h) * WAVES * 64),
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
+                for (int c = 0; c < CH; ++c) {
+                    const int i = c0 + c;
+                    if (i >= ITEMS) continue;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        y[c][k][h] = __hip_atomic_load(scratch + (k * kPer2 + (size_t)(i * 2 + h) * WAVES * 64),
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
