@@ -184,17 +184,21 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
 //
 // At most 32 rows per grid.y slice: weights are streamed exactly once from HBM,
 // straight from global memory into MFMA operand registers.  A workgroup of four
-// wavefronts owns NT consecutive 32-row weight tiles and one k-split; its
+// or eight wavefronts owns NT consecutive 32-row weight tiles and one k-split; its
 // wavefronts divide the k range, keep U blocks per stream in flight (NT weight
 // streams plus the hi and lo activation streams out of L2, which every weight
 // tile reuses from registers), and combine their accumulators through LDS.  The
-// sum over k-splits (STORE mode) is taken, in a fixed order, by the LayerNorm
-// kernel that consumes it.
+// sum over k-splits (MODE_STORE_LN) is taken by the last-arriving workgroup (above).
 //
-// What bounds this kernel is the number of bytes one CU can keep in flight, so
-// the launcher picks NT (and the k-split) to put one equally loaded workgroup on
+// The launcher picks NT (and the k-split) to put one equally loaded workgroup on
 // as many of the CUs as the shape allows: more workgroups than CUs double up
-// on some CUs and the whole launch waits for those.
+// on some CUs and the whole launch waits for those.  Measured on the 13B shapes:
+// the stream itself runs at the HBM rate; what it competes for is the path from
+// L2 to the CU, which carries the activation panel (as many bytes again as the
+// weights when NT = 2) next to the weights.  Everything executed once per launch
+// (prologue, epilogue) is instruction-bound -- a wavefront issues one vector
+// instruction per four cycles -- so the code around the loop is kept short and
+// what the epilogue needs is requested behind the first round of weight loads.
 
 template <int NT, int U>
 struct SkinnyRegs {
