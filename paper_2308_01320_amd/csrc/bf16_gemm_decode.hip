@@ -25,16 +25,17 @@ namespace {
 // residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
 // (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
 // Returns to the caller, who returns.
-template <int ITEMS, int WAVES, int LG>
+// MT: 32-row slices the workgroup holds (rows mt*32 .. mt*32 + 32 MT - 1; mt = its first slice).
+template <int ITEMS, int WAVES, int LG, int MT = 1>
 __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, int grp, int groups, int mt, float cnt,
                                               const float (&v)[ITEMS][4], const int (&mrow)[ITEMS],
                                               const int (&n0)[ITEMS], const bool (&live)[ITEMS],
                                               const int (&rslot)[ITEMS]) {
-    constexpr int NSLOT = 32 / LG;
+    constexpr int NSLOT = 32 * MT / LG;
     __shared__ int s_last;
-    __shared__ float sred[2][WAVES][32];
+    __shared__ float sred[2][WAVES][32 * MT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const size_t cell = (size_t)grp * gridDim.y + mt;
+    const size_t cell = (size_t)grp * gridDim.y + blockIdx.y;
     constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
     // 64-bit words (two sums each): a wavefront can have 63 loads outstanding, and the wider they are, the more
     // of the last workgroup's read-back is in flight at once
@@ -170,11 +171,11 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
         if (lane < LG) sred[1][wave][LG * r + lane] = q[r];
     }
     __syncthreads();
-    if (threadIdx.x < 32) {
+    if (threadIdx.x < 32 * MT) {  // (wavefront 0: lane = row)
         float m2 = 0.f, tot = 0.f;
 #pragma unroll
         for (int ww = 0; ww < WAVES; ++ww) { m2 += sred[1][ww][lane]; tot += sred[0][ww][lane]; }
-        p.stats_out[((size_t)mt * groups + grp) * 32 + lane] = make_float2(tot / cnt, m2);
+        p.stats_out[((size_t)(mt + (lane >> 5)) * groups + grp) * 32 + (lane & 31)] = make_float2(tot / cnt, m2);
     }
     if (threadIdx.x == 0 && ksplit > 1)  // ready for the next launch
         __hip_atomic_store(p.counters + cell, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -447,14 +448,17 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4
 
 // One loop step of a wavefront covers KU = 1 (bf16 weights) or 2 (8-bit weights: one 16-byte load holds
 // two) k ranges of 32, U steps per round of loads.
-template <int HT, int U, bool W8>
+// MT: 32-row activation slices a workgroup multiplies its weights by (1, or 2 for decode steps of 33..64
+// sequences: the weights are still streamed once); xstride = 16-byte units between two slices
+template <int HT, int U, bool W8, int MT = 1>
 struct HalfRegs {
     static constexpr int KU = W8 ? 2 : 1;
-    u32x4 w[HT][U], xh[2][U * KU], xl[2][U * KU];
+    u32x4 w[HT][U], xh[2 * MT][U * KU], xl[2 * MT][U * KU];
 };
 
-template <int HT, int U, bool W8>
-__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl) {
+template <int HT, int U, bool W8, int MT = 1>
+__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MT>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl,
+                                          size_t xstride = 0) {
     constexpr int KU = W8 ? 2 : 1, WSTEP = W8 ? 64 : 128;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -463,9 +467,9 @@ __device__ __forceinline__ void half_load(HalfRegs<HT, U, W8>& r, const u32x4* (
 #pragma unroll
         for (int kp = 0; kp < KU; ++kp)
 #pragma unroll
-            for (int mh = 0; mh < 2; ++mh) {
-                r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + mh * 16];
-                r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + mh * 16];
+            for (int mh = 0; mh < 2 * MT; ++mh) {
+                r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
+                r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
             }
     }
 #pragma unroll
@@ -474,8 +478,8 @@ __device__ __forceinline__ void half_load(HalfRegs<HT, U, W8>& r, const u32x4* (
     xl += U * KU * 128;
 }
 
-template <int HT, int U, bool W8>
-__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&acc)[HT][2]) {
+template <int HT, int U, bool W8, int MT = 1>
+__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MT>& r, f32x4 (&acc)[HT][2 * MT]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if constexpr (W8) {
@@ -486,7 +490,7 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&a
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp)
 #pragma unroll
-                    for (int mh = 0; mh < 2; ++mh) {
+                    for (int mh = 0; mh < 2 * MT; ++mh) {
                         acc[t][mh] = mfma16_bf16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
                         acc[t][mh] = mfma16_bf16(a[kp], r.xl[mh][u * 2 + kp], acc[t][mh]);
                     }
@@ -495,11 +499,11 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&a
 #pragma unroll
             for (int t = 0; t < HT; ++t)
 #pragma unroll
-                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+                for (int mh = 0; mh < 2 * MT; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
 #pragma unroll
             for (int t = 0; t < HT; ++t)
 #pragma unroll
-                for (int mh = 0; mh < 2; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+                for (int mh = 0; mh < 2 * MT; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
         }
     }
 }
@@ -508,16 +512,18 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8>& r, f32x4 (&a
 // W8: the weights are E4M3 codes in units of [16 rows][64 k] -- lane l holds, for row l%16, the eight k
 // values 8 (l/16) + 0..7 of the unit's first 32 k in bytes 0-7 and those of its second 32 k in bytes
 // 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
-template <int MODE, int HT, int U, int WAVES, bool W8>
+template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1>
 __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                                const u32x4* __restrict__ Xlo, int KB, int n_half,
                                                                int ksplit, Epi p) {
-    constexpr int NI = HT * 2;  // (unit, row half) items of a workgroup
+    constexpr int MH = 2 * MT;   // 16-row halves of the activation rows
+    constexpr int NI = HT * MH;  // (unit, row half) items of a workgroup
     __shared__ float red[WAVES][NI][4][64];
-    __shared__ float lnp[WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
+    __shared__ float lnp[MT][WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
-    const int mt = blockIdx.y;
+    const int mt = blockIdx.y * MT;  // first 32-row slice
+    const size_t xstride = (size_t)KB * 64;
     constexpr int KU = W8 ? 2 : 1;       // 32-wide k ranges per loop step
     const int KP = KB / (2 * KU);        // loop steps over the whole of k
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
@@ -534,19 +540,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     }
     const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
     const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
-    constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/2, row half item%2
+    constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/MH, row half item%MH
     // epilogue operands: requested right behind the first round of weight loads (see gemm_skinny_kernel)
     uint2 bias_w[ITEMS];
     float4 c1w[ITEMS], c2w[ITEMS], wsc[ITEMS];
-    LnLoads lnl;
+    LnLoads lnl[MT];
     bool fold = false;
     int cur_len = 0;
     auto request_epilogue_operands = [&]() {
         fold = FOLDABLE && p.ln_stats != nullptr;
-        if (fold) ln_issue<WAVES>(lnl, p, mt, wave, lane);
+        if (fold) {
+#pragma unroll
+            for (int s2 = 0; s2 < MT; ++s2) ln_issue<WAVES>(lnl[s2], p, mt + s2, wave, lane);
+        }
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+            const int item = wave + i * WAVES, g = grp * HT + item / MH;
             const int n0 = g * 16 + 4 * (lane >> 4);
             const bool live = item < NI && g < n_half;
             bias_w[i] = live ? epilogue_bias<MODE>(p, n0) : make_uint2(0, 0);
@@ -560,49 +569,55 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         }
         cur_len = epilogue_len<MODE>(p);
     };
-    f32x4 acc[HT][2];
+    f32x4 acc[HT][MH];
 #pragma unroll
-    for (int t = 0; t < HT; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < HT; ++t)
+#pragma unroll
+        for (int mh = 0; mh < MH; ++mh) acc[t][mh] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto ln_partials = [&]() {
+#pragma unroll
+        for (int s2 = 0; s2 < MT; ++s2) ln_partial<WAVES>(lnl[s2], p, mt + s2, wave, lane, lnp[s2]);
+    };
     int n = kp1 - kp0;
     if (n >= U) {
-        HalfRegs<HT, U, W8> ra;
-        half_load<HT, U, W8>(ra, w, xh, xl);
+        HalfRegs<HT, U, W8, MT> ra;
+        half_load<HT, U, W8, MT>(ra, w, xh, xl, xstride);
         n -= U;
         request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off the loop)
         if (n >= U) {
-            HalfRegs<HT, U, W8> rb;
-            half_load<HT, U, W8>(rb, w, xh, xl);
+            HalfRegs<HT, U, W8, MT> rb;
+            half_load<HT, U, W8, MT>(rb, w, xh, xl, xstride);
             n -= U;
-            if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
-            half_mma<HT, U, W8>(ra, acc);
+            if (fold) ln_partials();
+            half_mma<HT, U, W8, MT>(ra, acc);
             ra = rb;
         } else if (fold) {
-            ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+            ln_partials();
         }
         while (n >= U) {
-            HalfRegs<HT, U, W8> rb;
-            half_load<HT, U, W8>(rb, w, xh, xl);
+            HalfRegs<HT, U, W8, MT> rb;
+            half_load<HT, U, W8, MT>(rb, w, xh, xl, xstride);
             n -= U;
-            half_mma<HT, U, W8>(ra, acc);
+            half_mma<HT, U, W8, MT>(ra, acc);
             ra = rb;
         }
-        half_mma<HT, U, W8>(ra, acc);
+        half_mma<HT, U, W8, MT>(ra, acc);
     } else {
         request_epilogue_operands();
-        if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
+        if (fold) ln_partials();
     }
     for (; n > 0; --n) {
-        HalfRegs<HT, 1, W8> r1;
-        half_load<HT, 1, W8>(r1, w, xh, xl);
-        half_mma<HT, 1, W8>(r1, acc);
+        HalfRegs<HT, 1, W8, MT> r1;
+        half_load<HT, 1, W8, MT>(r1, w, xh, xl, xstride);
+        half_mma<HT, 1, W8, MT>(r1, acc);
     }
 #pragma unroll
     for (int t = 0; t < HT; ++t)
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh)
+        for (int mh = 0; mh < MH; ++mh)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[wave][t * 2 + mh][r][lane] = acc[t][mh][r];
+            for (int r = 0; r < 4; ++r) red[wave][t * MH + mh][r][lane] = acc[t][mh][r];
     __syncthreads();
     float v[ITEMS][4];
 #pragma unroll
@@ -627,11 +642,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     if (fold) {  // W LN(x) = rstd * (W (gamma x) - mean * W gamma) + W beta; a lane's items sit in two rows
         // (selected, not indexed: an array indexed at run time would live in LDS, whose addressing
         // reads the dispatch packet -- microseconds, here in the tail of the kernel)
-        const float2 mr0 = ln_finish<WAVES>(lnp, lane & 15, p), mr1 = ln_finish<WAVES>(lnp, 16 + (lane & 15), p);
+        const float2 mr0 = ln_finish<WAVES>(lnp[0], lane & 15, p), mr1 = ln_finish<WAVES>(lnp[0], 16 + (lane & 15), p);
+        float2 mr2 = mr0, mr3 = mr1;
+        if (MT == 2) {
+            mr2 = ln_finish<WAVES>(lnp[MT - 1], lane & 15, p);
+            mr3 = ln_finish<WAVES>(lnp[MT - 1], 16 + (lane & 15), p);
+        }
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const bool odd = (wave + i * WAVES) & 1;
-            const float mean = odd ? mr1.x : mr0.x, rstd = odd ? mr1.y : mr0.y;
+            const int rh = (wave + i * WAVES) % MH;
+            const bool odd = rh & 1, second = rh >= 2;
+            const float mean = second ? (odd ? mr3.x : mr2.x) : (odd ? mr1.x : mr0.x);
+            const float rstd = second ? (odd ? mr3.y : mr2.y) : (odd ? mr1.y : mr0.y);
             v[i][0] = rstd * (v[i][0] - mean * c1w[i].x) + c2w[i].x;
             v[i][1] = rstd * (v[i][1] - mean * c1w[i].y) + c2w[i].y;
             v[i][2] = rstd * (v[i][2] - mean * c1w[i].z) + c2w[i].z;
@@ -643,21 +665,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         bool live[ITEMS];
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
-            mrow[i] = mt * 32 + 16 * (item & 1) + (lane & 15);
+            const int item = wave + i * WAVES, g = grp * HT + item / MH;
+            mrow[i] = mt * 32 + 16 * (item % MH) + (lane & 15);
             n0[i] = g * 16 + 4 * (lane >> 4);
             live[i] = item < NI && g < n_half && mrow[i] < p.M;
-            rslot[i] = item & 1;
+            rslot[i] = item % MH;
         }
-        store_ln_tail<ITEMS, WAVES, 16>(p, ksplit, ks, grp, (n_half + HT - 1) / HT, mt,
-                                        16.f * (float)min(HT, n_half - grp * HT), v, mrow, n0, live, rslot);
+        store_ln_tail<ITEMS, WAVES, 16, MT>(p, ksplit, ks, grp, (n_half + HT - 1) / HT, mt,
+                                            16.f * (float)min(HT, n_half - grp * HT), v, mrow, n0, live, rslot);
         return;
     }
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const int item = wave + i * WAVES, g = grp * HT + (item >> 1);
+        const int item = wave + i * WAVES, g = grp * HT + item / MH;
         if (item >= NI || g >= n_half) continue;
-        epilogue4<MODE>(p, mt * 32 + 16 * (item & 1) + (lane & 15), g * 16 + 4 * (lane >> 4), ks, v[i][0], v[i][1], v[i][2],
+        epilogue4<MODE>(p, mt * 32 + 16 * (item % MH) + (lane & 15), g * 16 + 4 * (lane >> 4), ks, v[i][0], v[i][1], v[i][2],
                         v[i][3], bias_w[i], cur_len);
     }
 }
@@ -749,6 +771,18 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
     constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
     constexpr int KU = W8 ? 2 : 1;
     dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
+    if constexpr (!W8 && HT <= 8) {  // (the accumulators of more units than that do not fit in LDS for the reduction)
+        if (m_tiles == 2) {  // both 32-row slices in one workgroup: the weights are streamed once
+            constexpr int U2 = HT <= 6 ? 2 : 1;
+            constexpr size_t kWant2 = 84 * 1024;
+            constexpr size_t kStatic = (size_t)4 * HT * 4 * 4 * 64 * sizeof(float);
+            const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
+            grid.y = 1;
+            gemm_half_kernel<MODE, HT, U2, 4, false, 2><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
+                                                                               (const u32x4*)Xlo, KB, n_half, ksplit, p);
+            return;
+        }
+    }
     // eight wavefronts have 256 registers each: three units with four rounds of operands twice over do not fit
     constexpr int U8 = (!W8 && HT == 3) ? 2 : U;
     const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U8;  // short chains per wavefront, as above
@@ -767,6 +801,7 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
 }
 
 constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the half-tile kernel is built for (8-bit: from 1)
+constexpr int kHalfMax2 = 8;                // ... with two 32-row activation slices per workgroup
 
 template <int MODE, bool W8>
 void launch_half(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles, int ht,
@@ -852,8 +887,12 @@ struct GemmPlan { bool half; int per_wg, ks; };
 static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no k-split
     const int n_tiles = (N + 31) / 32, m_tiles = (M + 31) / 32, cus = plan_cus();
     GemmPlan g{false, skinny_nt_fused(n_tiles, m_tiles), 1};
-    if (m_tiles > 1 || N % 16) return g;
+    if (m_tiles > 2 || N % 16) return g;
     const int n_half = N / 16, ht = (n_half + cus - 1) / cus;
+    if (m_tiles == 2) {  // two row slices per workgroup (16-row-unit kernel only): the weights are streamed once
+        if (ht >= kHalfMin && ht <= kHalfMax2) g = GemmPlan{true, ht, 1};
+        return g;
+    }
     if (ht >= kHalfMin && ht <= kHalfMax && 16 * ht < 32 * g.per_wg) g = GemmPlan{true, ht, 1};
     return g;
 }
@@ -862,17 +901,20 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
     GemmPlan g{false, 0, 0};
     bf16_store_shape(M, N, K, &g.per_wg, &g.ks);
-    if ((M + 31) / 32 > 1 || N % 16) return g;
+    const int m_tiles = (M + 31) / 32;
+    if (m_tiles > 2 || N % 16) return g;
     const int n_half = N / 16, kb = K / 16, cus = plan_cus();
-    double best = (double)g.per_wg * 32 / g.ks;  // rows x (k share) per workgroup
-    for (int ht = kHalfMax; ht >= kHalfMin; --ht) {
+    // two row slices: only the 16-row-unit kernel takes both in one workgroup, so any such plan beats the rest
+    double best = m_tiles == 2 ? 1e30 : (double)g.per_wg * 32 / g.ks;  // rows x (k share) per workgroup
+    const int mh = 2 * m_tiles;
+    for (int ht = m_tiles == 2 ? kHalfMax2 : kHalfMax; ht >= kHalfMin; --ht) {
         const int groups = (n_half + ht - 1) / ht;
         int ks = cus / groups;
         if (ks < 1) continue;
         if (ks > 8) ks = 8;
         while (ks > 1 && kb / (ks * 4) < 8) --ks;
         // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
-        if (capacity && (size_t)groups * ks * (size_t)(2 * ht + 7) * 256 > capacity) continue;
+        if (capacity && (size_t)groups * ks * (size_t)(mh * ht + 7) * 256 > capacity) continue;
         const double load = (double)ht * 16 / ks;
         // fewer, longer k ranges per wavefront cost a 16-row plan some of its balance back (measured on the
         // 5120x5120 and 5120x20480 shapes: 6 % less load per workgroup ran no faster), so it has to win clearly

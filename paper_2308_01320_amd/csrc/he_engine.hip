@@ -455,10 +455,14 @@ void pass_decode_wide_bf16(he_engine* e, const int32_t* d_ids, int id_stride, in
     e->step += 1;
 }
 
+// Decode steps of up to 32 sequences, and of up to 64 with bf16 weights (two 32-row slices per workgroup),
+// stream the weights through the decode GEMMs; larger ones take the prompt pass's tiles.
+bool wide_decode(const he_engine* e, int B) { return B > 64 || (B > 32 && e->w8); }
+
 he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
                            int out_stride, int out_at_step, float* d_logits_opt) {
     if (S > 1) pass_tiled_bf16(e, d_ids, S, B, S - 1);
-    if (B > 32) pass_decode_wide_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
+    if (wide_decode(e, B)) pass_decode_wide_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
     else pass_decode_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
     return check_hip(e, hipGetLastError(), "kernel launch");
 }
@@ -1064,7 +1068,7 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
     for (int r = 0; r < reps; ++r)
         for (int l = 0; l < c.n_layers; ++l) {
             bf16_gemm_args a = base;
-            if (B > 32) {  // the GEMMs of the wide decode step
+            if (wide_decode(e, B)) {  // the GEMMs of the wide decode step
                 if (e->w8) return fail(e, HE_ERR_STATE, "he_kernel_sweep: with 8-bit weights only for batches up to 32");
                 if (kernel_class == HE_K_FC1) {
                     a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;

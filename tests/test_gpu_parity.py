@@ -154,7 +154,9 @@ def test_bf16_shapes(impl, L, H, nh, F, V, B, S, G, tied):
     ("opt-13b", 1, 32, 9, 3),     # full decode batch of the headline workload
     ("opt-13b", 1, 5, 221, 2),    # 1100 prompt rows: QKV and FC1 tiles two to a CU, ragged last tile
     ("opt-6.7b", 2, 16, 64, 3),
-    ("opt-13b", 1, 96, 5, 3),     # more than 32 sequences: the decode step on k-split prompt-pass tiles
+    ("opt-13b", 1, 64, 5, 3),     # 33..64 sequences: two 32-row slices per workgroup of the weight-streaming GEMMs
+    ("opt-13b", 1, 40, 4, 3),     # ... with a ragged second slice
+    ("opt-13b", 1, 96, 5, 3),     # more than 64 sequences: the decode step on k-split prompt-pass tiles
 ])
 def test_bf16_real_layer_shapes(name, L, B, S, G):
     """Layer-truncated models at the real GEMM / head / vocabulary shapes of the benchmark configs."""
