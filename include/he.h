@@ -278,7 +278,7 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps);
 he_status he_fp8_quantize_rows(const void* d_src, int rows, int cols, void* d_codes, int32_t* d_exps, float* d_scales,
                                void* stream);
 
-/* Test hook, host logic only (no device work): how a decode-shaped GEMM of M <= 32 rows with an [N, K] weight
+/* Test hook, host logic only (no device work): how a decode-shaped GEMM of M <= 64 rows with an [N, K] weight
  * matrix is shared out over `cus` compute units (0 = the current device's count, 256 if there is none): weight
  * rows per unit (32, or 16 for the half-tile kernel), units per workgroup, and k-splits (always 1 unless
  * ksplit_allowed, i.e. for the out-projection and FC2, whose partial sums go through scratch_floats floats of

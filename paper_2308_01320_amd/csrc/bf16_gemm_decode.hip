@@ -918,7 +918,7 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
         const double load = (double)ht * 16 / ks;
         // fewer, longer k ranges per wavefront cost a 16-row plan some of its balance back (measured on the
         // 5120x5120 and 5120x20480 shapes: 6 % less load per workgroup ran no faster), so it has to win clearly
-        if (load < best * 0.9) { best = load; g = GemmPlan{true, ht, ks}; }
+        if (load < best * (m_tiles == 2 ? 1.0 : 0.9)) { best = load; g = GemmPlan{true, ht, ks}; }
     }
     return g;
 }

@@ -383,8 +383,8 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     e->step += 1;
 }
 
-// The same pass for more than 32 sequences: rows no longer fit one matrix-core tile, so the GEMMs are
-// the prompt-pass tiles (weights shared through LDS by all rows), cut along k until they fill the
+// The same pass for more than 64 sequences (more than 32 with 8-bit weights): the rows no longer fit the
+// weight-streaming kernels, so the GEMMs are the prompt-pass tiles (weights shared through LDS by all rows), cut along k until they fill the
 // chip; LayerNorms are kernels of their own again and add the partial sums.
 void pass_decode_wide_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int32_t* ids_out, float* lp_out,
                            int out_stride, int out_at_step, float* d_logits_opt) {

@@ -81,6 +81,10 @@ def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
                 assert unit * per_wg <= 32 * math.ceil(N // 32 / cus)  # the most loaded workgroup
             else:
                 assert groups * ks * (2 * per_wg + 7) * 256 <= cap or unit == 32
+    # 33..64 rows: two 32-row slices per workgroup, which only the 16-row-unit kernel takes, at most 8 units
+    for (N, K, store) in ((3 * 5120, 5120, False), (20480, 5120, False), (5120, 5120, True), (5120, 20480, True)):
+        unit, per_wg, ks = binding.he_plan_decode_gemm(64, N, K, store, 2 * 8 * 64 * 5120 if store else 0, 256)
+        assert unit == 16 and 2 <= per_wg <= 8 and math.ceil(N // 16 / per_wg) * ks <= 256, (N, K, unit, per_wg, ks)
     # the case the 16-row units exist for: 640 tiles do not divide over 256 CUs, 1280 units do
     assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 256) == (16, 5, 1)
     assert binding.he_plan_decode_gemm(32, 15360, 5120, False, 0, 256) == (32, 2, 1)
