@@ -898,14 +898,29 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 }
 
 // capacity: floats the k-split scratch can hold (0 = not checked)
+//
+// Cost of a one-slice plan, in microseconds, fitted to launches of the 13B and 6.7B shapes: what the most loaded
+// workgroup moves (its weight rows and the two-term activation rows over its k range, at the ~48 GB/s one CU
+// sustains while all stream; never less than the whole matrix takes at the HBM rate) plus the tail after the
+// stream: ~1.1 us per k-split whose partial sums the last arriver waits for and reads back, ~0.2 us per quad of
+// outputs a thread finishes.  (Balance alone, the earlier criterion, chose four 32-row tiles and six splits on
+// 5120x5120 and 5120x20480; five 16-row units and four splits move 12 % more bytes per workgroup and run 1-2 us
+// faster; on 4096x4096 four units and four splits run 3.4 us faster than four tiles and eight splits.)
+static double store_cost_us(int N, int K, int rows, int items, int ks) {
+    const double per_cu = (double)K / ks * (2.0 * rows + 128.0) / 48e3;  // us at 48 GB/s
+    const double hbm = 2.0 * N * K / 6.5e6;                              // the whole matrix at 6.5 TB/s
+    return (per_cu > hbm ? per_cu : hbm) + 0.2 * items + 1.1 * ks;
+}
+
 static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
     GemmPlan g{false, 0, 0};
     bf16_store_shape(M, N, K, &g.per_wg, &g.ks);
     const int m_tiles = (M + 31) / 32;
     if (m_tiles > 2 || N % 16) return g;
     const int n_half = N / 16, kb = K / 16, cus = plan_cus();
-    // two row slices: only the 16-row-unit kernel takes both in one workgroup, so any such plan beats the rest
-    double best = m_tiles == 2 ? 1e30 : (double)g.per_wg * 32 / g.ks;  // rows x (k share) per workgroup
+    // two row slices: only the 16-row-unit kernel takes both in one workgroup, so any such plan beats the rest;
+    // among them the one with the fewest weight rows x k share on a workgroup
+    double best = m_tiles == 2 ? 1e30 : store_cost_us(N, K, g.per_wg * 32, g.per_wg, g.ks);
     const int mh = 2 * m_tiles;
     for (int ht = m_tiles == 2 ? kHalfMax2 : kHalfMax; ht >= kHalfMin; --ht) {
         const int groups = (n_half + ht - 1) / ht;
@@ -915,10 +930,8 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
         while (ks > 1 && kb / (ks * 4) < 8) --ks;
         // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
         if (capacity && (size_t)groups * ks * (size_t)(mh * ht + 7) * 256 > capacity) continue;
-        const double load = (double)ht * 16 / ks;
-        // fewer, longer k ranges per wavefront cost a 16-row plan some of its balance back (measured on the
-        // 5120x5120 and 5120x20480 shapes: 6 % less load per workgroup ran no faster), so it has to win clearly
-        if (load < best * (m_tiles == 2 ? 1.0 : 0.9)) { best = load; g = GemmPlan{true, ht, ks}; }
+        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * mh + 3) / 4, ks);
+        if (cost < best) { best = cost; g = GemmPlan{true, ht, ks}; }
     }
     return g;
 }
