@@ -81,10 +81,19 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
                                                       const bf16_t* __restrict__ gamma,
                                                       const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
                                                       u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
-                                                      int in_add, int writeback) {
+                                                      int in_add, int writeback, int rows) {
     constexpr int NW = THREADS / 64;
     __shared__ float red[2][NW];
-    const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int m = blockIdx.x;
+    if (THREADS == 256) {
+        // Many rows: a row writes 16-byte slots of the 32-row blocks, 512 bytes apart, and the 32 rows of a block
+        // together fill whole cache lines.  Workgroups go round the eight XCDs by index, so the rows of one block
+        // are kept on one XCD (block b on XCD b mod 8): its L2 then holds complete lines to write back.
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+        m = (((j >> 5) << 3) + x) * 32 + (j & 31);
+        if (m >= rows) return;  // the whole workgroup: the grid is padded to eight blocks
+    }
     const size_t src = (size_t)m * in_mul + in_add;
     const int nq = H >> 2;  // float4 per row
     float4 v[NV];
@@ -294,9 +303,9 @@ void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part
              int in_mul, int in_add, int writeback) {
     const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
 #define HE_LN_ROW(NV, T)                                                                                                \
-    ln_row_kernel<NV, T><<<rows, T, 0, s>>>(r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma,    \
-                                            (const bf16_t*)beta, (u32x4*)a_blocks, (u32x4*)a_blocks_lo, H, eps, in_mul, \
-                                            in_add, writeback)
+    ln_row_kernel<NV, T><<<(T == 256 ? (rows + 255) / 256 * 256 : rows), T, 0, s>>>(                                    \
+        r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks, \
+        (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback, rows)
     if (rows <= 256 && nv <= 3) {  // a decode step
         if (nv == 1) HE_LN_ROW(1, 1024);
         else if (nv == 2) HE_LN_ROW(2, 1024);
