@@ -321,10 +321,10 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
 // scores of query lane%32 in that lane's 16 accumulators (online soft-max needs one exchange
 // with lane^32), and O^T = V^T P^T accumulates that query's output column, so the soft-max
 // rescaling is a per-lane scalar.  Q and P enter the MFMA as two bf16 terms (hi + lo).  The
-// keys of a PV step are taken in the order the score accumulators already hold them; V is
-// transposed into that order while it is staged in LDS.
+// keys of a PV step are taken in the order the score accumulators already hold them; the V^T
+// operand is gathered in that order from the staged rows with 16-bit LDS reads.
 template <int D>
-__global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __restrict__ q,
+__global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* __restrict__ q,
                                                                const bf16_t* __restrict__ kv, u32x4* __restrict__ o,
                                                                u32x4* __restrict__ o_lo,
                                                                const he_dev_state* __restrict__ st, int S, int layer,
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __re
     constexpr int DB = D / 32;       // 32-wide blocks of output dimensions
     constexpr int KPITCH = D + 8;    // bf16 per K row in LDS (16 bytes of padding)
     __shared__ __align__(16) bf16_t ks[32 * KPITCH];
-    __shared__ __align__(16) bf16_t vt[DB * 2 * 2 * 32 * 8];  // [dim block][k-step][lane half][dim][8 keys]
+    __shared__ __align__(16) bf16_t vs[32 * KPITCH];
     const int h = blockIdx.y, b = blockIdx.z;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int j = lane & 31, hh = lane >> 5;
@@ -370,26 +370,35 @@ __global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __re
     for (int i = 0; i < DB; ++i) oacc[i] = f32x16{};
     float m_run = -INFINITY, l_run = 0.f;
 
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        __syncthreads();  // the previous tile has been consumed
-        // stage K rows as they are, V transposed into the PV operand order
-        for (int c = threadIdx.x; c < 32 * (D / 8); c += 256) {
-            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8, kabs = kt * 32 + key;
-            u32x4 kk = u32x4{0u, 0u, 0u, 0u}, vv = kk;
-            if (kabs < T) {
-                kk = *reinterpret_cast<const u32x4*>(Kg + (size_t)kabs * D + d0);
-                vv = *reinterpret_cast<const u32x4*>(Vg + (size_t)kabs * D + d0);
-            }
-            *reinterpret_cast<u32x4*>(&ks[key * KPITCH + d0]) = kk;
-            const int s2 = key >> 4, k16 = key & 15, vh = (k16 >> 2) & 1, e = 4 * (k16 >> 3) + (k16 & 3);
-            const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+    // A tile's K and V rows are requested one tile ahead and wait in registers while the tile before
+    // them is multiplied, so that their latency is not paid between two barriers.
+    constexpr int NI = 32 * (D / 8) / 256;  // 16-byte pieces of K (and of V) per thread and tile
+    u32x4 kreg[NI], vreg[NI];
+    auto request_tile = [&](int kt) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) {
-                const int d = d0 + x;
-                vt[((((d >> 5) * 2 + s2) * 2 + vh) * 32 + (d & 31)) * 8 + e] = (bf16_t)(w[x >> 1] >> ((x & 1) * 16));
+        for (int n = 0; n < NI; ++n) {
+            const int c = threadIdx.x + n * 256;
+            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8, kabs = kt * 32 + key;
+            kreg[n] = vreg[n] = u32x4{0u, 0u, 0u, 0u};
+            if (kabs < T) {
+                kreg[n] = *reinterpret_cast<const u32x4*>(Kg + (size_t)kabs * D + d0);
+                vreg[n] = *reinterpret_cast<const u32x4*>(Vg + (size_t)kabs * D + d0);
             }
         }
+    };
+    request_tile(0);
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        __syncthreads();  // the previous tile has been consumed
+        // stage the K and V rows as they are (a padded pitch keeps the reads below off each other's banks)
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            const int c = threadIdx.x + n * 256;
+            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8;
+            *reinterpret_cast<u32x4*>(&ks[key * KPITCH + d0]) = kreg[n];
+            *reinterpret_cast<u32x4*>(&vs[key * KPITCH + d0]) = vreg[n];
+        }
         __syncthreads();
+        if (kt + 1 < n_tiles) request_tile(kt + 1);
         if (kt > my_last_tile) continue;  // wholly above the diagonal for this wavefront (uniform per wavefront)
         f32x16 sacc = f32x16{};
 #pragma unroll
@@ -426,7 +435,17 @@ __global__ __launch_bounds__(256) void attn_prompt_mfma_kernel(const float* __re
             const u32x4 phi = u32x4{ph[0], ph[1], ph[2], ph[3]}, plo = u32x4{pl[0], pl[1], pl[2], pl[3]};
 #pragma unroll
             for (int i = 0; i < DB; ++i) {
-                const u32x4 vblk = *reinterpret_cast<const u32x4*>(&vt[(((i * 2 + s2) * 2 + hh) * 32 + j) * 8]);
+                // V^T operand: this lane's output dimension, the eight keys in the order the score
+                // accumulators hold them (16-bit reads down a column of the staged rows: the 32 lanes of
+                // a half read 64 consecutive bytes, the two halves sit 16 banks apart)
+                const bf16_t* vcol = &vs[(s2 * 16 + 4 * hh) * KPITCH + i * 32 + j];
+                uint32_t vw[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int k0 = 8 * (x >> 1) + 2 * (x & 1);  // element 2x of the operand; 2x+1 is the next key
+                    vw[x] = (uint32_t)vcol[k0 * KPITCH] | ((uint32_t)vcol[(k0 + 1) * KPITCH] << 16);
+                }
+                const u32x4 vblk = u32x4{vw[0], vw[1], vw[2], vw[3]};
                 oacc[i] = mfma_bf16(vblk, phi, oacc[i]);
                 oacc[i] = mfma_bf16(vblk, plo, oacc[i]);
             }
