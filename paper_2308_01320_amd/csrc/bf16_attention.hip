@@ -416,17 +416,21 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible to every query
-        const float alpha = expf(m_run - m_new);
+        // the hardware's exponential (2^(x log2 e), a few ulp): the library routine's ~20 instructions per
+        // value were more work per tile than its matrix products
+        const float alpha = __expf(m_run - m_new);
         float psum = 0.f;
         float pr[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { pr[r] = expf(sacc[r] - m_new); psum += pr[r]; }
+        for (int r = 0; r < 16; ++r) { pr[r] = __expf(sacc[r] - m_new); psum += pr[r]; }
         l_run = l_run * alpha + psum;
+        if (__any(m_new != m_run)) {  // no query of this wavefront met a larger score: nothing to rescale
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        }
         m_run = m_new;
-#pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
             uint32_t ph[4], pl[4];
