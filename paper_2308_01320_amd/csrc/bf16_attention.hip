@@ -400,20 +400,26 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
         __syncthreads();
         if (kt + 1 < n_tiles) request_tile(kt + 1);
         if (kt > my_last_tile) continue;  // wholly above the diagonal for this wavefront (uniform per wavefront)
-        f32x16 sacc = f32x16{};
+        // two accumulators (one per term of Q), so that consecutive MFMAs do not wait for each other's result
+        f32x16 sacc = f32x16{}, sacc_lo = f32x16{};
 #pragma unroll
         for (int kb = 0; kb < KBD; ++kb) {
             const u32x4 kblk = *reinterpret_cast<const u32x4*>(&ks[j * KPITCH + kb * 16 + hh * 8]);
             sacc = mfma_bf16(kblk, qhi[kb], sacc);
-            sacc = mfma_bf16(kblk, qlo[kb], sacc);
+            sacc_lo = mfma_bf16(kblk, qlo[kb], sacc_lo);
         }
-        float mx = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int kabs = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (kabs > qpos) sacc[r] = -INFINITY;
-            mx = fmaxf(mx, sacc[r]);
+        for (int r = 0; r < 16; ++r) sacc[r] += sacc_lo[r];
+        float mx = -INFINITY;
+        if (kt * 32 + 31 > cur + t0) {  // the tile reaches past the first query's last key: mask per query
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kabs = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                if (kabs > qpos) sacc[r] = -INFINITY;
+            }
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible to every query
         // the hardware's exponential (2^(x log2 e), a few ulp): the library routine's ~20 instructions per
