@@ -906,9 +906,12 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 // outputs a thread finishes.  (Balance alone, the earlier criterion, chose four 32-row tiles and six splits on
 // 5120x5120 and 5120x20480; five 16-row units and four splits move 12 % more bytes per workgroup and run 1-2 us
 // faster; on 4096x4096 four units and four splits run 3.4 us faster than four tiles and eight splits.)
-static double store_cost_us(int N, int K, int rows, int items, int ks) {
+static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, int cus) {
     const double per_cu = (double)K / ks * (2.0 * rows + 128.0) / 48e3;  // us at 48 GB/s
-    const double hbm = 2.0 * N * K / 6.5e6;                              // the whole matrix at 6.5 TB/s
+    // the whole matrix at 6.5 TB/s; CUs left without a workgroup request nothing, and the stream slows by about
+    // half their share (9216x36864: 216 workgroups on 256 CUs ran 8 % slower than 256)
+    const double idle = wgs < cus ? 1.0 - (double)wgs / cus : 0.0;
+    const double hbm = 2.0 * N * K / 6.5e6 * (1.0 + 0.5 * idle);
     return (per_cu > hbm ? per_cu : hbm) + 0.2 * items + 1.1 * ks;
 }
 
@@ -920,7 +923,9 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
     const int n_half = N / 16, kb = K / 16, cus = plan_cus();
     // two row slices: only the 16-row-unit kernel takes both in one workgroup, so any such plan beats the rest;
     // among them the one with the fewest weight rows x k share on a workgroup
-    double best = m_tiles == 2 ? 1e30 : store_cost_us(N, K, g.per_wg * 32, g.per_wg, g.ks);
+    double best = m_tiles == 2 ? 1e30
+                               : store_cost_us(N, K, g.per_wg * 32, g.per_wg, g.ks,
+                                               ((N + 31) / 32 + g.per_wg - 1) / g.per_wg * g.ks, cus);
     const int mh = 2 * m_tiles;
     for (int ht = m_tiles == 2 ? kHalfMax2 : kHalfMax; ht >= kHalfMin; --ht) {
         const int groups = (n_half + ht - 1) / ht;
@@ -930,7 +935,7 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
         while (ks > 1 && kb / (ks * 4) < 8) --ks;
         // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
         if (capacity && (size_t)groups * ks * (size_t)(mh * ht + 7) * 256 > capacity) continue;
-        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * mh + 3) / 4, ks);
+        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * mh + 3) / 4, ks, groups * ks, cus);
         if (cost < best) { best = cost; g = GemmPlan{true, ht, ks}; }
     }
     return g;
