@@ -94,3 +94,29 @@ def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
     assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 200) == (16, 7, 1)
     with pytest.raises(binding.HeError):
         binding.he_plan_decode_gemm(32, 100, 64)
+
+
+def test_bench_clock_sampler_reads_the_marked_level(tmp_path):
+    """bench.py's clock record: the level the driver marks with '*' in its text files, sampled from a thread."""
+    import importlib.util
+    import time
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(os.path.dirname(__file__), "..", "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    (tmp_path / "sclk").write_text("0: 132Mhz\n1: 500Mhz\n2: 2400Mhz *\n")
+    (tmp_path / "mclk").write_text("0: 900Mhz\n1: 2000Mhz *\n")
+    (tmp_path / "level").write_text("auto\n")
+    c = bench.ClockSampler(period_s=0.005)
+    c.files = {"sclk": str(tmp_path / "sclk"), "mclk": str(tmp_path / "mclk"), "level": str(tmp_path / "level")}
+    c.start()
+    time.sleep(0.03)
+    c.finish()
+    rec = c.record()
+    assert rec["sclk_mhz"]["min"] == rec["sclk_mhz"]["max"] == 2400 and rec["sclk_mhz"]["samples"] >= 1
+    assert rec["mclk_mhz"]["median"] == 2000 and rec["performance_level"] == "auto"
+    # no driver files (as on a box without the GPU): the record says so instead of failing
+    d = bench.ClockSampler()
+    d.files = {}
+    d.start()
+    d.finish()
+    assert d.record()["sclk_mhz"] is None
