@@ -448,16 +448,18 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4
 
 // One loop step of a wavefront covers KU = 1 (bf16 weights) or 2 (8-bit weights: one 16-byte load holds
 // two) k ranges of 32, U steps per round of loads.
-// MT: 32-row activation slices a workgroup multiplies its weights by (1, or 2 for decode steps of 33..64
-// sequences: the weights are still streamed once); xstride = 16-byte units between two slices
-template <int HT, int U, bool W8, int MT = 1>
+// MH: 16-row halves of the activation rows a workgroup multiplies its weights by: 2 = one 32-row slice, 4 = two
+// slices (decode steps of 33..64 sequences: the weights are still streamed once), 1 = the first half only (at
+// most 16 sequences: the other half's loads and products would be thrown away); xstride = 16-byte units
+// between two slices
+template <int HT, int U, bool W8, int MH = 2>
 struct HalfRegs {
     static constexpr int KU = W8 ? 2 : 1;
-    u32x4 w[HT][U], xh[2 * MT][U * KU], xl[2 * MT][U * KU];
+    u32x4 w[HT][U], xh[MH][U * KU], xl[MH][U * KU];
 };
 
-template <int HT, int U, bool W8, int MT = 1>
-__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MT>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl,
+template <int HT, int U, bool W8, int MH = 2>
+__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MH>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl,
                                           size_t xstride = 0) {
     constexpr int KU = W8 ? 2 : 1, WSTEP = W8 ? 64 : 128;
 #pragma unroll
@@ -467,7 +469,7 @@ __device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MT>& r, const u32x
 #pragma unroll
         for (int kp = 0; kp < KU; ++kp)
 #pragma unroll
-            for (int mh = 0; mh < 2 * MT; ++mh) {
+            for (int mh = 0; mh < MH; ++mh) {
                 r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
                 r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
             }
@@ -478,8 +480,8 @@ __device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MT>& r, const u32x
     xl += U * KU * 128;
 }
 
-template <int HT, int U, bool W8, int MT = 1>
-__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MT>& r, f32x4 (&acc)[HT][2 * MT]) {
+template <int HT, int U, bool W8, int MH = 2>
+__device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MH>& r, f32x4 (&acc)[HT][MH]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if constexpr (W8) {
@@ -490,7 +492,7 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MT>& r, f32x4
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp)
 #pragma unroll
-                    for (int mh = 0; mh < 2 * MT; ++mh) {
+                    for (int mh = 0; mh < MH; ++mh) {
                         acc[t][mh] = mfma16_bf16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
                         acc[t][mh] = mfma16_bf16(a[kp], r.xl[mh][u * 2 + kp], acc[t][mh]);
                     }
@@ -499,11 +501,11 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MT>& r, f32x4
 #pragma unroll
             for (int t = 0; t < HT; ++t)
 #pragma unroll
-                for (int mh = 0; mh < 2 * MT; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
+                for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
 #pragma unroll
             for (int t = 0; t < HT; ++t)
 #pragma unroll
-                for (int mh = 0; mh < 2 * MT; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+                for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
         }
     }
 }
@@ -512,11 +514,12 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MT>& r, f32x4
 // W8: the weights are E4M3 codes in units of [16 rows][64 k] -- lane l holds, for row l%16, the eight k
 // values 8 (l/16) + 0..7 of the unit's first 32 k in bytes 0-7 and those of its second 32 k in bytes
 // 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
-template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1>
+template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1, bool R16 = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                                const u32x4* __restrict__ Xlo, int KB, int n_half,
                                                                int ksplit, Epi p) {
-    constexpr int MH = 2 * MT;   // 16-row halves of the activation rows
+    static_assert(!R16 || MT == 1, "the first 16 rows only: one slice");
+    constexpr int MH = R16 ? 1 : 2 * MT;  // 16-row halves of the activation rows (R16: at most 16 rows in use)
     constexpr int NI = HT * MH;  // (unit, row half) items of a workgroup
     __shared__ float red[WAVES][NI][4][64];
     __shared__ float lnp[MT][WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
@@ -580,37 +583,37 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     };
     int n = kp1 - kp0;
     if (n >= U) {
-        HalfRegs<HT, U, W8, MT> ra;
-        half_load<HT, U, W8, MT>(ra, w, xh, xl, xstride);
+        HalfRegs<HT, U, W8, MH> ra;
+        half_load<HT, U, W8, MH>(ra, w, xh, xl, xstride);
         n -= U;
         request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off the loop)
         if (n >= U) {
-            HalfRegs<HT, U, W8, MT> rb;
-            half_load<HT, U, W8, MT>(rb, w, xh, xl, xstride);
+            HalfRegs<HT, U, W8, MH> rb;
+            half_load<HT, U, W8, MH>(rb, w, xh, xl, xstride);
             n -= U;
             if (fold) ln_partials();
-            half_mma<HT, U, W8, MT>(ra, acc);
+            half_mma<HT, U, W8, MH>(ra, acc);
             ra = rb;
         } else if (fold) {
             ln_partials();
         }
         while (n >= U) {
-            HalfRegs<HT, U, W8, MT> rb;
-            half_load<HT, U, W8, MT>(rb, w, xh, xl, xstride);
+            HalfRegs<HT, U, W8, MH> rb;
+            half_load<HT, U, W8, MH>(rb, w, xh, xl, xstride);
             n -= U;
-            half_mma<HT, U, W8, MT>(ra, acc);
+            half_mma<HT, U, W8, MH>(ra, acc);
             ra = rb;
         }
-        half_mma<HT, U, W8, MT>(ra, acc);
+        half_mma<HT, U, W8, MH>(ra, acc);
     } else {
         request_epilogue_operands();
         if (fold) ln_partials();
     }
     for (; n > 0; --n) {
-        HalfRegs<HT, 1, W8, MT> r1;
-        half_load<HT, 1, W8, MT>(r1, w, xh, xl, xstride);
-        half_mma<HT, 1, W8, MT>(r1, acc);
+        HalfRegs<HT, 1, W8, MH> r1;
+        half_load<HT, 1, W8, MH>(r1, w, xh, xl, xstride);
+        half_mma<HT, 1, W8, MH>(r1, acc);
     }
 #pragma unroll
     for (int t = 0; t < HT; ++t)
@@ -787,6 +790,22 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
     constexpr int U8 = (!W8 && HT == 3) ? 2 : U;
     const bool eight = HT <= 4 && (KB / (2 * KU)) / (ksplit * 8) >= 2 * U8;  // short chains per wavefront, as above
     constexpr size_t kWant = 84 * 1024;                                      // one workgroup per CU
+    if constexpr (!W8) {
+        if (m_tiles == 1 && p.M <= 16) {  // the second half of the 32 activation rows is not in use: leave it out
+            if (eight) {
+                constexpr size_t kStatic = (size_t)8 * HT * 4 * 64 * sizeof(float);
+                const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+                gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, false, 1, true><<<grid, 512, pad, s>>>(
+                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+            } else {
+                constexpr size_t kStatic = (size_t)4 * HT * 4 * 64 * sizeof(float);
+                const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
+                gemm_half_kernel<MODE, HT, U, 4, false, 1, true><<<grid, 256, pad, s>>>(
+                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+            }
+            return;
+        }
+    }
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
@@ -893,7 +912,9 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
         if (ht >= kHalfMin && ht <= kHalfMax2) g = GemmPlan{true, ht, 1};
         return g;
     }
-    if (ht >= kHalfMin && ht <= kHalfMax && 16 * ht < 32 * g.per_wg) g = GemmPlan{true, ht, 1};
+    // up to 16 rows the 16-row-unit kernel also leaves out the unused half of the activation panel: it wins ties
+    if (ht >= kHalfMin && ht <= kHalfMax && (16 * ht < 32 * g.per_wg || (M <= 16 && 16 * ht == 32 * g.per_wg)))
+        g = GemmPlan{true, ht, 1};
     return g;
 }
 
@@ -906,8 +927,9 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 // outputs a thread finishes.  (Balance alone, the earlier criterion, chose four 32-row tiles and six splits on
 // 5120x5120 and 5120x20480; five 16-row units and four splits move 12 % more bytes per workgroup and run 1-2 us
 // faster; on 4096x4096 four units and four splits run 3.4 us faster than four tiles and eight splits.)
-static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, int cus) {
-    const double per_cu = (double)K / ks * (2.0 * rows + 128.0) / 48e3;  // us at 48 GB/s
+static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, int cus, double act = 128.0) {
+    // weight rows and the activation panel (act bytes per k: 32 rows, two bf16 terms) at 48 GB/s into the CU
+    const double per_cu = (double)K / ks * (2.0 * rows + act) / 48e3;
     // the whole matrix at 6.5 TB/s; CUs left without a workgroup request nothing, and the stream slows by about
     // half their share (9216x36864: 216 workgroups on 256 CUs ran 8 % slower than 256)
     const double idle = wgs < cus ? 1.0 - (double)wgs / cus : 0.0;
@@ -935,7 +957,7 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
         while (ks > 1 && kb / (ks * 4) < 8) --ks;
         // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
         if (capacity && (size_t)groups * ks * (size_t)(mh * ht + 7) * 256 > capacity) continue;
-        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * mh + 3) / 4, ks, groups * ks, cus);
+        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * (M <= 16 ? 1 : mh) + 3) / 4, ks, groups * ks, cus, M <= 16 ? 64.0 : 128.0);
         if (cost < best) { best = cost; g = GemmPlan{true, ht, ks}; }
     }
     return g;
