@@ -92,6 +92,15 @@ def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
     # over 200 CUs four tiles (128 rows) or seven halves (112 rows)
     assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 128) == (32, 5, 1)
     assert binding.he_plan_decode_gemm(32, 20480, 5120, False, 0, 200) == (16, 7, 1)
+    # at most 16 rows: the 16-row-unit kernel leaves out the unused half of the activation panel, so it wins
+    # ties with the 32-row tiles (6.7B-shaped FC1: four units = two tiles), and the general checks still hold
+    assert binding.he_plan_decode_gemm(16, 16384, 4096, False, 0, 256) == (16, 4, 1)
+    assert binding.he_plan_decode_gemm(32, 16384, 4096, False, 0, 256) == (32, 2, 1)
+    for M in (1, 8, 16):
+        for (H, F) in ((2048, 8192), (4096, 16384), (5120, 20480), (9216, 36864)):
+            for (N, K, store) in ((3 * H, H, False), (F, H, False), (H, H, True), (H, F, True)):
+                unit, per_wg, ks = binding.he_plan_decode_gemm(M, N, K, store, 2 * 8 * 32 * H if store else 0, 256)
+                assert math.ceil(N // unit / per_wg) * ks <= 256 and ((K // 16) // (ks * 4) >= 8 or ks == 1)
     with pytest.raises(binding.HeError):
         binding.he_plan_decode_gemm(32, 100, 64)
 
