@@ -514,12 +514,14 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MH>& r, f32x4
 // W8: the weights are E4M3 codes in units of [16 rows][64 k] -- lane l holds, for row l%16, the eight k
 // values 8 (l/16) + 0..7 of the unit's first 32 k in bytes 0-7 and those of its second 32 k in bytes
 // 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
-template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1, bool R16 = false>
+template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1, int HALVES = 0>
 __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                                const u32x4* __restrict__ Xlo, int KB, int n_half,
                                                                int ksplit, Epi p) {
-    static_assert(!R16 || MT == 1, "the first 16 rows only: one slice");
-    constexpr int MH = R16 ? 1 : 2 * MT;  // 16-row halves of the activation rows (R16: at most 16 rows in use)
+    // 16-row halves of the activation rows: both of every slice, or only the first HALVES of them when no more
+    // are in use (at most 16 rows of one slice, at most 48 of two): the rest would be loaded and multiplied for nothing
+    static_assert(HALVES == 0 || (HALVES < 2 * MT && HALVES > 2 * (MT - 1)), "HALVES ends inside the last slice");
+    constexpr int MH = HALVES ? HALVES : 2 * MT;
     constexpr int NI = HT * MH;  // (unit, row half) items of a workgroup
     __shared__ float red[WAVES][NI][4][64];
     __shared__ float lnp[MT][WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
@@ -778,9 +780,16 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
         if (m_tiles == 2) {  // both 32-row slices in one workgroup: the weights are streamed once
             constexpr int U2 = HT <= 6 ? 2 : 1;
             constexpr size_t kWant2 = 84 * 1024;
+            grid.y = 1;
+            if (p.M <= 48) {  // the last 16 of the 64 rows are not in use
+                constexpr size_t kStatic = (size_t)4 * HT * 3 * 4 * 64 * sizeof(float);
+                const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
+                gemm_half_kernel<MODE, HT, U2, 4, false, 2, 3><<<grid, 256, pad, s>>>(
+                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+                return;
+            }
             constexpr size_t kStatic = (size_t)4 * HT * 4 * 4 * 64 * sizeof(float);
             const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
-            grid.y = 1;
             gemm_half_kernel<MODE, HT, U2, 4, false, 2><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
                                                                                (const u32x4*)Xlo, KB, n_half, ksplit, p);
             return;
@@ -795,12 +804,12 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
             if (eight) {
                 constexpr size_t kStatic = (size_t)8 * HT * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
-                gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, false, 1, true><<<grid, 512, pad, s>>>(
+                gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, false, 1, 1><<<grid, 512, pad, s>>>(
                     (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
             } else {
                 constexpr size_t kStatic = (size_t)4 * HT * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
-                gemm_half_kernel<MODE, HT, U, 4, false, 1, true><<<grid, 256, pad, s>>>(
+                gemm_half_kernel<MODE, HT, U, 4, false, 1, 1><<<grid, 256, pad, s>>>(
                     (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
             }
             return;
