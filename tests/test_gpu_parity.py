@@ -156,6 +156,10 @@ def test_bf16_shapes(impl, L, H, nh, F, V, B, S, G, tied):
     ("opt-6.7b", 2, 16, 64, 3),
     ("opt-13b", 1, 64, 5, 3),     # 33..64 sequences: two 32-row slices per workgroup of the weight-streaming GEMMs
     ("opt-13b", 1, 40, 4, 3),     # ... with a ragged second slice
+    ("opt-13b", 1, 16, 4, 2),     # at most 16 sequences: only the first 16-row half of the activation panel is multiplied
+    ("opt-13b", 1, 17, 4, 2),     # ... one more: both halves
+    ("opt-13b", 1, 48, 3, 2),     # at most 48: three of the two slices' four halves
+    ("opt-13b", 1, 49, 3, 2),     # ... one more: all four
     ("opt-13b", 1, 96, 5, 3),     # more than 64 sequences: the decode step on k-split prompt-pass tiles
 ])
 def test_bf16_real_layer_shapes(name, L, B, S, G):
