@@ -241,8 +241,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     __shared__ float red[WAVES][NT][16][64];
     __shared__ float lnp[WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int grp = blockIdx.x / ksplit, ks = blockIdx.x % ksplit;
-    const int mt = blockIdx.y;
+    int bx = blockIdx.x, mt = blockIdx.y;
+    if (MODE == MODE_LMHEAD && gridDim.y > 1) {
+        // Several 32-row slices each stream the whole matrix.  Workgroups go round the XCDs by index: the slices
+        // of one group of tiles are placed on ONE XCD, next to each other in dispatch order, so that they run
+        // side by side and all but the first of them find the weights in that XCD's L2 (the grid's x is padded
+        // to a multiple of eight for this).
+        const int lid = blockIdx.y * gridDim.x + blockIdx.x, span = 8 * gridDim.y;
+        bx = (lid / span) * 8 + (lid % span) % 8;
+        mt = (lid % span) / 8;
+        if (bx >= (n_tiles + NT - 1) / NT) return;  // the whole workgroup
+    }
+    const int grp = bx / ksplit, ks = bx % ksplit;
     const int parts = ksplit * WAVES, part = ks * WAVES + wave;
     const int kb0 = (int)(((long)part * KB) / parts), kb1 = (int)(((long)(part + 1) * KB) / parts);
     constexpr bool FOLDABLE = MODE == MODE_BIAS_RELU || MODE == MODE_QKV || MODE == MODE_LMHEAD;
@@ -749,6 +759,7 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
                       int m_tiles, int ksplit, const Epi& p) {
     constexpr int U = HE_SKINNY_U(NT);
     dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
+    if (MODE == MODE_LMHEAD && m_tiles > 1) grid.x = (grid.x + 7) / 8 * 8;  // see the kernel: slices of a tile group share an XCD
     // What bounds a wavefront is its serial chain of load rounds (K/16 blocks / wavefronts / U
     // rounds, about 1.7 us each under load): eight wavefronts halve the chain when K leaves each
     // of them two rounds (and their accumulators still fit in LDS for the final reduction).
