@@ -162,6 +162,23 @@ he_status he_prefill(he_engine* e, const int32_t* d_prompt_ids, int B, int S, co
 he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
                          float* d_logprobs, float* d_logits_opt);
 
+/* he_decode_step for callers that cannot allocate device memory or tolerate a call that might: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * (bit for bit) as he_decode_step.  The step's scratch -- the k-split partial sums of the out-projection
+ * and FC2, the column-group statistics and arrival counters of the folded LayerNorms, and the LM head's
+ * per-tile soft-max / arg-max partials -- lives in a file-scope device array of 16 MiB inside the library
+ * (every GPU the library runs on holds its own copy until the process ends) instead of the engine's
+ * workspace; the call makes no hipMalloc / hipFree / event or graph creation and launches its kernels one by
+ * one on cfg.stream.  KV arena, activations and weights are still the engine's (he_create allocated them).
+ * Limits: dtype bf16 with impl 0; at most 64 sequences (32 with weights_fp8); HE_ERR_CAPACITY with the byte
+ * counts in he_last_error when model width, vocabulary and batch together need more than the 16 MiB
+ * (the OPT-13B-shaped headline workload needs about 5.3 MiB); HE_ERR_STATE when the engine's device is not the
+ * current device.  All engines on one GPU share that GPU's array, which keeps the last call's contents:
+ * the call clears what must start at zero itself, and two such calls that overlap in time on one GPU
+ * (different streams, different engines) race -- serialise them. */
+he_status he_decode_step_static(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
+                                float* d_logprobs, float* d_logits_opt);
+
 /* The whole generation phase: reset, prefill, then G-1 decode steps that feed
  * each sampled token back (the steps run as replays of one captured HIP
  * graph).  d_out_ids [B, G] int32 and d_out_logprobs [B, G] float, row-major.

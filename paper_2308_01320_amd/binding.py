@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
     L.he_prefill.argtypes = [vp, ip, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp, fp]
     L.he_decode_step.restype = C.c_int
     L.he_decode_step.argtypes = [vp, ip, C.POINTER(he_sampling), ip, fp, fp]
+    L.he_decode_step_static.restype = C.c_int
+    L.he_decode_step_static.argtypes = [vp, ip, C.POINTER(he_sampling), ip, fp, fp]
     L.he_generate.restype = C.c_int
     L.he_generate.argtypes = [vp, ip, C.c_int, C.c_int, C.c_int, C.POINTER(he_sampling), ip, fp]
     L.he_prefill_ragged.restype = C.c_int
@@ -132,7 +134,7 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
            "he_tile_matrix", "he_score", "he_prefill_ragged",
            "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena",
-           "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows")
+           "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows", "he_decode_step_static")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -241,6 +243,16 @@ class Engine:
         lg = t.empty(B, self.cfg.vocab, dtype=t.float32, device=self.device) if want_logits else None
         self._check(lib().he_decode_step(self.handle, in_ids.data_ptr(), C.byref(samp), ids.data_ptr(),
                                          lp.data_ptr(), _ptr(lg)))
+        return ids, lp, lg
+
+    def he_decode_step_static(self, in_ids, samp: he_sampling, want_logits=False):
+        t = self._torch
+        B = in_ids.shape[0]
+        ids = t.empty(B, dtype=t.int32, device=self.device)
+        lp = t.empty(B, dtype=t.float32, device=self.device)
+        lg = t.empty(B, self.cfg.vocab, dtype=t.float32, device=self.device) if want_logits else None
+        self._check(lib().he_decode_step_static(self.handle, in_ids.data_ptr(), C.byref(samp), ids.data_ptr(),
+                                                lp.data_ptr(), _ptr(lg)))
         return ids, lp, lg
 
     def he_generate(self, prompt_ids, G: int, samp: he_sampling, out_ids=None, out_lp=None):

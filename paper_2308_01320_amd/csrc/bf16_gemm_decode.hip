@@ -1029,6 +1029,25 @@ void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int*
     *ks = g.ks;
 }
 
+// Floats of k-split scratch the EPI_STORE_LN launch of this shape may index (an upper bound: per column
+// group, row-slice pair and split, one 256-float run per item, items rounded up to whole wavefronts).
+size_t bf16_store_need(int M, int N, int K, size_t capacity, int w8) {
+    const int m_tiles = (M + 31) / 32;
+    if (w8) {
+        const GemmPlan g = plan_store_w8(N, K, capacity);
+        const size_t groups = (size_t)(N / 16 + g.per_wg - 1) / g.per_wg;
+        return groups * m_tiles * g.ks * (size_t)(2 * g.per_wg + 7) * 256;
+    }
+    const GemmPlan g = plan_store(M, N, K, capacity);
+    if (g.half) {
+        const size_t groups = (size_t)(N / 16 + g.per_wg - 1) / g.per_wg;
+        const int grid_y = m_tiles == 2 ? 1 : m_tiles, mh = m_tiles == 2 ? 4 : 2;
+        return groups * grid_y * g.ks * (size_t)(mh * g.per_wg + 7) * 256;
+    }
+    const size_t groups = (size_t)((N + 31) / 32 + g.per_wg - 1) / g.per_wg;
+    return groups * m_tiles * g.ks * (size_t)(4 * g.per_wg + 7) * 256;
+}
+
 void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
                       int ksplit, const bf16_gemm_args& a) {
     (void)ksplit;

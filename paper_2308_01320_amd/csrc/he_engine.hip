@@ -71,6 +71,21 @@ struct he_engine {
 
 static std::string g_create_error;
 
+// ---- he_decode_step_static: the decode step's scratch in memory that is never allocated
+//
+// A file-scope device array that every GPU the library runs on holds from load to exit.  In host code the
+// array's name is only a stand-in; the device address is looked up once per device (with that device
+// current) and kept, and only that pointer is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char he_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_static_ptr[kMaxDevices] = {};
+
+// zeroes `count` 32-bit words (a kernel, not hipMemsetAsync: the caller may be capturing a graph)
+__global__ void zero_words_kernel(uint32_t* __restrict__ p, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 namespace {
 
 struct Sizes {
@@ -853,6 +868,73 @@ he_status he_decode_step(he_engine* e, const int32_t* d_in_ids, const he_samplin
     if (e->cur_len + 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_decode_step: position table exhausted");
     launch_set_state(e->stream, e->st, 0, 0, 0, sampling->mode, sampling->temperature, sampling->seed);
     return run_forward(e, d_in_ids, e->batch, 1, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
+}
+
+// How the static array is shared out for a decode step of engine e (256-byte aligned pieces):
+// k-split partial sums | column-group statistics | arrival counters | LM-head partials | their ids.
+struct StaticLayout { size_t part, ln_stats, ln_counters, stats, stats_idx, total, part_floats; };
+static StaticLayout static_layout(const he_engine* e, int B) {
+    const he_config& c = e->cfg;
+    const int H = c.hidden, F = c.ffn;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    StaticLayout L{};
+    // what the two k-split GEMMs of this step will index, planned exactly as he_decode_step plans them
+    const size_t n1 = bf16_store_need(B, H, H, e->part_floats, e->w8), n2 = bf16_store_need(B, H, F, e->part_floats, e->w8);
+    L.part_floats = std::max(n1, n2);
+    const Sizes z = sizes_of(c);
+    L.part = 0;
+    L.ln_stats = up(L.part + L.part_floats * sizeof(float));
+    L.ln_counters = up(L.ln_stats + z.ln_stats);
+    L.stats = up(L.ln_counters + z.ln_counters);
+    L.stats_idx = up(L.stats + z.stats);
+    L.total = up(L.stats_idx + z.stats_idx);
+    return L;
+}
+
+he_status he_decode_step_static(he_engine* e, const int32_t* d_in_ids, const he_sampling* sampling, int32_t* d_next_ids,
+                                float* d_logprobs, float* d_logits_opt) {
+    if (!e) return HE_ERR_INVALID_ARG;
+    if (!d_in_ids || !d_next_ids || !d_logprobs) return fail(e, HE_ERR_INVALID_ARG, "he_decode_step_static: NULL buffer");
+    if (const char* m = check_sampling(sampling)) return fail(e, HE_ERR_INVALID_ARG, m);
+    if (!e->fast) return fail(e, HE_ERR_STATE, "he_decode_step_static: dtype bf16, impl 0 only");
+    if (e->cur_len == 0 || e->batch == 0) return fail(e, HE_ERR_STATE, "he_decode_step_static: no prompt has been prefilled");
+    if (e->cur_len + 1 > e->cfg.max_seq_len) return fail(e, HE_ERR_CAPACITY, "he_decode_step_static: KV cache is full");
+    if (e->cur_len + 1 > e->cfg.max_positions) return fail(e, HE_ERR_CAPACITY, "he_decode_step_static: position table exhausted");
+    if (wide_decode(e, e->batch))
+        return fail(e, HE_ERR_CAPACITY, "he_decode_step_static: the batch is too large for the weight-streaming decode kernels "
+                                        "(at most 64 sequences, 32 with 8-bit weights)");
+    const StaticLayout L = static_layout(e, e->batch);
+    if (L.total > kStaticScratchBytes)
+        return fail(e, HE_ERR_CAPACITY, "he_decode_step_static: this model and batch need " + std::to_string(L.total) +
+                                            " bytes of scratch, the static array holds " + std::to_string(kStaticScratchBytes));
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != e->cfg.device)
+        return fail(e, HE_ERR_STATE, "he_decode_step_static: the engine's device is not the current device");
+    if (dev >= kMaxDevices) return fail(e, HE_ERR_CAPACITY, "he_decode_step_static: device ordinal beyond the table");
+    if (!g_static_ptr[dev]) {  // once per device, with that device current
+        void* ptr = nullptr;
+        const hipError_t r = hipGetSymbolAddress(&ptr, HIP_SYMBOL(he_static_scratch));
+        if (r != hipSuccess || !ptr) return check_hip(e, r != hipSuccess ? r : hipErrorInvalidSymbol, "hipGetSymbolAddress");
+        g_static_ptr[dev] = ptr;
+    }
+    unsigned char* base = (unsigned char*)g_static_ptr[dev];
+    // The array keeps the last call's contents: statistics and counters start from zero (the k-split partial
+    // sums and the LM-head partials are written before they are read).
+    const size_t zero_words = (L.stats - L.ln_stats) / sizeof(uint32_t);
+    zero_words_kernel<<<(unsigned)std::min<size_t>((zero_words + 255) / 256, 64), 256, 0, e->stream>>>(
+        (uint32_t*)(base + L.ln_stats), zero_words);
+    launch_set_state(e->stream, e->st, 0, 0, 0, sampling->mode, sampling->temperature, sampling->seed);
+    // the step itself: the same launches as he_decode_step, one by one, with the five scratch pointers swapped
+    float *part = e->part, *ln_stats = e->ln_stats, *stats = e->stats;
+    int *ln_counters = e->ln_counters, *stats_idx = e->stats_idx;
+    e->part = (float*)(base + L.part); e->ln_stats = (float*)(base + L.ln_stats); e->ln_counters = (int*)(base + L.ln_counters);
+    e->stats = (float*)(base + L.stats); e->stats_idx = (int*)(base + L.stats_idx);
+    const bool timing = e->timing;  // the timing hook creates events on demand: off for this call
+    e->timing = false;
+    const he_status rc = run_forward(e, d_in_ids, e->batch, 1, d_next_ids, d_logprobs, 1, 0, d_logits_opt);
+    e->timing = timing;
+    e->part = part; e->ln_stats = ln_stats; e->ln_counters = ln_counters; e->stats = stats; e->stats_idx = stats_idx;
+    return rc;
 }
 
 static he_status generate_impl(he_engine* e, const char* who, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens,

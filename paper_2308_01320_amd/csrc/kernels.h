@@ -74,6 +74,8 @@ void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
 // EPI_STORE_LN GEMM of M <= 32 rows: columns per workgroup (= per group of LayerNorm statistics) and k-splits;
 // capacity = floats of k-split scratch available (the value passed as bf16_gemm_args.out_capacity)
 void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks);
+// floats of k-split scratch that launch may index (upper bound); w8 != 0: the 8-bit-weight plan
+size_t bf16_store_need(int M, int N, int K, size_t capacity, int w8);
 // the launch plan itself (host logic only; cus > 0 overrides the device's CU count): rows per unit (32 or 16),
 // units per workgroup, k-splits; store != 0 for the k-split GEMMs
 void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks);
