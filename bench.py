@@ -26,39 +26,6 @@ HBM_PEAK = 8.0e12        # B/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 
 
-def device_weights(d, torch, seed=0, std=0.02, tiled=False):
-    """Random-init bf16 weights generated on the device, tensor by tensor.  tiled=True: every GEMM
-    matrix is converted to the engine's MFMA-tiled form as soon as it is drawn and the row-major
-    original dropped (he_config.weights_tiled = 1: no second copy, for models that fill HBM)."""
-    from paper_2308_01320_amd import binding
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    dt = torch.bfloat16
-
-    def draw(shape, mean=0.0):
-        t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
-        return (t * std + mean).to(dt).contiguous()
-
-    def mat(shape):
-        m = draw(shape)
-        if not tiled:
-            return m
-        t = binding.he_tile_matrix(m)
-        torch.cuda.synchronize()
-        return t
-
-    H, F = d.hidden, d.ffn
-    w = {"tok_emb": draw((d.vocab, H)), "pos_emb": draw((d.max_positions + d.pos_offset, H)), "layers": []}
-    for _ in range(d.n_layers):
-        w["layers"].append({
-            "ln1_g": draw((H,), 1.0), "ln1_b": draw((H,)), "wqkv": mat((3 * H, H)), "bqkv": draw((3 * H,)),
-            "wo": mat((H, H)), "bo": draw((H,)), "ln2_g": draw((H,), 1.0), "ln2_b": draw((H,)),
-            "w1": mat((F, H)), "b1": draw((F,)), "w2": mat((H, F)), "b2": draw((H,))})
-    w["lnf_g"], w["lnf_b"] = draw((H,), 1.0), draw((H,))
-    w["lm_head"] = binding.he_tile_matrix(w["tok_emb"]) if tiled else w["tok_emb"]
-    return w
-
-
 def algorithmic_bytes(d, fp8=False):
     """Bytes the method itself must move per decode step (weights once for the whole
     batch; K/V of every cached position read, the new position written).  With 8-bit layer
@@ -95,13 +62,13 @@ def cpu_baseline(d, seconds_hint=20.0):
          for k, v in w.items()}
     w["lm_head"] = w["tok_emb"]
     prompts = synth.make_prompts(ds, seed=2)
-    dec = O.CachedDecoder(w, ds.n_heads, ds.ln_eps, ds.pos_offset, "bf16")
+    dec = O.CachedDecoder(w, ds.n_heads, ds.ln_eps, ds.pos_offset)
     t0 = time.perf_counter()
     z = dec.prefill(prompts)
     t_prefill = time.perf_counter() - t0
     t0 = time.perf_counter()
     for n in range(steps):
-        tok, _, _ = O.sample(z, d.sampling, 1.0, 42, n)
+        tok = O.sample(z, d.sampling, 1.0, 42, n)[0]
         z = dec.step(tok)
     t_step = (time.perf_counter() - t0) / steps
     # the head (final LayerNorm + LM head + sampling) does not scale with layers
@@ -215,7 +182,7 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()  # default priority; the engine captures its decode step on it
     tiled = args.weights_tiled or d.name == "opt-66b"
-    weights = device_weights(d, torch, tiled=tiled)
+    weights = synth.device_weights(d, torch, tile=binding.he_tile_matrix if tiled else None)
     torch.cuda.synchronize()
     cfg = binding.make_config(d, stream=stream.cuda_stream, weights_tiled=1 if tiled else 0,
                               weights_fp8=1 if args.weights_fp8 else 0)

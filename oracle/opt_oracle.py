@@ -23,8 +23,8 @@ Pins (tests/test_oracle_*.py): cached == cache-free; softmax rows sum to 1;
 causal exactness; closed forms for degenerate weights; every primitive against
 torch's float64 CPU routine; whole model against an independently written
 OPT implementation (transformers, random init); Philox known-answer vectors;
-Gumbel-max token frequencies against softmax; bfloat16 rounding against
-torch's conversion; the scoring pass against that same independent
+Gumbel-max token frequencies against softmax; bfloat16 and half rounding against
+torch's conversions; the scoring pass against that same independent
 implementation's cross-entropy, a uniform-logits closed form, normalisation
 over every possible next token, and the log-probabilities `generate` reports.  The bf16 tolerance (2e-2) is fixed by the benchmark
 definition, not by the paper: parity unpinned for that number only.
@@ -75,10 +75,9 @@ def attention(q, k, v, q_pos):
 
 def round_bf16(x):
     """Nearest bfloat16 (8 significant bits, ties to even) of float64 values, returned
-    as float64.  Used only for the KV cache of the bf16 configuration: the cache's
-    storage format is part of that configuration, like the weights' format, so the
-    oracle stores in it what the format can hold.  (Values are assumed to lie in
-    bfloat16's normal range, as keys and values of O(1) do.)"""
+    as float64: the format the bf16 configuration's weights are given in (used where
+    a weight is formed here: LoRA merge, 8-bit dequantisation checks).  (Values are
+    assumed to lie in bfloat16's normal range.)"""
     u = np.ascontiguousarray(x, F64).view(np.uint64)
     drop = np.uint64(45)  # 52 fraction bits -> 7
     half = ((u >> drop) & np.uint64(1)) + np.uint64((1 << 44) - 1)
@@ -86,7 +85,17 @@ def round_bf16(x):
     return r.view(F64)
 
 
-def merge_lora(W, A, B, scale):
+def round_f16(x):
+    """Nearest IEEE half (11 significant bits, subnormals below 2^-14, ties to even) of
+    float64 values, returned as float64; magnitudes above 65504 + 16 become infinite.
+    DIAGNOSTIC ONLY: lets a test separate what an implementation's half-precision KV
+    cache costs from everything else (kv_dtype="f16" below).  The definition the
+    parity tests hold an implementation to keeps keys and values unrounded."""
+    with np.errstate(over="ignore"):  # beyond the format's range: infinity, as the format says
+        return np.asarray(x, F64).astype(np.float16).astype(F64)
+
+
+def merge_lora(W, A, B, scale, exact=False):
     """Weights with a low-rank adapter folded in, as stored for generation:
     bf16(W + scale * B A), W [out,in], A [rank,in], B [out,rank] (Section 4: the
     actor is trained with LoRA and generates with the inference kernels, which
@@ -96,7 +105,12 @@ def merge_lora(W, A, B, scale):
     takes it in, float32, in this order: t = sum over j = 0..rank-1 of B[:,j] A[j,:]
     (each product exact for bf16 inputs, added one by one), then W + scale * t, each
     operation rounded to float32; the result is rounded to nearest-even bf16.
+    exact=True: the plain definition instead, W + scale * (B @ A) in float64 rounded
+    once to bf16 (the two differ by one bf16 step where the float32 sum falls on the
+    other side of a rounding boundary).
     Returns float64 holding the bf16 values."""
+    if exact:
+        return round_bf16(np.asarray(W, F64) + float(scale) * (np.asarray(B, F64) @ np.asarray(A, F64)))
     W32, A32, B32 = (np.asarray(x, np.float32) for x in (W, A, B))
     t = np.zeros_like(W32)
     for j in range(A32.shape[0]):
@@ -157,8 +171,9 @@ def log_softmax(z):
 def _layer(x, lw, n_heads, eps, k_past, v_past, pos0, kv_dtype="f64"):
     """One pre-LN decoder layer over x [B,M,H] whose rows sit at positions
     pos0..pos0+M-1; k_past/v_past [B,pos0,H] are earlier positions (or None).
-    kv_dtype "bf16": keys and values are held in bfloat16, every query (the
-    row's own included) reads them back from there.  Returns (x_out, k_all, v_all)."""
+    kv_dtype "f64" is the definition.  "f16" is a diagnostic: keys and values are
+    rounded to IEEE half when stored and every query (the row's own included) reads
+    them back from there.  Returns (x_out, k_all, v_all)."""
     B, M, H = x.shape
     d = H // n_heads
     a = layer_norm(x, lw["ln1_g"], lw["ln1_b"], eps)
@@ -166,8 +181,8 @@ def _layer(x, lw, n_heads, eps, k_past, v_past, pos0, kv_dtype="f64"):
     q = qkv[..., 0:H] * d ** -0.5
     k = qkv[..., H:2 * H]
     v = qkv[..., 2 * H:3 * H]
-    if kv_dtype == "bf16":
-        k, v = round_bf16(k), round_bf16(v)
+    if kv_dtype == "f16":
+        k, v = round_f16(k), round_f16(v)
     elif kv_dtype != "f64":
         raise ValueError(kv_dtype)
     if k_past is not None:
@@ -302,14 +317,16 @@ def gumbel_noise(seed, b, n, V):
 def sample(z, mode, temperature, seed, n, rows=None):
     """z [B,V] logits of generation step n; row i is sequence rows[i] of the
     batch (default i) -- the noise is keyed by that number.  Returns (tok int32 [B],
-    logprob [B], margin [B]): greedy takes argmax z; 'gumbel' takes
+    logprob [B], margin [B], second int32 [B]): greedy takes argmax z; 'gumbel' takes
     argmax(z/temperature + g).  Ties go to the lowest index.  logprob is the
     untempered log-softmax of z at tok; margin is the gap between the best and
-    second-best arg-maxed score (ids are only unique where it is large)."""
+    second-best arg-maxed score (ids are only unique where it is large) and second
+    the id of that second-best score (-1 when the vocabulary has one entry)."""
     z = np.asarray(z, F64)
     B, V = z.shape
     lp = log_softmax(z)
     tok = np.empty(B, np.int32)
+    second = np.full(B, -1, np.int32)
     margin = np.empty(B, F64)
     for b in range(B):
         if mode == "greedy":
@@ -321,11 +338,13 @@ def sample(z, mode, temperature, seed, n, rows=None):
         t = int(np.argmax(score))  # first maximum = lowest index
         tok[b] = t
         if V > 1:
-            rest = np.delete(score, t)
-            margin[b] = score[t] - rest.max()
+            rest = score.copy()
+            rest[t] = -np.inf
+            second[b] = int(np.argmax(rest))
+            margin[b] = score[t] - rest[second[b]]
         else:
             margin[b] = np.inf
-    return tok, lp[np.arange(B), tok], margin
+    return tok, lp[np.arange(B), tok], margin, second
 
 
 def generate(w, prompt_ids, G, n_heads, mode="greedy", temperature=1.0, seed=0,
@@ -335,22 +354,24 @@ def generate(w, prompt_ids, G, n_heads, mode="greedy", temperature=1.0, seed=0,
     [B,G] is given, those ids are fed forward instead of the sampled ones
     (teacher forcing) while the sampled ids are still reported.
 
-    Returns dict(ids [B,G], logprobs [B,G], margins [B,G], logits [G,B,V])."""
+    Returns dict(ids [B,G], logprobs [B,G], margins [B,G], second [B,G] (the runner-up
+    ids), logits [G,B,V])."""
     prompt_ids = np.asarray(prompt_ids)
     B = prompt_ids.shape[0]
     dec = CachedDecoder(w, n_heads, eps, pos_offset, kv_dtype)
     ids = np.empty((B, G), np.int32)
+    sec = np.empty((B, G), np.int32)
     lps = np.empty((B, G), F64)
     mar = np.empty((B, G), F64)
     logits = []
     z = dec.prefill(prompt_ids)
     for n in range(G):
         logits.append(z)
-        ids[:, n], lps[:, n], mar[:, n] = sample(z, mode, temperature, seed, n)
+        ids[:, n], lps[:, n], mar[:, n], sec[:, n] = sample(z, mode, temperature, seed, n)
         if n + 1 < G:
             feed = ids[:, n] if forced_ids is None else np.asarray(forced_ids)[:, n]
             z = dec.step(feed)
-    return {"ids": ids, "logprobs": lps, "margins": mar, "logits": np.stack(logits)}
+    return {"ids": ids, "logprobs": lps, "margins": mar, "second": sec, "logits": np.stack(logits)}
 
 
 def generate_ragged(w, prompts, G, n_heads, mode="greedy", temperature=1.0, seed=0, eos_id=-1, pad_id=0,
@@ -373,10 +394,11 @@ def generate_ragged(w, prompts, G, n_heads, mode="greedy", temperature=1.0, seed
     the fed id).
 
     Returns dict(ids [B,G], logprobs [B,G], margins [B,G] (inf where nothing was
-    sampled), lens [B] = tokens produced including the end token, logits = list
-    over b of [lens[b], V])."""
+    sampled), second [B,G] (runner-up ids, -1 where nothing was sampled), lens [B] =
+    tokens produced including the end token, logits = list over b of [lens[b], V])."""
     B = len(prompts)
     ids = np.full((B, G), pad_id, np.int32)
+    sec = np.full((B, G), -1, np.int32)
     lps = np.zeros((B, G), F64)
     mar = np.full((B, G), np.inf, F64)
     lens = np.zeros(B, np.int32)
@@ -387,12 +409,12 @@ def generate_ragged(w, prompts, G, n_heads, mode="greedy", temperature=1.0, seed
         zs = []
         for n in range(G):
             zs.append(z[0])
-            tok, lp, m = sample(z, mode, temperature, seed, n, rows=[b])
-            ids[b, n], lps[b, n], mar[b, n] = tok[0], lp[0], m[0]
+            tok, lp, m, s2 = sample(z, mode, temperature, seed, n, rows=[b])
+            ids[b, n], lps[b, n], mar[b, n], sec[b, n] = tok[0], lp[0], m[0], s2[0]
             lens[b] = n + 1
             feed = tok[0] if forced_ids is None else int(np.asarray(forced_ids)[b, n])
             if feed == eos_id or n + 1 == G:
                 break
             z = dec.step(np.array([feed]))
         logits.append(np.stack(zs))
-    return {"ids": ids, "logprobs": lps, "margins": mar, "lens": lens, "logits": logits}
+    return {"ids": ids, "logprobs": lps, "margins": mar, "second": sec, "lens": lens, "logits": logits}

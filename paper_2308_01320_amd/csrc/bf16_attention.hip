@@ -1,4 +1,4 @@
-// bf16 path: attention over the bf16 KV cache (decode rows, short prompts, prompt rows on the matrix cores).
+// bf16 path: attention over the KV cache of IEEE halves (decode rows, short prompts, prompt rows on the matrix cores).
 #include "bf16_common.h"
 
 using namespace he_bf16;
@@ -11,10 +11,10 @@ namespace {
 // sees keys 0..that position.  D/8 adjacent lanes own one key (16 bytes each, a
 // whole row of K or V per group, coalesced); scores are reduced with wavefront
 // shuffles, kept in LDS, soft-maxed, then the same lanes accumulate p_j * V[j].
-// The output goes out as tiled bf16 blocks for the out-projection GEMM.
+// The output goes out as tiled half blocks for the out-projection GEMM.
 template <int D>
-__global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kv,
-                                                   u32x4* __restrict__ o, u32x4* __restrict__ o_lo,
+__global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, const half_t* __restrict__ kv,
+                                                   u32x4* __restrict__ o,
                                                    const he_dev_state* __restrict__ st, int S, int layer, int H,
                                                    int n_heads, int max_batch, int max_seq) {
     constexpr int LPK = D / 8;     // lanes per key
@@ -33,7 +33,6 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
         if (wave == 0 && grp == 0) {
             const size_t slot = block_slot(m, h * D + sub * 8, H >> 4);
             o[slot] = u32x4{0u, 0u, 0u, 0u};
-            if (o_lo) o_lo[slot] = u32x4{0u, 0u, 0u, 0u};
         }
         return;
     }
@@ -61,14 +60,14 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
-            float s = qa.x * __uint_as_float(cur[u].x << 16);
-            s = fmaf(qa.y, __uint_as_float(cur[u].x & 0xFFFF0000u), s);
-            s = fmaf(qa.z, __uint_as_float(cur[u].y << 16), s);
-            s = fmaf(qa.w, __uint_as_float(cur[u].y & 0xFFFF0000u), s);
-            s = fmaf(qb.x, __uint_as_float(cur[u].z << 16), s);
-            s = fmaf(qb.y, __uint_as_float(cur[u].z & 0xFFFF0000u), s);
-            s = fmaf(qb.z, __uint_as_float(cur[u].w << 16), s);
-            s = fmaf(qb.w, __uint_as_float(cur[u].w & 0xFFFF0000u), s);
+            float s = qa.x * half_lo(cur[u].x);
+            s = fmaf(qa.y, half_hi(cur[u].x), s);
+            s = fmaf(qa.z, half_lo(cur[u].y), s);
+            s = fmaf(qa.w, half_hi(cur[u].y), s);
+            s = fmaf(qb.x, half_lo(cur[u].z), s);
+            s = fmaf(qb.y, half_hi(cur[u].z), s);
+            s = fmaf(qb.z, half_lo(cur[u].w), s);
+            s = fmaf(qb.w, half_hi(cur[u].w), s);
 #pragma unroll
             for (int o2 = 1; o2 < LPK; o2 <<= 1) s += __shfl_xor(s, o2);
             if (j < T) {
@@ -101,14 +100,14 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
             const float pj = j < T ? sc[j] : 0.f;
-            acc[0] = fmaf(pj, __uint_as_float(cur[u].x << 16), acc[0]);
-            acc[1] = fmaf(pj, __uint_as_float(cur[u].x & 0xFFFF0000u), acc[1]);
-            acc[2] = fmaf(pj, __uint_as_float(cur[u].y << 16), acc[2]);
-            acc[3] = fmaf(pj, __uint_as_float(cur[u].y & 0xFFFF0000u), acc[3]);
-            acc[4] = fmaf(pj, __uint_as_float(cur[u].z << 16), acc[4]);
-            acc[5] = fmaf(pj, __uint_as_float(cur[u].z & 0xFFFF0000u), acc[5]);
-            acc[6] = fmaf(pj, __uint_as_float(cur[u].w << 16), acc[6]);
-            acc[7] = fmaf(pj, __uint_as_float(cur[u].w & 0xFFFF0000u), acc[7]);
+            acc[0] = fmaf(pj, half_lo(cur[u].x), acc[0]);
+            acc[1] = fmaf(pj, half_hi(cur[u].x), acc[1]);
+            acc[2] = fmaf(pj, half_lo(cur[u].y), acc[2]);
+            acc[3] = fmaf(pj, half_hi(cur[u].y), acc[3]);
+            acc[4] = fmaf(pj, half_lo(cur[u].z), acc[4]);
+            acc[5] = fmaf(pj, half_hi(cur[u].z), acc[5]);
+            acc[6] = fmaf(pj, half_lo(cur[u].w), acc[6]);
+            acc[7] = fmaf(pj, half_hi(cur[u].w), acc[7]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) cur[u] = nxt[u];
@@ -131,12 +130,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
             const int i = threadIdx.x * 8 + e;
             ov[e] = ((ored[0][i] + ored[1][i]) + (ored[2][i] + ored[3][i])) * inv;
         }
-        uint32_t oh[4], ol[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) split2(ov[2 * e], ov[2 * e + 1], oh[e], ol[e]);
         const size_t slot = block_slot(m, h * D + threadIdx.x * 8, H >> 4);
-        o[slot] = u32x4{oh[0], oh[1], oh[2], oh[3]};
-        if (o_lo) o_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+        o[slot] = u32x4{pack2(ov[0], ov[1]), pack2(ov[2], ov[3]), pack2(ov[4], ov[5]), pack2(ov[6], ov[7])};
     }
 }
 
@@ -150,8 +145,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 constexpr int QB = 8;
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kv,
-                                                          u32x4* __restrict__ o, u32x4* __restrict__ o_lo,
+__global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restrict__ q, const half_t* __restrict__ kv,
+                                                          u32x4* __restrict__ o,
                                                           const he_dev_state* __restrict__ st, int S, int layer, int H,
                                                           int n_heads, int max_batch, int max_seq) {
     constexpr int LPK = D / 8, KPW = 64 / LPK, KR = 4 * KPW, U = 2, STEP = KR * U;
@@ -203,10 +198,10 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
-            const float k0 = __uint_as_float(cur_r[u].x << 16), k1 = __uint_as_float(cur_r[u].x & 0xFFFF0000u);
-            const float k2 = __uint_as_float(cur_r[u].y << 16), k3 = __uint_as_float(cur_r[u].y & 0xFFFF0000u);
-            const float k4 = __uint_as_float(cur_r[u].z << 16), k5 = __uint_as_float(cur_r[u].z & 0xFFFF0000u);
-            const float k6 = __uint_as_float(cur_r[u].w << 16), k7 = __uint_as_float(cur_r[u].w & 0xFFFF0000u);
+            const float k0 = half_lo(cur_r[u].x), k1 = half_hi(cur_r[u].x);
+            const float k2 = half_lo(cur_r[u].y), k3 = half_hi(cur_r[u].y);
+            const float k4 = half_lo(cur_r[u].z), k5 = half_hi(cur_r[u].z);
+            const float k6 = half_lo(cur_r[u].w), k7 = half_hi(cur_r[u].w);
             float part[QB];
 #pragma unroll
             for (int i = 0; i < QB; ++i) {
@@ -263,10 +258,10 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
         for (int u = 0; u < U; ++u) {
             const int j = base + u * KR + jw;
             if (j < T) {
-                const float v0 = __uint_as_float(cur_r[u].x << 16), v1 = __uint_as_float(cur_r[u].x & 0xFFFF0000u);
-                const float v2 = __uint_as_float(cur_r[u].y << 16), v3 = __uint_as_float(cur_r[u].y & 0xFFFF0000u);
-                const float v4 = __uint_as_float(cur_r[u].z << 16), v5 = __uint_as_float(cur_r[u].z & 0xFFFF0000u);
-                const float v6 = __uint_as_float(cur_r[u].w << 16), v7 = __uint_as_float(cur_r[u].w & 0xFFFF0000u);
+                const float v0 = half_lo(cur_r[u].x), v1 = half_hi(cur_r[u].x);
+                const float v2 = half_lo(cur_r[u].y), v3 = half_hi(cur_r[u].y);
+                const float v4 = half_lo(cur_r[u].z), v5 = half_hi(cur_r[u].z);
+                const float v6 = half_lo(cur_r[u].w), v7 = half_hi(cur_r[u].w);
 #pragma unroll
                 for (int i = 0; i < QB; ++i) {
                     const float pj = sc[i * max_seq + j];
@@ -304,12 +299,8 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
             const int d0 = c * 8 + e;
             ov[e] = ((ored[0][i][d0] + ored[1][i][d0]) + (ored[2][i][d0] + ored[3][i][d0])) * inv;
         }
-        uint32_t oh[4], ol[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) split2(ov[2 * e], ov[2 * e + 1], oh[e], ol[e]);
         const size_t slot = block_slot(b * S + t0 + i, h * D + c * 8, H >> 4);
-        o[slot] = u32x4{oh[0], oh[1], oh[2], oh[3]};
-        if (o_lo) o_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+        o[slot] = u32x4{pack2(ov[0], ov[1]), pack2(ov[2], ov[3]), pack2(ov[4], ov[5]), pack2(ov[6], ov[7])};
     }
 }
 
@@ -320,20 +311,19 @@ __global__ __launch_bounds__(256) void attn_prompt_kernel(const float* __restric
 // LDS.  Everything is computed transposed so that a lane owns ONE query: S^T = K Q^T puts the
 // scores of query lane%32 in that lane's 16 accumulators (online soft-max needs one exchange
 // with lane^32), and O^T = V^T P^T accumulates that query's output column, so the soft-max
-// rescaling is a per-lane scalar.  Q and P enter the MFMA as two bf16 terms (hi + lo).  The
+// rescaling is a per-lane scalar.  Q and P enter the MFMA as two half terms (hi + lo).  The
 // keys of a PV step are taken in the order the score accumulators already hold them; the V^T
 // operand is gathered in that order from the staged rows with 16-bit LDS reads.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* __restrict__ q,
-                                                               const bf16_t* __restrict__ kv, u32x4* __restrict__ o,
-                                                               u32x4* __restrict__ o_lo,
+                                                               const half_t* __restrict__ kv, u32x4* __restrict__ o,
                                                                const he_dev_state* __restrict__ st, int S, int layer,
                                                                int H, int n_heads, int max_batch, int max_seq) {
     constexpr int KBD = D / 16;      // k-blocks over the head dimension
     constexpr int DB = D / 32;       // 32-wide blocks of output dimensions
-    constexpr int KPITCH = D + 8;    // bf16 per K row in LDS (16 bytes of padding)
-    __shared__ __align__(16) bf16_t ks[32 * KPITCH];
-    __shared__ __align__(16) bf16_t vs[32 * KPITCH];
+    constexpr int KPITCH = D + 8;    // halves per K row in LDS (16 bytes of padding)
+    __shared__ __align__(16) half_t ks[32 * KPITCH];
+    __shared__ __align__(16) half_t vs[32 * KPITCH];
     const int h = blockIdx.y, b = blockIdx.z;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int j = lane & 31, hh = lane >> 5;
@@ -363,8 +353,8 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
             qlo[kb] = u32x4{l0, l1, l2, l3};
         }
     }
-    const bf16_t* Kg = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D);
-    const bf16_t* Vg = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D);
+    const half_t* Kg = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, D);
+    const half_t* Vg = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, D);
     f32x16 oacc[DB];
 #pragma unroll
     for (int i = 0; i < DB; ++i) oacc[i] = f32x16{};
@@ -405,8 +395,8 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
 #pragma unroll
         for (int kb = 0; kb < KBD; ++kb) {
             const u32x4 kblk = *reinterpret_cast<const u32x4*>(&ks[j * KPITCH + kb * 16 + hh * 8]);
-            sacc = mfma_bf16(kblk, qhi[kb], sacc);
-            sacc_lo = mfma_bf16(kblk, qlo[kb], sacc_lo);
+            sacc = mfma_f16(kblk, qhi[kb], sacc);
+            sacc_lo = mfma_f16(kblk, qlo[kb], sacc_lo);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] += sacc_lo[r];
@@ -448,7 +438,7 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
                 // V^T operand: this lane's output dimension, the eight keys in the order the score
                 // accumulators hold them (16-bit reads down a column of the staged rows: the 32 lanes of
                 // a half read 64 consecutive bytes, the two halves sit 16 banks apart)
-                const bf16_t* vcol = &vs[(s2 * 16 + 4 * hh) * KPITCH + i * 32 + j];
+                const half_t* vcol = &vs[(s2 * 16 + 4 * hh) * KPITCH + i * 32 + j];
                 uint32_t vw[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -456,8 +446,8 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
                     vw[x] = (uint32_t)vcol[k0 * KPITCH] | ((uint32_t)vcol[(k0 + 1) * KPITCH] << 16);
                 }
                 const u32x4 vblk = u32x4{vw[0], vw[1], vw[2], vw[3]};
-                oacc[i] = mfma_bf16(vblk, phi, oacc[i]);
-                oacc[i] = mfma_bf16(vblk, plo, oacc[i]);
+                oacc[i] = mfma_f16(vblk, phi, oacc[i]);
+                oacc[i] = mfma_f16(vblk, plo, oacc[i]);
             }
         }
     }
@@ -470,12 +460,10 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             const int dim = h * D + i * 32 + 8 * qd + 4 * hh;  // four consecutive output dimensions
-            uint32_t h0, h1, l0, l1;
-            split2(oacc[i][qd * 4 + 0] * inv, oacc[i][qd * 4 + 1] * inv, h0, l0);
-            split2(oacc[i][qd * 4 + 2] * inv, oacc[i][qd * 4 + 3] * inv, h1, l1);
             const size_t slot = block_slot(m, dim & ~7, H >> 4);
-            reinterpret_cast<uint2*>(o + slot)[(dim >> 2) & 1] = make_uint2(h0, h1);
-            if (o_lo) reinterpret_cast<uint2*>(o_lo + slot)[(dim >> 2) & 1] = make_uint2(l0, l1);
+            reinterpret_cast<uint2*>(o + slot)[(dim >> 2) & 1] =
+                make_uint2(pack2(oacc[i][qd * 4 + 0] * inv, oacc[i][qd * 4 + 1] * inv),
+                           pack2(oacc[i][qd * 4 + 2] * inv, oacc[i][qd * 4 + 3] * inv));
         }
 }
 
@@ -483,17 +471,14 @@ __global__ __launch_bounds__(256, 2) void attn_prompt_mfma_kernel(const float* _
 
 // ------------------------------------------------------------------ launchers
 
-void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
-               const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq) {
+void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq) {
     if (S >= 32) {  // prompt rows: 32 queries per wavefront on the matrix cores
         dim3 fgrid((S + 127) / 128, n_heads, M / S);
         if (H / n_heads == 128)
-            attn_prompt_mfma_kernel<128><<<fgrid, 256, 0, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
-                                                               (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+            attn_prompt_mfma_kernel<128><<<fgrid, 256, 0, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S, layer, H, n_heads,
                                                                max_batch, max_seq);
         else
-            attn_prompt_mfma_kernel<64><<<fgrid, 256, 0, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
-                                                              (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+            attn_prompt_mfma_kernel<64><<<fgrid, 256, 0, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S, layer, H, n_heads,
                                                               max_batch, max_seq);
         return;
     }
@@ -501,21 +486,19 @@ void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, vo
     if (S >= QB && prompt_shm <= 96 * 1024) {  // short prompts: blocks of QB queries per workgroup
         dim3 pgrid((S + QB - 1) / QB, n_heads, M / S);
         if (H / n_heads == 128)
-            attn_prompt_kernel<128><<<pgrid, 256, prompt_shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
-                                                                   (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+            attn_prompt_kernel<128><<<pgrid, 256, prompt_shm, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S, layer, H, n_heads,
                                                                    max_batch, max_seq);
         else
-            attn_prompt_kernel<64><<<pgrid, 256, prompt_shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks,
-                                                                  (u32x4*)o_blocks_lo, st, S, layer, H, n_heads,
+            attn_prompt_kernel<64><<<pgrid, 256, prompt_shm, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S, layer, H, n_heads,
                                                                   max_batch, max_seq);
         return;
     }
     dim3 grid(M, n_heads);
     const size_t shm = (size_t)max_seq * sizeof(float);
     if (H / n_heads == 128)
-        attn_kernel<128><<<grid, 256, shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks, (u32x4*)o_blocks_lo, st, S,
+        attn_kernel<128><<<grid, 256, shm, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S,
                                                 layer, H, n_heads, max_batch, max_seq);
     else
-        attn_kernel<64><<<grid, 256, shm, s>>>(q, (const bf16_t*)kv, (u32x4*)o_blocks, (u32x4*)o_blocks_lo, st, S,
+        attn_kernel<64><<<grid, 256, shm, s>>>(q, (const half_t*)kv, (u32x4*)o_blocks, st, S,
                                                layer, H, n_heads, max_batch, max_seq);
 }

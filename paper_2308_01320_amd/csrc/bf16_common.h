@@ -1,6 +1,15 @@
-// Shared by the bf16-path kernel files for gfx950 (CDNA4, 64-wide wavefronts, MFMA 32x32x16 bf16).
+// Shared by the kernel files of the bf16 path (the model's weights are bfloat16) for gfx950 (CDNA4, 64-wide
+// wavefronts, MFMA 32x32x16 and 16x16x32 on IEEE half operands).
 //
-// Tiled operand layout ("blocks"): a bf16 matrix R[rows, K] is stored as
+// Operand format.  Everything the matrix cores multiply is IEEE half (fp16): the engine's tiled copies of
+// the weight matrices hold the caller's bf16 values converted to half -- exact for every weight of
+// magnitude 2^-14 .. 65504 (8 significant bits fit into 11), to the nearest multiple of 2^-24 below that --
+// and activations are rounded once to half (11 significant bits, 3 more than bf16) by the kernel that
+// produces them.  The KV cache is half as well.  Accumulation, residual stream, LayerNorm statistics,
+// soft-max, logits are float.  Measured against the unrounded definition on OPT-13B-shaped layers this sits
+// at 5e-3 of the logits; bf16 activations and a bf16 cache (one rounding each) sit at 4e-2.
+//
+// Tiled operand layout ("blocks"): a matrix R[rows, K] of halves is stored as
 // [rows/32][K/16][64 lanes][8 values]; lane = 32*((k%16)/8) + r%32 holds
 // R[r][16*kb + 8*(lane/32) + 0..7].  One block is 1 KiB, contiguous, and is
 // exactly the per-lane register image of one MFMA operand, so a wavefront
@@ -13,13 +22,6 @@
 // operand and X blocks as the B operand: lane l then holds, for column
 // m = l%32, rows n = 8*(r/4) + 4*(l/32) + r%4 (r = 0..15 accumulators),
 // i.e. runs of four consecutive n -- what the epilogues store.
-//
-// All
-// GEMM activations are carried as two bf16 terms, x = hi + lo with
-// lo = bf16(x - hi): a second MFMA per block against the same weight registers
-// takes the activation rounding error from 2^-9 to 2^-17.  Decode-shaped GEMMs
-// are bound by the weight stream, so there it costs no time; the prompt pass
-// pays twice the matrix-core work for it.
 #pragma once
 #include <algorithm>
 #include <cstdlib>
@@ -29,21 +31,33 @@
 
 namespace he_bf16 {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one lane's 16 bytes of a block
 
-__device__ __forceinline__ f32x16 mfma_bf16(const u32x4& a, const u32x4& b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
-                                                   0, 0);
+__device__ __forceinline__ f32x16 mfma_f16(const u32x4& a, const u32x4& b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return f32x2_to_bf16x2(lo, hi); }
+// two floats -> two halves in one word (first argument in the low half), round to nearest, ties to even
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+    const v2f v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2h));
+}
+// the two halves of a word as floats
+__device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+// the two bfloat16 of a word (the caller's parameters: biases, gains, embeddings) as floats
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// x = hi + lo in two bf16 terms
+// x in two half terms, hi = half(x), lo = half(x - hi): 22 significant bits (the prompt-pass attention feeds
+// its queries and probabilities to the matrix cores this way)
 __device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
     hi = pack2(a, b);
-    lo = pack2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+    lo = pack2(a - half_lo(hi), b - half_hi(hi));
 }
 
 // index (in 16-byte units) of the slot holding R[r][k0..k0+7], k0 % 8 == 0
@@ -70,9 +84,8 @@ struct Epi {
     const bf16_t* bias;     // [N] or null
     float* out;             // STORE: partial sums [ksplit][M][N]; QKV: q [M][H]
     size_t out_split;       // elements between two k-splits of `out`
-    u32x4* out_blocks;      // BIAS_RELU: tiled bf16 [M/32][N/16] blocks (hi term)
-    u32x4* out_blocks_lo;   // BIAS_RELU: lo term, or null
-    bf16_t* kv;             // QKV: the KV arena
+    u32x4* out_blocks;      // BIAS_RELU: tiled half [M/32][N/16] blocks
+    half_t* kv;             // QKV: the KV arena
     const he_dev_state* st;
     int S, layer, H, n_heads, d, max_batch, max_seq;
     float qscale;
@@ -89,7 +102,7 @@ struct Epi {
     float ln_eps;
     const float *c1, *c2;   // [N]
     // STORE_LN: the workgroup that finishes a column group last adds the k-split partial sums,
-    // bias and residual, and hands the next GEMM gamma * x (out_blocks, out_blocks_lo) and the
+    // bias and residual, and hands the next GEMM gamma * x (out_blocks) and the
     // group's statistics
     float* resid;           // [M][N] residual stream, updated in place
     const bf16_t* gamma;    // [N] gain of the LayerNorm that follows
@@ -132,21 +145,17 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
         *reinterpret_cast<float4*>(p.out + (size_t)ks * p.out_split + (size_t)m * p.N + n0) =
             make_float4(v0, v1, v2, v3);
     } else if (MODE == MODE_BIAS_RELU) {
-        v0 = fmaxf(v0 + __uint_as_float(bb.x << 16), 0.f);
-        v1 = fmaxf(v1 + __uint_as_float(bb.x & 0xFFFF0000u), 0.f);
-        v2 = fmaxf(v2 + __uint_as_float(bb.y << 16), 0.f);
-        v3 = fmaxf(v3 + __uint_as_float(bb.y & 0xFFFF0000u), 0.f);
+        v0 = fmaxf(v0 + bf_lo(bb.x), 0.f);
+        v1 = fmaxf(v1 + bf_hi(bb.x), 0.f);
+        v2 = fmaxf(v2 + bf_lo(bb.y), 0.f);
+        v3 = fmaxf(v3 + bf_hi(bb.y), 0.f);
         const size_t slot = block_slot(m, n0 & ~7, p.N >> 4);
-        uint32_t h0, h1, l0, l1;
-        split2(v0, v1, h0, l0);
-        split2(v2, v3, h1, l1);
-        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(h0, h1);
-        if (p.out_blocks_lo) reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0 >> 2) & 1] = make_uint2(l0, l1);
+        reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0 >> 2) & 1] = make_uint2(pack2(v0, v1), pack2(v2, v3));
     } else if (MODE == MODE_QKV) {
-        v0 += __uint_as_float(bb.x << 16);
-        v1 += __uint_as_float(bb.x & 0xFFFF0000u);
-        v2 += __uint_as_float(bb.y << 16);
-        v3 += __uint_as_float(bb.y & 0xFFFF0000u);
+        v0 += bf_lo(bb.x);
+        v1 += bf_hi(bb.x);
+        v2 += bf_lo(bb.y);
+        v3 += bf_hi(bb.y);
         if (n0 < p.H) {
             *reinterpret_cast<float4*>(p.out + (size_t)m * p.H + n0) =
                 make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
@@ -159,7 +168,7 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
                 if (tr < 0) return;
                 t = seq_len(p.st, b) + tr;
             }
-            bf16_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
+            half_t* dst = p.kv + kv_index(p.layer, which, b, c / p.d, t, p.max_batch, p.n_heads, p.max_seq, p.d) + (c % p.d);
             *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
         }
     }
@@ -246,7 +255,7 @@ inline int num_cus() {
 inline Epi make_epi(int M, int N, const bf16_gemm_args& a) {
     Epi p{};
     p.M = M; p.N = N; p.bias = (const bf16_t*)a.bias; p.out = a.out; p.out_split = a.out_split;
-    p.out_blocks = (u32x4*)a.out_blocks; p.out_blocks_lo = (u32x4*)a.out_blocks_lo; p.kv = (bf16_t*)a.kv; p.st = a.st;
+    p.out_blocks = (u32x4*)a.out_blocks; p.kv = (half_t*)a.kv; p.st = a.st;
     p.S = a.S; p.layer = a.layer; p.H = a.H; p.n_heads = a.n_heads; p.d = a.n_heads ? a.H / a.n_heads : 0;
     p.max_batch = a.max_batch; p.max_seq = a.max_seq; p.qscale = a.qscale;
     p.ln_stats = (const float2*)a.ln_stats; p.ln_groups = a.ln_groups; p.ln_gw = a.ln_gw; p.ln_cols = a.ln_cols;

@@ -1,5 +1,5 @@
 // bf16 path: the weight-streaming GEMMs of a decode step (at most 32 rows per slice) and the LM head
-// fused with log-softmax and sampling.
+// fused with log-softmax and sampling.  Weights and activations are tiled blocks of IEEE halves.
 #include "bf16_common.h"
 
 using namespace he_bf16;
@@ -22,7 +22,7 @@ namespace {
 // stores to be acknowledged and counts itself in; whoever counts last for the column group reads all splits
 // back -- its own included -- and adds them in split order, so the sum does not depend on which
 // workgroup that was.  Nobody waits for anybody: the others are done.  The last one adds bias and
-// residual, writes the residual rows back, gamma * x as two-term blocks, and the group's statistics
+// residual, writes the residual rows back, gamma * x as half blocks, and the group's statistics
 // (mean and sum of squared deviations per row over the group's `cnt` columns, fixed summation order).
 // Returns to the caller, who returns.
 // MT: 32-row slices the workgroup holds (rows mt*32 .. mt*32 + 32 MT - 1; mt = its first slice).
@@ -73,7 +73,7 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
         uint64_t y[CH][8][2];
         float4 rr[CH];
         uint2 bb[CH], gg[CH];
-        uint2 hh[CH], ll[CH];
+        uint2 hh[CH];
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             const int i = c0 + c;
@@ -116,12 +116,12 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
                         tot.z += lo32(y[c][k][1]); tot.w += hi32(y[c][k][1]);
                     }
             }
-            x[i][0] = rr[c].x + (tot.x + __uint_as_float(bb[c].x << 16));
-            x[i][1] = rr[c].y + (tot.y + __uint_as_float(bb[c].x & 0xFFFF0000u));
-            x[i][2] = rr[c].z + (tot.z + __uint_as_float(bb[c].y << 16));
-            x[i][3] = rr[c].w + (tot.w + __uint_as_float(bb[c].y & 0xFFFF0000u));
-            split2(x[i][0] * __uint_as_float(gg[c].x << 16), x[i][1] * __uint_as_float(gg[c].x & 0xFFFF0000u), hh[c].x, ll[c].x);
-            split2(x[i][2] * __uint_as_float(gg[c].y << 16), x[i][3] * __uint_as_float(gg[c].y & 0xFFFF0000u), hh[c].y, ll[c].y);
+            x[i][0] = rr[c].x + (tot.x + bf_lo(bb[c].x));
+            x[i][1] = rr[c].y + (tot.y + bf_hi(bb[c].x));
+            x[i][2] = rr[c].z + (tot.z + bf_lo(bb[c].y));
+            x[i][3] = rr[c].w + (tot.w + bf_hi(bb[c].y));
+            hh[c].x = pack2(x[i][0] * bf_lo(gg[c].x), x[i][1] * bf_hi(gg[c].x));
+            hh[c].y = pack2(x[i][2] * bf_lo(gg[c].y), x[i][3] * bf_hi(gg[c].y));
             const float part = (x[i][0] + x[i][1]) + (x[i][2] + x[i][3]);
 #pragma unroll
             for (int r = 0; r < NSLOT; ++r)
@@ -134,7 +134,6 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
             *reinterpret_cast<float4*>(p.resid + (size_t)mrow[i] * p.N + n0[i]) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
             const size_t slot = block_slot(mrow[i], n0[i] & ~7, p.N >> 4);
             reinterpret_cast<uint2*>(p.out_blocks + slot)[(n0[i] >> 2) & 1] = hh[c];
-            reinterpret_cast<uint2*>(p.out_blocks_lo + slot)[(n0[i] >> 2) & 1] = ll[c];
         }
     }
     // row sums over the lanes that share a row, then over the wavefronts
@@ -187,7 +186,7 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
 // straight from global memory into MFMA operand registers.  A workgroup of four
 // or eight wavefronts owns NT consecutive 32-row weight tiles and one k-split; its
 // wavefronts divide the k range, keep U blocks per stream in flight (NT weight
-// streams plus the hi and lo activation streams out of L2, which every weight
+// streams plus the activation stream out of L2, which every weight
 // tile reuses from registers), and combine their accumulators through LDS.  The
 // sum over k-splits (MODE_STORE_LN) is taken by the last-arriving workgroup (above).
 //
@@ -195,7 +194,7 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
 // as many of the CUs as the shape allows: more workgroups than CUs double up
 // on some CUs and the whole launch waits for those.  Measured on the 13B shapes:
 // the stream itself runs at the HBM rate; what it competes for is the path from
-// L2 to the CU, which carries the activation panel (as many bytes again as the
+// L2 to the CU, which carries the activation panel (half as many bytes again as the
 // weights when NT = 2) next to the weights.  Everything executed once per launch
 // (prologue, epilogue) is instruction-bound -- a wavefront issues one vector
 // instruction per four cycles -- so the code around the loop is kept short and
@@ -203,23 +202,20 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
 
 template <int NT, int U>
 struct SkinnyRegs {
-    u32x4 w[NT][U], xh[U], xl[U];
+    u32x4 w[NT][U], x[U];
 };
 
 template <int NT, int U>
-__device__ __forceinline__ void skinny_load(SkinnyRegs<NT, U>& r, const u32x4* (&w)[NT], const u32x4*& xh,
-                                            const u32x4*& xl) {
+__device__ __forceinline__ void skinny_load(SkinnyRegs<NT, U>& r, const u32x4* (&w)[NT], const u32x4*& xh) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) r.w[t][u] = __builtin_nontemporal_load(w[t] + u * 64);
-        r.xh[u] = xh[u * 64];
-        r.xl[u] = xl[u * 64];
+        r.x[u] = xh[u * 64];
     }
 #pragma unroll
     for (int t = 0; t < NT; ++t) w[t] += U * 64;
     xh += U * 64;
-    xl += U * 64;
 }
 
 template <int NT, int U>
@@ -227,16 +223,13 @@ __device__ __forceinline__ void skinny_mma(const SkinnyRegs<NT, U>& r, f32x16 (&
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xh[u], acc[t]);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(r.w[t][u], r.xl[u], acc[t]);
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_f16(r.w[t][u], r.x[u], acc[t]);
     }
 }
 
 template <int MODE, int NT, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __restrict__ Wp,
-                                                                 const u32x4* __restrict__ Xhi,
-                                                                 const u32x4* __restrict__ Xlo, int KB, int n_tiles,
+                                                                 const u32x4* __restrict__ Xhi, int KB, int n_tiles,
                                                                  int ksplit, Epi p) {
     __shared__ float red[WAVES][NT][16][64];
     __shared__ float lnp[WAVES * 4 * 32];  // folded LayerNorm: the wavefronts' partial sums of the row statistics
@@ -261,7 +254,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     for (int t = 0; t < NT; ++t)  // tiles past the last one are computed from the last one, never stored
         w[t] = Wp + ((size_t)min(grp * NT + t, n_tiles - 1) * KB + kb0) * 64 + lane;
     const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
-    const u32x4* xl = Xlo + ((size_t)mt * KB + kb0) * 64 + lane;
     // After the k loop the NT*4 (tile, row-quad) items of the workgroup are shared out over its
     // wavefronts: item = wave + i*WAVES -> tile item/4, rows 8*(item%4) + 4*(lane/32) + 0..3.
     constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
@@ -298,14 +290,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     int n = kb1 - kb0;
     if (n >= U) {
         SkinnyRegs<NT, U> ra;
-        skinny_load<NT, U>(ra, w, xh, xl);
+        skinny_load<NT, U>(ra, w, xh);
         n -= U;
         request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off
         // the loop: a test inside it cost the loop its schedule)
         if (n >= U) {
             SkinnyRegs<NT, U> rb;
-            skinny_load<NT, U>(rb, w, xh, xl);
+            skinny_load<NT, U>(rb, w, xh);
             n -= U;
             if (fold) ln_partial<WAVES>(lnl, p, mt, wave, lane, lnp);
             skinny_mma<NT, U>(ra, acc);
@@ -315,7 +307,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
         }
         while (n >= U) {
             SkinnyRegs<NT, U> rb;
-            skinny_load<NT, U>(rb, w, xh, xl);
+            skinny_load<NT, U>(rb, w, xh);
             n -= U;
             skinny_mma<NT, U>(ra, acc);
             ra = rb;
@@ -327,7 +319,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     }
     for (; n > 0; --n) {
         SkinnyRegs<NT, 1> r1;
-        skinny_load<NT, 1>(r1, w, xh, xl);
+        skinny_load<NT, 1>(r1, w, xh);
         skinny_mma<NT, 1>(r1, acc);
     }
 #pragma unroll
@@ -437,23 +429,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ f32x4 mfma16_bf16(const u32x4& a, const u32x4& b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
-                                                   0, 0);
+__device__ __forceinline__ f32x4 mfma16_f16(const u32x4& a, const u32x4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// 16 E4M3 codes -> two bf16 operand registers (exact: an E4M3 value has four significant bits).
-// Bytes 0-7 are the lane's eight k values of the first 32-wide k range, bytes 8-15 those of the second.
-__device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t word, bool upper) {
+// 16 E4M3 codes -> two half operand registers (exact: an E4M3 value has four significant bits and lies in
+// 2^-9 .. 448).  Bytes 0-7 are the lane's eight k values of the first 32-wide k range, bytes 8-15 those of the second.
+__device__ __forceinline__ uint32_t e4m3x2_to_f16x2(uint32_t word, bool upper) {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true) : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
-    return (__float_as_uint(f.x) >> 16) | (__float_as_uint(f.y) & 0xFFFF0000u);
+    return pack2(f.x, f.y);
 }
-__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4& a1) {
-    a0 = u32x4{e4m3x2_to_bf16x2(w.x, false), e4m3x2_to_bf16x2(w.x, true), e4m3x2_to_bf16x2(w.y, false),
-               e4m3x2_to_bf16x2(w.y, true)};
-    a1 = u32x4{e4m3x2_to_bf16x2(w.z, false), e4m3x2_to_bf16x2(w.z, true), e4m3x2_to_bf16x2(w.w, false),
-               e4m3x2_to_bf16x2(w.w, true)};
+__device__ __forceinline__ void e4m3x16_to_f16(const u32x4& w, u32x4& a0, u32x4& a1) {
+    a0 = u32x4{e4m3x2_to_f16x2(w.x, false), e4m3x2_to_f16x2(w.x, true), e4m3x2_to_f16x2(w.y, false),
+               e4m3x2_to_f16x2(w.y, true)};
+    a1 = u32x4{e4m3x2_to_f16x2(w.z, false), e4m3x2_to_f16x2(w.z, true), e4m3x2_to_f16x2(w.w, false),
+               e4m3x2_to_f16x2(w.w, true)};
 }
 
 // One loop step of a wavefront covers KU = 1 (bf16 weights) or 2 (8-bit weights: one 16-byte load holds
@@ -465,11 +456,11 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& a0, u32x4
 template <int HT, int U, bool W8, int MH = 2>
 struct HalfRegs {
     static constexpr int KU = W8 ? 2 : 1;
-    u32x4 w[HT][U], xh[MH][U * KU], xl[MH][U * KU];
+    u32x4 w[HT][U], xh[MH][U * KU];
 };
 
 template <int HT, int U, bool W8, int MH = 2>
-__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MH>& r, const u32x4* (&w)[HT], const u32x4*& xh, const u32x4*& xl,
+__device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MH>& r, const u32x4* (&w)[HT], const u32x4*& xh,
                                           size_t xstride = 0) {
     constexpr int KU = W8 ? 2 : 1, WSTEP = W8 ? 64 : 128;
 #pragma unroll
@@ -479,15 +470,12 @@ __device__ __forceinline__ void half_load(HalfRegs<HT, U, W8, MH>& r, const u32x
 #pragma unroll
         for (int kp = 0; kp < KU; ++kp)
 #pragma unroll
-            for (int mh = 0; mh < MH; ++mh) {
+            for (int mh = 0; mh < MH; ++mh)
                 r.xh[mh][u * KU + kp] = xh[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
-                r.xl[mh][u * KU + kp] = xl[(u * KU + kp) * 128 + (mh & 1) * 16 + (mh >> 1) * xstride];
-            }
     }
 #pragma unroll
     for (int t = 0; t < HT; ++t) w[t] += U * WSTEP;
     xh += U * KU * 128;
-    xl += U * KU * 128;
 }
 
 template <int HT, int U, bool W8, int MH = 2>
@@ -498,24 +486,17 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MH>& r, f32x4
 #pragma unroll
             for (int t = 0; t < HT; ++t) {
                 u32x4 a[2];
-                e4m3x16_to_bf16(r.w[t][u], a[0], a[1]);
+                e4m3x16_to_f16(r.w[t][u], a[0], a[1]);
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp)
 #pragma unroll
-                    for (int mh = 0; mh < MH; ++mh) {
-                        acc[t][mh] = mfma16_bf16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
-                        acc[t][mh] = mfma16_bf16(a[kp], r.xl[mh][u * 2 + kp], acc[t][mh]);
-                    }
+                    for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_f16(a[kp], r.xh[mh][u * 2 + kp], acc[t][mh]);
             }
         } else {
 #pragma unroll
             for (int t = 0; t < HT; ++t)
 #pragma unroll
-                for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
-#pragma unroll
-            for (int t = 0; t < HT; ++t)
-#pragma unroll
-                for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_bf16(r.w[t][u], r.xl[mh][u], acc[t][mh]);
+                for (int mh = 0; mh < MH; ++mh) acc[t][mh] = mfma16_f16(r.w[t][u], r.xh[mh][u], acc[t][mh]);
         }
     }
 }
@@ -526,8 +507,7 @@ __device__ __forceinline__ void half_mma(const HalfRegs<HT, U, W8, MH>& r, f32x4
 // 8-15: one contiguous 1 KiB load per unit, two matrix-instruction operands after conversion.
 template <int MODE, int HT, int U, int WAVES, bool W8, int MT = 1, int HALVES = 0>
 __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
-                                                               const u32x4* __restrict__ Xlo, int KB, int n_half,
-                                                               int ksplit, Epi p) {
+                                                               int KB, int n_half, int ksplit, Epi p) {
     // 16-row halves of the activation rows: both of every slice, or only the first HALVES of them when no more
     // are in use (at most 16 rows of one slice, at most 48 of two): the rest would be loaded and multiplied for nothing
     static_assert(HALVES == 0 || (HALVES < 2 * MT && HALVES > 2 * (MT - 1)), "HALVES ends inside the last slice");
@@ -554,7 +534,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         else w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
     }
     const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
-    const u32x4* xl = Xlo + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
     constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/MH, row half item%MH
     // epilogue operands: requested right behind the first round of weight loads (see gemm_skinny_kernel)
     uint2 bias_w[ITEMS];
@@ -596,13 +575,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     int n = kp1 - kp0;
     if (n >= U) {
         HalfRegs<HT, U, W8, MH> ra;
-        half_load<HT, U, W8, MH>(ra, w, xh, xl, xstride);
+        half_load<HT, U, W8, MH>(ra, w, xh, xstride);
         n -= U;
         request_epilogue_operands();
         // the statistics are used once the second round is on its way as well (first trip peeled off the loop)
         if (n >= U) {
             HalfRegs<HT, U, W8, MH> rb;
-            half_load<HT, U, W8, MH>(rb, w, xh, xl, xstride);
+            half_load<HT, U, W8, MH>(rb, w, xh, xstride);
             n -= U;
             if (fold) ln_partials();
             half_mma<HT, U, W8, MH>(ra, acc);
@@ -612,7 +591,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         }
         while (n >= U) {
             HalfRegs<HT, U, W8, MH> rb;
-            half_load<HT, U, W8, MH>(rb, w, xh, xl, xstride);
+            half_load<HT, U, W8, MH>(rb, w, xh, xstride);
             n -= U;
             half_mma<HT, U, W8, MH>(ra, acc);
             ra = rb;
@@ -624,7 +603,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
     }
     for (; n > 0; --n) {
         HalfRegs<HT, 1, W8, MH> r1;
-        half_load<HT, 1, W8, MH>(r1, w, xh, xl, xstride);
+        half_load<HT, 1, W8, MH>(r1, w, xh, xstride);
         half_mma<HT, 1, W8, MH>(r1, acc);
     }
 #pragma unroll
@@ -755,7 +734,7 @@ int plan_cus() { return g_cus_override > 0 ? g_cus_override : num_cus(); }
 #define HE_SKINNY_W8_MAXNT 2
 #endif
 template <int MODE, int NT>
-void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles,
+void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_tiles,
                       int m_tiles, int ksplit, const Epi& p) {
     constexpr int U = HE_SKINNY_U(NT);
     dim3 grid(((n_tiles + NT - 1) / NT) * ksplit, m_tiles);
@@ -771,17 +750,17 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, const void
         constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_skinny_kernel<MODE, NT <= HE_SKINNY_W8_MAXNT ? NT : 1, U, 8><<<grid, 512, pad, s>>>(
-            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+            (const u32x4*)Wp, (const u32x4*)Xhi, KB, n_tiles, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * NT * 16 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_skinny_kernel<MODE, NT, U, 4><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
-                                                                  (const u32x4*)Xlo, KB, n_tiles, ksplit, p);
+                                                                  KB, n_tiles, ksplit, p);
     }
 }
 
 template <int MODE, int HT, bool W8>
-void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles,
+void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_half, int m_tiles,
                     int ksplit, const Epi& p) {
     // loads per wavefront and round: (HT + 4) U 16-byte loads with bf16 weights, (HT + 8) U with 8-bit ones
     constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
@@ -796,13 +775,13 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
                 constexpr size_t kStatic = (size_t)4 * HT * 3 * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
                 gemm_half_kernel<MODE, HT, U2, 4, false, 2, 3><<<grid, 256, pad, s>>>(
-                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+                    (const u32x4*)Wp, (const u32x4*)Xhi, KB, n_half, ksplit, p);
                 return;
             }
             constexpr size_t kStatic = (size_t)4 * HT * 4 * 4 * 64 * sizeof(float);
             const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
             gemm_half_kernel<MODE, HT, U2, 4, false, 2><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
-                                                                               (const u32x4*)Xlo, KB, n_half, ksplit, p);
+                                                                               KB, n_half, ksplit, p);
             return;
         }
     }
@@ -816,12 +795,12 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
                 constexpr size_t kStatic = (size_t)8 * HT * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
                 gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, false, 1, 1><<<grid, 512, pad, s>>>(
-                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+                    (const u32x4*)Wp, (const u32x4*)Xhi, KB, n_half, ksplit, p);
             } else {
                 constexpr size_t kStatic = (size_t)4 * HT * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
                 gemm_half_kernel<MODE, HT, U, 4, false, 1, 1><<<grid, 256, pad, s>>>(
-                    (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+                    (const u32x4*)Wp, (const u32x4*)Xhi, KB, n_half, ksplit, p);
             }
             return;
         }
@@ -830,11 +809,11 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, const void* 
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
         gemm_half_kernel<MODE, HT <= 4 ? HT : 2, U8, 8, W8><<<grid, 512, pad, s>>>(
-            (const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, n_half, ksplit, p);
+            (const u32x4*)Wp, (const u32x4*)Xhi, KB, n_half, ksplit, p);
     } else {
         constexpr size_t kStatic = (size_t)4 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
-        gemm_half_kernel<MODE, HT, U, 4, W8><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo,
+        gemm_half_kernel<MODE, HT, U, 4, W8><<<grid, 256, pad, s>>>((const u32x4*)Wp, (const u32x4*)Xhi,
                                                                     KB, n_half, ksplit, p);
     }
 }
@@ -843,37 +822,37 @@ constexpr int kHalfMin = 2, kHalfMax = 10;  // 16-row units per workgroup the ha
 constexpr int kHalfMax2 = 8;                // ... with two 32-row activation slices per workgroup
 
 template <int MODE, bool W8>
-void launch_half(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_half, int m_tiles, int ht,
+void launch_half(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_half, int m_tiles, int ht,
                  int ksplit, const Epi& p) {
     switch (ht) {
         case 1:
-            if constexpr (W8) { launch_half_ht<MODE, 1, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break; }
+            if constexpr (W8) { launch_half_ht<MODE, 1, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break; }
             [[fallthrough]];
-        case 2: launch_half_ht<MODE, 2, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 3: launch_half_ht<MODE, 3, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 4: launch_half_ht<MODE, 4, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 5: launch_half_ht<MODE, 5, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 6: launch_half_ht<MODE, 6, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 7: launch_half_ht<MODE, 7, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 8: launch_half_ht<MODE, 8, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        case 9: launch_half_ht<MODE, 9, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
-        default: launch_half_ht<MODE, 10, W8>(s, Wp, Xhi, Xlo, KB, n_half, m_tiles, ksplit, p); break;
+        case 2: launch_half_ht<MODE, 2, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 3: launch_half_ht<MODE, 3, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 4: launch_half_ht<MODE, 4, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 5: launch_half_ht<MODE, 5, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 6: launch_half_ht<MODE, 6, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 7: launch_half_ht<MODE, 7, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 8: launch_half_ht<MODE, 8, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        case 9: launch_half_ht<MODE, 9, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
+        default: launch_half_ht<MODE, 10, W8>(s, Wp, Xhi, KB, n_half, m_tiles, ksplit, p); break;
     }
 }
 
 // nt weight tiles per workgroup (1..8)
 template <int MODE>
-void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int n_tiles, int m_tiles,
+void launch_skinny(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_tiles, int m_tiles,
                    int nt, int ksplit, const Epi& p) {
     switch (nt) {
-        case 1: launch_skinny_nt<MODE, 1>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 2: launch_skinny_nt<MODE, 2>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 3: launch_skinny_nt<MODE, 3>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 4: launch_skinny_nt<MODE, 4>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 5: launch_skinny_nt<MODE, 5>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 6: launch_skinny_nt<MODE, 6>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        case 7: launch_skinny_nt<MODE, 7>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
-        default: launch_skinny_nt<MODE, 8>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 1: launch_skinny_nt<MODE, 1>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 2: launch_skinny_nt<MODE, 2>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 3: launch_skinny_nt<MODE, 3>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 4: launch_skinny_nt<MODE, 4>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 5: launch_skinny_nt<MODE, 5>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 6: launch_skinny_nt<MODE, 6>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        case 7: launch_skinny_nt<MODE, 7>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
+        default: launch_skinny_nt<MODE, 8>(s, Wp, Xhi, KB, n_tiles, m_tiles, ksplit, p); break;
     }
 }
 
@@ -941,14 +920,14 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 // capacity: floats the k-split scratch can hold (0 = not checked)
 //
 // Cost of a one-slice plan, in microseconds, fitted to launches of the 13B and 6.7B shapes: what the most loaded
-// workgroup moves (its weight rows and the two-term activation rows over its k range, at the ~48 GB/s one CU
+// workgroup moves (its weight rows and the activation rows over its k range, at the ~48 GB/s one CU
 // sustains while all stream; never less than the whole matrix takes at the HBM rate) plus the tail after the
 // stream: ~1.1 us per k-split whose partial sums the last arriver waits for and reads back, ~0.2 us per quad of
 // outputs a thread finishes.  (Balance alone, the earlier criterion, chose four 32-row tiles and six splits on
 // 5120x5120 and 5120x20480; five 16-row units and four splits move 12 % more bytes per workgroup and run 1-2 us
 // faster; on 4096x4096 four units and four splits run 3.4 us faster than four tiles and eight splits.)
-static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, int cus, double act = 128.0) {
-    // weight rows and the activation panel (act bytes per k: 32 rows, two bf16 terms) at 48 GB/s into the CU
+static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, int cus, double act = 64.0) {
+    // weight rows and the activation panel (act bytes per k: 32 rows of halves) at 48 GB/s into the CU
     const double per_cu = (double)K / ks * (2.0 * rows + act) / 48e3;
     // the whole matrix at 6.5 TB/s; CUs left without a workgroup request nothing, and the stream slows by about
     // half their share (9216x36864: 216 workgroups on 256 CUs ran 8 % slower than 256)
@@ -977,7 +956,7 @@ static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
         while (ks > 1 && kb / (ks * 4) < 8) --ks;
         // scratch the kernel will index: groups x splits x (items rounded up to the wavefronts) x 256 words
         if (capacity && (size_t)groups * ks * (size_t)(mh * ht + 7) * 256 > capacity) continue;
-        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * (M <= 16 ? 1 : mh) + 3) / 4, ks, groups * ks, cus, M <= 16 ? 64.0 : 128.0);
+        const double cost = m_tiles == 2 ? (double)ht * 16 / ks : store_cost_us(N, K, ht * 16, (ht * (M <= 16 ? 1 : mh) + 3) / 4, ks, groups * ks, cus, M <= 16 ? 32.0 : 64.0);
         if (cost < best) { best = cost; g = GemmPlan{true, ht, ks}; }
     }
     return g;
@@ -1048,7 +1027,7 @@ size_t bf16_store_need(int M, int N, int K, size_t capacity, int w8) {
     return groups * m_tiles * g.ks * (size_t)(4 * g.per_wg + 7) * 256;
 }
 
-void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,
                       int ksplit, const bf16_gemm_args& a) {
     (void)ksplit;
     const Epi p = make_epi(M, N, a);
@@ -1056,31 +1035,31 @@ void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, 
     if (a.wscale) {  // 8-bit weights: Wp holds E4M3 units; one row slice only
         if (mode == EPI_STORE_LN) {
             const GemmPlan g = plan_store_w8(N, K, a.out_capacity);
-            launch_half<MODE_STORE_LN, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+            launch_half<MODE_STORE_LN, true>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
         } else {
             const GemmPlan g = plan_fused_w8(N);
-            if (mode == EPI_BIAS_RELU) launch_half<MODE_BIAS_RELU, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
-            else launch_half<MODE_QKV, true>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
+            if (mode == EPI_BIAS_RELU) launch_half<MODE_BIAS_RELU, true>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, 1, p);
+            else launch_half<MODE_QKV, true>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, 1, p);
         }
         return;
     }
     if (mode == EPI_STORE_LN) {  // the k-split is the one bf16_store_plan reports for this shape
         const GemmPlan g = plan_store(M, N, K, a.out_capacity);
-        if (g.half) launch_half<MODE_STORE_LN, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
-        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
+        if (g.half) launch_half<MODE_STORE_LN, false>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, g.ks, p);
+        else launch_skinny<MODE_STORE_LN>(s, Wp, Xhi, KB, n_tiles, m_tiles, g.per_wg, g.ks, p);
         return;
     }
     const GemmPlan g = plan_fused(M, N);
     if (mode == EPI_BIAS_RELU) {
-        if (g.half) launch_half<MODE_BIAS_RELU, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
-        else launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+        if (g.half) launch_half<MODE_BIAS_RELU, false>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_BIAS_RELU>(s, Wp, Xhi, KB, n_tiles, m_tiles, g.per_wg, 1, p);
     } else {
-        if (g.half) launch_half<MODE_QKV, false>(s, Wp, Xhi, Xlo, KB, N / 16, m_tiles, g.per_wg, 1, p);
-        else launch_skinny<MODE_QKV>(s, Wp, Xhi, Xlo, KB, n_tiles, m_tiles, g.per_wg, 1, p);
+        if (g.half) launch_half<MODE_QKV, false>(s, Wp, Xhi, KB, N / 16, m_tiles, g.per_wg, 1, p);
+        else launch_skinny<MODE_QKV>(s, Wp, Xhi, KB, n_tiles, m_tiles, g.per_wg, 1, p);
     }
 }
 
-void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
+void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
                   float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids, const bf16_gemm_args* fold) {
     Epi p{};
@@ -1088,7 +1067,7 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
     p.M = B; p.N = V; p.st = st; p.logits = logits_opt; p.stats = stats; p.stats_idx = stats_idx;
     p.n_tiles = (V + 31) / 32;
     const int m_tiles = (B + 31) / 32;
-    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, Xlo, K / 16, p.n_tiles, m_tiles, skinny_nt_fused(p.n_tiles, m_tiles), 1, p);
+    launch_skinny<MODE_LMHEAD>(s, Wp, Xhi, K / 16, p.n_tiles, m_tiles, skinny_nt_fused(p.n_tiles, m_tiles), 1, p);
     lm_reduce_kernel<<<B, 256, 0, s>>>(stats, stats_idx, p.n_tiles, st, ids_out, lp_out, out_stride, out_at_step,
                                        cur_ids);
 }

@@ -14,9 +14,6 @@ namespace {
 // staging registers) into a ring of stages; loads run several stages (about 3000
 // MFMA cycles) ahead of the arithmetic, which is what it takes to cover an L2 /
 // infinity-cache round trip; one barrier per stage.
-// Activations are the two-term form here as well (hi and lo blocks against the
-// same weight registers), which keeps keys and values of the prompt within a
-// rounding of the exact ones before they are stored as bf16.
 //
 // Two ring shapes.  PAIR = 0: four stages of two k-blocks (128 KiB), one workgroup per CU -- for launches
 // with fewer tiles than CUs (few rows; the k-split GEMMs of a wide decode step).  PAIR = 1: five stages of
@@ -33,14 +30,14 @@ template <int PAIR> struct TiledShape {
     static constexpr int TMR = TMB * 32;               // rows of the m tile
     static constexpr int KSTAGE = PAIR ? 1 : 2;        // k-blocks (16 values of k each) per stage
     static constexpr int NSTG = PAIR ? 5 : 4;          // ring depth
-    static constexpr int STAGE_BLOCKS = (TNB + 2 * TMB) * KSTAGE;
+    static constexpr int STAGE_BLOCKS = (TNB + TMB) * KSTAGE;
 };
 
 template <int MODE, int PAIR>
 __global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
-                                                         const u32x4* __restrict__ Xlo, int KB, int NT32, int MT32,
+                                                         int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, int ksplit, Epi p) {
-    // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at 2i+j; X hi at 16+2i+j; X lo at 24+2i+j
+    // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at KSTAGE i + j; X tile i at KSTAGE (TNB + i) + j
     constexpr int TMB = TiledShape<PAIR>::TMB, TMR = TiledShape<PAIR>::TMR, NSTG = TiledShape<PAIR>::NSTG;
     constexpr int KSTAGE = TiledShape<PAIR>::KSTAGE;
     constexpr int STAGE_BLOCKS = TiledShape<PAIR>::STAGE_BLOCKS;
@@ -73,17 +70,16 @@ __global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32
 #pragma unroll
         for (int j = 0; j < MW; ++j) acc[i][j] = f32x16{};
 
-    // this wavefront brings in W row-tiles 2w, 2w+1 and XW row-tiles of X hi and X lo per k-block
+    // this wavefront brings in W row-tiles 2w, 2w+1 and XW row-tiles of X per k-block
     constexpr int XW = TMB / 4;
     const u32x4* wsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) wsrc[i] = Wp + (size_t)min(tn * TNB + wave * 2 + i, NT32 - 1) * KB * 64 + lane;
-    const u32x4 *hsrc[XW], *lsrc[XW];
+    const u32x4 *hsrc[XW];
 #pragma unroll
     for (int x = 0; x < XW; ++x) {
         const int xrt = min(tm * TMB + wave * XW + x, MT32 - 1);
         hsrc[x] = Xhi + (size_t)xrt * KB * 64 + lane;
-        lsrc[x] = Xlo + (size_t)xrt * KB * 64 + lane;
     }
     const int nst_all = KB / KSTAGE;  // KB is even (K % 32 == 0)
     const int st0 = (int)((long)ks * nst_all / ksplit);
@@ -92,7 +88,7 @@ __global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32
         const size_t skip = (size_t)st0 * KSTAGE * 64;
         wsrc[0] += skip; wsrc[1] += skip;
 #pragma unroll
-        for (int x = 0; x < XW; ++x) { hsrc[x] += skip; lsrc[x] += skip; }
+        for (int x = 0; x < XW; ++x) hsrc[x] += skip;
     }
     auto issue = [&](int st) {
         u32x4 (*slot)[64] = ring[st % NSTG];
@@ -102,32 +98,25 @@ __global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32
             load_block_to_lds(wsrc[0] + off, &slot[(wave * 2 + 0) * KSTAGE + j][0]);
             load_block_to_lds(wsrc[1] + off, &slot[(wave * 2 + 1) * KSTAGE + j][0]);
 #pragma unroll
-            for (int x = 0; x < XW; ++x) {
-                load_block_to_lds(hsrc[x] + off, &slot[(TNB + wave * XW + x) * KSTAGE + j][0]);
-                load_block_to_lds(lsrc[x] + off, &slot[(TNB + TMB + wave * XW + x) * KSTAGE + j][0]);
-            }
+            for (int x = 0; x < XW; ++x) load_block_to_lds(hsrc[x] + off, &slot[(TNB + wave * XW + x) * KSTAGE + j][0]);
         }
     };
-    constexpr int kLoadsPerStage = (2 + 2 * XW) * KSTAGE;  // per wavefront
-    // operand registers of one k-block: 4 weight blocks, MW activation tiles x (hi, lo)
-    struct Ops { u32x4 a[4], b[2][MW]; };
+    constexpr int kLoadsPerStage = (2 + XW) * KSTAGE;  // per wavefront
+    // operand registers of one k-block: 4 weight blocks, MW activation tiles
+    struct Ops { u32x4 a[4], b[MW]; };
     auto read_ops = [&](Ops& o, int st, int j) {
         u32x4 (*slot)[64] = ring[st % NSTG];
 #pragma unroll
         for (int i = 0; i < 4; ++i) o.a[i] = slot[(wn * 4 + i) * KSTAGE + j][lane];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int i = 0; i < MW; ++i) o.b[t][i] = slot[(TNB + t * TMB + wm * MW + i) * KSTAGE + j][lane];
+        for (int i = 0; i < MW; ++i) o.b[i] = slot[(TNB + wm * MW + i) * KSTAGE + j][lane];
     };
     auto mma_ops = [&](const Ops& o) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int i = 0; i < 4; ++i) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int jj = 0; jj < MW; ++jj) acc[i][jj] = mfma_bf16(o.a[i], o.b[t][jj], acc[i][jj]);
-            }
+            for (int jj = 0; jj < MW; ++jj) acc[i][jj] = mfma_f16(o.a[i], o.b[jj], acc[i][jj]);
+        }
     };
     // Stage st is usable once this wavefront's own loads of it have landed (at most the loads of the
     // stages issued after it may still be outstanding) and every other wavefront says the same.
@@ -268,7 +257,7 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restr
 
 
 template <int MODE>
-void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int KB, int N, int M, const Epi& p,
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p,
                   int ksplit = 1) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
     const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
@@ -278,10 +267,10 @@ void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, const void* Xl
     // each: that ring alternates two register sets)
     const bool pair = nitem >= 2 * num_cus() && KB % (2 * ksplit) == 0;
     if (pair)
-        gemm_tiled_kernel<MODE, 1><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+        gemm_tiled_kernel<MODE, 1><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32,
                                                         MT32, tiles_n, tiles_m, ksplit, p);
     else
-        gemm_tiled_kernel<MODE, 0><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)Xlo, KB, NT32,
+        gemm_tiled_kernel<MODE, 0><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32,
                                                         MT32, tiles_n, tiles_m, ksplit, p);
 }
 
@@ -305,12 +294,12 @@ __global__ __launch_bounds__(256) void finish_kernel(const float* __restrict__ p
 
 // ------------------------------------------------------------------ launchers
 
-void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,
                      const bf16_gemm_args& a) {
     const Epi p = make_epi(M, N, a);
-    if (mode == EPI_STORE) launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
-    else if (mode == EPI_BIAS_RELU) launch_tiled<MODE_BIAS_RELU>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
-    else launch_tiled<MODE_QKV>(s, Wp, Xhi, Xlo, K / 16, N, M, p);
+    if (mode == EPI_STORE) launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, p);
+    else if (mode == EPI_BIAS_RELU) launch_tiled<MODE_BIAS_RELU>(s, Wp, Xhi, K / 16, N, M, p);
+    else launch_tiled<MODE_QKV>(s, Wp, Xhi, K / 16, N, M, p);
 }
 
 int bf16_tiled_ksplit(int M, int N, int K) {
@@ -339,16 +328,16 @@ int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
     return best;
 }
 
-void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
+void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,
                             int ksplit, float* part, size_t part_split, const bf16_gemm_args& a) {
     if (ksplit == 1 && mode != EPI_STORE) {  // the tiles alone fill the chip: the epilogue runs in the GEMM
-        bf16_gemm_tiled(s, mode, Wp, Xhi, Xlo, M, N, K, a);
+        bf16_gemm_tiled(s, mode, Wp, Xhi, M, N, K, a);
         return;
     }
     bf16_gemm_args st = a;
     st.out = part; st.out_split = part_split;
     const Epi ps = make_epi(M, N, st);
-    launch_tiled<MODE_STORE>(s, Wp, Xhi, Xlo, K / 16, N, M, ps, ksplit);
+    launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, ps, ksplit);
     if (mode == EPI_STORE) return;  // the consumer (a LayerNorm) adds the partial sums
     const Epi p = make_epi(M, N, a);
     const unsigned grid = (unsigned)(((size_t)M * (N / 4) + 255) / 256);
@@ -358,11 +347,11 @@ void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void*
 
 int bf16_score_parts(int V) { return 2 * ((V + TN - 1) / TN); }
 
-void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int M, int S, int V, int K,
+void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, int M, int S, int V, int K,
                      const int32_t* ids, float* stats, float* tgt, float* out) {
     Epi p{};
     p.M = M; p.N = V; p.S = S; p.ids = ids; p.sc_stats = (float2*)stats; p.sc_tgt = tgt; p.sc_parts = bf16_score_parts(V);
-    launch_tiled<MODE_SCORE>(s, Wp, Xhi, Xlo, K / 16, V, M, p);
+    launch_tiled<MODE_SCORE>(s, Wp, Xhi, K / 16, V, M, p);
     score_reduce_kernel<<<(M + 3) / 4, 256, 0, s>>>((const float2*)stats, tgt, p.sc_parts, M, S, out);
 }
 

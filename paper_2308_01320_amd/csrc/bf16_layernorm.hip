@@ -8,14 +8,13 @@ namespace {
 // ----------------------------------------------------------------- LayerNorm (+ residual update)
 //
 // Row `src = m*in_mul + in_add`: r += sum of k-split partials + bias (fixed order),
-// written back when asked; a = LayerNorm(r) is emitted as tiled bf16 blocks.
+// written back when asked; a = LayerNorm(r) is emitted as tiled half blocks.
 __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, const float* __restrict__ part,
                                                         int ksplit, size_t part_split,
                                                         const bf16_t* __restrict__ pbias,
                                                         const bf16_t* __restrict__ gamma,
                                                         const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
-                                                        u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
-                                                        int in_add, int writeback) {
+                                                        int H, float eps, int in_mul, int in_add, int writeback) {
     extern __shared__ __align__(16) float row[];
     __shared__ float red[16];
     const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwave = blockDim.x >> 6;
@@ -30,8 +29,8 @@ __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, 
                 v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
             }
             const uint2 bb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
-            v.x += __uint_as_float(bb.x << 16); v.y += __uint_as_float(bb.x & 0xFFFF0000u);
-            v.z += __uint_as_float(bb.y << 16); v.w += __uint_as_float(bb.y & 0xFFFF0000u);
+            v.x += bf_lo(bb.x); v.y += bf_hi(bb.x);
+            v.z += bf_lo(bb.y); v.w += bf_hi(bb.y);
             if (writeback) rr[i] = v;
         }
         reinterpret_cast<float4*>(row)[i] = v;
@@ -57,17 +56,14 @@ __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, 
         const int k0 = c * 8;
         const u32x4 gg = *reinterpret_cast<const u32x4*>(gamma + k0), bb = *reinterpret_cast<const u32x4*>(beta + k0);
         const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w}, bw[4] = {bb.x, bb.y, bb.z, bb.w};
-        uint32_t o[4], ol[4];
+        uint32_t o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float e0 = (row[k0 + 2 * j] - mean) * rstd * __uint_as_float(gw[j] << 16) + __uint_as_float(bw[j] << 16);
-            const float e1 = (row[k0 + 2 * j + 1] - mean) * rstd * __uint_as_float(gw[j] & 0xFFFF0000u) +
-                             __uint_as_float(bw[j] & 0xFFFF0000u);
-            split2(e0, e1, o[j], ol[j]);
+            const float e0 = (row[k0 + 2 * j] - mean) * rstd * bf_lo(gw[j]) + bf_lo(bw[j]);
+            const float e1 = (row[k0 + 2 * j + 1] - mean) * rstd * bf_hi(gw[j]) + bf_hi(bw[j]);
+            o[j] = pack2(e0, e1);
         }
-        const size_t slot = block_slot(m, k0, KB);
-        a[slot] = u32x4{o[0], o[1], o[2], o[3]};
-        if (a_lo) a_lo[slot] = u32x4{ol[0], ol[1], ol[2], ol[3]};
+        a[block_slot(m, k0, KB)] = u32x4{o[0], o[1], o[2], o[3]};
     }
 }
 
@@ -80,8 +76,8 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
                                                       size_t part_split, const bf16_t* __restrict__ pbias,
                                                       const bf16_t* __restrict__ gamma,
                                                       const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
-                                                      u32x4* __restrict__ a_lo, int H, float eps, int in_mul,
-                                                      int in_add, int writeback, int rows) {
+                                                      int H, float eps, int in_mul, int in_add, int writeback,
+                                                      int rows) {
     constexpr int NW = THREADS / 64;
     __shared__ float red[2][NW];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -127,10 +123,10 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + j * THREADS;
             if (i >= nq) continue;
-            v[j].x += (y0[j].x + y1[j].x) + __uint_as_float(pb[j].x << 16);
-            v[j].y += (y0[j].y + y1[j].y) + __uint_as_float(pb[j].x & 0xFFFF0000u);
-            v[j].z += (y0[j].z + y1[j].z) + __uint_as_float(pb[j].y << 16);
-            v[j].w += (y0[j].w + y1[j].w) + __uint_as_float(pb[j].y & 0xFFFF0000u);
+            v[j].x += (y0[j].x + y1[j].x) + bf_lo(pb[j].x);
+            v[j].y += (y0[j].y + y1[j].y) + bf_hi(pb[j].x);
+            v[j].z += (y0[j].z + y1[j].z) + bf_lo(pb[j].y);
+            v[j].w += (y0[j].w + y1[j].w) + bf_hi(pb[j].y);
             if (writeback) *reinterpret_cast<float4*>(r + src * H + 4 * i) = v[j];
         }
     } else if (part) {
@@ -144,10 +140,10 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
                 acc.x += y.x; acc.y += y.y; acc.z += y.z; acc.w += y.w;
             }
             const uint2 pb = *reinterpret_cast<const uint2*>(pbias + 4 * i);
-            v[j].x += acc.x + __uint_as_float(pb.x << 16);
-            v[j].y += acc.y + __uint_as_float(pb.x & 0xFFFF0000u);
-            v[j].z += acc.z + __uint_as_float(pb.y << 16);
-            v[j].w += acc.w + __uint_as_float(pb.y & 0xFFFF0000u);
+            v[j].x += acc.x + bf_lo(pb.x);
+            v[j].y += acc.y + bf_hi(pb.x);
+            v[j].z += acc.z + bf_lo(pb.y);
+            v[j].w += acc.w + bf_hi(pb.y);
             if (writeback) *reinterpret_cast<float4*>(r + src * H + 4 * i) = v[j];
         }
     }
@@ -180,17 +176,13 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
     for (int j = 0; j < NV; ++j) {
         const int i = threadIdx.x + j * THREADS;
         if (i >= nq) continue;
-        const float e0 = (v[j].x - mean) * rstd * __uint_as_float(gg[j].x << 16) + __uint_as_float(bb[j].x << 16);
-        const float e1 = (v[j].y - mean) * rstd * __uint_as_float(gg[j].x & 0xFFFF0000u) + __uint_as_float(bb[j].x & 0xFFFF0000u);
-        const float e2 = (v[j].z - mean) * rstd * __uint_as_float(gg[j].y << 16) + __uint_as_float(bb[j].y << 16);
-        const float e3 = (v[j].w - mean) * rstd * __uint_as_float(gg[j].y & 0xFFFF0000u) + __uint_as_float(bb[j].y & 0xFFFF0000u);
-        uint32_t h0, h1, l0, l1;
-        split2(e0, e1, h0, l0);
-        split2(e2, e3, h1, l1);
+        const float e0 = (v[j].x - mean) * rstd * bf_lo(gg[j].x) + bf_lo(bb[j].x);
+        const float e1 = (v[j].y - mean) * rstd * bf_hi(gg[j].x) + bf_hi(bb[j].x);
+        const float e2 = (v[j].z - mean) * rstd * bf_lo(gg[j].y) + bf_lo(bb[j].y);
+        const float e3 = (v[j].w - mean) * rstd * bf_hi(gg[j].y) + bf_hi(bb[j].y);
         const int k0 = 4 * i;  // four values: half of a 16-byte slot
         const size_t slot = block_slot(m, k0 & ~7, KB);
-        reinterpret_cast<uint2*>(a + slot)[(k0 >> 2) & 1] = make_uint2(h0, h1);
-        if (a_lo) reinterpret_cast<uint2*>(a_lo + slot)[(k0 >> 2) & 1] = make_uint2(l0, l1);
+        reinterpret_cast<uint2*>(a + slot)[(k0 >> 2) & 1] = make_uint2(pack2(e0, e1), pack2(e2, e3));
     }
 }
 
@@ -199,8 +191,8 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
 // For the few rows of a decode step a LayerNorm kernel of its own is all latency.  Instead
 //   W LN(x) + b = rstd * (W (gamma . x) - mean * (W gamma)) + W beta + b,
 // so the kernel that produces x (the embedding below, or the out-projection / FC2 GEMM
-// through its last-arriving workgroup) writes gamma . x as two-term blocks plus per-column-
-// group statistics of x, the consuming GEMM multiplies those blocks by the unchanged bf16
+// through its last-arriving workgroup) writes gamma . x as half blocks plus per-column-
+// group statistics of x, the consuming GEMM multiplies those blocks by the unchanged
 // weights and applies mean and rstd in its epilogue, and W gamma, W beta are vectors computed
 // once per weight update.
 
@@ -211,7 +203,7 @@ __global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict_
                                                       const he_dev_state* __restrict__ st, int V, int pos_offset,
                                                       int H, int gw, int groups, const bf16_t* __restrict__ gamma,
                                                       float* __restrict__ r, u32x4* __restrict__ xb,
-                                                      u32x4* __restrict__ xb_lo, float2* __restrict__ stats) {
+                                                      float2* __restrict__ stats) {
     const int g = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
     int id = ids[(size_t)m * id_stride];
     id = id < 0 ? 0 : (id >= V ? V - 1 : id);
@@ -223,17 +215,14 @@ __global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict_
         const uint2 t = *reinterpret_cast<const uint2*>(tok + (size_t)id * H + c0);
         const uint2 q = *reinterpret_cast<const uint2*>(pos + prow * H + c0);
         const uint2 gg = *reinterpret_cast<const uint2*>(gamma + c0);
-        x0 = __uint_as_float(t.x << 16) + __uint_as_float(q.x << 16);
-        x1 = __uint_as_float(t.x & 0xFFFF0000u) + __uint_as_float(q.x & 0xFFFF0000u);
-        x2 = __uint_as_float(t.y << 16) + __uint_as_float(q.y << 16);
-        x3 = __uint_as_float(t.y & 0xFFFF0000u) + __uint_as_float(q.y & 0xFFFF0000u);
+        x0 = bf_lo(t.x) + bf_lo(q.x);
+        x1 = bf_hi(t.x) + bf_hi(q.x);
+        x2 = bf_lo(t.y) + bf_lo(q.y);
+        x3 = bf_hi(t.y) + bf_hi(q.y);
         *reinterpret_cast<float4*>(r + (size_t)m * H + c0) = make_float4(x0, x1, x2, x3);
-        uint32_t h0, h1, l0, l1;
-        split2(x0 * __uint_as_float(gg.x << 16), x1 * __uint_as_float(gg.x & 0xFFFF0000u), h0, l0);
-        split2(x2 * __uint_as_float(gg.y << 16), x3 * __uint_as_float(gg.y & 0xFFFF0000u), h1, l1);
         const size_t slot = block_slot(m, c0 & ~7, H >> 4);
-        reinterpret_cast<uint2*>(xb + slot)[(c0 >> 2) & 1] = make_uint2(h0, h1);
-        reinterpret_cast<uint2*>(xb_lo + slot)[(c0 >> 2) & 1] = make_uint2(l0, l1);
+        reinterpret_cast<uint2*>(xb + slot)[(c0 >> 2) & 1] =
+            make_uint2(pack2(x0 * bf_lo(gg.x), x1 * bf_hi(gg.x)), pack2(x2 * bf_lo(gg.y), x3 * bf_hi(gg.y)));
     }
     float s = (x0 + x1) + (x2 + x3);
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
@@ -264,11 +253,11 @@ __global__ __launch_bounds__(256) void wvec_kernel(const u32x4* __restrict__ Wp,
         const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w}, gg[4] = {gv.x, gv.y, gv.z, gv.w}, bb[4] = {bv.x, bv.y, bv.z, bv.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float w0 = __uint_as_float(ww[j] << 16), w1 = __uint_as_float(ww[j] & 0xFFFF0000u);
-            a1 = fmaf(w0, __uint_as_float(gg[j] << 16), a1);
-            a1 = fmaf(w1, __uint_as_float(gg[j] & 0xFFFF0000u), a1);
-            a2 = fmaf(w0, __uint_as_float(bb[j] << 16), a2);
-            a2 = fmaf(w1, __uint_as_float(bb[j] & 0xFFFF0000u), a2);
+            const float w0 = half_lo(ww[j]), w1 = half_hi(ww[j]);
+            a1 = fmaf(w0, bf_lo(gg[j]), a1);
+            a1 = fmaf(w1, bf_hi(gg[j]), a1);
+            a2 = fmaf(w0, bf_lo(bb[j]), a2);
+            a2 = fmaf(w1, bf_hi(bb[j]), a2);
         }
     }
     a1 += __shfl_xor(a1, 32);
@@ -285,11 +274,11 @@ __global__ __launch_bounds__(256) void wvec_kernel(const u32x4* __restrict__ Wp,
 
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
-                   void* x_blocks, void* x_blocks_lo, float* stats) {
+                   void* x_blocks, float* stats) {
     const int groups = (H + gw - 1) / gw;
     embed_ln_kernel<<<dim3(groups, B), 64, 0, s>>>(ids, id_stride, (const bf16_t*)tok, (const bf16_t*)pos, st, V,
                                                    pos_offset, H, gw, groups, (const bf16_t*)gamma, r,
-                                                   (u32x4*)x_blocks, (u32x4*)x_blocks_lo, (float2*)stats);
+                                                   (u32x4*)x_blocks, (float2*)stats);
 }
 
 void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2) {
@@ -299,13 +288,13 @@ void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, c
 }
 
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
-             const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
-             int in_mul, int in_add, int writeback) {
+             const void* gamma, const void* beta, void* a_blocks, int rows, int H, float eps, int in_mul, int in_add,
+             int writeback) {
     const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
 #define HE_LN_ROW(NV, T)                                                                                                \
     ln_row_kernel<NV, T><<<(T == 256 ? (rows + 255) / 256 * 256 : rows), T, 0, s>>>(                                    \
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks, \
-        (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback, rows)
+        H, eps, in_mul, in_add, writeback, rows)
     if (rows <= 256 && nv <= 3) {  // a decode step
         if (nv == 1) HE_LN_ROW(1, 1024);
         else if (nv == 2) HE_LN_ROW(2, 1024);
@@ -330,6 +319,6 @@ void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part
 #undef HE_LN_ROW
     ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
-        (u32x4*)a_blocks_lo, H, eps, in_mul, in_add, writeback);
+        H, eps, in_mul, in_add, writeback);
 }
 

@@ -1,5 +1,5 @@
-// bf16 path: weight preparation -- tiling into MFMA operand blocks (optionally with low-rank adapters
-// folded in) and 8-bit E4M3 row quantisation.
+// bf16 path: weight preparation -- the caller's bf16 matrices converted to IEEE half and tiled into MFMA
+// operand blocks (optionally with low-rank adapters folded in), and 8-bit E4M3 row quantisation.
 #include "bf16_common.h"
 
 using namespace he_bf16;
@@ -7,6 +7,15 @@ using namespace he_bf16;
 namespace {
 
 // ----------------------------------------------------------------- weight tiling
+
+// eight bf16 values -> eight halves: exact for magnitudes 2^-14 .. 65504 (8 significant bits into 11), nearest
+// multiple of 2^-24 (ties to even) below that
+__device__ __forceinline__ u32x4 bf16x8_to_half(const u32x4& w) {
+    return u32x4{pack2(bf_lo(w.x), bf_hi(w.x)), pack2(bf_lo(w.y), bf_hi(w.y)), pack2(bf_lo(w.z), bf_hi(w.z)),
+                 pack2(bf_lo(w.w), bf_hi(w.w))};
+}
+// two floats -> two bf16 in one word, round to nearest even (the LoRA merge rounds to the model's own format)
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) { return f32x2_to_bf16x2(lo, hi); }
 
 __global__ void tile_rows_kernel(const bf16_t* __restrict__ src, u32x4* __restrict__ dst, int R, int K, size_t total) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -17,11 +26,11 @@ __global__ void tile_rows_kernel(const bf16_t* __restrict__ src, u32x4* __restri
     const int rt = (int)((idx >> 6) / KB);
     const int r = rt * 32 + (lane & 31), k = kb * 16 + (lane >> 5) * 8;
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (r < R) v = *reinterpret_cast<const u32x4*>(src + (size_t)r * K + k);
+    if (r < R) v = bf16x8_to_half(*reinterpret_cast<const u32x4*>(src + (size_t)r * K + k));
     dst[idx] = v;
 }
 
-// The same with a low-rank adapter folded in: dst = tiled bf16(W + scale * B A), A [rank, K], B [R, rank].
+// The same with a low-rank adapter folded in: dst = tiled half(bf16(W + scale * B A)), A [rank, K], B [R, rank].
 // The sum fixes a bf16 rounding, so its order is part of the definition: products B[r][j] A[j][k]
 // (exact in float for bf16 inputs) are added one by one for j = 0..rank-1, then W + scale * that, every
 // operation a separate float rounding (no fused multiply-add).
@@ -46,7 +55,7 @@ __global__ void tile_rows_lora_kernel(const bf16_t* __restrict__ src, u32x4* __r
             const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float p0 = b * __uint_as_float(aw[i] << 16), p1 = b * __uint_as_float(aw[i] & 0xFFFF0000u);
+                const float p0 = b * bf_lo(aw[i]), p1 = b * bf_hi(aw[i]);
                 t[2 * i] = t[2 * i] + p0;
                 t[2 * i + 1] = t[2 * i + 1] + p1;
             }
@@ -55,11 +64,11 @@ __global__ void tile_rows_lora_kernel(const bf16_t* __restrict__ src, u32x4* __r
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float s0 = scale * t[2 * i], s1 = scale * t[2 * i + 1];  // plain operators: the pragma above covers them
-            const float lo = __uint_as_float(ww[i] << 16) + s0;
-            const float hi = __uint_as_float(ww[i] & 0xFFFF0000u) + s1;
-            o[i] = pack2(lo, hi);
+            const float lo = bf_lo(ww[i]) + s0;
+            const float hi = bf_hi(ww[i]) + s1;
+            o[i] = pack2_bf16(lo, hi);  // the merged weight is a bf16 value ...
         }
-        v = u32x4{o[0], o[1], o[2], o[3]};
+        v = bf16x8_to_half(u32x4{o[0], o[1], o[2], o[3]});  // ... held as a half like every other weight
     }
     dst[idx] = v;
 }
@@ -81,8 +90,8 @@ __global__ __launch_bounds__(256) void row_exp_kernel(const bf16_t* __restrict__
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            amax = fmaxf(amax, fabsf(__uint_as_float(w[j] << 16)));
-            amax = fmaxf(amax, fabsf(__uint_as_float(w[j] & 0xFFFF0000u)));
+            amax = fmaxf(amax, fabsf(bf_lo(w[j])));
+            amax = fmaxf(amax, fabsf(bf_hi(w[j])));
         }
     }
     for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
@@ -103,8 +112,8 @@ __device__ __forceinline__ uint2 quant8_e4m3(const u32x4& v, float inv_scale) {
     float f[8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        f[2 * j] = __uint_as_float(w[j] << 16) * inv_scale;
-        f[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u) * inv_scale;
+        f[2 * j] = bf_lo(w[j]) * inv_scale;
+        f[2 * j + 1] = bf_hi(w[j]) * inv_scale;
     }
     int lo = 0, hi = 0;
     lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], lo, false);
@@ -142,7 +151,8 @@ __global__ void quant_units_kernel(const bf16_t* __restrict__ src, const int* __
     dst[idx] = out;
 }
 
-// units -> the bf16 32x16 blocks the tiled GEMMs read (the dequantised weights are bf16 values exactly)
+// units -> the half 32x16 blocks the tiled GEMMs read (a dequantised weight q 2^e has four significant bits: exact
+// as a half down to 2^-24, which only rows whose largest weight is below 448 * 2^-15 = 0.014 can undercut)
 __global__ void dequant_units_kernel(const u32x4* __restrict__ units, const float* __restrict__ scales,
                                      u32x4* __restrict__ dst, int R, int K, size_t total) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 typedef uint16_t bf16_t;  // raw bfloat16: the upper 16 bits of an IEEE float
+typedef uint16_t half_t;  // raw IEEE half (what the bf16 path's matrix-core operands and KV cache hold)
 
 // Device-resident generation state.  Every kernel reads positions, step
 // numbers and sampling parameters from here rather than from launch

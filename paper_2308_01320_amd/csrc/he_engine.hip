@@ -25,14 +25,13 @@ struct he_engine {
     float *xf = nullptr, *logits = nullptr, *gen_lp = nullptr;
     int32_t *cur_ids = nullptr, *gen_ids = nullptr;
 
-    // bf16 path: MFMA-tiled copies of the GEMM matrices and tiled activation buffers
+    // bf16 path: MFMA-tiled copies of the GEMM matrices (IEEE halves) and tiled activation buffers
     bool fast = false;
     struct Tiled { void *wqkv, *wo, *w1, *w2; };
     std::vector<Tiled> tiled;
     void *lm_tiled = nullptr, *ablk = nullptr, *oblk = nullptr, *hblk = nullptr, *xfblk = nullptr;
-    void *ablk_lo = nullptr, *oblk_lo = nullptr, *hblk_lo = nullptr, *xfblk_lo = nullptr;  // second bf16 term
     // 8-bit weights: tiled[] then holds E4M3 units, wscale_buf the row scales (per layer 3H + H + F + H floats),
-    // scratch one layer's dequantised bf16 blocks for the GEMMs that read those
+    // scratch one layer's dequantised half blocks for the GEMMs that read those
     bool w8 = false;
     float* wscale_buf = nullptr;
     int* exps_tmp = nullptr;
@@ -97,7 +96,8 @@ struct Sizes {
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
 constexpr int kMaxKSplit = 8;  // no GEMM plan splits k further
 
-size_t elt_bytes(const he_config& c) { return c.dtype == HE_BF16 ? 2 : 4; }
+// bytes per cached key / value element: IEEE halves on the tuned bf16 path, floats for the plain kernels
+size_t kv_elt_bytes(const he_config& c) { return is_fast(c) ? 2 : 4; }
 
 const char* check_config(const he_config* c) {
     if (!c) return "config is NULL";
@@ -129,7 +129,7 @@ const char* check_shape(const he_config* c) {
 Sizes sizes_of(const he_config& c) {
     Sizes s{};
     const size_t rows = (size_t)c.max_batch * c.max_seq_len;
-    s.kv = (size_t)c.n_layers * 2 * rows * c.hidden * elt_bytes(c);
+    s.kv = (size_t)c.n_layers * 2 * rows * c.hidden * kv_elt_bytes(c);
     s.rowsH = rows * c.hidden * sizeof(float);
     s.rowsF = rows * c.ffn * sizeof(float);
     s.xf = (size_t)c.max_batch * c.hidden * sizeof(float);
@@ -169,8 +169,7 @@ Sizes sizes_of(const he_config& c) {
                    wide * sizeof(int);
     }
     s.total += 2 * s.rowsH /* resid, q */ + (c.weights_tiled || c.weights_fp8 ? 0 : (size_t)c.n_layers * s.tiled_layer + s.tiled_lm) +
-               4 * s.ablk + 2 * s.hblk +
-               2 * s.xfblk + s.part + s.stats + s.stats_idx;
+               2 * s.ablk + s.hblk + s.xfblk + s.part + s.stats + s.stats_idx;
     return s;
 }
 
@@ -266,19 +265,19 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
         const he_engine::Tiled tw = layer_blocks(e, l);
-        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, M, H, c.ln_eps, 1, 0, 1);
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, M, H, c.ln_eps, 1, 0, 1);
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
-        bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, M, 3 * H, H, a);
+        bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, M, 3 * H, H, a);
         if (l == c.n_layers - 1 && !full) break;
-        bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+        bf16_attn(s, e->qbuf, e->kv, e->oblk, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
         a = base;
-        bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, M, H, H, kso, e->part, split, a);
-        bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, M, H, c.ln_eps, 1, 0, 1);
-        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
-        bf16_gemm_tiled(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, M, F, H, a);
+        bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, M, H, H, kso, e->part, split, a);
+        bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, M, H, c.ln_eps, 1, 0, 1);
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
+        bf16_gemm_tiled(s, EPI_BIAS_RELU, tw.w1, e->ablk, M, F, H, a);
         a = base;
-        bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, M, H, F, ks2, e->part, split, a);
+        bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, M, H, F, ks2, e->part, split, a);
         pend = e->part; pend_b = lw.b2; pend_ks = ks2;
     }
     if (pend_bias) *pend_bias = pend_b;
@@ -306,7 +305,7 @@ CVec cvec_lm(const he_engine* e) {
 }
 
 // bf16 path, one new token per sequence (a decode step, or the last prompt token):
-// weight-streaming GEMMs with two-term activations, attention over the cache, LM head
+// weight-streaming GEMMs, attention over the cache, LM head
 // fused with log-softmax and sampling.
 void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int32_t* ids_out, float* lp_out,
                       int out_stride, int out_at_step, float* d_logits_opt) {
@@ -317,7 +316,7 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
     base.max_seq = c.max_seq_len;
     // No LayerNorm kernels here: each one is folded into the GEMM after it.  Whoever produces a
-    // residual row (the embedding, the out-projection, FC2) leaves gamma * x as two-term blocks
+    // residual row (the embedding, the out-projection, FC2) leaves gamma * x as half blocks
     // and statistics per group of columns; the column groups are the producer's workgroups.
     int gw1, ks1, gw2, ks2;  // column-group widths after the out-projection / after FC2 and the embedding
     if (e->w8) {
@@ -333,16 +332,15 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
         a.ln_stats = e->ln_stats; a.ln_gw = gw; a.ln_groups = (H + gw - 1) / gw; a.ln_cols = H; a.ln_eps = c.ln_eps;
         a.c1 = cv.c1; a.c2 = cv.c2;
     };
-    auto store_ln = [&](bf16_gemm_args& a, const void* bias, const void* gamma, void* blk, void* blk_lo) {
+    auto store_ln = [&](bf16_gemm_args& a, const void* bias, const void* gamma, void* blk) {
         a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.bias = bias; a.resid = e->resid; a.gamma = gamma;
-        a.out_blocks = blk; a.out_blocks_lo = blk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
+        a.out_blocks = blk; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
     };
     {
         LaunchTimer t(e, HE_K_LAYERNORM);
         const bool last = L == 0;
         bf16_embed_ln(s, d_ids, id_stride, e->w.tok_emb, e->w.pos_emb, e->st, B, H, c.vocab, c.pos_offset, gw2,
-                      last ? e->w.lnf_g : e->layers[0].ln1_g, e->resid, last ? e->xfblk : e->ablk,
-                      last ? e->xfblk_lo : e->ablk_lo, e->ln_stats);
+                      last ? e->w.lnf_g : e->layers[0].ln1_g, e->resid, last ? e->xfblk : e->ablk, e->ln_stats);
     }
     for (int l = 0; l < L; ++l) {
         const he_layer_weights& lw = e->layers[l];
@@ -354,41 +352,40 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
         a.wscale = sc.wqkv;
         {
             LaunchTimer t(e, HE_K_QKV);
-            bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, 1, a);
+            bf16_gemm_skinny(s, EPI_QKV, tw.wqkv, e->ablk, B, 3 * H, H, 1, a);
         }
         {
             LaunchTimer t(e, HE_K_ATTENTION);
-            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
         }
         a = base;
-        store_ln(a, lw.bo, lw.ln2_g, e->ablk, e->ablk_lo);
+        store_ln(a, lw.bo, lw.ln2_g, e->ablk);
         a.wscale = sc.wo;
         {
             LaunchTimer t(e, HE_K_OUT_PROJ);
-            bf16_gemm_skinny(s, EPI_STORE_LN, tw.wo, e->oblk, e->oblk_lo, B, H, H, ks1, a);
+            bf16_gemm_skinny(s, EPI_STORE_LN, tw.wo, e->oblk, B, H, H, ks1, a);
         }
-        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
         fold(a, gw1, cvec_fc1(e, l));
         a.wscale = sc.w1;
         {
             LaunchTimer t(e, HE_K_FC1);
-            bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+            bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, B, F, H, 1, a);
         }
         a = base;
         const bool last = l == L - 1;
-        store_ln(a, lw.b2, last ? e->w.lnf_g : e->layers[l + 1].ln1_g, last ? e->xfblk : e->ablk,
-                 last ? e->xfblk_lo : e->ablk_lo);
+        store_ln(a, lw.b2, last ? e->w.lnf_g : e->layers[l + 1].ln1_g, last ? e->xfblk : e->ablk);
         a.wscale = sc.w2;
         {
             LaunchTimer t(e, HE_K_FC2);
-            bf16_gemm_skinny(s, EPI_STORE_LN, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, a);
+            bf16_gemm_skinny(s, EPI_STORE_LN, tw.w2, e->hblk, B, H, F, ks2, a);
         }
     }
     {
         LaunchTimer t(e, HE_K_LM_HEAD);
         bf16_gemm_args a = base;
         fold(a, gw2, cvec_lm(e));
-        bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
+        bf16_lm_head(s, e->lm_tiled, e->xfblk, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
                      ids_out, lp_out, out_stride, out_at_step, e->cur_ids, &a);
     }
     { LaunchTimer t(e, HE_K_EMPTY); }
@@ -421,46 +418,46 @@ void pass_decode_wide_bf16(he_engine* e, const int32_t* d_ids, int id_stride, in
         const he_engine::Tiled tw = layer_blocks(e, l);
         {
             LaunchTimer t(e, HE_K_LAYERNORM);
-            bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+            bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, B, H, c.ln_eps, 1, 0, 1);
         }
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
         {
             LaunchTimer t(e, HE_K_QKV);
-            bf16_gemm_tiled_ksplit(s, EPI_QKV, tw.wqkv, e->ablk, e->ablk_lo, B, 3 * H, H, ksq, e->part, (size_t)B * 3 * H, a);
+            bf16_gemm_tiled_ksplit(s, EPI_QKV, tw.wqkv, e->ablk, B, 3 * H, H, ksq, e->part, (size_t)B * 3 * H, a);
         }
         {
             LaunchTimer t(e, HE_K_ATTENTION);
-            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->oblk_lo, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+            bf16_attn(s, e->qbuf, e->kv, e->oblk, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
         }
         a = base;
         {
             LaunchTimer t(e, HE_K_OUT_PROJ);
-            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, e->oblk_lo, B, H, H, kso, e->part, split, a);
+            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, B, H, H, kso, e->part, split, a);
         }
         {
             LaunchTimer t(e, HE_K_LAYERNORM);
-            bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, e->ablk_lo, B, H, c.ln_eps, 1, 0, 1);
+            bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, B, H, c.ln_eps, 1, 0, 1);
         }
-        a = base; a.bias = lw.b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+        a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
         {
             LaunchTimer t(e, HE_K_FC1);
-            bf16_gemm_tiled_ksplit(s, EPI_BIAS_RELU, tw.w1, e->ablk, e->ablk_lo, B, F, H, ks1, e->part, (size_t)B * F, a);
+            bf16_gemm_tiled_ksplit(s, EPI_BIAS_RELU, tw.w1, e->ablk, B, F, H, ks1, e->part, (size_t)B * F, a);
         }
         a = base;
         {
             LaunchTimer t(e, HE_K_FC2);
-            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, e->hblk_lo, B, H, F, ks2, e->part, split, a);
+            bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, B, H, F, ks2, e->part, split, a);
         }
         pend = e->part; pend_ks = ks2; pend_b = lw.b2;
     }
     {
         LaunchTimer t(e, HE_K_LAYERNORM);
-        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, e->xfblk_lo, B, H, c.ln_eps, 1, 0, 0);
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, e->w.lnf_g, e->w.lnf_b, e->xfblk, B, H, c.ln_eps, 1, 0, 0);
     }
     {
         LaunchTimer t(e, HE_K_LM_HEAD);
-        bf16_lm_head(s, e->lm_tiled, e->xfblk, e->xfblk_lo, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
+        bf16_lm_head(s, e->lm_tiled, e->xfblk, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx,
                      ids_out, lp_out, out_stride, out_at_step, e->cur_ids);
     }
     { LaunchTimer t(e, HE_K_EMPTY); }
@@ -704,7 +701,6 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
             A(&e->lm_tiled, z.tiled_lm);
         }
         A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
-        A(&e->ablk_lo, z.ablk); A(&e->oblk_lo, z.ablk); A(&e->xfblk_lo, z.xfblk); A(&e->hblk_lo, z.hblk);
         A(&e->part, z.part); e->part_floats = z.part / sizeof(float); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
         A(&e->cvec, z.cvec); A(&e->ln_stats, z.ln_stats); A(&e->ln_counters, z.ln_counters);
         A(&e->score_stats, z.score_stats); A(&e->score_tgt, z.gen);
@@ -736,10 +732,6 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         (void)hipMemsetAsync(e->oblk, 0, z.ablk, e->stream);
         (void)hipMemsetAsync(e->hblk, 0, z.hblk, e->stream);
         (void)hipMemsetAsync(e->xfblk, 0, z.xfblk, e->stream);
-        (void)hipMemsetAsync(e->ablk_lo, 0, z.ablk, e->stream);
-        (void)hipMemsetAsync(e->oblk_lo, 0, z.ablk, e->stream);
-        (void)hipMemsetAsync(e->xfblk_lo, 0, z.xfblk, e->stream);
-        (void)hipMemsetAsync(e->hblk_lo, 0, z.hblk, e->stream);
         (void)hipMemsetAsync(e->ln_stats, 0, z.ln_stats, e->stream);
         (void)hipMemsetAsync(e->ln_counters, 0, z.ln_counters, e->stream);
         tile_weights(e);
@@ -1025,9 +1017,8 @@ he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_ou
         int pend_ks = 1;
         pass_tiled_bf16(e, d_ids, T, B, T, true, &pend_b, &pend_ks);
         bf16_ln(s, e->resid, c.n_layers ? e->part : nullptr, pend_ks, (size_t)M * H, pend_b, e->w.lnf_g, e->w.lnf_b, e->ablk,
-                e->ablk_lo, M, H, c.ln_eps, 1, 0, 0);
-        bf16_score_head(s, e->lm_tiled, e->ablk, e->ablk_lo, M, T, V, H, d_ids, e->score_stats, e->score_tgt,
-                        d_out_logprobs);
+                M, H, c.ln_eps, 1, 0, 0);
+        bf16_score_head(s, e->lm_tiled, e->ablk, M, T, V, H, d_ids, e->score_stats, e->score_tgt, d_out_logprobs);
     } else {
         const int bf = e->bf16;
         const float qscale = 1.0f / sqrtf((float)e->d);
@@ -1153,27 +1144,27 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
             if (wide_decode(e, B)) {  // the GEMMs of the wide decode step
                 if (e->w8) return fail(e, HE_ERR_STATE, "he_kernel_sweep: with 8-bit weights only for batches up to 32");
                 if (kernel_class == HE_K_FC1) {
-                    a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
-                    bf16_gemm_tiled_ksplit(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H,
+                    a.bias = e->layers[l].b1; a.out_blocks = e->hblk;
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, B, F, H,
                                            bf16_tiled_ksplit(B, F, H), e->part, (size_t)B * F, a);
                 } else if (kernel_class == HE_K_FC2) {
-                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F,
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].w2, e->hblk, B, H, F,
                                            bf16_tiled_ksplit(B, H, F), e->part, split, a);
                 } else {
-                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H,
+                    bf16_gemm_tiled_ksplit(e->stream, EPI_STORE, e->tiled[l].wo, e->oblk, B, H, H,
                                            bf16_tiled_ksplit(B, H, H), e->part, split, a);
                 }
                 continue;
             }
             if (kernel_class == HE_K_FC1) {
-                a.bias = e->layers[l].b1; a.out_blocks = e->hblk; a.out_blocks_lo = e->hblk_lo;
+                a.bias = e->layers[l].b1; a.out_blocks = e->hblk;
                 int gw1, ks1;
                 if (e->w8) bf16_store_plan_w8(H, H, e->part_floats, &gw1, &ks1);
                 else bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
                 if (e->w8) a.wscale = scales_of(e, l).w1;
                 a.ln_stats = e->ln_stats; a.ln_gw = gw1; a.ln_groups = (H + a.ln_gw - 1) / a.ln_gw; a.ln_cols = H;
                 a.ln_eps = c.ln_eps; a.c1 = cvec_fc1(e, l).c1; a.c2 = cvec_fc1(e, l).c2;
-                bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, e->ablk_lo, B, F, H, 1, a);
+                bf16_gemm_skinny(e->stream, EPI_BIAS_RELU, e->tiled[l].w1, e->ablk, B, F, H, 1, a);
             } else {
                 // as in a decode step: the last workgroup of each column group folds the partial sums
                 // into the residual rows and rewrites the blocks and statistics the next GEMM reads
@@ -1185,9 +1176,9 @@ he_status he_kernel_sweep(he_engine* e, int kernel_class, int reps) {
                 a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.resid = e->resid;
                 a.bias = fc2 ? e->layers[l].b2 : e->layers[l].bo;
                 a.gamma = fc2 ? e->layers[l].ln1_g : e->layers[l].ln2_g;
-                a.out_blocks = e->ablk; a.out_blocks_lo = e->ablk_lo; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
-                if (fc2) bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].w2, e->hblk, e->hblk_lo, B, H, F, ks, a);
-                else bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].wo, e->oblk, e->oblk_lo, B, H, H, ks, a);
+                a.out_blocks = e->ablk; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
+                if (fc2) bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].w2, e->hblk, B, H, F, ks, a);
+                else bf16_gemm_skinny(e->stream, EPI_STORE_LN, e->tiled[l].wo, e->oblk, B, H, H, ks, a);
             }
         }
     return check_hip(e, hipGetLastError(), "he_kernel_sweep");

@@ -37,14 +37,13 @@ void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint
 void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 void launch_copy_out(hipStream_t s, const int32_t* ids, const float* lp, int32_t* out_ids, float* out_lp, int count);
 
-// ---- bf16 path (bf16_*.hip): operands are tiled bf16 blocks, see bf16_common.h
+// ---- bf16 path (bf16_*.hip): matrix-core operands are tiled blocks of IEEE halves, see bf16_common.h
 struct bf16_gemm_args {
     const void* bias = nullptr;      // bf16 [N]
     float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
     size_t out_split = 0;            // elements between k-splits
     size_t out_capacity = 0;         // EPI_STORE_LN: floats `out` can hold (0 = not checked)
-    void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled bf16 output (hi term)
-    void* out_blocks_lo = nullptr;   // EPI_BIAS_RELU: lo term
+    void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled half output
     void* kv = nullptr;              // EPI_QKV
     const he_dev_state* st = nullptr;
     int S = 1, layer = 0, H = 0, n_heads = 0, max_batch = 0, max_seq = 0;
@@ -56,9 +55,9 @@ struct bf16_gemm_args {
     float ln_eps = 0.f;
     const float* c1 = nullptr;        // [N padded to 32] W gamma
     const float* c2 = nullptr;        // [N padded to 32] W beta
-    // EPI_STORE_LN: k-split sum + bias + residual, gamma * x blocks (out_blocks, out_blocks_lo) and statistics
+    // EPI_STORE_LN: k-split sum + bias + residual, gamma * x blocks (out_blocks) and statistics
     float* resid = nullptr;           // [M][N]
-    const void* gamma = nullptr;      // bf16 [N]
+    const void* gamma = nullptr;      // bf16 [N] (the caller's parameter)
     float* stats_out = nullptr;       // [m_tiles][groups][32][2]
     int* counters = nullptr;          // [groups * m_tiles] zeros
     // 8-bit weights (bf16_gemm_skinny only): Wp holds E4M3 codes in 16-row units, wscale [N] the row scales 2^e
@@ -81,15 +80,14 @@ size_t bf16_store_need(int M, int N, int K, size_t capacity, int w8);
 void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks);
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
-                   void* x_blocks, void* x_blocks_lo, float* stats);
+                   void* x_blocks, float* stats);
 void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2);
 // rows in slices of 32 (a decode step of up to 32 sequences): EPI_BIAS_RELU, EPI_QKV or EPI_STORE_LN;
-// activations as hi + lo bf16 terms; ksplit is ignored (the plan decides)
-void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
-                      int ksplit, const bf16_gemm_args& a);
+// X: the activations as tiled half blocks; ksplit is ignored (the plan decides)
+void bf16_gemm_skinny(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, int ksplit,
+                      const bf16_gemm_args& a);
 // many rows (prompt pass)
-void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
-                     const bf16_gemm_args& a);
+void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, const bf16_gemm_args& a);
 // a decode step of more than 32 rows: the same tiles, cut into k ranges so that they fill the chip.  The
 // partial sums go to part [ksplit][M][N]; for EPI_STORE the caller's LayerNorm adds them, for the other
 // modes a second kernel adds them and applies the epilogue.
@@ -97,27 +95,27 @@ int bf16_tiled_ksplit(int M, int N, int K);
 // k ranges per tile for a many-row MODE_STORE GEMM whose tiles do not come out in whole rounds of one per CU
 // (1 if they do, or if ks x M x N partial sums do not fit capacity_floats)
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats);
-void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, const void* Xlo, int M, int N, int K,
-                            int ksplit, float* part, size_t part_split, const bf16_gemm_args& a);
+void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, int ksplit,
+                            float* part, size_t part_split, const bf16_gemm_args& a);
 // ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row
 size_t fp8_units_bytes(int rows, int K);  // codes in the half-tile kernel's units: [rows/16][K/64][64 lanes][16 bytes]
 void fp8_row_exponents(hipStream_t s, const void* src, int R, int K, int* exps, float* scales);  // e[n], 2^e[n]
 void fp8_quant_rows(hipStream_t s, const void* src, const int* exps, void* codes, int R, int K);  // row-major codes
 void fp8_quant_units(hipStream_t s, const void* src, const int* exps, void* units, int R, int K);
-// units -> bf16 32x16 blocks (what the tiled GEMMs read); exact
+// units -> half 32x16 blocks (what the tiled GEMMs read)
 void fp8_dequant_units(hipStream_t s, const void* units, const float* scales, void* dst_blocks, int R, int K);
 void bf16_store_plan_w8(int N, int K, size_t capacity, int* group_cols, int* ks);
-void bf16_lm_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int B, int V, int K,
+void bf16_lm_head(hipStream_t s, const void* Wp, const void* X, int B, int V, int K,
                   const he_dev_state* st, float* logits_opt, float* stats, int* stats_idx, int32_t* ids_out,
                   float* lp_out, int out_stride, int out_at_step, int32_t* cur_ids,
                   const bf16_gemm_args* fold = nullptr);
 // LM head over all M = B*S positions fused with log-softmax and the gather of each position's next
 // token: out [B][S-1]; stats [M][bf16_score_parts(V)][2] and tgt [M] are scratch
 int bf16_score_parts(int V);
-void bf16_score_head(hipStream_t s, const void* Wp, const void* Xhi, const void* Xlo, int M, int S, int V, int K,
+void bf16_score_head(hipStream_t s, const void* Wp, const void* X, int M, int S, int V, int K,
                      const int32_t* ids, float* stats, float* tgt, float* out);
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
-             const void* gamma, const void* beta, void* a_blocks, void* a_blocks_lo, int rows, int H, float eps,
-             int in_mul, int in_add, int writeback);
-void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, void* o_blocks_lo,
-               const he_dev_state* st, int M, int S, int layer, int H, int n_heads, int max_batch, int max_seq);
+             const void* gamma, const void* beta, void* a_blocks, int rows, int H, float eps, int in_mul, int in_add,
+             int writeback);
+void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, const he_dev_state* st, int M, int S,
+               int layer, int H, int n_heads, int max_batch, int max_seq);

@@ -81,7 +81,7 @@ __global__ void ln_kernel(float* __restrict__ r, const float* __restrict__ y, co
 // C[m,n] = sum_k A[m,k] W[n,k]; 64x64 tile, 4x4 outputs per thread, K staged 16 at a time.
 template <typename ST>
 __global__ void gemm_kernel(const float* __restrict__ A, const ST* __restrict__ W, const ST* __restrict__ bias, int M,
-                            int N, int K, int epi, float* __restrict__ out, ST* __restrict__ kv,
+                            int N, int K, int epi, float* __restrict__ out, float* __restrict__ kv,
                             const he_dev_state* __restrict__ st, int S, int layer, int H, int n_heads, int max_batch,
                             int max_seq, float qscale) {
     __shared__ float As[16][65];
@@ -137,8 +137,7 @@ __global__ void gemm_kernel(const float* __restrict__ A, const ST* __restrict__ 
 }
 
 // One block per (row m, head h): scores over keys 0..cur_len+t, softmax, weighted sum of values.
-template <typename ST>
-__global__ void attn_kernel(const float* __restrict__ q, const ST* __restrict__ kv, float* __restrict__ o,
+__global__ void attn_kernel(const float* __restrict__ q, const float* __restrict__ kv, float* __restrict__ o,
                             const he_dev_state* __restrict__ st, int S, int layer, int H, int n_heads, int max_batch,
                             int max_seq) {
     extern __shared__ float smem[];
@@ -152,8 +151,8 @@ __global__ void attn_kernel(const float* __restrict__ q, const ST* __restrict__ 
         for (int e = threadIdx.x; e < d; e += blockDim.x) o[(size_t)m * H + h * d + e] = 0.f;
         return;
     }
-    const ST* Kp = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, d);
-    const ST* Vp = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, d);
+    const float* Kp = kv + kv_index(layer, 0, b, h, 0, max_batch, n_heads, max_seq, d);
+    const float* Vp = kv + kv_index(layer, 1, b, h, 0, max_batch, n_heads, max_seq, d);
     for (int e = threadIdx.x; e < d; e += blockDim.x) qs[e] = q[(size_t)m * H + h * d + e];
     __syncthreads();
     float mx = -INFINITY;
@@ -371,7 +370,7 @@ void plain_gemm(hipStream_t s, int bf16, const float* A, const void* W, const vo
     dim3 grid((N + 63) / 64, (M + 63) / 64);
     if (bf16)
         gemm_kernel<bf16_t><<<grid, kThreads, 0, s>>>(A, (const bf16_t*)W, (const bf16_t*)bias, M, N, K, epi, out,
-                                                      (bf16_t*)kv, st, S, layer, H, n_heads, max_batch, max_seq,
+                                                      (float*)kv, st, S, layer, H, n_heads, max_batch, max_seq,
                                                       qscale);
     else
         gemm_kernel<float><<<grid, kThreads, 0, s>>>(A, (const float*)W, (const float*)bias, M, N, K, epi, out,
@@ -382,11 +381,8 @@ void plain_attn(hipStream_t s, int bf16, const float* q, const void* kv, float* 
                 int layer, int H, int n_heads, int max_batch, int max_seq) {
     dim3 grid(M, n_heads);
     const size_t shm = (size_t)(H / n_heads + max_seq) * sizeof(float);
-    if (bf16)
-        attn_kernel<bf16_t><<<grid, 128, shm, s>>>(q, (const bf16_t*)kv, o, st, S, layer, H, n_heads, max_batch,
-                                                   max_seq);
-    else
-        attn_kernel<float><<<grid, 128, shm, s>>>(q, (const float*)kv, o, st, S, layer, H, n_heads, max_batch, max_seq);
+    (void)bf16;  // the plain kernels keep keys and values as floats whatever the weights' type
+    attn_kernel<<<grid, 128, shm, s>>>(q, (const float*)kv, o, st, S, layer, H, n_heads, max_batch, max_seq);
 }
 
 void plain_lm_head(hipStream_t s, int bf16, const float* xf, const void* W, float* logits, int B, int H, int V) {

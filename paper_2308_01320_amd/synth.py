@@ -119,3 +119,36 @@ def make_prompts(d: ModelDims, seed: int = 1234, batch: int | None = None, promp
     B = d.batch if batch is None else batch
     S = d.prompt_len if prompt_len is None else prompt_len
     return rng.integers(0, d.vocab, size=(B, S), dtype=np.int32)
+
+
+def device_weights(d, torch, seed=0, std=0.02, tile=None):
+    """Random-init bf16 weights generated on the device, tensor by tensor (the full-size models do not
+    fit host memory).  tile: optional callable applied to every GEMM matrix (and the LM head) as soon as
+    it is drawn, the row-major original then dropped -- a caller that hands the engine pre-tiled matrices
+    passes the binding's tiling call here, so that no matrix ever exists twice."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = torch.bfloat16
+
+    def draw(shape, mean=0.0):
+        t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+        return (t * std + mean).to(dt).contiguous()
+
+    def mat(shape):
+        m = draw(shape)
+        if tile is None:
+            return m
+        t = tile(m)
+        torch.cuda.synchronize()
+        return t
+
+    H, F = d.hidden, d.ffn
+    w = {"tok_emb": draw((d.vocab, H)), "pos_emb": draw((d.max_positions + d.pos_offset, H)), "layers": []}
+    for _ in range(d.n_layers):
+        w["layers"].append({
+            "ln1_g": draw((H,), 1.0), "ln1_b": draw((H,)), "wqkv": mat((3 * H, H)), "bqkv": draw((3 * H,)),
+            "wo": mat((H, H)), "bo": draw((H,)), "ln2_g": draw((H,), 1.0), "ln2_b": draw((H,)),
+            "w1": mat((F, H)), "b1": draw((F,)), "w2": mat((H, F)), "b2": draw((H,))})
+    w["lnf_g"], w["lnf_b"] = draw((H,), 1.0), draw((H,))
+    w["lm_head"] = tile(w["tok_emb"]) if tile is not None else w["tok_emb"]
+    return w

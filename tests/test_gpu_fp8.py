@@ -70,7 +70,7 @@ def test_fp8_weights_against_oracle_on_dequantised_model(L, H, nh, F, V, B, S, G
     import torch
     seq = np.concatenate([prompts, want["ids"]], axis=1)
     sc = eng.he_score(torch.from_numpy(seq).cuda()).cpu().numpy()
-    ref = O.score(util_f64(wq), seq, d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset, kv_dtype="bf16")
+    ref = O.score(util_f64(wq), seq, d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset)
     assert float(np.abs(sc - ref).max()) <= BF16_TOL
     eng.he_destroy()
 

@@ -17,10 +17,7 @@ BF16_TOL, MARGIN = 2e-2, 1e-2
 
 
 def _f64(w):
-    out = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
-           for k, v in w.items()}
-    out["lm_head"] = out["tok_emb"]
-    return out
+    return util.weights_f64(w)
 
 
 def test_headline_launch_shape_sampled_sequences_against_oracle():
@@ -47,16 +44,19 @@ def test_headline_launch_shape_sampled_sequences_against_oracle():
     for b in (0, 17, 31):
         # the oracle on sequence b alone; its Gumbel noise is keyed by the row index, so give it
         # the noise of row b by sampling from its logits with the engine's row number
-        dec = O.CachedDecoder(w64, d.n_heads, d.ln_eps, d.pos_offset, "bf16")
+        dec = O.CachedDecoder(w64, d.n_heads, d.ln_eps, d.pos_offset)
         z = dec.prefill(prompts[b:b + 1])
         for n in range(G):
             err = np.abs(got_lg[n, b] - z[0]).max()
+            print("sequence", b, "step", n, "logit err", err, flush=True)
             assert err <= BF16_TOL, (b, n, err)
             score = z[0] + O.gumbel_noise(42, b, n, d.vocab)
             order = np.argsort(score)
             margin = score[order[-1]] - score[order[-2]]
-            if margin > max(MARGIN, 2 * err):
+            if margin > MARGIN:
                 assert got_ids[b, n] == order[-1], (b, n)
+            else:
+                assert got_ids[b, n] in (order[-1], order[-2]), (b, n)
             want_lp = O.log_softmax(z)[0, got_ids[b, n]]
             assert abs(got_lp[b, n] - want_lp) <= BF16_TOL
             if n + 1 < G:
@@ -64,12 +64,34 @@ def test_headline_launch_shape_sampled_sequences_against_oracle():
     print("sampled sequences ok")
 
 
+@pytest.mark.parametrize("name,B,S,G", [
+    ("opt-13b", 2, 498, 15),   # 40 heads of 128: contexts 499 .. 512, the benchmark's last steps and its capacity limit
+    ("opt-66b", 2, 300, 4),    # 72 heads of 128
+    ("opt-1.3b", 3, 505, 8),   # 32 heads of 64, for the other instantiation
+])
+def test_decode_attention_at_long_context_against_oracle(name, B, S, G):
+    """The decode attention kernel over the contexts the benchmark runs it at (257 .. 511 cached positions, head
+    dimension 128): one layer at the real shape, a long prompt, then decode steps across the end of the range,
+    teacher-forced on the oracle's ids, every logit compared."""
+    base = synth.CONFIGS[name]
+    d = base.sliced(n_layers=1, batch=B, prompt_len=S, gen_len=G, max_positions=S + G)
+    w = synth.make_weights(d, seed=5)
+    prompts = synth.make_prompts(d, seed=6)
+    want = util.oracle_run(d, util.weights_f64(w), prompts, G, "gumbel", 1.0, seed=42)
+    eng = util.make_engine(d, w, max_batch=B, max_seq_len=S + G - 1)  # the cache is filled to its last slot
+    got = util.engine_teacher_forced(eng, prompts, want["ids"], G, binding.sampling("gumbel", 1.0, 42))
+    assert eng.cache_len() == S + G - 1
+    rep = util.compare(got, want, BF16_TOL, MARGIN)
+    per_step = np.abs(got["logits"] - want["logits"]).reshape(G, -1).max(axis=1)
+    print(name, rep, "per step", per_step, flush=True)
+    eng.he_destroy()
+
+
 def test_headline_full_depth_properties():
     """All 40 layers, batch 32, prompt 256: properties that hold at any size."""
     import torch
-    import bench
     d = synth.CONFIGS["opt-13b"]
-    weights = bench.device_weights(d, torch)
+    weights = synth.device_weights(d, torch)
     stream = torch.cuda.Stream()
     eng = binding.Engine(binding.make_config(d, stream=stream.cuda_stream), weights)
     prompts = torch.from_numpy(synth.make_prompts(d, seed=9)).cuda()
@@ -94,7 +116,7 @@ def test_headline_full_depth_properties():
     for n, (i, lp, lg) in enumerate(steps):
         assert torch.equal(i, a_ids[:, n]) and torch.equal(lp, a_lp[:, n]), n
         z = lg.cpu().numpy().astype(np.float64)
-        tok, want_lp, margin = O.sample(z, "gumbel", 1.0, 7, n)
+        tok, want_lp, margin, _ = O.sample(z, "gumbel", 1.0, 7, n)
         sure = margin > 1e-3  # same logits on both sides: only log/exp rounding separates them
         assert np.array_equal(i.cpu().numpy()[sure], tok[sure])
         same = i.cpu().numpy() == tok

@@ -1,9 +1,9 @@
 """GPU parity: the HIP engine, called through the C ABI, against the CPU oracle
 on the same seeded inputs.  Tolerances: logits / log-probs max-abs 1e-4 on the
 f32 path and 2e-2 on the bf16 path; token ids bit-exact wherever the oracle's
-top-2 margin of the arg-maxed score exceeds the stated margin.  On the bf16
-path the oracle runs on the configuration's storage formats: bf16-valued
-weights and a bf16 KV cache, float64 everywhere else."""
+top-2 margin of the arg-maxed score exceeds 1e-2, one of the oracle's two best
+elsewhere.  The oracle is the unrounded definition in both cases: float64
+arithmetic on the configuration's weights (bf16 values on the bf16 path)."""
 import numpy as np
 import pytest
 from ctypes import byref as C_byref
@@ -116,19 +116,17 @@ def test_capacity_and_state_errors():
 
 # ------------------------------------------------------------------ bf16 path
 
-def _bf16_case(d, tied, G, mode, temp, impl, seed=3):
+def _bf16_case(d, tied, G, mode, temp, impl, seed=3, half_cache_diagnostic=False):
     w = synth.make_weights(d, seed=5, tied=tied)
     prompts = synth.make_prompts(d, seed=6)
-    w64 = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
-           for k, v in w.items()}
-    if tied:
-        w64["lm_head"] = w64["tok_emb"]
+    w64 = util.weights_f64(w)
     want = util.oracle_run(d, w64, prompts, G, mode, temp, seed=seed)
     eng = util.make_engine(d, w, impl=impl)
     got = util.engine_teacher_forced(eng, prompts, want["ids"], G, binding.sampling(mode, temp, seed))
-    err = float(np.abs(got["logits"] - want["logits"]).max())
-    # ids must agree wherever the oracle's margin exceeds twice the observed logit error (and 1e-2)
-    rep = util.compare(got, want, BF16_TOL, max(MARGIN, 2.0 * err + 1e-6))
+    rep = util.compare(got, want, BF16_TOL, MARGIN)
+    if half_cache_diagnostic:  # how much of the distance is the half-precision KV cache: the oracle with that one rounding
+        diag = util.oracle_run(d, w64, prompts, G, mode, temp, seed=seed, kv_dtype="f16")
+        rep["logit_err_vs_half_cache_oracle"] = float(np.abs(got["logits"] - diag["logits"]).max())
     eng.he_destroy()
     return rep
 
@@ -166,8 +164,11 @@ def test_bf16_real_layer_shapes(name, L, B, S, G):
     """Layer-truncated models at the real GEMM / head / vocabulary shapes of the benchmark configs."""
     base = synth.CONFIGS[name]
     d = base.sliced(n_layers=L, batch=B, prompt_len=S, gen_len=G, max_positions=256)
-    rep = _bf16_case(d, True, G, base.sampling, 1.0, 0, seed=42)
-    print(name, rep)
+    rep = _bf16_case(d, True, G, base.sampling, 1.0, 0, seed=42, half_cache_diagnostic=(B == 32 and name == "opt-13b"))
+    print(name, L, B, S, G, rep)
+    # measured against the unrounded definition: 13B / 6.7B layer shapes 3e-3 .. 6e-3, 1.3B 2e-3; half of the stated
+    # tolerance is kept as a regression bound so that a loss of precision shows before the tolerance is reached
+    assert rep["logit_err"] <= 1e-2
     assert rep["id_match"] > 0.9
 
 
@@ -258,14 +259,12 @@ def test_bf16_long_cache_and_generate_to_capacity():
     with pytest.raises(binding.HeError) as ei:
         eng.he_decode_step(ids[:, -1].contiguous(), binding.sampling("greedy"))
     assert ei.value.status == 3
-    w64 = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
-           for k, v in w.items()}
-    w64["lm_head"] = w64["tok_emb"]
-    want = O.generate(w64, prompts, d.gen_len, d.n_heads, forced_ids=ids.cpu().numpy(), kv_dtype="bf16")
-    sure = want["margins"] > 0.02
+    want = O.generate(util.weights_f64(w), prompts, d.gen_len, d.n_heads, forced_ids=ids.cpu().numpy())
+    sure = want["margins"] > MARGIN
     got = ids.cpu().numpy()
     assert np.array_equal(got[sure], want["ids"][sure])
     same = got == want["ids"]
+    assert (same | (got == want["second"])).all()
     assert np.abs(lp.cpu().numpy()[same] - want["logprobs"][same]).max() <= BF16_TOL
     eng.he_destroy()
 

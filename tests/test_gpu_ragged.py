@@ -1,5 +1,5 @@
 """GPU parity of the ragged entry points (left-padded prompts of different lengths, end-token
-stop) against the oracle, which runs every sequence alone on its own tokens."""
+stop) against the oracle (the unrounded definition), which runs every sequence alone on its own tokens."""
 import numpy as np
 import pytest
 
@@ -13,11 +13,7 @@ F32_TOL, BF16_TOL, MARGIN = 1e-4, 2e-2, 1e-2
 
 
 def _f64(w, tied):
-    out = {k: (v.astype(np.float64) if k != "layers" else [{n: a.astype(np.float64) for n, a in lw.items()} for lw in v])
-           for k, v in w.items()}
-    if tied:
-        out["lm_head"] = out["tok_emb"]
-    return out
+    return util.weights_f64(w)
 
 
 def _ragged_batch(d, lens, S, seed, junk=True):
@@ -51,7 +47,7 @@ def _check_teacher_forced(d, lens, S, G, tied, tol, impl=0, mode="gumbel", seed=
     w = synth.make_weights(d, seed=seed, tied=tied)
     ids, prompts, ln = _ragged_batch(d, lens, S, seed + 1)
     want = O.generate_ragged(_f64(w, tied), prompts, G, d.n_heads, mode=mode, temperature=0.9, seed=7, eps=d.ln_eps,
-                             pos_offset=d.pos_offset, kv_dtype="bf16" if d.dtype == "bf16" else "f64")
+                             pos_offset=d.pos_offset)
     eng = util.make_engine(d, w, max_batch=len(lens), max_seq_len=S + G, impl=impl)
     got = _teacher_forced(eng, ids, ln, want["ids"], G, binding.sampling(mode, 0.9, 7))
     eng.he_destroy()
@@ -62,9 +58,11 @@ def _check_teacher_forced(d, lens, S, G, tied, tol, impl=0, mode="gumbel", seed=
             err = float(np.abs(glg[b] - want["logits"][b][n]).max())
             worst = max(worst, err)
             assert err <= tol, (b, n, err)
-            if want["margins"][b, n] > max(MARGIN, 2 * err):
+            if want["margins"][b, n] > MARGIN:
                 sure += 1
                 assert gi[b] == want["ids"][b, n], (b, n)
+            else:  # a thin margin: one of the oracle's two best
+                assert gi[b] in (want["ids"][b, n], want["second"][b, n]), (b, n)
             if gi[b] == want["ids"][b, n]:
                 match += 1
                 assert abs(glp[b] - want["logprobs"][b, n]) <= tol
@@ -107,7 +105,8 @@ def _compare_generation(got_ids, got_lp, got_lens, want, tol, eos, pad):
         assert (got_ids[b, n_own:] == pad).all() and (got_lp[b, n_own:] == 0).all()
         assert (got_lp[b, :n_own] <= 0).all()
         for n in range(int(want["lens"][b])):
-            if want["margins"][b, n] <= 5 * MARGIN:
+            if want["margins"][b, n] <= MARGIN:  # a thin margin: either of the oracle's two best, and the rows part ways
+                assert got_ids[b, n] in (want["ids"][b, n], want["second"][b, n]), (b, n)
                 break
             assert got_ids[b, n] == want["ids"][b, n], (b, n)
             assert abs(got_lp[b, n] - want["logprobs"][b, n]) <= tol, (b, n)
@@ -126,10 +125,9 @@ def test_generate_ragged_with_end_token(dtype, tol, mode):
     w = synth.make_weights(d, seed=11, tied=True)
     ids, prompts, ln = _ragged_batch(d, lens, S, 12)
     w64 = _f64(w, True)
-    kvd = "bf16" if dtype == "bf16" else "f64"
-    free = O.generate_ragged(w64, prompts, G, d.n_heads, mode=mode, seed=5, eps=d.ln_eps, kv_dtype=kvd)
+    free = O.generate_ragged(w64, prompts, G, d.n_heads, mode=mode, seed=5, eps=d.ln_eps)
     eos = int(free["ids"][2, 3])  # sequence 2 ends after four tokens, others wherever they meet this token
-    want = O.generate_ragged(w64, prompts, G, d.n_heads, mode=mode, seed=5, eos_id=eos, pad_id=1, eps=d.ln_eps, kv_dtype=kvd)
+    want = O.generate_ragged(w64, prompts, G, d.n_heads, mode=mode, seed=5, eos_id=eos, pad_id=1, eps=d.ln_eps)
     assert want["lens"][2] <= 4
     eng = util.make_engine(d, w, max_batch=len(lens), max_seq_len=S + G)
     gi, glp, gl = eng.he_generate_ragged(torch.from_numpy(ids).cuda(), torch.from_numpy(ln).cuda(), G,
@@ -230,7 +228,7 @@ def test_ragged_headline_layer_shape_sampled_sequences():
     eng.he_destroy()
     w64 = _f64(w, True)
     for b in (0, 17, 31):
-        dec = O.CachedDecoder(w64, d.n_heads, d.ln_eps, d.pos_offset, "bf16")
+        dec = O.CachedDecoder(w64, d.n_heads, d.ln_eps, d.pos_offset)
         z = dec.prefill(prompts[b].reshape(1, -1))
         for n in range(G):
             err = float(np.abs(got[n][2][b] - z[0]).max())
@@ -238,8 +236,10 @@ def test_ragged_headline_layer_shape_sampled_sequences():
             assert err <= BF16_TOL
             score = z[0] + O.gumbel_noise(42, b, n, d.vocab)
             order = np.argsort(score)
-            if score[order[-1]] - score[order[-2]] > max(MARGIN, 2 * err):
+            if score[order[-1]] - score[order[-2]] > MARGIN:
                 assert got[n][0][b] == order[-1]
+            else:
+                assert got[n][0][b] in (order[-1], order[-2])
             assert abs(got[n][1][b] - O.log_softmax(z)[0, got[n][0][b]]) <= BF16_TOL
             if n + 1 < G:
                 z = dec.step(got[n][0][b:b + 1])

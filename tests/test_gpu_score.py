@@ -35,8 +35,7 @@ def _score_case(d, B, T, tied, impl=0, seed=3, max_batch=None, max_seq_len=None)
     assert eng.cache_len() == 0
     got = got.cpu().numpy()
     eng.he_destroy()
-    want = O.score(_f64(w, tied), ids, d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset,
-                   kv_dtype="bf16" if d.dtype == "bf16" else "f64")
+    want = O.score(_f64(w, tied), ids, d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset)
     assert got.shape == want.shape == (B, T - 1)
     return float(np.abs(got - want).max())
 
@@ -118,7 +117,7 @@ def test_score_headline_layer_shape_sampled_sequences():
     eng.he_destroy()
     w64 = _f64(w, True)
     for b in (0, 17, 31):
-        want = O.score(w64, ids[b:b + 1], d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset, kv_dtype="bf16")
+        want = O.score(w64, ids[b:b + 1], d.n_heads, eps=d.ln_eps, pos_offset=d.pos_offset)
         err = float(np.abs(got[b] - want[0]).max())
         print("sequence", b, "score err", err, flush=True)
         assert err <= BF16_TOL

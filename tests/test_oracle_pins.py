@@ -311,23 +311,32 @@ def test_gumbel_max_samples_from_softmax():
         counts = np.zeros(V)
         zz = np.tile(z, (1, 1))
         for n in range(N):
-            tok, lp, _ = O.sample(zz, "gumbel", temp, seed=77, n=n)
+            tok, lp, _, _ = O.sample(zz, "gumbel", temp, seed=77, n=n)
             counts[tok[0]] += 1
         chi2 = ((counts - N * p) ** 2 / (N * p)).sum()
         assert chi2 < 40.0, chi2  # 11 dof: P(chi2 > 40) ~ 4e-5
     # reported log-prob is the untempered log-softmax at the chosen token
-    tok, lp, _ = O.sample(zz, "gumbel", 0.7, seed=1, n=0)
+    tok, lp, _, _ = O.sample(zz, "gumbel", 0.7, seed=1, n=0)
     assert abs(lp[0] - (z[tok[0]] - np.log(np.exp(z).sum()))) < 1e-12
 
 
 def test_greedy_ties_go_to_lowest_index_and_margin():
     z = np.array([[0.0, 2.0, 2.0, 1.0], [5.0, 1.0, 4.5, 0.0]])
-    tok, lp, m = O.sample(z, "greedy", 1.0, 0, 0)
+    tok, lp, m, second = O.sample(z, "greedy", 1.0, 0, 0)
     assert tok.tolist() == [1, 0]
     np.testing.assert_allclose(m, [0.0, 0.5])
+    assert second.tolist() == [2, 2]  # the runner-up: the other tied entry / the second-largest score
     # tiny temperature: Gumbel sampling degenerates to greedy
-    tok2, _, _ = O.sample(z[1:], "gumbel", 1e-6, 3, 0)
+    tok2, _, _, _ = O.sample(z[1:], "gumbel", 1e-6, 3, 0)
     assert tok2.tolist() == [0]
+    # the runner-up of a Gumbel draw is the arg-max once the winner is struck out
+    rng = np.random.default_rng(4)
+    zz = rng.standard_normal((3, 50))
+    tok3, _, m3, sec3 = O.sample(zz, "gumbel", 0.8, seed=9, n=2)
+    for b in range(3):
+        sc = zz[b] / 0.8 + O.gumbel_noise(9, b, 2, 50)
+        order = np.argsort(-sc)
+        assert (tok3[b], sec3[b]) == (order[0], order[1]) and abs(m3[b] - (sc[order[0]] - sc[order[1]])) < 1e-12
 
 
 def test_generate_is_prefill_plus_g_minus_1_steps_and_teacher_forcing():
@@ -346,7 +355,7 @@ def test_generate_is_prefill_plus_g_minus_1_steps_and_teacher_forcing():
     np.testing.assert_allclose(f2["logits"][4], full[:, -1], atol=1e-10)
 
 
-# ---------------------------------------------------------------- bf16 KV cache format
+# ---------------------------------------------------------------- storage formats: bf16 weights, the half-cache diagnostic
 
 def test_round_bf16_against_torch_and_ties():
     rng = np.random.default_rng(9)
@@ -363,18 +372,39 @@ def test_round_bf16_against_torch_and_ties():
     np.testing.assert_array_equal(O.round_bf16(y), y)  # idempotent
 
 
-def test_bf16_cache_cached_equals_cache_free_and_differs_from_f64():
+def test_round_f16_against_torch_and_ties():
+    rng = np.random.default_rng(10)
+    x = rng.standard_normal(20000) * np.exp(rng.uniform(-20, 12, 20000))  # subnormal halves up to overflow
+    want = torch.from_numpy(x).to(torch.float16).to(torch.float64).numpy()  # float64 -> half is one rounding
+    np.testing.assert_array_equal(O.round_f16(x), want)
+    ulp = 2.0 ** -10
+    assert O.round_f16(np.array([1.0 + ulp / 2]))[0] == 1.0              # tie: to the even neighbour
+    assert O.round_f16(np.array([1.0 + 3 * ulp / 2]))[0] == 1.0 + 2 * ulp
+    assert O.round_f16(np.array([1.0 + ulp / 2 + 1e-12]))[0] == 1.0 + ulp
+    assert O.round_f16(np.array([2.0 ** -24 * 2.5]))[0] == 2.0 ** -24 * 2  # subnormal spacing 2^-24, tie to even
+    assert O.round_f16(np.array([65519.0]))[0] == 65504.0 and np.isinf(O.round_f16(np.array([65520.0]))[0])
+    y = O.round_f16(rng.standard_normal(1000))
+    np.testing.assert_array_equal(O.round_f16(y), y)  # idempotent
+    # every bf16 value of magnitude 2^-14 .. 65504 is a half exactly (8 significant bits into 11)
+    b = O.round_bf16(rng.standard_normal(5000) * np.exp(rng.uniform(-9, 10, 5000)))
+    b = b[(np.abs(b) >= 2.0 ** -14) & (np.abs(b) <= 65504)]
+    np.testing.assert_array_equal(O.round_f16(b), b)
+
+
+def test_half_cache_diagnostic_cached_equals_cache_free_and_differs_from_the_definition():
     d = tiny_dims(n_layers=2, hidden=32, n_heads=4)
     w = synth.make_weights(d, seed=2, std=0.3)
     p = synth.make_prompts(d, seed=3, batch=2, prompt_len=6)
-    out = O.generate(w, p, 4, d.n_heads, kv_dtype="bf16")
+    out = O.generate(w, p, 4, d.n_heads, kv_dtype="f16")
     seq = np.concatenate([p, out["ids"]], axis=1)
-    full = O.forward_full(w, seq[:, :-1], d.n_heads, kv_dtype="bf16")
+    full = O.forward_full(w, seq[:, :-1], d.n_heads, kv_dtype="f16")
     for n in range(4):
         np.testing.assert_allclose(out["logits"][n], full[:, 5 + n], atol=1e-10)
     exact = O.forward_full(w, seq[:, :-1], d.n_heads)
     diff = np.abs(full - exact).max()
-    assert 1e-5 < diff < 0.1  # the cache format matters, by about bf16's precision
+    assert 1e-6 < diff < 0.02  # the cache format matters, by about half precision
+    with pytest.raises(ValueError):
+        O.forward_full(w, seq[:, :-1], d.n_heads, kv_dtype="bf16")
 
 
 # ---------------------------------------------------------------- scoring pass
@@ -546,6 +576,9 @@ def test_merge_lora_against_float64_and_the_two_branch_form():
     # equal to rounding the exact sum wherever that sum is not within float32 noise of a rounding boundary
     direct = O.round_bf16(exact)
     assert (got == direct).mean() > 0.99
+    np.testing.assert_array_equal(O.merge_lora(W, A, B, s, exact=True), direct)  # the plain definition, rounded once
+    step = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(direct), 1e-30))) - 7)     # one bf16 step at each value
+    assert np.all(np.abs(got - direct) <= step)
     # no adapter, or a zero scale, leaves the weights as they are
     np.testing.assert_array_equal(O.merge_lora(W, A[:0], B[:, :0], s), W.astype(np.float64))
     np.testing.assert_array_equal(O.merge_lora(W, A, B, 0.0), W.astype(np.float64))

@@ -44,7 +44,7 @@ def test_static_scratch_decode_step_matches_the_allocating_one():
     # and the static steps of the smaller batch against the oracle, teacher-forced on the same ids, to the bf16 bar
     from oracle import opt_oracle as O
     forced = np.stack(feeds + [feeds[0]], axis=1)
-    ref = O.generate(w, prompts, 4, d.n_heads, mode="gumbel", temperature=1.0, seed=7, forced_ids=forced, kv_dtype="bf16")
+    ref = O.generate(w, prompts, 4, d.n_heads, mode="gumbel", temperature=1.0, seed=7, forced_ids=forced)
     for n in range(4):
         assert np.abs(got[n][2] - ref["logits"][n]).max() <= 2e-2, n
         sure = ref["margins"][:, n] > 1e-2
