@@ -22,25 +22,27 @@ namespace {
 // cores busy (one workgroup per CU left them idle 40-50 % of the time, and a 256-row tile that moves a
 // quarter less operand data per flop, but fits only once, still 39 %).
 
-constexpr int TN = 256, TM = 128;
+constexpr int TN = 256;
 constexpr int TNB = TN / 32;   // 32-row operand blocks on the n side
-constexpr int MW = 2;          // 32-row m blocks per wavefront
-template <int PAIR> struct TiledShape {
+// MW: 32-row m blocks per wavefront (2: a 128-row m tile; 4: a 256-row m tile whose 16 accumulator tiles take a
+// wavefront's whole register file, so one workgroup per CU)
+template <int PAIR, int MW> struct TiledShape {
     static constexpr int TMB = 2 * MW;                 // 32-row operand blocks on the m side
     static constexpr int TMR = TMB * 32;               // rows of the m tile
     static constexpr int KSTAGE = PAIR ? 1 : 2;        // k-blocks (16 values of k each) per stage
-    static constexpr int NSTG = PAIR ? 5 : 4;          // ring depth
+    static constexpr int NSTG = PAIR ? (MW == 4 ? 8 : 5) : 4;  // ring depth
     static constexpr int STAGE_BLOCKS = (TNB + TMB) * KSTAGE;
 };
 
-template <int MODE, int PAIR>
-__global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
+template <int MODE, int PAIR, int MW>
+__global__ __launch_bounds__(256, (PAIR && MW == 2) ? 2 : 1) void gemm_tiled_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xhi,
                                                          int KB, int NT32, int MT32,
                                                          int tiles_n, int tiles_m, int ksplit, Epi p) {
     // ring[stage][block][lane]; blocks of a stage: W tile i, k-block j at KSTAGE i + j; X tile i at KSTAGE (TNB + i) + j
-    constexpr int TMB = TiledShape<PAIR>::TMB, TMR = TiledShape<PAIR>::TMR, NSTG = TiledShape<PAIR>::NSTG;
-    constexpr int KSTAGE = TiledShape<PAIR>::KSTAGE;
-    constexpr int STAGE_BLOCKS = TiledShape<PAIR>::STAGE_BLOCKS;
+    typedef TiledShape<PAIR, MW> Shape;
+    constexpr int TMB = Shape::TMB, TMR = Shape::TMR, NSTG = Shape::NSTG;
+    constexpr int KSTAGE = Shape::KSTAGE;
+    constexpr int STAGE_BLOCKS = Shape::STAGE_BLOCKS;
     __shared__ u32x4 ring[NSTG][STAGE_BLOCKS][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // XCD-aware order: consecutive workgroups land on different XCDs, so give each XCD a
@@ -236,6 +238,209 @@ __global__ __launch_bounds__(256, PAIR ? 2 : 1) void gemm_tiled_kernel(const u32
         }
 }
 
+// ----------------------------------------------------------------- 256 x 256 tiles (prompt and scoring passes)
+//
+// With one half term per activation the 256 x 128 tile above no longer keeps the matrix cores busy: it pulls
+// 12 KiB of operands out of L2 for every 32 matrix instructions, and at eight rounds of 512 tiles on 256 CUs that
+// is 10 TB/s -- what the L2s deliver.  This kernel takes 16 KiB for 64: a 256 x 256 tile per workgroup, four
+// wavefronts with a 128 x 128 sub-tile each (16 accumulator tiles: the whole accumulator file, so one workgroup
+// per CU).  Nothing else runs on a CU while its four wavefronts sit at a barrier or issue loads, so the schedule is
+// laid out by hand: a stage is two k-blocks (32 KiB, ring of four); LDS reads and global -> LDS copies are dealt out
+// one per pair of matrix instructions, each read at least nine matrix instructions ahead of its first use.  Measured
+// on the 8160 x 20480 x 5120 product (loop only): matrix instructions alone on random operands 1015 us (the clock
+// drops under data toggling), + LDS reads 1082 us, + copies 1310 us = 1.31 PFLOP/s; with reads and copies issued in
+// bursts after the barrier, as a compiler left to itself schedules them, 1690 us.
+constexpr int BN = 256, BM = 256;  // tile of the big kernel
+constexpr int BSTAGES = 4;
+
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ X,
+                                                               const u32x4* __restrict__ bias8, int KB, int NT32, int MT32,
+                                                               int tiles_n, int tiles_m, int ksplit, Epi p) {
+    // ring[stage][block][lane]; blocks of a stage: W row-tile i, k-block j at 2 i + j; X row-tile i at 16 + 2 i + j
+    __shared__ u32x4 ring[BSTAGES][32][64];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int nblk = tiles_n * tiles_m;
+    const int nitem = nblk * ksplit;
+    const int per_xcd = (nitem + 7) / 8;
+    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;  // an XCD gets a contiguous run of tiles
+    if (item >= nitem) return;
+    const int lin = item % nblk, ks = item / nblk;  // k range after k range
+    constexpr int GROUP = 4;  // m-tiles per super-row: the 32 tiles an XCD works on at once share 4 X panels and 8 W panels
+    const int gsize = GROUP * tiles_n;
+    const int g = lin / gsize, first_m = g * GROUP;
+    const int gm = min(GROUP, tiles_m - first_m);
+    const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 128 (m) sub-tile
+    const int cur_len = epilogue_len<MODE>(p);
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{};
+
+    const int nst_all = KB / 2;  // KB is even (K % 32 == 0)
+    const int st0 = (int)((long)ks * nst_all / ksplit);
+    const int nstage = (int)((long)(ks + 1) * nst_all / ksplit) - st0;
+    // this wavefront copies W row-tiles 2w, 2w+1 and X row-tiles 2w, 2w+1 of every stage (tiles past the matrix: the last one)
+    const u32x4* src[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        src[i] = Wp + ((size_t)min(tn * 8 + wave * 2 + i, NT32 - 1) * KB + (size_t)st0 * 2) * 64;
+        src[2 + i] = X + ((size_t)min(tm * 8 + wave * 2 + i, MT32 - 1) * KB + (size_t)st0 * 2) * 64;
+    }
+    // copy q (0..7) of a stage: x = q / 4 picks W or X, i = (q / 2) % 2 the row-tile, j = q % 2 the k-block
+    auto copy1 = [&](int st, int q) {
+        u32x4 (*slot)[64] = ring[st & (BSTAGES - 1)];
+        const int x = q >> 2, i = (q >> 1) & 1, j = q & 1;
+        load_block_to_lds(src[2 * x + i] + ((size_t)st * 2 + j) * 64 + lane, &slot[16 * x + (wave * 2 + i) * 2 + j][0]);
+    };
+    auto issue = [&](int st) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) copy1(st, q);
+    };
+    constexpr int kLoads = 8;  // copies per wavefront and stage
+    struct Ops { u32x4 a[4], b[4]; };
+    // LDS read q (0..7) of a k-block, in the order the matrix instructions below first need the operands:
+    // a0, b0, b1, b2, b3, a1, a2, a3
+    auto read1 = [&](Ops& o, int st, int j, int q) {
+        u32x4 (*slot)[64] = ring[st & (BSTAGES - 1)];
+        constexpr int ord[8] = {0, 4, 5, 6, 7, 1, 2, 3};
+        const int idx = ord[q];
+        if (idx < 4) o.a[idx] = slot[(wn * 4 + idx) * 2 + j][lane];
+        else o.b[idx - 4] = slot[16 + (wm * 4 + idx - 4) * 2 + j][lane];
+    };
+    auto read_ops = [&](Ops& o, int st, int j) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) read1(o, st, j, q);
+    };
+    // matrix instruction n (0..15) of a k-block: accumulator tile (n / 4, n % 4)
+    auto mma1 = [&](const Ops& o, int n) { acc[n >> 2][n & 3] = mfma_f16(o.a[n >> 2], o.b[n & 3], acc[n >> 2][n & 3]); };
+    auto mma_all = [&](const Ops& o) {
+#pragma unroll
+        for (int n = 0; n < 16; ++n) mma1(o, n);
+    };
+#pragma unroll
+    for (int st = 0; st < BSTAGES - 1; ++st)
+        if (st < nstage) issue(st);
+    if (nstage >= 3) wait_vmcnt<2 * kLoads>();
+    else if (nstage == 2) wait_vmcnt<kLoads>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    Ops opa, opb;
+    read_ops(opa, 0, 0);
+    int s = 0;
+    // Steady state: stages s+1 and s+2 are in flight, stage s+3 goes into the slot stage s-1 has left.  Every pair of
+    // matrix instructions is followed by one LDS read of the operand set used next (sixteen instructions later at
+    // the earliest use, nine at the latest) and, in the stage's second half, by one global -> LDS copy; scheduling
+    // barriers keep that order.  The workgroup barrier is the bare instruction: what it orders are the copies,
+    // which the wait before it covers -- the LDS reads in flight across it belong to the stage in use, not to the
+    // slot about to be refilled (a fence would wait for them).
+    for (; s + 3 < nstage; ++s) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            mma1(opa, 2 * q);
+            mma1(opa, 2 * q + 1);
+            read1(opb, s, 1, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_vmcnt<kLoads>();  // this wavefront's copies of stage s+1 have landed ...
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // ... and everybody's; everybody is done with stage s-1
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            mma1(opb, 2 * q);
+            mma1(opb, 2 * q + 1);
+            read1(opa, s + 1, 0, q);
+            copy1(s + 3, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    for (; s < nstage; ++s) {  // the last three stages: nothing left to request
+        read_ops(opb, s, 1);
+        mma_all(opa);
+        if (s + 1 < nstage) {
+            if (s + 2 < nstage) wait_vmcnt<kLoads>();
+            else wait_vmcnt<0>();
+            __syncthreads();
+            read_ops(opa, s + 1, 0);
+        }
+        mma_all(opb);
+    }
+    // Epilogue.  The CU runs nothing else meanwhile, so it is written out per mode with everything that depends on
+    // the row alone (sequence, cache position, row base address) computed once per 32-row block and everything
+    // that depends on the column alone wave-uniform (the generic per-quad form recomputes both, with run-time
+    // integer divisions, for each of a lane's 64 quads: 22 us per tile for FC1, 44 us for QKV, against 130 us of
+    // matrix instructions).  N is a multiple of 32 here, so a 32-column block is inside or outside as a whole.
+    const int hh = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = tm * BM + (wm * 4 + j) * 32 + (lane & 31);
+        if (m >= p.M) continue;
+        size_t row = 0;       // MODE_STORE: float index of (m, 4 hh); BIAS_RELU: uint2 index; QKV: float index into q
+        size_t kvrow = 0;     // QKV: half index of (sequence, head 0, position, 4 hh) inside one (layer, k|v) plane
+        bool append = true;   // QKV: the row is a token (not padding): its key and value go into the cache
+        if (MODE == MODE_STORE) {
+            row = (size_t)ks * p.out_split + (size_t)m * p.N + 4 * hh;
+        } else if (MODE == MODE_BIAS_RELU) {
+            row = ((size_t)(m >> 5) * (p.N >> 4) * 64 + (m & 31)) * 2 + hh;
+        } else {
+            row = (size_t)m * p.H + 4 * hh;
+            const int b = m / p.S, r = m - b * p.S;
+            int t = cur_len + r;
+            if (cur_len < 0) {  // sequences of different lengths; padding rows append nothing
+                const int tr = r - row_pad(p.st, b);
+                append = tr >= 0;
+                t = seq_len(p.st, b) + tr;
+            }
+            kvrow = ((size_t)b * p.n_heads * p.max_seq + t) * p.d + 4 * hh;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n32 = tn * BN + (wn * 4 + i) * 32;  // wave-uniform
+            if (n32 >= p.N) continue;
+            if (MODE == MODE_STORE) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(p.out + row + n32 + 8 * q) =
+                        make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+            } else if (MODE == MODE_BIAS_RELU) {
+                uint2* ob = reinterpret_cast<uint2*>(p.out_blocks) + row + (size_t)(n32 >> 4) * 128;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const u32x4 b8 = bias8[(n32 >> 3) + q];  // wave-uniform address: a scalar load
+                    const uint2 bb = hh ? make_uint2(b8.z, b8.w) : make_uint2(b8.x, b8.y);
+                    const float v0 = fmaxf(acc[i][j][q * 4 + 0] + bf_lo(bb.x), 0.f), v1 = fmaxf(acc[i][j][q * 4 + 1] + bf_hi(bb.x), 0.f);
+                    const float v2 = fmaxf(acc[i][j][q * 4 + 2] + bf_lo(bb.y), 0.f), v3 = fmaxf(acc[i][j][q * 4 + 3] + bf_hi(bb.y), 0.f);
+                    ob[(q >> 1) * 128 + (q & 1) * 64] = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                }
+            } else {
+                const int part = n32 >= 2 * p.H ? 2 : (n32 >= p.H ? 1 : 0);  // query, key or value columns (uniform)
+                half_t* kvcol = nullptr;
+                if (part) {
+                    const int c32 = n32 - part * p.H, head = c32 / p.d;
+                    kvcol = p.kv + (((size_t)(p.layer * 2 + (part - 1)) * p.max_batch) * p.n_heads + head) * p.max_seq * (size_t)p.d +
+                            (c32 - head * p.d);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const u32x4 b8 = bias8[(n32 >> 3) + q];
+                    const uint2 bb = hh ? make_uint2(b8.z, b8.w) : make_uint2(b8.x, b8.y);
+                    const float v0 = acc[i][j][q * 4 + 0] + bf_lo(bb.x), v1 = acc[i][j][q * 4 + 1] + bf_hi(bb.x);
+                    const float v2 = acc[i][j][q * 4 + 2] + bf_lo(bb.y), v3 = acc[i][j][q * 4 + 3] + bf_hi(bb.y);
+                    if (!part)
+                        *reinterpret_cast<float4*>(p.out + row + n32 + 8 * q) =
+                            make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
+                    else if (append)
+                        *reinterpret_cast<uint2*>(kvcol + kvrow + 8 * q) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                }
+            }
+        }
+    }
+}
+
 // One wavefront per scored row: log-sum-exp over the vocabulary slices in slice order, then
 // out[b][t] = z[next token] - lse  (out is [B][S-1]; the last position of a sequence scores nothing).
 __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restrict__ stats, const float* __restrict__ tgt,
@@ -256,22 +461,47 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restr
 }
 
 
+// Many rows (a prompt or scoring pass): 256 x 256 tiles, one workgroup per CU, once there are enough of them to
+// give every CU one.  HE_TILED_SHAPE (tuning aid, read once): 0 = never.
+static int big_tile_shape() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("HE_TILED_SHAPE");
+        v = e ? atoi(e) : 1;
+    }
+    return v;
+}
+static bool use_big_tile(int M, int N) {
+    return big_tile_shape() != 0 && M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
+}
+
 template <int MODE>
-void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p,
-                  int ksplit = 1) {
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p, int ksplit = 1) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
+    // (the scoring head's epilogue keeps a soft-max over all of a wavefront's accumulators: it does not fit next to 16 of them)
+    const bool big = MODE != MODE_SCORE && use_big_tile(M, N);
+    const int TM = big ? 256 : 128;
     const int tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
     const int nitem = tiles_n * tiles_m * ksplit;
     const int grid = ((nitem + 7) / 8) * 8;
+    if constexpr (MODE != MODE_SCORE) {
+        if (big) {
+            // (the bias through a pointer of its own: declared never to alias the outputs, its values can be fetched
+            // with scalar loads, which do not queue behind the epilogue's stores)
+            gemm_tiled256_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias, KB, NT32,
+                                                            MT32, tiles_n, tiles_m, ksplit, p);
+            return;
+        }
+    }
     // two workgroups per CU once there are that many (their k ranges must hold an even number of k-blocks
     // each: that ring alternates two register sets)
     const bool pair = nitem >= 2 * num_cus() && KB % (2 * ksplit) == 0;
     if (pair)
-        gemm_tiled_kernel<MODE, 1><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32,
-                                                        MT32, tiles_n, tiles_m, ksplit, p);
+        gemm_tiled_kernel<MODE, 1, 2><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32, MT32, tiles_n,
+                                                           tiles_m, ksplit, p);
     else
-        gemm_tiled_kernel<MODE, 0><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32,
-                                                        MT32, tiles_n, tiles_m, ksplit, p);
+        gemm_tiled_kernel<MODE, 0, 2><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, KB, NT32, MT32, tiles_n,
+                                                           tiles_m, ksplit, p);
 }
 
 // After a k-split MODE_STORE GEMM whose epilogue needs the whole sum: adds the partial sums in split
@@ -303,7 +533,7 @@ void bf16_gemm_tiled(hipStream_t s, int mode, const void* Wp, const void* Xhi, i
 }
 
 int bf16_tiled_ksplit(int M, int N, int K) {
-    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM), stages = K / 16 / TiledShape<0>::KSTAGE;
+    const int tiles = ((N + TN - 1) / TN) * ((M + 127) / 128), stages = K / 16 / TiledShape<0, 2>::KSTAGE;
     int ks = num_cus() / tiles;
     if (ks > 8) ks = 8;
     while (ks > 1 && stages / ks < 8) --ks;  // keep the ring worth filling
@@ -315,13 +545,14 @@ int bf16_tiled_ksplit(int M, int N, int K) {
 // for the work of two and a half).  Cutting every tile into ks k ranges makes the rounds shorter and the
 // last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
-    const long slots = 2L * num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + TM - 1) / TM);
+    const bool big = use_big_tile(M, N);
+    const long slots = (big ? 1L : 2L) * num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + (big ? 255 : 127)) / (big ? 256 : 128));
     const int KB = K / 16;
     if (tiles < slots || KB % 2) return 1;
     int best = 1;
     double best_cost = (double)((tiles + slots - 1) / slots);  // in units of one full-K tile
     for (int ks = 2; ks <= 4; ++ks) {
-        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<1>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
+        if (KB % (2 * ks) || KB / ks < 8 * TiledShape<1, 2>::NSTG || (size_t)ks * M * N > capacity_floats) continue;
         const double cost = (double)((tiles * ks + slots - 1) / slots) / ks * (1.0 + 0.02 * ks);
         if (cost < 0.95 * best_cost) { best_cost = cost; best = ks; }
     }
