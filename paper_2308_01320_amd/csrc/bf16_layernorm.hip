@@ -268,9 +268,24 @@ __global__ __launch_bounds__(256) void wvec_kernel(const u32x4* __restrict__ Wp,
     }
 }
 
+// Rows b*S + S-1 (each sequence's last prompt row) of two [B*S][H] float arrays -> rows b of two [B][H] arrays.
+__global__ __launch_bounds__(256) void gather_last_rows_kernel(const float* __restrict__ r, const float* __restrict__ q,
+                                                               float* __restrict__ r_out, float* __restrict__ q_out, int S,
+                                                               int H) {
+    const size_t src = ((size_t)blockIdx.x * S + S - 1) * H, dst = (size_t)blockIdx.x * H;
+    for (int i = threadIdx.x; i < H / 4; i += 256) {
+        reinterpret_cast<float4*>(r_out + dst)[i] = reinterpret_cast<const float4*>(r + src)[i];
+        reinterpret_cast<float4*>(q_out + dst)[i] = reinterpret_cast<const float4*>(q + src)[i];
+    }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
+
+void bf16_gather_last_rows(hipStream_t s, const float* r, const float* q, float* r_out, float* q_out, int B, int S, int H) {
+    gather_last_rows_kernel<<<B, 256, 0, s>>>(r, q, r_out, q_out, S, H);
+}
 
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,

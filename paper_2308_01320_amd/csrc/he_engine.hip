@@ -44,6 +44,7 @@ struct he_engine {
     float *ln_stats = nullptr; // per-column-group mean / squared deviations of the residual rows
     int* ln_counters = nullptr;
     float *score_stats = nullptr, *score_tgt = nullptr;  // scoring pass: soft-max partials per row and vocabulary slice
+    float* tail_buf = nullptr;  // prompt pass: residual and query rows of each sequence's last token, 2 x [max_batch][H]
 
     // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
     hipGraphExec_t step_graph = nullptr;
@@ -90,7 +91,7 @@ namespace {
 struct Sizes {
     size_t kv, rowsH, rowsF, xf, logits, gen, total;
     // bf16 path
-    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx, cvec, ln_stats, ln_counters, score_stats;
+    size_t tiled_layer, tiled_lm, ablk, hblk, xfblk, part, stats, stats_idx, cvec, ln_stats, ln_counters, score_stats, tail;
 };
 
 bool is_fast(const he_config& c) { return c.dtype == HE_BF16 && c.impl == 0; }
@@ -162,7 +163,8 @@ Sizes sizes_of(const he_config& c) {
     s.ln_stats = mtiles * (H / 32) * 32 * 2 * sizeof(float) + 1024;  // at most one group per 32 columns
     s.ln_counters = mtiles * (H / 32) * sizeof(int);
     s.score_stats = rows * bf16_score_parts(c.vocab) * 2 * sizeof(float);
-    s.total += s.cvec + s.ln_stats + s.ln_counters + s.score_stats + s.gen;
+    s.tail = (size_t)2 * c.max_batch * H * sizeof(float);
+    s.total += s.cvec + s.ln_stats + s.ln_counters + s.score_stats + s.gen + s.tail;
     if (c.weights_fp8) {  // E4M3 units (half the bytes), row scales, one layer of bf16 scratch
         const size_t q8_layer = fp8_units_bytes(3 * H, H) + fp8_units_bytes(H, H) + fp8_units_bytes(F, H) + fp8_units_bytes(H, F);
         s.total += (size_t)c.n_layers * (q8_layer + (size_t)(5 * H + F) * sizeof(float)) + s.tiled_layer + s.tiled_lm +
@@ -242,13 +244,14 @@ he_engine::Tiled layer_blocks(he_engine* e, int l) {
     return e->scratch;
 }
 
-// bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  Only the
-// K/V cache is wanted from these rows (the last prompt token takes the decode-shaped pass
-// below), so the final layer stops once its keys and values are stored.
+// bf16 path, prompt rows: Sp tokens per sequence through the tiled MFMA GEMMs.  From all but each sequence's
+// last token only the K/V cache is wanted, so the final layer stops once its keys and values are stored (the
+// last tokens' rows are then finished by pass_last_token_bf16, or, where that does not apply, the last token
+// is left out here and takes the whole decode-shaped pass).
 // With `full` (the scoring pass) every layer is completed and the last FC2's output is left
 // pending, as k-split partial sums plus *pend_bias, for the final LayerNorm.
 void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int Sp, bool full = false,
-                     const void** pend_bias = nullptr, int* pend_ksplit = nullptr) {
+                     const void** pend_bias = nullptr, int* pend_ksplit = nullptr, int advance = -1) {
     const he_config& c = e->cfg;
     hipStream_t s = e->stream;
     const int M = B * Sp, H = c.hidden, F = c.ffn;
@@ -282,8 +285,9 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     }
     if (pend_bias) *pend_bias = pend_b;
     if (pend_ksplit) *pend_ksplit = pend_ks;
-    launch_advance_state(s, e->st, Sp, 0);
-    e->cur_len += Sp;
+    if (advance < 0) advance = Sp;  // (the caller that finishes the last token itself advances by one row less)
+    launch_advance_state(s, e->st, advance, 0);
+    e->cur_len += advance;
 }
 
 // Where the vectors W gamma (c1) and W beta (c2) of the GEMMs that follow a LayerNorm live.
@@ -395,6 +399,81 @@ void pass_decode_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, 
     e->step += 1;
 }
 
+// The end of a prompt pass whose tiled GEMMs took every token up to the last layer's QKV projection: what is
+// left of that layer, for each sequence's LAST token only -- attention over the cache, out-projection, FC1, FC2
+// on the weight-streaming kernels -- then the LM head and sampling.  (The last token used to take the whole
+// decode-shaped pass, streaming all layers' weights once more: one decode step's time per prompt pass.)
+// On entry the device state still counts the last token as not cached (cur_len = S - 1), as in a decode step
+// after its QKV projection.
+void pass_last_token_bf16(he_engine* e, int B, int S, int32_t* ids_out, float* lp_out, int out_stride, int out_at_step,
+                          float* d_logits_opt) {
+    const he_config& c = e->cfg;
+    hipStream_t s = e->stream;
+    const int H = c.hidden, F = c.ffn, l = c.n_layers - 1;
+    bf16_gemm_args base;
+    base.st = e->st; base.S = 1; base.H = H; base.n_heads = c.n_heads; base.max_batch = c.max_batch;
+    base.max_seq = c.max_seq_len;
+    int gw1, ks1, gw2, ks2;
+    if (e->w8) {
+        bf16_store_plan_w8(H, H, e->part_floats, &gw1, &ks1);
+        bf16_store_plan_w8(H, F, e->part_floats, &gw2, &ks2);
+    } else {
+        bf16_store_plan(B, H, H, e->part_floats, &gw1, &ks1);
+        bf16_store_plan(B, H, F, e->part_floats, &gw2, &ks2);
+    }
+    const size_t split = (size_t)B * H;
+    float *r_last = e->tail_buf, *q_last = e->tail_buf + (size_t)c.max_batch * H;
+    bf16_gather_last_rows(s, e->resid, e->qbuf, r_last, q_last, B, S, H);
+    const he_layer_weights& lw = e->layers[l];
+    const he_engine::Tiled& tw = e->tiled[l];
+    const Scales sc = e->w8 ? scales_of(e, l) : Scales{nullptr, nullptr, nullptr, nullptr};
+    auto fold = [&](bf16_gemm_args& a, int gw, const CVec& cv) {
+        a.ln_stats = e->ln_stats; a.ln_gw = gw; a.ln_groups = (H + gw - 1) / gw; a.ln_cols = H; a.ln_eps = c.ln_eps;
+        a.c1 = cv.c1; a.c2 = cv.c2;
+    };
+    auto store_ln = [&](bf16_gemm_args& a, const void* bias, const void* gamma, void* blk) {
+        a.out = e->part; a.out_split = split; a.out_capacity = e->part_floats; a.bias = bias; a.resid = r_last; a.gamma = gamma;
+        a.out_blocks = blk; a.stats_out = e->ln_stats; a.counters = e->ln_counters;
+    };
+    {
+        LaunchTimer t(e, HE_K_ATTENTION);
+        bf16_attn(s, q_last, e->kv, e->oblk, e->st, B, 1, l, H, c.n_heads, c.max_batch, c.max_seq_len);
+    }
+    bf16_gemm_args a = base;
+    store_ln(a, lw.bo, lw.ln2_g, e->ablk);
+    a.wscale = sc.wo;
+    {
+        LaunchTimer t(e, HE_K_OUT_PROJ);
+        bf16_gemm_skinny(s, EPI_STORE_LN, tw.wo, e->oblk, B, H, H, ks1, a);
+    }
+    a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
+    fold(a, gw1, cvec_fc1(e, l));
+    a.wscale = sc.w1;
+    {
+        LaunchTimer t(e, HE_K_FC1);
+        bf16_gemm_skinny(s, EPI_BIAS_RELU, tw.w1, e->ablk, B, F, H, 1, a);
+    }
+    a = base;
+    store_ln(a, lw.b2, e->w.lnf_g, e->xfblk);
+    a.wscale = sc.w2;
+    {
+        LaunchTimer t(e, HE_K_FC2);
+        bf16_gemm_skinny(s, EPI_STORE_LN, tw.w2, e->hblk, B, H, F, ks2, a);
+    }
+    {
+        LaunchTimer t(e, HE_K_LM_HEAD);
+        a = base;
+        fold(a, gw2, cvec_lm(e));
+        bf16_lm_head(s, e->lm_tiled, e->xfblk, B, c.vocab, H, e->st, d_logits_opt, e->stats, e->stats_idx, ids_out, lp_out,
+                     out_stride, out_at_step, e->cur_ids, &a);
+    }
+    { LaunchTimer t(e, HE_K_EMPTY); }
+    if (e->ragged_gen) launch_ragged_post(s, e->st, ids_out, lp_out, e->cur_ids, out_stride, B);
+    launch_advance_state(s, e->st, 1, 1);
+    e->cur_len += 1;
+    e->step += 1;
+}
+
 // The same pass for more than 64 sequences (more than 32 with 8-bit weights): the rows no longer fit the
 // weight-streaming kernels, so the GEMMs are the prompt-pass tiles (weights shared through LDS by all rows), cut along k until they fill the
 // chip; LayerNorms are kernels of their own again and add the partial sums.
@@ -473,6 +552,13 @@ bool wide_decode(const he_engine* e, int B) { return B > 64 || (B > 32 && e->w8)
 
 he_status run_forward_bf16(he_engine* e, const int32_t* d_ids, int B, int S, int32_t* ids_out, float* lp_out,
                            int out_stride, int out_at_step, float* d_logits_opt) {
+    if (S > 1 && e->cfg.n_layers > 0 && !wide_decode(e, B)) {
+        // every prompt token through the tiled GEMMs up to the last layer's keys and values, then the rest of
+        // that layer for the last tokens alone
+        pass_tiled_bf16(e, d_ids, S, B, S, false, nullptr, nullptr, S - 1);
+        pass_last_token_bf16(e, B, S, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
+        return check_hip(e, hipGetLastError(), "kernel launch");
+    }
     if (S > 1) pass_tiled_bf16(e, d_ids, S, B, S - 1);
     if (wide_decode(e, B)) pass_decode_wide_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
     else pass_decode_bf16(e, d_ids + (S - 1), S, B, ids_out, lp_out, out_stride, out_at_step, d_logits_opt);
@@ -703,7 +789,7 @@ he_status he_create(const he_config* cfg, const he_weights* weights, he_engine**
         A(&e->ablk, z.ablk); A(&e->oblk, z.ablk); A(&e->hblk, z.hblk); A(&e->xfblk, z.xfblk);
         A(&e->part, z.part); e->part_floats = z.part / sizeof(float); A(&e->stats, z.stats); A(&e->stats_idx, z.stats_idx);
         A(&e->cvec, z.cvec); A(&e->ln_stats, z.ln_stats); A(&e->ln_counters, z.ln_counters);
-        A(&e->score_stats, z.score_stats); A(&e->score_tgt, z.gen);
+        A(&e->score_stats, z.score_stats); A(&e->score_tgt, z.gen); A(&e->tail_buf, z.tail);
     }
     A(&e->gen_lp, z.gen); A(&e->gen_ids, z.gen);
     A(&e->cur_ids, cfg->max_batch * sizeof(int32_t));

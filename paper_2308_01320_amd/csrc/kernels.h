@@ -81,6 +81,8 @@ void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, i
 void bf16_embed_ln(hipStream_t s, const int32_t* ids, int id_stride, const void* tok, const void* pos,
                    const he_dev_state* st, int B, int H, int V, int pos_offset, int gw, const void* gamma, float* r,
                    void* x_blocks, float* stats);
+// rows b*S + S-1 of r and q ([B*S][H] floats) -> rows b of r_out and q_out ([B][H])
+void bf16_gather_last_rows(hipStream_t s, const float* r, const float* q, float* r_out, float* q_out, int B, int S, int H);
 void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, const void* beta, float* c1, float* c2);
 // rows in slices of 32 (a decode step of up to 32 sequences): EPI_BIAS_RELU, EPI_QKV or EPI_STORE_LN;
 // X: the activations as tiled half blocks; ksplit is ignored (the plan decides)
