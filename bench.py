@@ -38,6 +38,22 @@ def algorithmic_bytes(d, fp8=False):
     return wbytes, kvtok
 
 
+def measured_traffic(workload, kernel_class, fp8):
+    """HBM bytes per launch of a decode kernel class from the tracked counter summary
+    profiles/decode_kernels_traffic.txt (lines: workload class fetch_bytes write_bytes), or (None, None)."""
+    if fp8:
+        return None, None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_kernels_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 4 and not line.startswith("#") and f[0] == workload and f[1] == kernel_class:
+                return float(f[2]) + float(f[3]), "profiles/decode_kernels_traffic.txt"
+    except OSError:
+        pass
+    return None, None
+
+
 def prefill_flops(d):
     H, F, L, V, B, S = d.hidden, d.ffn, d.n_layers, d.vocab, d.batch, d.prompt_len
     return 2 * B * S * L * (4 * H * H + 2 * H * F) + L * B * 2 * S * S * H + 2 * B * V * H
@@ -160,7 +176,8 @@ def main():
                     help="hand the engine pre-tiled matrices (no second copy); implied by opt-66b")
     ap.add_argument("--weights-fp8", action="store_true",
                     help="8-bit (E4M3) layer matrices: a second workload, not the headline number")
-    ap.add_argument("--timing-steps", type=int, default=24, help="decode steps run with per-kernel HIP events")
+    ap.add_argument("--timing-steps", type=int, default=32,
+                    help="decode steps run with per-kernel HIP events, spread evenly over the answer's contexts")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no cross-GPU sharding or collectives); use --gpus 1",
@@ -224,33 +241,47 @@ def main():
         prefill_ms = e0.elapsed_time(e1)
         decode_ms = dev_ms / args.steps - prefill_ms
 
-        # per-kernel durations of the decode step, live, with HIP events around every launch
-        eng.he_timing_enable(True)
+        # Per-kernel durations of the decode step, live, with HIP events around every launch.  The job's decode steps
+        # see contexts S+1 .. S+G-1, and attention's launch grows with the context, so the timed steps are spread
+        # evenly over the whole answer (every `stride`-th step is timed, the others just run).
         nt = max(1, min(args.timing_steps, G - 1))
-        for _ in range(nt):
+        stride = max(1, (G - 1) // nt)
+        timing = {k: [0.0, 0] for k in binding.KERNEL_CLASSES}
+        timed_contexts = []
+        for n in range(1, G):
+            timed = n % stride == 0 and len(timed_contexts) < nt
+            if timed:
+                eng.he_timing_enable(True)
             ids, _, _ = eng.he_decode_step(ids, samp)
-        timing = eng.he_timing_read()
-        eng.he_timing_enable(False)
-        # the dominant kernel's launch duration: one event pair around a sweep that launches it once
-        # per layer (each launch streams a different layer's matrix, as in a decode step)
+            if timed:
+                for k, (ms, cnt) in eng.he_timing_read().items():
+                    timing[k][0] += ms
+                    timing[k][1] += cnt
+                eng.he_timing_enable(False)
+                timed_contexts.append(S + n)  # cached positions the step's attention reads
+        torch.cuda.synchronize()
+        # launch duration of each weight-streaming GEMM class without the per-launch cost of an event pair: one pair
+        # around a sweep that launches the class once per layer (each launch streams a different layer's matrix, as
+        # in a decode step); the median of five sweeps, one alone moves by a few per cent with the clocks
         sweep_reps = 4
-        try:
-            eng.he_kernel_sweep("fc1", 1)  # warm
-            sweeps = []
-            for _ in range(5):  # the median of five sweeps: one sweep alone moves by a few per cent with the clocks
-                s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                s0.record(stream)
-                eng.he_kernel_sweep("fc1", sweep_reps)
-                s1.record(stream)
-                torch.cuda.synchronize()
-                sweeps.append(s0.elapsed_time(s1) * 1e3 / (sweep_reps * d.n_layers))
-            fc1_sweep_us = sorted(sweeps)[len(sweeps) // 2]
-        except binding.HeError as err:
-            # no sweep for this combination (8-bit matrices at more than 32 sequences decode through
-            # several kernels per GEMM): the per-launch event pairs of the decode steps above stand in
-            if err.status != binding.HE_ERR_STATE:
-                raise
-            fc1_sweep_us, sweeps = None, None
+        sweep_us = {}
+        for cls in ("out_proj", "fc1", "fc2"):
+            try:
+                eng.he_kernel_sweep(cls, 1)  # warm
+                runs = []
+                for _ in range(5):
+                    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    s0.record(stream)
+                    eng.he_kernel_sweep(cls, sweep_reps)
+                    s1.record(stream)
+                    torch.cuda.synchronize()
+                    runs.append(s0.elapsed_time(s1) * 1e3 / (sweep_reps * d.n_layers))
+                sweep_us[cls] = {"median": sorted(runs)[len(runs) // 2], "runs": runs}
+            except binding.HeError as err:
+                # no sweep for this combination (8-bit matrices at more than 32 sequences decode through
+                # several kernels per GEMM): the per-launch event pairs of the decode steps above stand in
+                if err.status != binding.HE_ERR_STATE:
+                    raise
         # the scoring pass that follows generation: prompt + answer, all positions at once
         score = None
         if not args.no_score and S + G <= cfg.max_seq_len and S + G <= d.max_positions:
@@ -287,34 +318,48 @@ def main():
     kern_bytes = {  # algorithmic bytes per launch: the weights (and biases) the kernel must stream
         "qkv": 2 * (3 * H * H + 3 * H), "out_proj": 2 * (H * H + H), "fc1": 2 * (F * H + F), "fc2": 2 * (H * F + H),
         "lm_head": 2 * d.vocab * H,
-        # attention during the timed decode steps: contexts S+1 .. S+nt, K and V of one layer
-        "attention": sum(2 * B * T * H * 2 for T in range(S + 1, S + nt + 1)) / nt,
+        # attention over the timed decode steps: K and V of one layer at the contexts those steps saw
+        "attention": sum(2 * B * T * H * 2 for T in timed_contexts) / max(1, len(timed_contexts)),
     }
     if args.weights_fp8:  # codes + row scales + bias
         kern_bytes.update({"qkv": 3 * H * H + 3 * H * 6, "out_proj": H * H + H * 6, "fc1": F * H + F * 6, "fc2": H * F + H * 6})
     # an event pair brackets more than the kernel (the two timestamp packets); the same pair
     # around nothing measures that, and it is taken off every bracket
     pair_ms = timing["empty"][0] / max(1, timing["empty"][1])
-    kernels = {"event_pair_us": pair_ms * 1e3}
+    kernels = {"event_pair_us": pair_ms * 1e3, "timed_steps": len(timed_contexts),
+               "timed_contexts": [timed_contexts[0], timed_contexts[-1]] if timed_contexts else None}
     for k, (ms, cnt) in timing.items():
         if cnt and k != "empty":
             avg = max(ms / cnt - pair_ms, 1e-6)
             kernels[k] = {"avg_us": avg * 1e3, "launches": cnt}
             if k in kern_bytes:
                 kernels[k]["GB/s"] = kern_bytes[k] / (avg * 1e-3) / 1e9
-    dom = "fc1"
-    kernels["fc1_sweep_us"] = fc1_sweep_us
-    kernels["fc1_sweeps_us"] = sweeps if fc1_sweep_us is not None else None
-    dom_avg_s = (fc1_sweep_us if fc1_sweep_us is not None else kernels[dom]["avg_us"]) * 1e-6
+            if k in sweep_us:
+                kernels[k]["sweep_us"] = sweep_us[k]["median"]
+                kernels[k]["sweep_runs_us"] = sweep_us[k]["runs"]
+    # The roofline object is about the DOMINANT kernel of the decode step: the class with the largest summed launch
+    # time over the timed steps (per layer every class launches once, so that is the longest launch on average).
+    # Its launch duration: the event-bracketed average; for a GEMM class the sweep's figure when there is one (it
+    # carries no event-pair cost, and the two agree within a few per cent).
+    per_layer = ("qkv", "attention", "out_proj", "fc1", "fc2")
+    dom = max((k for k in per_layer if k in kernels), key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
+    dom_avg_s = kernels[dom].get("sweep_us", kernels[dom]["avg_us"]) * 1e-6
     achieved = kern_bytes[dom] / dom_avg_s / 1e9 if dom_avg_s > 0 else 0.0
+    names = {"qkv": "decode QKV GEMM, LayerNorm folded in, K/V appended to the cache (gemm_skinny_kernel / gemm_half_kernel, mode 2)",
+             "attention": "decode attention over the KV cache (attn_kernel), mean context of the timed steps",
+             "out_proj": "decode out-projection GEMM, k-split + residual + next LayerNorm's input (gemm_half_kernel, mode 4)",
+             "fc1": "decode FC1 GEMM + bias + ReLU, LayerNorm folded in (gemm_half_kernel / gemm_skinny_kernel, mode 1)",
+             "fc2": "decode FC2 GEMM, k-split + residual + next LayerNorm's input (gemm_half_kernel, mode 4)"}
+    traffic, traffic_src = measured_traffic(d.name, dom, args.weights_fp8)
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": achieved / (HBM_PEAK / 1e9),
-                # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this command, scaled by
-                # the counters' readings for kernels of known size (profiles/decode_fc1_gemm_opt13b_pmc.txt);
-                # measured for the OPT-13B layer shape only
-                "traffic": 218.1e6 if (H, F) == (5120, 20480) and not args.weights_fp8 else None,
-                "kernel": "decode FC1 GEMM + bias + ReLU, LayerNorm folded in (gemm_half_kernel / gemm_skinny_kernel, mode 1)",
-                "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6}
+                # HBM bytes per launch from the tracked rocprofv3 --pmc summary (fetch measured and scaled by the plain
+                # copy kernel's reading, write side stated as algorithmic); null where no such measurement is tracked
+                "traffic": traffic, "traffic_source": traffic_src,
+                "kernel": names[dom], "kernel_class": dom,
+                "bytes_per_launch": kern_bytes[dom], "avg_launch_us": dom_avg_s * 1e6,
+                # the whole decode step against the same peak (every kernel, launch gaps included)
+                "decode_step_frac": decode_gbs / (HBM_PEAK / 1e9)}
 
     result = {
         "metric": "generated tokens/s (1 GPU) + decode HBM GB/s as % of 8 TB/s peak",

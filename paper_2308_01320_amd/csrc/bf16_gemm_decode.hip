@@ -763,6 +763,8 @@ template <int MODE, int HT, bool W8>
 void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_half, int m_tiles,
                     int ksplit, const Epi& p) {
     // loads per wavefront and round: (HT + 4) U 16-byte loads with bf16 weights, (HT + 8) U with 8-bit ones
+    // (with the activations' second term gone there are registers for deeper rounds at four to six units; three or
+    // four blocks per round measured 1-3 % slower than two on the 13B shapes)
     constexpr int U = W8 ? (HT <= 3 ? 2 : 1) : (HT <= 3 ? 4 : 2);
     constexpr int KU = W8 ? 2 : 1;
     dim3 grid(((n_half + HT - 1) / HT) * ksplit, m_tiles);
@@ -922,7 +924,7 @@ static GemmPlan plan_fused(int M, int N) {  // epilogue needs the whole sum: no 
 // Cost of a one-slice plan, in microseconds, fitted to launches of the 13B and 6.7B shapes: what the most loaded
 // workgroup moves (its weight rows and the activation rows over its k range, at the ~48 GB/s one CU
 // sustains while all stream; never less than the whole matrix takes at the HBM rate) plus the tail after the
-// stream: ~1.1 us per k-split whose partial sums the last arriver waits for and reads back, ~0.2 us per quad of
+// stream: ~0.6 us per k-split whose partial sums the last arriver waits for and reads back, ~0.2 us per quad of
 // outputs a thread finishes.  (Balance alone, the earlier criterion, chose four 32-row tiles and six splits on
 // 5120x5120 and 5120x20480; five 16-row units and four splits move 12 % more bytes per workgroup and run 1-2 us
 // faster; on 4096x4096 four units and four splits run 3.4 us faster than four tiles and eight splits.)
@@ -933,7 +935,7 @@ static double store_cost_us(int N, int K, int rows, int items, int ks, int wgs, 
     // half their share (9216x36864: 216 workgroups on 256 CUs ran 8 % slower than 256)
     const double idle = wgs < cus ? 1.0 - (double)wgs / cus : 0.0;
     const double hbm = 2.0 * N * K / 6.5e6 * (1.0 + 0.5 * idle);
-    return (per_cu > hbm ? per_cu : hbm) + 0.2 * items + 1.1 * ks;
+    return (per_cu > hbm ? per_cu : hbm) + 0.2 * items + 0.6 * ks;
 }
 
 static GemmPlan plan_store(int M, int N, int K, size_t capacity) {
