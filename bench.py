@@ -243,13 +243,13 @@ def main():
 
         # Per-kernel durations of the decode step, live, with HIP events around every launch.  The job's decode steps
         # see contexts S+1 .. S+G-1, and attention's launch grows with the context, so the timed steps are spread
-        # evenly over the whole answer (every `stride`-th step is timed, the others just run).
+        # evenly over the whole answer (the other steps just run).
         nt = max(1, min(args.timing_steps, G - 1))
-        stride = max(1, (G - 1) // nt)
+        timed_steps = sorted({1 + int((i + 0.5) * (G - 1) / nt) for i in range(nt)} & set(range(1, G)))
         timing = {k: [0.0, 0] for k in binding.KERNEL_CLASSES}
         timed_contexts = []
         for n in range(1, G):
-            timed = n % stride == 0 and len(timed_contexts) < nt
+            timed = n in timed_steps
             if timed:
                 eng.he_timing_enable(True)
             ids, _, _ = eng.he_decode_step(ids, samp)
