@@ -14,16 +14,28 @@
  *    DEVICE pointer on cfg.device.  Structs and scalars are host memory.
  *  - Linear weights are row-major [out, in]:  y = x W^T + b.
  *  - dtype HE_F32: weights, biases, LayerNorm parameters and the KV cache are
- *    float.  dtype HE_BF16: they are bfloat16 (raw 16-bit, upper half of an
- *    IEEE float); accumulation, residual stream, LayerNorm statistics,
- *    softmax, logits and log-probs are float in both cases.
+ *    float.  dtype HE_BF16: the caller's weights, biases and LayerNorm
+ *    parameters are bfloat16 (raw 16-bit, upper half of an IEEE float).
+ *    Accumulation, residual stream, LayerNorm statistics, softmax, logits and
+ *    log-probs are float in both cases.  Inside the engine the HE_BF16 path
+ *    feeds the matrix cores IEEE binary16 operands: the tiled copies hold the
+ *    caller's bf16 weights converted to binary16 (the same value for
+ *    magnitudes from 2^-14 to 65504, the nearest multiple of 2^-24 below that,
+ *    infinity above -- no trained weight is that large), every GEMM input and
+ *    the KV cache are float values rounded once, to nearest even, to binary16.
  *  - The caller owns weights and all input/output buffers.  The engine
  *    borrows the weight pointers until he_destroy; it owns only its KV arena,
  *    workspace and (bf16) MFMA-tiled copies of the GEMM matrices, all
- *    allocated once in he_create -- no call on the generation path allocates
- *    (Section 4: pre-reserved KV cache and intermediate buffers).  After the
- *    caller overwrites weights in place (a training update between two
- *    generation phases) it calls he_refresh_weights.
+ *    allocated once in he_create -- the engine allocates no device memory on
+ *    the generation path (Section 4: pre-reserved KV cache and intermediate
+ *    buffers).  One exception is the runtime's, not the engine's: the first
+ *    he_generate / he_generate_ragged with a new (batch, answer length)
+ *    captures the decode step into a HIP graph and instantiates it, and the
+ *    runtime may back that with memory of its own; later calls of that shape
+ *    replay the graph.  he_decode_step_static is the call for a caller that
+ *    tolerates no allocation at all.  After the caller overwrites weights in
+ *    place (a training update between two generation phases) it calls
+ *    he_refresh_weights.
  *  - All work is enqueued on cfg.stream (a hipStream_t, NULL = default
  *    stream) and is asynchronous; only he_create / he_refresh_weights /
  *    he_destroy synchronise.  Outputs are valid once the stream has drained.
@@ -121,7 +133,8 @@ typedef struct {
  * cols must be a multiple of 16), and the conversion itself: d_src row-major bf16 [rows, cols],
  * d_dst the tiled form, distinct buffers, on `stream`.  The tiled form is [rows/32][cols/16]
  * blocks of 64 lanes x 8 values: lane 32*((c%16)/8) + r%32 holds columns 16*(c/16) + 8*(lane/32)
- * + 0..7 of row r -- one MFMA 32x32x16 operand per block. */
+ * + 0..7 of row r -- one MFMA 32x32x16 operand per block.  The 16-bit values of the tiled form are
+ * IEEE binary16, each the bf16 source value converted as the conventions above state. */
 size_t he_tiled_bytes(int rows, int cols);
 he_status he_tile_matrix(const void* d_src, void* d_dst, int rows, int cols, void* stream);
 /* The same with a low-rank adapter folded in: d_dst = tiled bf16(src + scale * B A), d_a bf16 [rank, cols],
@@ -302,6 +315,28 @@ he_status he_fp8_quantize_rows(const void* d_src, int rows, int cols, void* d_co
  * scratch; 0 = unlimited).  N and K multiples of 32. */
 he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t scratch_floats, int cus, int* unit_rows,
                               int* units_per_workgroup, int* ksplit);
+
+/* Test hook, host logic only (no device work, no engine): what the k-split GEMM of a decode step of B <= 64
+ * sequences (which = 0: out-projection, 1: FC2) would index in an engine created with cfg, next to what he_create
+ * reserves for it.  The partial sums of one launch cross workgroups through scratch, each (column group, row
+ * slice, split) in words of its own, and one arrival counter per (column group, row slice); the account comes
+ * from the launcher's own choice of kernel variant and grid.  cus as in he_plan_decode_gemm.  bf16, impl 0 only. */
+typedef struct {
+    size_t scratch_floats;   /* floats of scratch the launch indexes (0 without a k-split) */
+    size_t scratch_reserved; /* floats he_create reserves */
+    size_t static_floats;    /* floats he_decode_step_static sets aside for this launch */
+    int counters;            /* arrival counters the launch indexes */
+    int counters_reserved;
+    int stat_pairs;          /* (mean, sum of squares) pairs of column-group statistics it writes */
+    int stat_pairs_reserved;
+    int ksplit;
+} he_scratch_account;
+he_status he_decode_scratch_account(const he_config* cfg, int B, int which, int cus, he_scratch_account* out);
+
+/* Test hook: waits for the engine's stream, then counts the engine's arrival counters that are not zero.  Every
+ * k-split launch leaves its counters at zero for the next one (its last workgroup clears them), and he_reset
+ * clears them all: between calls the answer is 0.  bf16, impl 0 only. */
+he_status he_arrival_counters_nonzero(he_engine* e, int* nonzero);
 
 /* Measurement hook: a plain copy kernel (reads `bytes`, writes `bytes`, a multiple of 16,
  * device pointers, on `stream`).  Hardware byte counters (rocprofv3 FETCH_SIZE /

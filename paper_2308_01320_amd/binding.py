@@ -47,6 +47,12 @@ class he_weights(C.Structure):
                 ("lm_head", C.c_void_p), ("layers", C.POINTER(he_layer_weights))]
 
 
+class he_scratch_account(C.Structure):
+    _fields_ = [("scratch_floats", C.c_size_t), ("scratch_reserved", C.c_size_t), ("static_floats", C.c_size_t),
+                ("counters", C.c_int), ("counters_reserved", C.c_int), ("stat_pairs", C.c_int),
+                ("stat_pairs_reserved", C.c_int), ("ksplit", C.c_int)]
+
+
 class he_sampling(C.Structure):
     _fields_ = [("mode", C.c_int), ("temperature", C.c_float), ("seed", C.c_uint64)]
 
@@ -119,6 +125,10 @@ def lib() -> C.CDLL:
     L.he_plan_decode_gemm.restype = C.c_int
     L.he_plan_decode_gemm.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_int, C.POINTER(C.c_int),
                                       C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    L.he_decode_scratch_account.restype = C.c_int
+    L.he_decode_scratch_account.argtypes = [C.POINTER(he_config), C.c_int, C.c_int, C.c_int, C.POINTER(he_scratch_account)]
+    L.he_arrival_counters_nonzero.restype = C.c_int
+    L.he_arrival_counters_nonzero.argtypes = [vp, C.POINTER(C.c_int)]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -134,7 +144,8 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_timing_read", "he_calibration_copy", "he_kernel_sweep", "he_tiled_bytes",
            "he_tile_matrix", "he_score", "he_prefill_ragged",
            "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena",
-           "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows", "he_decode_step_static")
+           "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows", "he_decode_step_static",
+           "he_decode_scratch_account", "he_arrival_counters_nonzero")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -305,6 +316,11 @@ class Engine:
         self._check(lib().he_timing_read(self.handle, ms, cnt, n))
         return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
+    def he_arrival_counters_nonzero(self) -> int:
+        n = C.c_int()
+        self._check(lib().he_arrival_counters_nonzero(self.handle, C.byref(n)))
+        return n.value
+
     def he_kernel_sweep(self, kernel_class: str, reps: int = 1):
         self._check(lib().he_kernel_sweep(self.handle, KERNEL_CLASSES.index(kernel_class), reps))
 
@@ -373,6 +389,15 @@ def he_plan_decode_gemm(M, N, K, ksplit_allowed=False, scratch_floats=0, cus=256
     if rc != HE_OK:
         raise HeError(rc, "he_plan_decode_gemm")
     return u.value, n.value, k.value
+
+
+def he_decode_scratch_account(cfg: he_config, B: int, which: int, cus: int = 256) -> he_scratch_account:
+    """What the k-split GEMM (which = 0 out-projection, 1 FC2) of a B-row decode step indexes; host logic only."""
+    out = he_scratch_account()
+    rc = lib().he_decode_scratch_account(C.byref(cfg), B, which, cus, C.byref(out))
+    if rc != HE_OK:
+        raise HeError(rc, "he_decode_scratch_account")
+    return out
 
 
 def he_tile_matrix_lora(src, a, b, scale, stream=None):

@@ -6,6 +6,13 @@ using namespace he_bf16;
 
 namespace {
 
+// Quads of outputs a thread of a workgroup holds after the k loop: the workgroup's (tile or unit, row part) items
+// dealt out over its wavefronts.  One definition for the kernels and for the launchers' account of the scratch a
+// launch indexes.
+constexpr int items_per_wave(int items, int waves) { return (items + waves - 1) / waves; }
+// Floats of k-split scratch one split of one column group covers (store_ln_tail's layout).
+constexpr size_t tail_floats_per_split(int items, int waves) { return (size_t)items * 4 * waves * 64; }
+
 // ----------------------------------------------------------------- k-split GEMM -> residual rows + next LayerNorm's input
 //
 // Tail of the decode-shaped out-projection / FC2 GEMMs (MODE_STORE_LN), shared by the 32-row and the
@@ -36,7 +43,7 @@ __device__ __forceinline__ void store_ln_tail(const Epi& p, int ksplit, int ks, 
     __shared__ float sred[2][WAVES][32 * MT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const size_t cell = (size_t)grp * gridDim.y + blockIdx.y;
-    constexpr size_t kPer = (size_t)ITEMS * 4 * WAVES * 64;  // words of one split of one column group
+    constexpr size_t kPer = tail_floats_per_split(ITEMS, WAVES);  // words of one split of one column group
     // 64-bit words (two sums each): a wavefront can have 63 loads outstanding, and the wider they are, the more
     // of the last workgroup's read-back is in flight at once
     uint64_t* scratch = reinterpret_cast<uint64_t*>(p.out + cell * ksplit * kPer) + threadIdx.x;
@@ -256,7 +263,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
     const u32x4* xh = Xhi + ((size_t)mt * KB + kb0) * 64 + lane;
     // After the k loop the NT*4 (tile, row-quad) items of the workgroup are shared out over its
     // wavefronts: item = wave + i*WAVES -> tile item/4, rows 8*(item%4) + 4*(lane/32) + 0..3.
-    constexpr int ITEMS = (NT * 4 + WAVES - 1) / WAVES;
+    constexpr int ITEMS = items_per_wave(NT * 4, WAVES);
     // What the epilogue needs (bias, the folded LayerNorm's vectors and statistics, the cache length) is
     // requested right behind the first round of weight loads: long before it is used, and without holding
     // up the start of the weight stream, which then waits for three pointers and three sizes only.
@@ -534,7 +541,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_half_kernel(const u32x4* __re
         else w[t] = Wp + ((size_t)(g >> 1) * KB + 2 * kp0) * 64 + in_pair + 16 * (g & 1);
     }
     const u32x4* xh = Xhi + ((size_t)mt * KB + 2 * KU * kp0) * 64 + in_pair;
-    constexpr int ITEMS = (NI + WAVES - 1) / WAVES;  // item = wave + i*WAVES -> unit item/MH, row half item%MH
+    constexpr int ITEMS = items_per_wave(NI, WAVES);  // item = wave + i*WAVES -> unit item/MH, row half item%MH
     // epilogue operands: requested right behind the first round of weight loads (see gemm_skinny_kernel)
     uint2 bias_w[ITEMS];
     float4 c1w[ITEMS], c2w[ITEMS], wsc[ITEMS];
@@ -733,6 +740,21 @@ int plan_cus() { return g_cus_override > 0 ? g_cus_override : num_cus(); }
 #ifndef HE_SKINNY_W8_MAXNT
 #define HE_SKINNY_W8_MAXNT 2
 #endif
+// Host-side account of a MODE_STORE_LN launch: when `g_dry` is set the launchers below go through their choice of
+// kernel variant and grid as usual, then record what that launch would index instead of launching it.
+struct StoreFootprint { size_t scratch_floats; int cells; int stat_groups; int ksplit; };
+StoreFootprint* g_dry = nullptr;
+// grid: the launch's; items, waves: of the kernel variant chosen.  True if the launch is to be left out.
+inline bool dry_run(const dim3& grid, int ksplit, int items, int waves) {
+    if (!g_dry) return false;
+    const int groups = grid.x / ksplit;
+    g_dry->cells = groups * grid.y;
+    g_dry->stat_groups = groups;
+    g_dry->ksplit = ksplit;
+    g_dry->scratch_floats = ksplit > 1 ? (size_t)g_dry->cells * ksplit * tail_floats_per_split(items, waves) : 0;
+    return true;
+}
+
 template <int MODE, int NT>
 void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, int KB, int n_tiles,
                       int m_tiles, int ksplit, const Epi& p) {
@@ -746,6 +768,7 @@ void launch_skinny_nt(hipStream_t s, const void* Wp, const void* Xhi, int KB, in
     // Ask for more than half of a CU's LDS so that no two workgroups share a CU: with at most one
     // workgroup per CU the dispatcher has to spread a launch of <= #CUs workgroups evenly.
     constexpr size_t kWant = 84 * 1024;
+    if (dry_run(grid, ksplit, items_per_wave(NT * 4, eight ? 8 : 4), eight ? 8 : 4)) return;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * NT * 16 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
@@ -773,6 +796,7 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, int KB, int 
             constexpr int U2 = HT <= 6 ? 2 : 1;
             constexpr size_t kWant2 = 84 * 1024;
             grid.y = 1;
+            if (dry_run(grid, ksplit, items_per_wave(HT * (p.M <= 48 ? 3 : 4), 4), 4)) return;
             if (p.M <= 48) {  // the last 16 of the 64 rows are not in use
                 constexpr size_t kStatic = (size_t)4 * HT * 3 * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant2 ? 0 : kWant2 - kStatic;
@@ -793,6 +817,7 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, int KB, int 
     constexpr size_t kWant = 84 * 1024;                                      // one workgroup per CU
     if constexpr (!W8) {
         if (m_tiles == 1 && p.M <= 16) {  // the second half of the 32 activation rows is not in use: leave it out
+            if (dry_run(grid, ksplit, items_per_wave(HT, eight ? 8 : 4), eight ? 8 : 4)) return;
             if (eight) {
                 constexpr size_t kStatic = (size_t)8 * HT * 4 * 64 * sizeof(float);
                 const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
@@ -807,6 +832,7 @@ void launch_half_ht(hipStream_t s, const void* Wp, const void* Xhi, int KB, int 
             return;
         }
     }
+    if (dry_run(grid, ksplit, items_per_wave(HT * 2, eight ? 8 : 4), eight ? 8 : 4)) return;
     if (eight) {
         constexpr size_t kStatic = (size_t)8 * HT * 2 * 4 * 64 * sizeof(float);
         const size_t pad = kStatic >= kWant ? 0 : kWant - kStatic;
@@ -1002,6 +1028,27 @@ void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, i
     *unit_rows = g.half ? 16 : 32;
     *per_wg = g.per_wg;
     *ks = g.ks;
+}
+
+// What the MODE_STORE_LN launch of this shape indexes (host logic only): floats of k-split scratch, arrival
+// counters, column groups of statistics per 32-row slice, and its k-split.
+void bf16_store_footprint(int M, int N, int K, size_t capacity, int w8, int cus, size_t* scratch_floats,
+                          size_t* need_floats, int* cells, int* stat_groups, int* ksplit) {
+    StoreFootprint f{};
+    g_cus_override = cus;
+    bf16_gemm_args a{};
+    a.out_capacity = capacity;
+    float one = 1.f;
+    if (w8) a.wscale = &one;  // (never read: nothing is launched)
+    g_dry = &f;
+    bf16_gemm_skinny(nullptr, EPI_STORE_LN, nullptr, nullptr, M, N, K, 0, a);
+    g_dry = nullptr;
+    *need_floats = bf16_store_need(M, N, K, capacity, w8);
+    g_cus_override = 0;
+    *scratch_floats = f.scratch_floats;
+    *cells = f.cells;
+    *stat_groups = f.stat_groups;
+    *ksplit = f.ksplit;
 }
 
 void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks) {

@@ -160,8 +160,10 @@ Sizes sizes_of(const he_config& c) {
     s.stats_idx = (size_t)c.max_batch * ntile * sizeof(int);
     const size_t vpad = ((size_t)c.vocab + 31) / 32 * 32, mtiles = ((size_t)c.max_batch + 31) / 32;
     s.cvec = ((size_t)c.n_layers * 2 * (3 * H + F) + 2 * vpad) * sizeof(float);
-    s.ln_stats = mtiles * (H / 32) * 32 * 2 * sizeof(float) + 1024;  // at most one group per 32 columns
-    s.ln_counters = mtiles * (H / 32) * sizeof(int);
+    // column groups of the k-split GEMMs: at most one per 16 columns (8-bit weights on a narrow model; 16-bit
+    // weights never go below 32)
+    s.ln_stats = mtiles * (H / 16) * 32 * 2 * sizeof(float) + 1024;
+    s.ln_counters = mtiles * (H / 16) * sizeof(int);
     s.score_stats = rows * bf16_score_parts(c.vocab) * 2 * sizeof(float);
     s.tail = (size_t)2 * c.max_batch * H * sizeof(float);
     s.total += s.cvec + s.ln_stats + s.ln_counters + s.score_stats + s.gen + s.tail;
@@ -1209,6 +1211,39 @@ he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t sc
                               int* units_per_workgroup, int* ksplit) {
     if (M < 1 || N < 1 || K < 1 || N % 32 || K % 32 || !unit_rows || !units_per_workgroup || !ksplit) return HE_ERR_INVALID_ARG;
     bf16_plan_query(M, N, K, ksplit_allowed, scratch_floats, cus, unit_rows, units_per_workgroup, ksplit);
+    return HE_OK;
+}
+
+he_status he_decode_scratch_account(const he_config* cfg, int B, int which, int cus, he_scratch_account* out) {
+    if (!out || check_config(cfg) || check_shape(cfg) || !is_fast(*cfg)) return HE_ERR_INVALID_ARG;
+    if (B < 1 || B > cfg->max_batch || B > 64 || (which != 0 && which != 1) || cus < 0) return HE_ERR_INVALID_ARG;
+    if (cfg->weights_fp8 && B > 32) return HE_ERR_INVALID_ARG;  // those steps take the wide path
+    const Sizes z = sizes_of(*cfg);
+    const int H = cfg->hidden, K = which ? cfg->ffn : H;
+    const size_t cap = z.part / sizeof(float);
+    size_t need = 0;
+    int groups = 0;
+    bf16_store_footprint(B, H, K, cap, cfg->weights_fp8, cus, &out->scratch_floats, &need, &out->counters, &groups,
+                         &out->ksplit);
+    out->scratch_reserved = cap;
+    out->static_floats = need;
+    out->counters_reserved = (int)(z.ln_counters / sizeof(int));
+    out->stat_pairs = (B + 31) / 32 * groups * 32;
+    out->stat_pairs_reserved = (int)(z.ln_stats / (2 * sizeof(float)));
+    return HE_OK;
+}
+
+he_status he_arrival_counters_nonzero(he_engine* e, int* nonzero) {
+    if (!e || !nonzero) return HE_ERR_INVALID_ARG;
+    if (!e->fast || !e->ln_counters) return fail(e, HE_ERR_STATE, "he_arrival_counters_nonzero: bf16 path only");
+    const size_t n = sizes_of(e->cfg).ln_counters / sizeof(int);
+    std::vector<int> host(n);
+    hipError_t r = hipStreamSynchronize(e->stream);
+    if (r == hipSuccess) r = hipMemcpy(host.data(), e->ln_counters, n * sizeof(int), hipMemcpyDeviceToHost);
+    if (r != hipSuccess) return check_hip(e, r, "he_arrival_counters_nonzero");
+    int c = 0;
+    for (int v : host) c += v != 0;
+    *nonzero = c;
     return HE_OK;
 }
 

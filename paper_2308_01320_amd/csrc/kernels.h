@@ -75,6 +75,10 @@ void bf16_store_shape(int M, int N, int K, int* nt, int* ks);
 void bf16_store_plan(int M, int N, int K, size_t capacity, int* group_cols, int* ks);
 // floats of k-split scratch that launch may index (upper bound); w8 != 0: the 8-bit-weight plan
 size_t bf16_store_need(int M, int N, int K, size_t capacity, int w8);
+// What that launch indexes, from the launcher's own choice of kernel variant and grid (host logic, no launch).
+// cus: compute units to plan for (0 = the current device's).  need_floats: what bf16_store_need answers.
+void bf16_store_footprint(int M, int N, int K, size_t capacity, int w8, int cus, size_t* scratch_floats,
+                          size_t* need_floats, int* cells, int* stat_groups, int* ksplit);
 // the launch plan itself (host logic only; cus > 0 overrides the device's CU count): rows per unit (32 or 16),
 // units per workgroup, k-splits; store != 0 for the k-split GEMMs
 void bf16_plan_query(int M, int N, int K, int store, size_t capacity, int cus, int* unit_rows, int* per_wg, int* ks);

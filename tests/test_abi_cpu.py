@@ -105,6 +105,52 @@ def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
         binding.he_plan_decode_gemm(32, 100, 64)
 
 
+def test_ksplit_hand_off_stays_inside_what_he_create_reserves():
+    """The invariant the k-split hand-off of the decode out-projection / FC2 rests on.  Partial sums cross
+    workgroups inside one launch through scratch, every (column group, row slice, split) in words of its own, with
+    one arrival counter per (column group, row slice).  The account comes from the launcher's own choice of kernel
+    variant and grid (a dry run of the launch, no device), so an index formula that outgrows the reserve shows here
+    and not as a stray write on the GPU.  Checked: the words indexed fit the engine's scratch and the static
+    entry point's share of its array; the counters and the column-group statistics fit their reserves -- for
+    every model shape of the benchmark configurations and a set of narrow ones, 16-bit and 8-bit weights, every
+    batch up to 64 and three chip sizes."""
+    import dataclasses
+    shapes = [synth.CONFIGS[n] for n in synth.CONFIGS]
+    for H, nh, F in ((64, 1, 64), (64, 1, 256), (128, 2, 512), (192, 3, 768), (256, 2, 1024), (512, 4, 2048),
+                     (1024, 8, 4096)):
+        shapes.append(dataclasses.replace(synth.CONFIGS["tiny"], hidden=H, n_heads=nh, ffn=F))
+    seen_split = False
+    for d in shapes:
+        d = dataclasses.replace(d, dtype="bf16")
+        for fp8 in (0, 1):
+            for max_batch in (1, 16, 32, 64):
+                cfg = binding.make_config(d, max_batch=max_batch, max_seq_len=64, weights_fp8=fp8)
+                for B in sorted({1, 8, 16, 17, 32, 33, 48, 49, 64, max_batch}):
+                    if B > max_batch or (fp8 and B > 32):
+                        continue
+                    for which in (0, 1):
+                        for cus in (64, 256, 304):
+                            a = binding.he_decode_scratch_account(cfg, B, which, cus)
+                            case = (d.hidden, d.ffn, fp8, max_batch, B, which, cus)
+                            assert 1 <= a.ksplit <= 8, case
+                            assert a.scratch_floats <= a.scratch_reserved, case
+                            assert a.scratch_floats <= a.static_floats, case
+                            assert a.counters <= a.counters_reserved, case
+                            assert a.stat_pairs <= a.stat_pairs_reserved, case
+                            # (column group, row slice, split) regions are equal runs laid end to end: whole
+                            # numbers of 256-float wavefront rows, so no two of them share a word
+                            if a.ksplit > 1:
+                                seen_split = True
+                                assert a.scratch_floats % (a.counters * a.ksplit * 256) == 0, case
+    assert seen_split
+    d = dataclasses.replace(synth.CONFIGS["tiny"], dtype="bf16")
+    with pytest.raises(binding.HeError):
+        binding.he_decode_scratch_account(binding.make_config(d, max_batch=8, max_seq_len=64), 9, 0, 256)
+    with pytest.raises(binding.HeError):
+        binding.he_decode_scratch_account(binding.make_config(dataclasses.replace(d, dtype="f32"), max_batch=8,
+                                                              max_seq_len=64), 8, 0, 256)
+
+
 def test_bench_clock_sampler_reads_the_marked_level(tmp_path):
     """bench.py's clock record: the level the driver marks with '*' in its text files, sampled from a thread."""
     import importlib.util

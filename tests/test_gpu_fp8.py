@@ -63,6 +63,7 @@ def test_fp8_weights_against_oracle_on_dequantised_model(L, H, nh, F, V, B, S, G
     got = util.engine_teacher_forced(eng, prompts, want["ids"], G, binding.sampling("gumbel", 0.9, 7))
     rep = util.compare(got, want, BF16_TOL, MARGIN)
     print(rep)
+    assert eng.he_arrival_counters_nonzero() == 0  # the k-split launches left their counters ready for the next
     # against the unquantised model the logits differ by far more than the tolerance: the codes are in use
     plain = util.oracle_run(d, w, prompts, G, "gumbel", 0.9, 7)
     assert float(np.abs(plain["logits"] - want["logits"]).max()) > 10 * rep["logit_err"]
@@ -105,6 +106,7 @@ def test_fp8_real_layer_shape_and_memory():
     got = util.engine_teacher_forced(eng, prompts, want["ids"], 3, binding.sampling("gumbel", 1.0, 42))
     rep = util.compare(got, want, BF16_TOL, MARGIN)
     print(rep)
+    assert eng.he_arrival_counters_nonzero() == 0
     eng.he_destroy()
 
 

@@ -101,8 +101,10 @@ def test_headline_full_depth_properties():
         a_ids, a_lp = eng.he_generate(prompts, G, samp)
         b_ids, b_lp = eng.he_generate(prompts, G, samp)
     stream.synchronize()
-    # 1. determinism: a second run is bit-identical (no atomics, fixed reduction orders)
+    # 1. determinism: a second run is bit-identical (fixed reduction orders: the k-split sums are added in split
+    #    order by whichever workgroup arrives last), and every k-split launch left its arrival counters at zero
     assert torch.equal(a_ids, b_ids) and torch.equal(a_lp, b_lp)
+    assert eng.he_arrival_counters_nonzero() == 0
     # 2. graph replay == step-by-step launches, and the reported log-prob / id are what the
     #    oracle's sampler gives on the engine's own logits
     with torch.cuda.stream(stream):
@@ -113,6 +115,7 @@ def test_headline_full_depth_properties():
             i, lp, lg = eng.he_decode_step(i, samp, want_logits=True)
             steps.append((i, lp, lg))
     stream.synchronize()
+    assert eng.he_arrival_counters_nonzero() == 0  # after he_reset + eager steps
     for n, (i, lp, lg) in enumerate(steps):
         assert torch.equal(i, a_ids[:, n]) and torch.equal(lp, a_lp[:, n]), n
         z = lg.cpu().numpy().astype(np.float64)
