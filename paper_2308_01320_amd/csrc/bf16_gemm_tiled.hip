@@ -246,10 +246,30 @@ __global__ __launch_bounds__(256, (PAIR && MW == 2) ? 2 : 1) void gemm_tiled_ker
 // wavefronts with a 128 x 128 sub-tile each (16 accumulator tiles: the whole accumulator file, so one workgroup
 // per CU).  Nothing else runs on a CU while its four wavefronts sit at a barrier or issue loads, so the schedule is
 // laid out by hand: a stage is two k-blocks (32 KiB, ring of four); LDS reads and global -> LDS copies are dealt out
-// one per pair of matrix instructions, each read at least nine matrix instructions ahead of its first use.  Measured
-// on the 8160 x 20480 x 5120 product (loop only): matrix instructions alone on random operands 1015 us (the clock
-// drops under data toggling), + LDS reads 1082 us, + copies 1310 us = 1.31 PFLOP/s; with reads and copies issued in
-// bursts after the barrier, as a compiler left to itself schedules them, 1690 us.
+// between pairs of matrix instructions, every read at least eight matrix instructions ahead of the wait that
+// covers it.  Measured on the 8160 x 20480 x 5120 product (loop only): matrix instructions alone on random operands
+// 1015 us (the clock drops under data toggling), + LDS reads 1082 us, + copies 1280 us = 1.34 PFLOP/s (1310 us with
+// one read per pair all through a half: the compiler's wait at the top of a half is for all reads, the newest
+// included); with reads and copies issued in bursts after the barrier, as a compiler left to itself schedules
+// them, 1690 us.  Copies issued by odd and even wavefronts behind different pairs: no change.
+// A lane of a 32x32 accumulator tile holds columns 8q + 4 (lane / 32) + 0..3 of row lane % 32: four halves of an
+// eight-column slot, the other four in the lane 32 away.  For a pair of slots (q even, q odd) packed as x, y: the
+// lower lane gets the whole even slot, the upper lane the whole odd one -- 16-byte stores instead of 8-byte ones
+// (the epilogue is bound by the number of store instructions).
+__device__ __forceinline__ u32x4 join_halves(uint2 x, uint2 y) {
+    const auto a = __builtin_amdgcn_permlane32_swap(x.x, y.x, false, false);  // [x low lanes | y low lanes], [x high | y high]
+    const auto b = __builtin_amdgcn_permlane32_swap(x.y, y.y, false, false);
+    return u32x4{a[0], b[0], a[1], b[1]};
+}
+
+// The big kernel's result stores, 16 bytes per lane.  (Nontemporal stores were tried: no gain for the half blocks,
+// 6 % slower for the float rows.)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16(void* dst, u32x4 v) { *reinterpret_cast<u32x4*>(dst) = v; }
+__device__ __forceinline__ void store16(void* dst, float a, float b, float c, float d) {
+    *reinterpret_cast<f32x4*>(dst) = f32x4{a, b, c, d};
+}
+
 constexpr int BN = 256, BM = 256;  // tile of the big kernel
 constexpr int BSTAGES = 4;
 
@@ -320,28 +340,39 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
 #pragma unroll
         for (int n = 0; n < 16; ++n) mma1(o, n);
     };
+    // The copies of stage t are issued in two halves: its W blocks (q = 0..3) in the second half of stage t-3, its X
+    // blocks (q = 4..7) in the first half of stage t-2 -- the prologue issues what would fall before stage 0.
+    issue(0);
+    if (nstage >= 2) issue(1);
+    if (nstage >= 3) {
 #pragma unroll
-    for (int st = 0; st < BSTAGES - 1; ++st)
-        if (st < nstage) issue(st);
-    if (nstage >= 3) wait_vmcnt<2 * kLoads>();
-    else if (nstage == 2) wait_vmcnt<kLoads>();
-    else wait_vmcnt<0>();
+        for (int q = 0; q < 4; ++q) copy1(2, q);
+        wait_vmcnt<kLoads + kLoads / 2>();
+    } else if (nstage == 2) {
+        wait_vmcnt<kLoads>();
+    } else {
+        wait_vmcnt<0>();
+    }
     __syncthreads();
     Ops opa, opb;
     read_ops(opa, 0, 0);
     int s = 0;
-    // Steady state: stages s+1 and s+2 are in flight, stage s+3 goes into the slot stage s-1 has left.  Every pair of
-    // matrix instructions is followed by one LDS read of the operand set used next (sixteen instructions later at
-    // the earliest use, nine at the latest) and, in the stage's second half, by one global -> LDS copy; scheduling
-    // barriers keep that order.  The workgroup barrier is the bare instruction: what it orders are the copies,
+    // Steady state: stage s+1 and the W blocks of stage s+2 are in flight; the first half of stage s requests the X
+    // blocks of stage s+2 (into the slot stage s-2 left: everybody passed the barrier of stage s-1 since), the second
+    // half the W blocks of stage s+3 (into the slot of stage s-1, behind this stage's barrier).  Scheduling barriers
+    // keep the order written here.  The workgroup barrier is the bare instruction: what it orders are the copies,
     // which the wait before it covers -- the LDS reads in flight across it belong to the stage in use, not to the
     // slot about to be refilled (a fence would wait for them).
+    // In each half of a stage the first four pairs of matrix instructions are followed by two LDS reads each (the
+    // operands of the other half: the last of them is eight matrix instructions old when the half ends, so the wait
+    // for the reads at the top of a half finds them done), the last four by one copy each.
     for (; s + 3 < nstage; ++s) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             mma1(opa, 2 * q);
             mma1(opa, 2 * q + 1);
-            read1(opb, s, 1, q);
+            if (q < 4) { read1(opb, s, 1, 2 * q); read1(opb, s, 1, 2 * q + 1); }
+            else copy1(s + 2, q);
             __builtin_amdgcn_sched_barrier(0);
         }
         wait_vmcnt<kLoads>();  // this wavefront's copies of stage s+1 have landed ...
@@ -353,12 +384,16 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
         for (int q = 0; q < 8; ++q) {
             mma1(opb, 2 * q);
             mma1(opb, 2 * q + 1);
-            read1(opa, s + 1, 0, q);
-            copy1(s + 3, q);
+            if (q < 4) { read1(opa, s + 1, 0, 2 * q); read1(opa, s + 1, 0, 2 * q + 1); }
+            else copy1(s + 3, q - 4);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    for (; s < nstage; ++s) {  // the last three stages: nothing left to request
+    for (; s < nstage; ++s) {  // the last three stages: only the X blocks of the last one are left to request
+        if (s + 2 < nstage) {
+#pragma unroll
+            for (int q = 4; q < 8; ++q) copy1(s + 2, q);
+        }
         read_ops(opb, s, 1);
         mma_all(opa);
         if (s + 1 < nstage) {
@@ -379,13 +414,14 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
     for (int j = 0; j < 4; ++j) {
         const int m = tm * BM + (wm * 4 + j) * 32 + (lane & 31);
         if (m >= p.M) continue;
-        size_t row = 0;       // MODE_STORE: float index of (m, 4 hh); BIAS_RELU: uint2 index; QKV: float index into q
-        size_t kvrow = 0;     // QKV: half index of (sequence, head 0, position, 4 hh) inside one (layer, k|v) plane
+        size_t row = 0;       // MODE_STORE: float index of (m, 4 hh); BIAS_RELU: 16-byte slot of (m, k half hh) in
+                              // the first block of its row of blocks; QKV: float index into q
+        size_t kvrow = 0;     // QKV: half index of (sequence, head 0, position, 0) inside one (layer, k|v) plane
         bool append = true;   // QKV: the row is a token (not padding): its key and value go into the cache
         if (MODE == MODE_STORE) {
             row = (size_t)ks * p.out_split + (size_t)m * p.N + 4 * hh;
         } else if (MODE == MODE_BIAS_RELU) {
-            row = ((size_t)(m >> 5) * (p.N >> 4) * 64 + (m & 31)) * 2 + hh;
+            row = (size_t)(m >> 5) * (p.N >> 4) * 64 + 32 * hh + (m & 31);
         } else {
             row = (size_t)m * p.H + 4 * hh;
             const int b = m / p.S, r = m - b * p.S;
@@ -395,7 +431,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
                 append = tr >= 0;
                 t = seq_len(p.st, b) + tr;
             }
-            kvrow = ((size_t)b * p.n_heads * p.max_seq + t) * p.d + 4 * hh;
+            kvrow = ((size_t)b * p.n_heads * p.max_seq + t) * p.d;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -404,18 +440,21 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
             if (MODE == MODE_STORE) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    *reinterpret_cast<float4*>(p.out + row + n32 + 8 * q) =
-                        make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+                    store16(p.out + row + n32 + 8 * q, acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
+                            acc[i][j][q * 4 + 3]);
             } else if (MODE == MODE_BIAS_RELU) {
-                uint2* ob = reinterpret_cast<uint2*>(p.out_blocks) + row + (size_t)(n32 >> 4) * 128;
+                u32x4* ob = p.out_blocks + row + (size_t)(n32 >> 4) * 64;
+                uint2 h4[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const u32x4 b8 = bias8[(n32 >> 3) + q];  // wave-uniform address: a scalar load
                     const uint2 bb = hh ? make_uint2(b8.z, b8.w) : make_uint2(b8.x, b8.y);
                     const float v0 = fmaxf(acc[i][j][q * 4 + 0] + bf_lo(bb.x), 0.f), v1 = fmaxf(acc[i][j][q * 4 + 1] + bf_hi(bb.x), 0.f);
                     const float v2 = fmaxf(acc[i][j][q * 4 + 2] + bf_lo(bb.y), 0.f), v3 = fmaxf(acc[i][j][q * 4 + 3] + bf_hi(bb.y), 0.f);
-                    ob[(q >> 1) * 128 + (q & 1) * 64] = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                    h4[q] = make_uint2(pack2(v0, v1), pack2(v2, v3));
                 }
+#pragma unroll
+                for (int qq = 0; qq < 2; ++qq) store16(ob + qq * 64, join_halves(h4[2 * qq], h4[2 * qq + 1]));
             } else {
                 const int part = n32 >= 2 * p.H ? 2 : (n32 >= p.H ? 1 : 0);  // query, key or value columns (uniform)
                 half_t* kvcol = nullptr;
@@ -424,6 +463,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
                     kvcol = p.kv + (((size_t)(p.layer * 2 + (part - 1)) * p.max_batch) * p.n_heads + head) * p.max_seq * (size_t)p.d +
                             (c32 - head * p.d);
                 }
+                uint2 h4[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const u32x4 b8 = bias8[(n32 >> 3) + q];
@@ -431,10 +471,16 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
                     const float v0 = acc[i][j][q * 4 + 0] + bf_lo(bb.x), v1 = acc[i][j][q * 4 + 1] + bf_hi(bb.x);
                     const float v2 = acc[i][j][q * 4 + 2] + bf_lo(bb.y), v3 = acc[i][j][q * 4 + 3] + bf_hi(bb.y);
                     if (!part)
-                        *reinterpret_cast<float4*>(p.out + row + n32 + 8 * q) =
-                            make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
-                    else if (append)
-                        *reinterpret_cast<uint2*>(kvcol + kvrow + 8 * q) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                        store16(p.out + row + n32 + 8 * q, v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
+                    else
+                        h4[q] = make_uint2(pack2(v0, v1), pack2(v2, v3));
+                }
+                if (part) {  // (uniform) keys / values: eight halves of a row per lane
+#pragma unroll
+                    for (int qq = 0; qq < 2; ++qq) {
+                        const u32x4 v8 = join_halves(h4[2 * qq], h4[2 * qq + 1]);
+                        if (append) store16(kvcol + kvrow + 8 * (2 * qq + hh), v8);
+                    }
                 }
             }
         }
