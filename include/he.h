@@ -238,9 +238,12 @@ he_status he_acquire_arena(he_engine* e);
  * eos_id (eos_id < 0: never) it produces nothing more -- its remaining d_out_ids are pad_id and their
  * d_out_logprobs 0 -- and d_out_lens [B] int32 receives the number of tokens each sequence produced,
  * the end token included.  When every sequence has ended, the remaining steps are skipped (the count
- * of running sequences is read back every 16 steps, which synchronises cfg.stream).  Rows of a
- * batch of at most 32 share one matrix-core tile, so ended sequences are not compacted away: their
- * attention is skipped and their rows ride along in the GEMMs at no cost. */
+ * of running sequences is read back every 16 steps, which synchronises cfg.stream).  A sequence that has
+ * ended skips attention at once; at those read-backs, on the HE_BF16 path, the rows of ended sequences are
+ * dropped from the following steps whenever that makes a step cheaper (the row count falls to fewer 16-row
+ * halves of the weight-streaming GEMMs' activation slices, up to 64 rows, or to fewer 128-row matrix-core
+ * tiles above): the running sequences move up in order, every result still goes to its sequence's place,
+ * and the sampling noise stays keyed by the sequence's number b -- results do not depend on it. */
 he_status he_prefill_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S,
                             const he_sampling* sampling, int32_t* d_next_ids, float* d_logprobs, float* d_logits_opt);
 he_status he_generate_ragged(he_engine* e, const int32_t* d_prompt_ids, const int32_t* d_prompt_lens, int B, int S, int G,
@@ -271,6 +274,9 @@ const char* he_last_error(const he_engine* e);
 
 /* Current number of cached positions per sequence, or -1 if e is NULL. */
 int he_cache_len(const he_engine* e);
+/* Test hook: rows of the last decode step of the last he_generate / he_generate_ragged (fewer than its batch once
+ * he_generate_ragged has dropped the rows of ended sequences); -1 for a NULL engine. */
+int he_last_step_rows(const he_engine* e);
 
 /* Measurement hook (bf16 path).  While on, he_prefill / he_decode_step / he_generate
  * launch their decode-shaped kernels one by one (no graph replay) and bracket every

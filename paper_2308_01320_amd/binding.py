@@ -129,6 +129,8 @@ def lib() -> C.CDLL:
     L.he_decode_scratch_account.argtypes = [C.POINTER(he_config), C.c_int, C.c_int, C.c_int, C.POINTER(he_scratch_account)]
     L.he_arrival_counters_nonzero.restype = C.c_int
     L.he_arrival_counters_nonzero.argtypes = [vp, C.POINTER(C.c_int)]
+    L.he_last_step_rows.restype = C.c_int
+    L.he_last_step_rows.argtypes = [vp]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -145,7 +147,7 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_tile_matrix", "he_score", "he_prefill_ragged",
            "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena",
            "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows", "he_decode_step_static",
-           "he_decode_scratch_account", "he_arrival_counters_nonzero")
+           "he_decode_scratch_account", "he_arrival_counters_nonzero", "he_last_step_rows")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -210,6 +212,9 @@ class Engine:
 
     def last_error(self) -> str:
         return (lib().he_last_error(self.handle) or b"").decode()
+
+    def he_last_step_rows(self) -> int:
+        return lib().he_last_step_rows(self.handle)
 
     def cache_len(self) -> int:
         return lib().he_cache_len(self.handle)

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     __shared__ float red[8];
     __shared__ float ored[4][LPK * 8];
     const int m = blockIdx.x, h = blockIdx.y;
-    const int b = m / S, T = seq_len(st, b) + (m % S) - row_pad(st, b) + 1;
+    const int b = row_seq(st, m, S), T = seq_len(st, b) + (m % S) - row_pad(st, b) + 1;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane % LPK, grp = lane / LPK;
     if (seq_done(st, b)) return;  // the sequence has ended: its row's output is not used any more

@@ -161,7 +161,7 @@ __device__ __forceinline__ void epilogue4(const Epi& p, int m, int n0, int ks, f
                 make_float4(v0 * p.qscale, v1 * p.qscale, v2 * p.qscale, v3 * p.qscale);
         } else {
             const int which = n0 >= 2 * p.H, c = n0 - (which ? 2 * p.H : p.H);
-            const int b = m / p.S;
+            const int b = row_seq(p.st, m, p.S);
             int t = cur_len + (m % p.S);
             if (cur_len < 0) {  // sequences of different lengths; padding rows append nothing
                 const int tr = m % p.S - row_pad(p.st, b);

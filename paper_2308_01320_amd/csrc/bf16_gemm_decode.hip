@@ -396,6 +396,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
             const int t = i0 >> 5, mm = mt * 32 + (i0 & 31), tile = grp * NT + t;
             if (mm >= p.M || tile >= n_tiles) continue;
             const int mode = p.st->mode, step = p.st->step;
+            const uint32_t seq = (uint32_t)row_seq(p.st, mm, 1);  // the noise is keyed by the sequence, not by its row
             const float temp = p.st->temperature;
             const uint32_t k0 = p.st->seed_lo, k1 = p.st->seed_hi;
             float mx = -INFINITY, best = -INFINITY, bestz = 0.f;
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const u32x4* __
                 mx = fmaxf(mx, z);
                 float s = z;
                 if (mode == 1)
-                    s = z / temp + gumbel_from_word(philox_word0((uint32_t)vid, (uint32_t)step, (uint32_t)mm, k0, k1));
+                    s = z / temp + gumbel_from_word(philox_word0((uint32_t)vid, (uint32_t)step, seq, k0, k1));
                 if (s > best) { best = s; besti = vid; bestz = z; }  // ascending ids: strict > keeps the lowest
             }
             float sum = 0.f;
@@ -723,10 +724,11 @@ __global__ void lm_reduce_kernel(const float* __restrict__ stats, const int* __r
         best = sbest[0]; bi = sidx[0]; bz = sz[0];
         for (int w = 1; w < 4; ++w)
             if (sbest[w] > best || (sbest[w] == best && sidx[w] < bi)) { best = sbest[w]; bi = sidx[w]; bz = sz[w]; }
-        const size_t at = (size_t)b * out_stride + (out_at_step ? st->step : 0);
+        const int q = row_seq(st, b, 1);  // outputs and the next input belong to the row's sequence
+        const size_t at = (size_t)q * out_stride + (out_at_step ? st->step : 0);
         ids_out[at] = bi;
         lp_out[at] = bz - (mx + logf(sum));
-        if (cur_ids) cur_ids[b] = bi;
+        if (cur_ids) cur_ids[q] = bi;
     }
 }
 

@@ -424,7 +424,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
             row = (size_t)(m >> 5) * (p.N >> 4) * 64 + 32 * hh + (m & 31);
         } else {
             row = (size_t)m * p.H + 4 * hh;
-            const int b = m / p.S, r = m - b * p.S;
+            const int b = row_seq(p.st, m, p.S), r = m % p.S;
             int t = cur_len + r;
             if (cur_len < 0) {  // sequences of different lengths; padding rows append nothing
                 const int tr = r - row_pad(p.st, b);
@@ -508,17 +508,9 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restr
 
 
 // Many rows (a prompt or scoring pass): 256 x 256 tiles, one workgroup per CU, once there are enough of them to
-// give every CU one.  HE_TILED_SHAPE (tuning aid, read once): 0 = never.
-static int big_tile_shape() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("HE_TILED_SHAPE");
-        v = e ? atoi(e) : 1;
-    }
-    return v;
-}
+// give every CU one.
 static bool use_big_tile(int M, int N) {
-    return big_tile_shape() != 0 && M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
+    return M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
 }
 
 template <int MODE>

@@ -205,9 +205,10 @@ __global__ __launch_bounds__(64) void embed_ln_kernel(const int32_t* __restrict_
                                                       float* __restrict__ r, u32x4* __restrict__ xb,
                                                       float2* __restrict__ stats) {
     const int g = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
-    int id = ids[(size_t)m * id_stride];
+    const int b = row_seq(st, m, 1);  // one row per running sequence here
+    int id = ids[(size_t)b * id_stride];
     id = id < 0 ? 0 : (id >= V ? V - 1 : id);
-    const size_t prow = (size_t)(seq_len(st, m) + pos_offset);  // one row per sequence here
+    const size_t prow = (size_t)(seq_len(st, b) + pos_offset);
     const int cols = min(gw, H - g * gw), c0 = g * gw + 4 * lane;
     const bool live = 4 * lane < cols;
     float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f;

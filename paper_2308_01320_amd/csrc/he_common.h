@@ -22,12 +22,14 @@ struct he_dev_state {
     int reserved[5];
     // [0 .. max_batch): cached positions of sequence b;  [max_batch .. 2 max_batch): left padding of
     // the rows now going through the model (0 outside a prompt pass);  [2 .. 3 max_batch): 1 once the
-    // sequence has produced eos_id;  [3 .. 4 max_batch): tokens produced so far
+    // sequence has produced eos_id;  [3 .. 4 max_batch): tokens produced so far;  [4 .. 5 max_batch): the
+    // sequence whose token goes through row r of a decode step (r itself, until he_generate_ragged drops the
+    // rows of sequences that have ended)
     int seq[1];
 };
 
 __host__ __device__ inline size_t he_dev_state_bytes(int max_batch) {
-    return sizeof(he_dev_state) + (size_t)4 * max_batch * sizeof(int);
+    return sizeof(he_dev_state) + (size_t)5 * max_batch * sizeof(int);
 }
 // positions of sequence b already in the cache
 __device__ __forceinline__ int seq_len(const he_dev_state* st, int b) { return st->ragged ? st->seq[b] : st->cur_len; }
@@ -35,6 +37,12 @@ __device__ __forceinline__ int seq_len(const he_dev_state* st, int b) { return s
 __device__ __forceinline__ int row_pad(const he_dev_state* st, int b) { return st->ragged ? st->seq[st->max_batch + b] : 0; }
 __device__ __forceinline__ bool seq_done(const he_dev_state* st, int b) {
     return st->ragged && st->seq[2 * st->max_batch + b] != 0;
+}
+// The sequence of row m of a pass of S rows per sequence.  Rows of a decode step (S = 1) go through the map;
+// cache slot, per-sequence state, sampling noise and outputs belong to the sequence, activations to the row.
+__device__ __forceinline__ int row_seq(const he_dev_state* st, int m, int S) {
+    if (S != 1) return m / S;
+    return st->ragged ? st->seq[4 * st->max_batch + m] : m;
 }
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }

@@ -66,6 +66,7 @@ struct he_engine {
     size_t kv_bytes = 0;
     bool ragged_gen = false;   // he_generate_ragged is running: sampling is followed by the end-token bookkeeping
     int* host_active = nullptr;  // pinned: sequences still generating, read back every few steps
+    int last_rows = 0;           // rows of the last decode step of the last he_generate / he_generate_ragged
     std::string err;
 };
 
@@ -663,6 +664,12 @@ he_status run_forward(he_engine* e, const int32_t* d_ids, int B, int S, int32_t*
     return check_hip(e, hipGetLastError(), "kernel launch");
 }
 
+// What a decode step of `rows` rows costs, as far as the row count decides it: 16-row halves of the activation
+// slices the weight-streaming GEMMs multiply by (up to 64 rows), 128-row tiles of the matrix-core GEMMs above.
+int step_cost_class(const he_engine* e, int rows) {
+    return wide_decode(e, rows) ? 4 + (rows + 127) / 128 : (rows + 15) / 16;
+}
+
 void drop_step_graph(he_engine* e) {
     if (e->step_graph) (void)hipGraphExecDestroy(e->step_graph);
     e->step_graph = nullptr;
@@ -1050,23 +1057,34 @@ static he_status generate_impl(he_engine* e, const char* who, const int32_t* d_p
     const bool use_graph = e->stream != nullptr && !e->timing && G > 2;
     if (use_graph) rc = ensure_step_graph(e, B, G);
     // With an end token, the number of sequences still running is read back every kCheck steps
-    // (one small copy and a stream synchronisation): once it is zero the remaining steps are skipped.
+    // (one small copy and a stream synchronisation): once it is zero the remaining steps are skipped, and once
+    // enough sequences have ended for the step to get cheaper, their rows are dropped (bf16 path): the running
+    // sequences move up in order, the following steps run on that many rows (a new graph for the new count).
     constexpr int kCheck = 16;
+    int rows = B;  // rows of a decode step: row r carries the r-th running sequence
     for (int n = 1; n < G && rc == HE_OK; ++n) {
         if (use_graph) {
             rc = check_hip(e, hipGraphLaunch(e->step_graph, e->stream), "hipGraphLaunch");
             e->cur_len += 1;
             e->step += 1;
         } else {
-            rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
+            rc = run_forward(e, e->cur_ids, rows, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
         }
         if (rc == HE_OK && ragged && eos_id >= 0 && n % kCheck == 0 && n + 1 < G) {
             hipError_t r = hipMemcpyAsync(e->host_active, &e->st->n_active, sizeof(int), hipMemcpyDeviceToHost, e->stream);
             if (r == hipSuccess) r = hipStreamSynchronize(e->stream);
             rc = check_hip(e, r, "reading the active count");
-            if (rc == HE_OK && *e->host_active == 0) break;
+            const int active = *e->host_active;
+            if (rc == HE_OK && active == 0) break;
+            if (rc == HE_OK && e->fast && active < rows && step_cost_class(e, active) < step_cost_class(e, rows)) {
+                launch_compact_rows(e->stream, e->st, rows);
+                rows = active;
+                if (use_graph) rc = ensure_step_graph(e, rows, G);
+            }
         }
     }
+    e->last_rows = rows;
+    if (rows != B) launch_identity_rows(e->stream, e->st);  // later he_decode_step calls: one row per sequence again
     if (rc != HE_OK) return rc;
     launch_copy_out(e->stream, e->gen_ids, e->gen_lp, d_out_ids, d_out_logprobs, B * G);
     if (ragged) launch_copy_lens(e->stream, e->st, d_out_lens, B);
@@ -1179,6 +1197,7 @@ he_status he_timing_read(he_engine* e, double* ms_per_class, long* launches_per_
 const char* he_last_error(const he_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
 
 int he_cache_len(const he_engine* e) { return e ? e->cur_len : -1; }
+int he_last_step_rows(const he_engine* e) { return e ? e->last_rows : -1; }
 
 size_t he_tiled_bytes(int rows, int cols) {
     if (rows <= 0 || cols <= 0 || cols % 16) return 0;

@@ -32,6 +32,10 @@ void launch_init_state(hipStream_t s, he_dev_state* st, int max_batch);
 void launch_set_ragged(hipStream_t s, he_dev_state* st, const int32_t* lens, int B, int S, int eos_id, int pad_id);
 void launch_ragged_post(hipStream_t s, he_dev_state* st, int32_t* gen_ids, float* gen_lp, int32_t* cur_ids, int G, int B);
 void launch_fill_gen(hipStream_t s, int32_t* ids, float* lp, int count, const he_dev_state* st);
+// Drops the rows of sequences that have ended from the row -> sequence map of the decode steps (`rows` rows so far;
+// afterwards as many as sequences are running), and the map back to one row per sequence.
+void launch_compact_rows(hipStream_t s, he_dev_state* st, int rows);
+void launch_identity_rows(hipStream_t s, he_dev_state* st);
 void launch_copy_lens(hipStream_t s, const he_dev_state* st, int32_t* out, int B);
 void launch_rng_words(hipStream_t s, uint64_t seed, uint32_t b, uint32_t n, uint32_t v0, int count, uint32_t* out);
 void launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);

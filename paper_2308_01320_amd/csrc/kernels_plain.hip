@@ -35,7 +35,7 @@ template <typename ST>
 __global__ void embed_kernel(const int32_t* __restrict__ ids, int id_stride, const ST* __restrict__ tok,
                              const ST* __restrict__ pos, float* __restrict__ x, const he_dev_state* __restrict__ st,
                              int S, int H, int V, int pos_offset) {
-    const int m = blockIdx.x, b = m / S, t = m % S - row_pad(st, b);
+    const int m = blockIdx.x, b = row_seq(st, m, S), t = m % S - row_pad(st, b);
     if (t < 0) {  // a padding row: not a token, nothing downstream uses it
         for (int i = threadIdx.x; i < H; i += blockDim.x) x[(size_t)m * H + i] = 0.f;
         return;
@@ -251,6 +251,7 @@ __global__ void set_state_kernel(he_dev_state* st, int cur_len, int step, int se
 
 __global__ void init_state_kernel(he_dev_state* st, int max_batch) {
     for (int i = threadIdx.x; i < 4 * max_batch; i += blockDim.x) st->seq[i] = 0;
+    for (int i = threadIdx.x; i < max_batch; i += blockDim.x) st->seq[4 * max_batch + i] = i;
     if (threadIdx.x == 0) {
         st->cur_len = 0; st->step = 0; st->mode = 0; st->temperature = 1.f; st->seed_lo = st->seed_hi = 0u;
         st->ragged = 0; st->max_batch = max_batch; st->eos_id = -1; st->pad_id = 0; st->n_active = 0;
@@ -268,6 +269,7 @@ __global__ void set_ragged_kernel(he_dev_state* st, const int32_t* __restrict__ 
         st->seq[mb + b] = S - n;
         st->seq[2 * mb + b] = 0;
         st->seq[3 * mb + b] = 0;
+        st->seq[4 * mb + b] = b;
     }
     if (threadIdx.x == 0) { st->ragged = 1; st->eos_id = eos_id; st->pad_id = pad_id; st->n_active = B; }
 }
@@ -295,7 +297,8 @@ __global__ void ragged_post_kernel(he_dev_state* st, int32_t* __restrict__ gen_i
     if (threadIdx.x == 0) active = 0;
     __syncthreads();
     const int mb = st->max_batch, n = st->step;
-    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    for (int r = threadIdx.x; r < B; r += blockDim.x) {  // the B rows of the step (sequences without a row have ended)
+        const int b = st->seq[4 * mb + r];
         const size_t at = (size_t)b * G + n;
         if (st->seq[2 * mb + b]) {
             gen_ids[at] = st->pad_id;
@@ -309,6 +312,25 @@ __global__ void ragged_post_kernel(he_dev_state* st, int32_t* __restrict__ gen_i
     }
     __syncthreads();
     if (threadIdx.x == 0) st->n_active = active;
+}
+
+// he_generate_ragged, between two steps: the rows of sequences that have ended are dropped, the others move up
+// in order.  rows: rows of the steps so far (new count = the running sequences: st->n_active).  One thread: the
+// order has to be the same every time, and there are a few hundred rows at most.
+__global__ void compact_rows_kernel(he_dev_state* st, int rows) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int mb = st->max_batch;
+    int k = 0;
+    for (int r = 0; r < rows; ++r) {
+        const int b = st->seq[4 * mb + r];
+        if (!st->seq[2 * mb + b]) st->seq[4 * mb + k++] = b;
+    }
+    for (; k < mb; ++k) st->seq[4 * mb + k] = k;  // (not in use: any valid sequence number)
+}
+// ... and back to one row per sequence, in sequence order.
+__global__ void identity_rows_kernel(he_dev_state* st) {
+    const int mb = st->max_batch;
+    for (int i = threadIdx.x; i < mb; i += blockDim.x) st->seq[4 * mb + i] = i;
 }
 
 __global__ void fill_gen_kernel(int32_t* ids, float* lp, int count, const he_dev_state* st) {
@@ -445,6 +467,8 @@ void launch_set_ragged(hipStream_t s, he_dev_state* st, const int32_t* lens, int
 void launch_ragged_post(hipStream_t s, he_dev_state* st, int32_t* gen_ids, float* gen_lp, int32_t* cur_ids, int G, int B) {
     ragged_post_kernel<<<1, 256, 0, s>>>(st, gen_ids, gen_lp, cur_ids, G, B);
 }
+void launch_compact_rows(hipStream_t s, he_dev_state* st, int rows) { compact_rows_kernel<<<1, 64, 0, s>>>(st, rows); }
+void launch_identity_rows(hipStream_t s, he_dev_state* st) { identity_rows_kernel<<<1, 256, 0, s>>>(st); }
 void launch_fill_gen(hipStream_t s, int32_t* ids, float* lp, int count, const he_dev_state* st) {
     fill_gen_kernel<<<(count + 255) / 256, 256, 0, s>>>(ids, lp, count, st);
 }

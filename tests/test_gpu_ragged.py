@@ -139,6 +139,59 @@ def test_generate_ragged_with_end_token(dtype, tol, mode):
     eng.he_destroy()
 
 
+@pytest.mark.parametrize("H,nh,fp8", [(128, 2, 0), (256, 2, 0), (128, 2, 1)])
+def test_generate_ragged_drops_rows_of_ended_sequences(H, nh, fp8):
+    """96 sequences, most of which end early (a vocabulary of 40 and near-uniform sampling: one in forty tokens is
+    the end token): the step starts on the matrix-core GEMMs of the wide path, and as the rows of ended sequences
+    are dropped at the read-backs it moves to two activation slices, one slice, half a slice.  Every sequence is
+    compared with the oracle's run of it alone; results must not depend on which row a sequence rides in."""
+    import torch
+    B, S, G, V = 96, 12, 72, 40
+    rng = np.random.default_rng(31)
+    lens = [int(x) for x in rng.integers(1, S + 1, B)]
+    d = synth.ModelDims("x", 2, H, nh, 2 * H, V, 128, B, S, G, "bf16", "gumbel")
+    w = synth.make_weights(d, seed=17, tied=True)
+    ids, prompts, ln = _ragged_batch(d, lens, S, 18)
+    eos, pad = 7, 1
+    wq = w
+    if fp8:
+        wq = {k: v for k, v in w.items()}
+        wq["layers"] = [{n: (O.quantize_e4m3_rows(a)[0] if n in ("wqkv", "wo", "w1", "w2") else a) for n, a in lw.items()}
+                        for lw in w["layers"]]
+    want = O.generate_ragged(_f64(wq, True), prompts, G, d.n_heads, mode="gumbel", seed=5, eos_id=eos, pad_id=pad,
+                             eps=d.ln_eps)
+    ended_early = int((want["lens"] < G - 8).sum())
+    print("oracle: sequences that end more than 8 steps before the cap:", ended_early, flush=True)
+    assert ended_early > B // 2
+    stream = torch.cuda.Stream()
+    eng = binding.Engine(binding.make_config(d, max_batch=B, max_seq_len=S + G, stream=stream.cuda_stream, weights_fp8=fp8),
+                         binding.upload_weights(w, d.dtype))
+    samp = binding.sampling("gumbel", 1.0, 5)
+    with torch.cuda.stream(stream):
+        gi, glp, gl = eng.he_generate_ragged(torch.from_numpy(ids).cuda(), torch.from_numpy(ln).cuda(), G, samp, eos, pad)
+        torch.cuda.synchronize()
+        rows = eng.he_last_step_rows()
+        n = _compare_generation(gi.cpu().numpy(), glp.cpu().numpy(), gl.cpu().numpy(), want, BF16_TOL, eos, pad)
+        print("compared", n, "tokens; rows of the last step", rows, flush=True)
+        assert n >= 10 * B
+        assert rows <= 64, rows  # rows were dropped: the last steps ran on the weight-streaming GEMMs
+        assert eng.he_arrival_counters_nonzero() == 0
+        # a second run is bit-identical, and the engine goes on as before: one row per sequence again
+        gi2, glp2, gl2 = eng.he_generate_ragged(torch.from_numpy(ids).cuda(), torch.from_numpy(ln).cuda(), G, samp, eos, pad)
+        torch.cuda.synchronize()
+        assert torch.equal(gi, gi2) and torch.equal(glp, glp2) and torch.equal(gl, gl2)
+        a_ids, a_lp, a_len = eng.he_generate_ragged(torch.from_numpy(ids).cuda(), torch.from_numpy(ln).cuda(), 6, samp, -1, pad)
+        torch.cuda.synchronize()
+        assert eng.he_last_step_rows() == B and (a_len == 6).all()
+        # without an end token nothing is dropped, and the first tokens are those of the run above wherever that
+        # run had not met its end token yet
+        g, a, own = gi.cpu().numpy(), a_ids.cpu().numpy(), gl.cpu().numpy()
+        for q in range(B):
+            k = min(6, int(own[q]))
+            assert (a[q, :k] == g[q, :k]).all(), q
+    eng.he_destroy()
+
+
 def test_ragged_with_equal_lengths_is_plain_generation_and_stops_early():
     import torch
     B, S, G = 5, 12, 40
