@@ -47,7 +47,8 @@ struct he_engine {
     float* tail_buf = nullptr;  // prompt pass: residual and query rows of each sequence's last token, 2 x [max_batch][H]
 
     // one decode step captured as a HIP graph (he_generate replays it); keyed by (B, G)
-    hipGraphExec_t step_graph = nullptr;
+    hipGraphExec_t step_graph = nullptr;   // one decode step of he_generate
+    hipGraphExec_t multi_graph = nullptr;  // kGraphSteps of them in a row (nullptr if the answer is shorter)
     int graph_B = 0, graph_G = 0;
     bool graph_ragged = false;
 
@@ -672,20 +673,23 @@ int step_cost_class(const he_engine* e, int rows) {
 
 void drop_step_graph(he_engine* e) {
     if (e->step_graph) (void)hipGraphExecDestroy(e->step_graph);
-    e->step_graph = nullptr;
+    if (e->multi_graph) (void)hipGraphExecDestroy(e->multi_graph);
+    e->step_graph = e->multi_graph = nullptr;
     e->graph_B = e->graph_G = 0;
     e->graph_ragged = false;
 }
 
-// Captures one decode step of he_generate (input ids from cur_ids, outputs into the
-// engine's [B, G] generation buffers at the device-side step index).
-he_status ensure_step_graph(he_engine* e, int B, int G) {
-    if (e->step_graph && e->graph_B == B && e->graph_G == G && e->graph_ragged == e->ragged_gen) return HE_OK;
-    drop_step_graph(e);
+// Decode steps of he_generate as HIP graphs (input ids from cur_ids, outputs into the engine's [B, G] generation
+// buffers at the device-side step index): one step, and kGraphSteps steps in a row -- between two graph launches
+// the device idles for 8-9 us, between two kernels of one graph for 0.7.
+constexpr int kGraphSteps = 8;
+
+he_status capture_steps(he_engine* e, int B, int G, int steps, hipGraphExec_t* out) {
     const int len = e->cur_len, step = e->step;
     hipError_t r = hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal);
     if (r != hipSuccess) return check_hip(e, r, "hipStreamBeginCapture");
-    const he_status rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
+    he_status rc = HE_OK;
+    for (int i = 0; i < steps && rc == HE_OK; ++i) rc = run_forward(e, e->cur_ids, B, 1, e->gen_ids, e->gen_lp, G, 1, nullptr);
     e->cur_len = len;  // capturing runs nothing
     e->step = step;
     hipGraph_t g = nullptr;
@@ -695,11 +699,25 @@ he_status ensure_step_graph(he_engine* e, int B, int G) {
         return rc;
     }
     if (r != hipSuccess) return check_hip(e, r, "hipStreamEndCapture");
-    r = hipGraphInstantiate(&e->step_graph, g, nullptr, nullptr, 0);
+    r = hipGraphInstantiate(out, g, nullptr, nullptr, 0);
     (void)hipGraphDestroy(g);
     if (r != hipSuccess) {
-        e->step_graph = nullptr;
+        *out = nullptr;
         return check_hip(e, r, "hipGraphInstantiate");
+    }
+    return HE_OK;
+}
+
+he_status ensure_step_graph(he_engine* e, int B, int G) {
+    if (e->step_graph && e->graph_B == B && e->graph_G == G && e->graph_ragged == e->ragged_gen) return HE_OK;
+    drop_step_graph(e);
+    he_status rc = capture_steps(e, B, G, 1, &e->step_graph);
+    // (the run of steps is captured where it is first needed: a call that is already close to its last step, as
+    // after rows were dropped late in an answer, gets along with the single step)
+    if (rc == HE_OK && G - 1 - e->step >= 2 * kGraphSteps) rc = capture_steps(e, B, G, kGraphSteps, &e->multi_graph);
+    if (rc != HE_OK) {
+        drop_step_graph(e);
+        return rc;
     }
     e->graph_B = B;
     e->graph_ragged = e->ragged_gen;
@@ -1061,9 +1079,15 @@ static he_status generate_impl(he_engine* e, const char* who, const int32_t* d_p
     // enough sequences have ended for the step to get cheaper, their rows are dropped (bf16 path): the running
     // sequences move up in order, the following steps run on that many rows (a new graph for the new count).
     constexpr int kCheck = 16;
+    static_assert(kCheck % kGraphSteps == 0, "a run of steps ends where the running count is read back, not beyond");
     int rows = B;  // rows of a decode step: row r carries the r-th running sequence
-    for (int n = 1; n < G && rc == HE_OK; ++n) {
-        if (use_graph) {
+    for (int n = 1; n < G && rc == HE_OK; ++n) {  // n: the step about to run; after the body, the last one that ran
+        if (use_graph && e->multi_graph && (n - 1) % kGraphSteps == 0 && n + kGraphSteps <= G) {
+            rc = check_hip(e, hipGraphLaunch(e->multi_graph, e->stream), "hipGraphLaunch");
+            e->cur_len += kGraphSteps;
+            e->step += kGraphSteps;
+            n += kGraphSteps - 1;
+        } else if (use_graph) {
             rc = check_hip(e, hipGraphLaunch(e->step_graph, e->stream), "hipGraphLaunch");
             e->cur_len += 1;
             e->step += 1;
