@@ -366,6 +366,9 @@ def main():
         "value": B * G * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        # the model is bf16 (weights, biases, LayerNorm parameters); the matrix cores take those weights converted
+        # exactly to IEEE binary16 and activations / KV cache rounded once to binary16, and accumulate in f32
+        "arithmetic": "bf16 model; fp16 MFMA operands (weights converted exactly), f32 accumulation",
         "config": {"workload": f"{d.name}-shaped actor, {d.n_layers} layers, hidden {H}, {d.n_heads} heads, ffn {F}, "
                                f"vocab {d.vocab}; batch {B}, prompt {S}, generate {G}, {d.sampling} sampling"
                                + ("; layer matrices stored as 8-bit E4M3 codes" if args.weights_fp8 else ""),

@@ -276,21 +276,29 @@ constexpr int BSTAGES = 4;
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ X,
                                                                const u32x4* __restrict__ bias8, int KB, int NT32, int MT32,
-                                                               int tiles_n, int tiles_m, int ksplit, Epi p) {
+                                                               int tiles_n, int tiles_m, int ksplit, int split_tn, Epi p) {
     // ring[stage][block][lane]; blocks of a stage: W row-tile i, k-block j at 2 i + j; X row-tile i at 16 + 2 i + j
     __shared__ u32x4 ring[BSTAGES][32][64];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int nblk = tiles_n * tiles_m;
-    const int nitem = nblk * ksplit;
+    // Work items, in launch order: the tiles of the first split_tn columns of tiles with their whole k range, then
+    // the tiles of the other columns once per k range (k range after k range).  Each of the two parts is dealt out
+    // so that an XCD gets a contiguous run of it.
+    const int n_whole = split_tn * tiles_m, whole_pad = (n_whole + 7) / 8 * 8;
+    const bool cut = (int)blockIdx.x >= whole_pad;
+    const int idx = cut ? blockIdx.x - whole_pad : blockIdx.x;
+    const int cols = cut ? tiles_n - split_tn : split_tn;  // columns of tiles of this part
+    const int nblk = cols * tiles_m;
+    const int nitem = cut ? nblk * ksplit : nblk;
     const int per_xcd = (nitem + 7) / 8;
-    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;  // an XCD gets a contiguous run of tiles
+    const int item = (idx % 8) * per_xcd + idx / 8;
     if (item >= nitem) return;
-    const int lin = item % nblk, ks = item / nblk;  // k range after k range
+    const int lin = item % nblk, ks = item / nblk;
+    const int nks = cut ? ksplit : 1;  // k ranges of this tile
     constexpr int GROUP = 4;  // m-tiles per super-row: the 32 tiles an XCD works on at once share 4 X panels and 8 W panels
-    const int gsize = GROUP * tiles_n;
+    const int gsize = GROUP * cols;
     const int g = lin / gsize, first_m = g * GROUP;
     const int gm = min(GROUP, tiles_m - first_m);
-    const int tm = first_m + (lin % gsize) % gm, tn = (lin % gsize) / gm;
+    const int tm = first_m + (lin % gsize) % gm, tn = (cut ? split_tn : 0) + (lin % gsize) / gm;
     const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 128 (m) sub-tile
     const int cur_len = epilogue_len<MODE>(p);
     f32x16 acc[4][4];
@@ -300,8 +308,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{};
 
     const int nst_all = KB / 2;  // KB is even (K % 32 == 0)
-    const int st0 = (int)((long)ks * nst_all / ksplit);
-    const int nstage = (int)((long)(ks + 1) * nst_all / ksplit) - st0;
+    const int st0 = (int)((long)ks * nst_all / nks);
+    const int nstage = (int)((long)(ks + 1) * nst_all / nks) - st0;
     // this wavefront copies W row-tiles 2w, 2w+1 and X row-tiles 2w, 2w+1 of every stage (tiles past the matrix: the last one)
     const u32x4* src[4];
 #pragma unroll
@@ -513,8 +521,10 @@ static bool use_big_tile(int M, int N) {
     return M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
 }
 
+// split_col: with a k-split on 256 x 256 tiles, the first column whose tiles are cut into k ranges (0: all of them)
 template <int MODE>
-void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p, int ksplit = 1) {
+void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p, int ksplit = 1,
+                  int split_col = 0) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
     // (the scoring head's epilogue keeps a soft-max over all of a wavefront's accumulators: it does not fit next to 16 of them)
     const bool big = MODE != MODE_SCORE && use_big_tile(M, N);
@@ -526,8 +536,11 @@ void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N,
         if (big) {
             // (the bias through a pointer of its own: declared never to alias the outputs, its values can be fetched
             // with scalar loads, which do not queue behind the epilogue's stores)
-            gemm_tiled256_kernel<MODE><<<grid, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias, KB, NT32,
-                                                            MT32, tiles_n, tiles_m, ksplit, p);
+            const int split_tn = ksplit > 1 ? split_col / BN : tiles_n;  // without a k-split every tile is whole
+            const int whole = split_tn * tiles_m, cutn = (tiles_n - split_tn) * tiles_m * ksplit;
+            const int grid2 = (whole + 7) / 8 * 8 + (cutn + 7) / 8 * 8;
+            gemm_tiled256_kernel<MODE><<<grid2, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias, KB,
+                                                             NT32, MT32, tiles_n, tiles_m, ksplit, split_tn, p);
             return;
         }
     }
@@ -597,6 +610,31 @@ int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
     return best;
 }
 
+// The same decision for the 256 x 256 tiles, which can cut the tiles of the last columns only: *split_col is the
+// first column whose tiles are cut into *ks k ranges (0: all; columns before it get one whole-k sum).  The whole
+// tiles come first, in rounds of one per CU, and the cut ones fill the last, shorter round: 640 tiles on 256 CUs
+// are two rounds of whole tiles and one of 256 half tiles, with a second set of partial sums for a fifth of the
+// columns only.  Other tile shapes: bf16_tiled_store_ksplit, every tile cut.
+void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col) {
+    *ks = bf16_tiled_store_ksplit(M, N, K, capacity_floats);
+    *split_col = 0;
+    const int KB = K / 16;
+    if (!use_big_tile(M, N) || KB % 4 || KB / 2 < 8 * BSTAGES || (size_t)2 * M * N > capacity_floats) return;
+    const long cus = num_cus(), tn = (N + BN - 1) / BN, tm = (M + BM - 1) / BM;
+    double best = 1e30;
+    int best_s = -1;
+    for (long s = 0; s <= tn; ++s) {  // s columns of tiles cut in two
+        const long whole = (tn - s) * tm, cutn = 2 * s * tm;
+        // in units of one whole-k tile; a cut tile costs a little more than half (its own ramp and epilogue),
+        // and every cut column a second set of partial sums for the LayerNorm to read
+        const double cost = (double)((whole + cus - 1) / cus) + 0.52 * (double)((cutn + cus - 1) / cus) + 0.004 * s;
+        if (cost < best - 1e-9) { best = cost; best_s = (int)s; }
+    }
+    if (best_s == 0) { *ks = 1; return; }
+    *ks = 2;
+    *split_col = (int)(tn - best_s) * BN;
+}
+
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,
                             int ksplit, float* part, size_t part_split, const bf16_gemm_args& a) {
     if (ksplit == 1 && mode != EPI_STORE) {  // the tiles alone fill the chip: the epilogue runs in the GEMM
@@ -606,7 +644,7 @@ void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void*
     bf16_gemm_args st = a;
     st.out = part; st.out_split = part_split;
     const Epi ps = make_epi(M, N, st);
-    launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, ps, ksplit);
+    launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, ps, ksplit, a.split_col);
     if (mode == EPI_STORE) return;  // the consumer (a LayerNorm) adds the partial sums
     const Epi p = make_epi(M, N, a);
     const unsigned grid = (unsigned)(((size_t)M * (N / 4) + 255) / 256);

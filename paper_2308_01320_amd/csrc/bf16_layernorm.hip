@@ -14,7 +14,8 @@ __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, 
                                                         const bf16_t* __restrict__ pbias,
                                                         const bf16_t* __restrict__ gamma,
                                                         const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
-                                                        int H, float eps, int in_mul, int in_add, int writeback) {
+                                                        int H, float eps, int in_mul, int in_add, int writeback,
+                                                        int split_col) {
     extern __shared__ __align__(16) float row[];
     __shared__ float red[16];
     const int m = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwave = blockDim.x >> 6;
@@ -25,6 +26,7 @@ __global__ __launch_bounds__(1024) void ln_blocks_kernel(float* __restrict__ r, 
         float4 v = rr[i];
         if (part) {
             for (int k = 0; k < ksplit; ++k) {
+                if (k > 0 && 4 * i < split_col) break;  // columns before split_col have one whole sum
                 const float4 y = *reinterpret_cast<const float4*>(part + (size_t)k * part_split + src * H + 4 * i);
                 v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
             }
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
                                                       const bf16_t* __restrict__ gamma,
                                                       const bf16_t* __restrict__ beta, u32x4* __restrict__ a,
                                                       int H, float eps, int in_mul, int in_add, int writeback,
-                                                      int rows) {
+                                                      int rows, int split_col) {
     constexpr int NW = THREADS / 64;
     __shared__ float red[2][NW];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -116,7 +118,8 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
             pb[j] = make_uint2(0, 0);
             if (i >= nq) continue;
             y0[j] = *reinterpret_cast<const float4*>(part + src * H + 4 * i);
-            if (ksplit == 2) y1[j] = *reinterpret_cast<const float4*>(part + part_split + src * H + 4 * i);
+            // (columns before split_col have one whole sum; a multiple of 256, so the test is the same for a wavefront)
+            if (ksplit == 2 && 4 * i >= split_col) y1[j] = *reinterpret_cast<const float4*>(part + part_split + src * H + 4 * i);
             pb[j] = *reinterpret_cast<const uint2*>(pbias + 4 * i);
         }
 #pragma unroll
@@ -305,12 +308,13 @@ void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, c
 
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, int rows, int H, float eps, int in_mul, int in_add,
-             int writeback) {
+             int writeback, int split_col) {
+    if (split_col && (ksplit != 2 || split_col % 256)) split_col = 0;  // (only the two-range form knows partly cut rows)
     const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
 #define HE_LN_ROW(NV, T)                                                                                                \
     ln_row_kernel<NV, T><<<(T == 256 ? (rows + 255) / 256 * 256 : rows), T, 0, s>>>(                                    \
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks, \
-        H, eps, in_mul, in_add, writeback, rows)
+        H, eps, in_mul, in_add, writeback, rows, split_col)
     if (rows <= 256 && nv <= 3) {  // a decode step
         if (nv == 1) HE_LN_ROW(1, 1024);
         else if (nv == 2) HE_LN_ROW(2, 1024);
@@ -335,6 +339,6 @@ void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part
 #undef HE_LN_ROW
     ln_blocks_kernel<<<rows, 256, (size_t)H * sizeof(float), s>>>(
         r, part, ksplit, part_split, (const bf16_t*)pbias, (const bf16_t*)gamma, (const bf16_t*)beta, (u32x4*)a_blocks,
-        H, eps, in_mul, in_add, writeback);
+        H, eps, in_mul, in_add, writeback, split_col);
 }
 

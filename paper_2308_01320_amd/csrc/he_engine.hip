@@ -255,7 +255,8 @@ he_engine::Tiled layer_blocks(he_engine* e, int l) {
 // With `full` (the scoring pass) every layer is completed and the last FC2's output is left
 // pending, as k-split partial sums plus *pend_bias, for the final LayerNorm.
 void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, int Sp, bool full = false,
-                     const void** pend_bias = nullptr, int* pend_ksplit = nullptr, int advance = -1) {
+                     const void** pend_bias = nullptr, int* pend_ksplit = nullptr, int advance = -1,
+                     int* pend_split_col = nullptr) {
     const he_config& c = e->cfg;
     hipStream_t s = e->stream;
     const int M = B * Sp, H = c.hidden, F = c.ffn;
@@ -266,29 +267,33 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     const float* pend = nullptr;  // GEMM output not yet added to the residual stream
     const void* pend_b = nullptr;
     const size_t split = (size_t)M * H;
-    // k ranges per tile of the two GEMMs whose partial sums the next LayerNorm adds
-    const int kso = bf16_tiled_store_ksplit(M, H, H, e->part_floats), ks2 = bf16_tiled_store_ksplit(M, H, F, e->part_floats);
-    int pend_ks = 1;
+    // k ranges per tile of the two GEMMs whose partial sums the next LayerNorm adds, and the first column whose
+    // tiles are cut at all
+    int kso, sco, ks2, sc2;
+    bf16_tiled_store_split(M, H, H, e->part_floats, &kso, &sco);
+    bf16_tiled_store_split(M, H, F, e->part_floats, &ks2, &sc2);
+    int pend_ks = 1, pend_sc = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
         const he_engine::Tiled tw = layer_blocks(e, l);
-        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, M, H, c.ln_eps, 1, 0, 1);
+        bf16_ln(s, e->resid, pend, pend_ks, split, pend_b, lw.ln1_g, lw.ln1_b, e->ablk, M, H, c.ln_eps, 1, 0, 1, pend_sc);
         bf16_gemm_args a = base;
         a.layer = l; a.bias = lw.bqkv; a.out = e->qbuf; a.kv = e->kv; a.qscale = 1.0f / sqrtf((float)e->d);
         bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, M, 3 * H, H, a);
         if (l == c.n_layers - 1 && !full) break;
         bf16_attn(s, e->qbuf, e->kv, e->oblk, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
-        a = base;
+        a = base; a.split_col = sco;
         bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, M, H, H, kso, e->part, split, a);
-        bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, M, H, c.ln_eps, 1, 0, 1);
+        bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, M, H, c.ln_eps, 1, 0, 1, sco);
         a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
         bf16_gemm_tiled(s, EPI_BIAS_RELU, tw.w1, e->ablk, M, F, H, a);
-        a = base;
+        a = base; a.split_col = sc2;
         bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, M, H, F, ks2, e->part, split, a);
-        pend = e->part; pend_b = lw.b2; pend_ks = ks2;
+        pend = e->part; pend_b = lw.b2; pend_ks = ks2; pend_sc = sc2;
     }
     if (pend_bias) *pend_bias = pend_b;
     if (pend_ksplit) *pend_ksplit = pend_ks;
+    if (pend_split_col) *pend_split_col = pend_sc;
     if (advance < 0) advance = Sp;  // (the caller that finishes the last token itself advances by one row less)
     launch_advance_state(s, e->st, advance, 0);
     e->cur_len += advance;
@@ -1144,10 +1149,10 @@ he_status he_score(he_engine* e, const int32_t* d_ids, int B, int T, float* d_ou
     const int M = B * T, H = c.hidden, F = c.ffn, V = c.vocab;
     if (e->fast) {
         const void* pend_b = nullptr;
-        int pend_ks = 1;
-        pass_tiled_bf16(e, d_ids, T, B, T, true, &pend_b, &pend_ks);
+        int pend_ks = 1, pend_sc = 0;
+        pass_tiled_bf16(e, d_ids, T, B, T, true, &pend_b, &pend_ks, -1, &pend_sc);
         bf16_ln(s, e->resid, c.n_layers ? e->part : nullptr, pend_ks, (size_t)M * H, pend_b, e->w.lnf_g, e->w.lnf_b, e->ablk,
-                M, H, c.ln_eps, 1, 0, 0);
+                M, H, c.ln_eps, 1, 0, 0, pend_sc);
         bf16_score_head(s, e->lm_tiled, e->ablk, M, T, V, H, d_ids, e->score_stats, e->score_tgt, d_out_logprobs);
     } else {
         const int bf = e->bf16;

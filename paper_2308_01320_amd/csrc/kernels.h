@@ -46,6 +46,7 @@ struct bf16_gemm_args {
     const void* bias = nullptr;      // bf16 [N]
     float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
     size_t out_split = 0;            // elements between k-splits
+    int split_col = 0;               // EPI_STORE on 256 x 256 tiles with a k-split: first column that has one
     size_t out_capacity = 0;         // EPI_STORE_LN: floats `out` can hold (0 = not checked)
     void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled half output
     void* kv = nullptr;              // EPI_QKV
@@ -105,6 +106,8 @@ int bf16_tiled_ksplit(int M, int N, int K);
 // k ranges per tile for a many-row MODE_STORE GEMM whose tiles do not come out in whole rounds of one per CU
 // (1 if they do, or if ks x M x N partial sums do not fit capacity_floats)
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats);
+// ... and for the 256 x 256 tiles: *ks k ranges for the tiles of columns >= *split_col, one for the columns before
+void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col);
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, int ksplit,
                             float* part, size_t part_split, const bf16_gemm_args& a);
 // ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row
@@ -124,8 +127,9 @@ void bf16_lm_head(hipStream_t s, const void* Wp, const void* X, int B, int V, in
 int bf16_score_parts(int V);
 void bf16_score_head(hipStream_t s, const void* Wp, const void* X, int M, int S, int V, int K,
                      const int32_t* ids, float* stats, float* tgt, float* out);
+// split_col: with two k ranges, the first column that has the second partial sum (0: every column; a multiple of 256)
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, int rows, int H, float eps, int in_mul, int in_add,
-             int writeback);
+             int writeback, int split_col = 0);
 void bf16_attn(hipStream_t s, const float* q, const void* kv, void* o_blocks, const he_dev_state* st, int M, int S,
                int layer, int H, int n_heads, int max_batch, int max_seq);
