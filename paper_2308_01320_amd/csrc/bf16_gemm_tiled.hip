@@ -270,15 +270,37 @@ __device__ __forceinline__ void store16(void* dst, float a, float b, float c, fl
     *reinterpret_cast<f32x4*>(dst) = f32x4{a, b, c, d};
 }
 
-constexpr int BN = 256, BM = 256;  // tile of the big kernel
+// One matrix instruction with the accumulator tile pinned to a register file: the accumulation registers (VG =
+// false) or the vector registers.  Twenty accumulator tiles do not fit into the 256 accumulation registers, and left
+// to itself the compiler keeps them all there and moves the overflow in and out around every instruction (832 moves
+// per stage).  Written as assembly the instruction is opaque to the compiler's hazard recogniser: nothing but these
+// instructions touches an accumulator inside the k loop, and the caller waits out the matrix pipeline before the
+// epilogue reads them.
+template <bool VG>
+__device__ __forceinline__ void mfma_f16_pinned(f32x16& c, const u32x4& a, const u32x4& b) {
+    if constexpr (VG) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+constexpr int BM = 256;  // rows of X per tile of the big kernel; its width is 64 NA columns (NA = 4 or 5)
 constexpr int BSTAGES = 4;
 
-template <int MODE>
+// NA: 32-column blocks of a wavefront's sub-tile (its 32 NA x 128 accumulators: 4 NA tiles of 32 x 32).  NA = 4 is the
+// 256-column tile described above.  NA = 5, a 320-column tile, takes 18 KiB of operands for 80 matrix instructions
+// (a tenth fewer bytes per flop), keeps a fifth of its accumulators in the vector registers, and is chosen where
+// its tiles divide the matrix and the CUs better: at hidden size 5120 the QKV GEMM is six full rounds instead of
+// seven and a half, FC1 eight instead of ten, and the out-projection and FC2 two, with nothing left to cut along k.
+// Measured on 8192 rows with the same operands launch after launch: FC1 1506 -> 1391 us, the QKV shape 1187 -> 1048;
+// inside the prompt pass, where every launch streams new weights, 180.2 -> 177.2 ms for the pass on one box (with
+// the wide tile for QKV and FC1 only: 178.9).
+template <int MODE, int NA>
 __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ X,
                                                                const u32x4* __restrict__ bias8, int KB, int NT32, int MT32,
                                                                int tiles_n, int tiles_m, int ksplit, int split_tn, Epi p) {
-    // ring[stage][block][lane]; blocks of a stage: W row-tile i, k-block j at 2 i + j; X row-tile i at 16 + 2 i + j
-    __shared__ u32x4 ring[BSTAGES][32][64];
+    constexpr int BN = 64 * NA;       // columns of the tile
+    constexpr int XOFF = 4 * NA;      // blocks of a stage: W row-tile i, k-block j at 2 i + j; X row-tile i at XOFF + 2 i + j
+    constexpr int SB = 4 * NA + 16;   // blocks of a stage (two k-blocks of 2 NA W row-tiles and 8 X row-tiles)
+    __shared__ u32x4 ring[BSTAGES][SB][64];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     // Work items, in launch order: the tiles of the first split_tn columns of tiles with their whole k range, then
     // the tiles of the other columns once per k range (k range after k range).  Each of the two parts is dealt out
@@ -299,65 +321,75 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
     const int g = lin / gsize, first_m = g * GROUP;
     const int gm = min(GROUP, tiles_m - first_m);
     const int tm = first_m + (lin % gsize) % gm, tn = (cut ? split_tn : 0) + (lin % gsize) / gm;
-    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 128 (n) x 128 (m) sub-tile
+    const int wn = wave & 1, wm = wave >> 1;  // this wavefront's 32 NA (n) x 128 (m) sub-tile
     const int cur_len = epilogue_len<MODE>(p);
-    f32x16 acc[4][4];
+    f32x16 acc[NA][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{};
 
     const int nst_all = KB / 2;  // KB is even (K % 32 == 0)
     const int st0 = (int)((long)ks * nst_all / nks);
     const int nstage = (int)((long)(ks + 1) * nst_all / nks) - st0;
-    // this wavefront copies W row-tiles 2w, 2w+1 and X row-tiles 2w, 2w+1 of every stage (tiles past the matrix: the last one)
-    const u32x4* src[4];
+    // The SB blocks of a stage are copied by the four wavefronts, CW each: wavefront w copies blocks w CW .. w CW + CW - 1
+    // (block c < XOFF: W row-tile c / 2, k-block c % 2; else X row-tile (c - XOFF) / 2).  Row-tiles past the matrix:
+    // the last one (computed, never stored).
+    constexpr int CW = NA + 4;  // copies per wavefront and stage
+    const u32x4* src[CW];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        src[i] = Wp + ((size_t)min(tn * 8 + wave * 2 + i, NT32 - 1) * KB + (size_t)st0 * 2) * 64;
-        src[2 + i] = X + ((size_t)min(tm * 8 + wave * 2 + i, MT32 - 1) * KB + (size_t)st0 * 2) * 64;
+    for (int q = 0; q < CW; ++q) {
+        const int c = wave * CW + q;
+        const bool isw = c < XOFF;
+        const int rt = isw ? min(tn * 2 * NA + (c >> 1), NT32 - 1) : min(tm * 8 + ((c - XOFF) >> 1), MT32 - 1);
+        src[q] = (isw ? Wp : X) + ((size_t)rt * KB + (size_t)st0 * 2 + (c & 1)) * 64 + lane;
     }
-    // copy q (0..7) of a stage: x = q / 4 picks W or X, i = (q / 2) % 2 the row-tile, j = q % 2 the k-block
     auto copy1 = [&](int st, int q) {
-        u32x4 (*slot)[64] = ring[st & (BSTAGES - 1)];
-        const int x = q >> 2, i = (q >> 1) & 1, j = q & 1;
-        load_block_to_lds(src[2 * x + i] + ((size_t)st * 2 + j) * 64 + lane, &slot[16 * x + (wave * 2 + i) * 2 + j][0]);
+        load_block_to_lds(src[q] + (size_t)st * 128, &ring[st & (BSTAGES - 1)][wave * CW + q][0]);
     };
     auto issue = [&](int st) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) copy1(st, q);
+        for (int q = 0; q < CW; ++q) copy1(st, q);
     };
-    constexpr int kLoads = 8;  // copies per wavefront and stage
-    struct Ops { u32x4 a[4], b[4]; };
-    // LDS read q (0..7) of a k-block, in the order the matrix instructions below first need the operands:
-    // a0, b0, b1, b2, b3, a1, a2, a3
+    constexpr int C2 = CW / 2;  // copies 0 .. C2-1 of a stage go out in the second half of stage t-3, the rest in the first of t-2
+    struct Ops { u32x4 a[NA], b[4]; };
+    // LDS read q (0 .. NA+3) of a k-block, in the order the matrix instructions below first need the operands:
+    // a0, b0, b1, b2, b3, a1, a2, ...
+    constexpr int NR = NA + 4;
     auto read1 = [&](Ops& o, int st, int j, int q) {
         u32x4 (*slot)[64] = ring[st & (BSTAGES - 1)];
-        constexpr int ord[8] = {0, 4, 5, 6, 7, 1, 2, 3};
-        const int idx = ord[q];
-        if (idx < 4) o.a[idx] = slot[(wn * 4 + idx) * 2 + j][lane];
-        else o.b[idx - 4] = slot[16 + (wm * 4 + idx - 4) * 2 + j][lane];
+        if (q == 0) o.a[0] = slot[(wn * NA) * 2 + j][lane];
+        else if (q <= 4) o.b[q - 1] = slot[XOFF + (wm * 4 + q - 1) * 2 + j][lane];
+        else o.a[q - 4] = slot[(wn * NA + q - 4) * 2 + j][lane];
     };
     auto read_ops = [&](Ops& o, int st, int j) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) read1(o, st, j, q);
+        for (int q = 0; q < NR; ++q) read1(o, st, j, q);
     };
-    // matrix instruction n (0..15) of a k-block: accumulator tile (n / 4, n % 4)
-    auto mma1 = [&](const Ops& o, int n) { acc[n >> 2][n & 3] = mfma_f16(o.a[n >> 2], o.b[n & 3], acc[n >> 2][n & 3]); };
+    // matrix instruction n (0 .. 4 NA - 1) of a k-block: accumulator tile (n / 4, n % 4)
+    // (NA = 5: the tiles of the first four column blocks live in the accumulation registers, the fifth block's in
+    // the vector registers)
+    auto mma1 = [&](const Ops& o, int n) {
+        if constexpr (NA > 4) {
+            if ((n >> 2) < 4) mfma_f16_pinned<false>(acc[n >> 2][n & 3], o.a[n >> 2], o.b[n & 3]);
+            else mfma_f16_pinned<true>(acc[n >> 2][n & 3], o.a[n >> 2], o.b[n & 3]);
+        } else {
+            acc[n >> 2][n & 3] = mfma_f16(o.a[n >> 2], o.b[n & 3], acc[n >> 2][n & 3]);
+        }
+    };
     auto mma_all = [&](const Ops& o) {
 #pragma unroll
-        for (int n = 0; n < 16; ++n) mma1(o, n);
+        for (int n = 0; n < 4 * NA; ++n) mma1(o, n);
     };
-    // The copies of stage t are issued in two halves: its W blocks (q = 0..3) in the second half of stage t-3, its X
-    // blocks (q = 4..7) in the first half of stage t-2 -- the prologue issues what would fall before stage 0.
+    // The prologue issues what would fall before stage 0.
     issue(0);
     if (nstage >= 2) issue(1);
     if (nstage >= 3) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) copy1(2, q);
-        wait_vmcnt<kLoads + kLoads / 2>();
+        for (int q = 0; q < C2; ++q) copy1(2, q);
+        wait_vmcnt<CW + C2>();
     } else if (nstage == 2) {
-        wait_vmcnt<kLoads>();
+        wait_vmcnt<CW>();
     } else {
         wait_vmcnt<0>();
     }
@@ -365,53 +397,64 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
     Ops opa, opb;
     read_ops(opa, 0, 0);
     int s = 0;
-    // Steady state: stage s+1 and the W blocks of stage s+2 are in flight; the first half of stage s requests the X
-    // blocks of stage s+2 (into the slot stage s-2 left: everybody passed the barrier of stage s-1 since), the second
-    // half the W blocks of stage s+3 (into the slot of stage s-1, behind this stage's barrier).  Scheduling barriers
-    // keep the order written here.  The workgroup barrier is the bare instruction: what it orders are the copies,
-    // which the wait before it covers -- the LDS reads in flight across it belong to the stage in use, not to the
-    // slot about to be refilled (a fence would wait for them).
-    // In each half of a stage the first four pairs of matrix instructions are followed by two LDS reads each (the
-    // operands of the other half: the last of them is eight matrix instructions old when the half ends, so the wait
-    // for the reads at the top of a half finds them done), the last four by one copy each.
+    // Steady state: stage s+1 and the first copies of stage s+2 are in flight; the first half of stage s requests the
+    // rest of stage s+2 (into the slot stage s-2 left: everybody passed the barrier of stage s-1 since), the second
+    // half the first copies of stage s+3 (into the slot of stage s-1, behind this stage's barrier).  Scheduling
+    // barriers keep the order written here.  The workgroup barrier is the bare instruction: what it orders are the
+    // copies, which the wait before it covers -- the LDS reads in flight across it belong to the stage in use, not to
+    // the slot about to be refilled (a fence would wait for them).
+    // In each half of a stage (2 NA pairs of matrix instructions) the first pairs are followed by two LDS reads each
+    // (the operands of the other half: the last of them is at least eight matrix instructions old when the half
+    // ends, so the wait for the reads at the top of a half finds them done), the last ones by one copy each.
+    constexpr int NP = 2 * NA;  // pairs of matrix instructions per half
+    static_assert((NR + 1) / 2 + (CW - C2) <= NP, "reads and copies of a half fit behind its pairs");
     for (; s + 3 < nstage; ++s) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < NP; ++q) {
             mma1(opa, 2 * q);
             mma1(opa, 2 * q + 1);
-            if (q < 4) { read1(opb, s, 1, 2 * q); read1(opb, s, 1, 2 * q + 1); }
-            else copy1(s + 2, q);
+            if (2 * q < NR) {
+                read1(opb, s, 1, 2 * q);
+                if (2 * q + 1 < NR) read1(opb, s, 1, 2 * q + 1);
+            } else if (q >= NP - (CW - C2)) {
+                copy1(s + 2, C2 + q - (NP - (CW - C2)));
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_vmcnt<kLoads>();  // this wavefront's copies of stage s+1 have landed ...
+        wait_vmcnt<CW>();  // this wavefront's copies of stage s+1 have landed ...
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();  // ... and everybody's; everybody is done with stage s-1
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < NP; ++q) {
             mma1(opb, 2 * q);
             mma1(opb, 2 * q + 1);
-            if (q < 4) { read1(opa, s + 1, 0, 2 * q); read1(opa, s + 1, 0, 2 * q + 1); }
-            else copy1(s + 3, q - 4);
+            if (2 * q < NR) {
+                read1(opa, s + 1, 0, 2 * q);
+                if (2 * q + 1 < NR) read1(opa, s + 1, 0, 2 * q + 1);
+            } else if (q >= NP - C2) {
+                copy1(s + 3, q - (NP - C2));
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    for (; s < nstage; ++s) {  // the last three stages: only the X blocks of the last one are left to request
+    for (; s < nstage; ++s) {  // the last three stages: only the late copies of the last one are left to request
         if (s + 2 < nstage) {
 #pragma unroll
-            for (int q = 4; q < 8; ++q) copy1(s + 2, q);
+            for (int q = C2; q < CW; ++q) copy1(s + 2, q);
         }
         read_ops(opb, s, 1);
         mma_all(opa);
         if (s + 1 < nstage) {
-            if (s + 2 < nstage) wait_vmcnt<kLoads>();
+            if (s + 2 < nstage) wait_vmcnt<CW>();
             else wait_vmcnt<0>();
             __syncthreads();
             read_ops(opa, s + 1, 0);
         }
         mma_all(opb);
     }
+    if constexpr (NA > 4) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last matrix instructions' results are in
     // Epilogue.  The CU runs nothing else meanwhile, so it is written out per mode with everything that depends on
     // the row alone (sequence, cache position, row base address) computed once per 32-row block and everything
     // that depends on the column alone wave-uniform (the generic per-quad form recomputes both, with run-time
@@ -442,8 +485,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tiled256_kernel(const u32x4* __re
             kvrow = ((size_t)b * p.n_heads * p.max_seq + t) * p.d;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n32 = tn * BN + (wn * 4 + i) * 32;  // wave-uniform
+        for (int i = 0; i < NA; ++i) {
+            const int n32 = tn * BN + (wn * NA + i) * 32;  // wave-uniform
             if (n32 >= p.N) continue;
             if (MODE == MODE_STORE) {
 #pragma unroll
@@ -521,10 +564,38 @@ static bool use_big_tile(int M, int N) {
     return M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
 }
 
-// split_col: with a k-split on 256 x 256 tiles, the first column whose tiles are cut into k ranges (0: all of them)
+// How a many-row GEMM is cut into tiles of 256 rows: 64 na columns wide (na = 4 or 5), and, where the partial sums
+// may go through scratch (may_cut), the tiles of the columns from split_col on in ks = 2 k ranges.  The tiles come in
+// rounds of one per CU and a partly empty round costs a full one; the cost is in units of a whole 256-column tile.
+struct BigPlan { int na, ks, split_col; };
+static BigPlan big_plan(int M, int N, int KB, bool may_cut) {
+    const long cus = num_cus(), tm = (M + BM - 1) / BM;
+    may_cut = may_cut && KB % 4 == 0 && KB / 2 >= 8 * BSTAGES;
+    BigPlan best{4, 1, 0};
+    double best_cost = 1e30;
+    for (int na = 4; na <= 5; ++na) {
+        const long tn = (N + 64 * na - 1) / (64 * na);
+        // a 320-column tile is five quarters of the work, done with a tenth fewer operand bytes per flop
+        const double unit = na == 5 ? 1.25 * 0.98 : 1.0;
+        for (long s = 0; s <= (may_cut ? tn : 0); ++s) {  // s columns of tiles cut in two
+            const long whole = (tn - s) * tm, cutn = 2 * s * tm;
+            // a cut tile costs a little more than half (its own ramp and epilogue), and every cut column a second
+            // set of partial sums for the LayerNorm to read
+            const double cost = ((double)((whole + cus - 1) / cus) + 0.52 * (double)((cutn + cus - 1) / cus) + 0.004 * s) * unit;
+            if (cost < best_cost - 1e-9) {
+                best_cost = cost;
+                best = BigPlan{na, s ? 2 : 1, s ? (int)(tn - s) * 64 * na : 0};
+            }
+        }
+    }
+    return best;
+}
+
+// split_col: with a k-split on the big tiles, the first column whose tiles are cut into k ranges (0: all of them);
+// tile_na: their width as planned by the caller (0: plan here, no cut)
 template <int MODE>
 void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N, int M, const Epi& p, int ksplit = 1,
-                  int split_col = 0) {
+                  int split_col = 0, int tile_na = 0) {
     const int NT32 = (N + 31) / 32, MT32 = (M + 31) / 32;
     // (the scoring head's epilogue keeps a soft-max over all of a wavefront's accumulators: it does not fit next to 16 of them)
     const bool big = MODE != MODE_SCORE && use_big_tile(M, N);
@@ -536,11 +607,17 @@ void launch_tiled(hipStream_t s, const void* Wp, const void* Xhi, int KB, int N,
         if (big) {
             // (the bias through a pointer of its own: declared never to alias the outputs, its values can be fetched
             // with scalar loads, which do not queue behind the epilogue's stores)
-            const int split_tn = ksplit > 1 ? split_col / BN : tiles_n;  // without a k-split every tile is whole
-            const int whole = split_tn * tiles_m, cutn = (tiles_n - split_tn) * tiles_m * ksplit;
+            const int na = tile_na ? tile_na : big_plan(M, N, KB, false).na;
+            const int bn = 64 * na, tn_big = (N + bn - 1) / bn;
+            const int split_tn = ksplit > 1 ? split_col / bn : tn_big;  // without a k-split every tile is whole
+            const int whole = split_tn * tiles_m, cutn = (tn_big - split_tn) * tiles_m * ksplit;
             const int grid2 = (whole + 7) / 8 * 8 + (cutn + 7) / 8 * 8;
-            gemm_tiled256_kernel<MODE><<<grid2, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias, KB,
-                                                             NT32, MT32, tiles_n, tiles_m, ksplit, split_tn, p);
+            if (na == 5)
+                gemm_tiled256_kernel<MODE, 5><<<grid2, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias,
+                                                                    KB, NT32, MT32, tn_big, tiles_m, ksplit, split_tn, p);
+            else
+                gemm_tiled256_kernel<MODE, 4><<<grid2, 256, 0, s>>>((const u32x4*)Wp, (const u32x4*)Xhi, (const u32x4*)p.bias,
+                                                                    KB, NT32, MT32, tn_big, tiles_m, ksplit, split_tn, p);
             return;
         }
     }
@@ -610,29 +687,21 @@ int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
     return best;
 }
 
-// The same decision for the 256 x 256 tiles, which can cut the tiles of the last columns only: *split_col is the
-// first column whose tiles are cut into *ks k ranges (0: all; columns before it get one whole-k sum).  The whole
-// tiles come first, in rounds of one per CU, and the cut ones fill the last, shorter round: 640 tiles on 256 CUs
-// are two rounds of whole tiles and one of 256 half tiles, with a second set of partial sums for a fifth of the
-// columns only.  Other tile shapes: bf16_tiled_store_ksplit, every tile cut.
-void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col) {
+// The same decision for the big tiles, which can cut the tiles of the last columns only: *split_col is the first
+// column whose tiles are cut into *ks k ranges (0: all; columns before it get one whole-k sum), *na the tiles' width
+// in 64 columns.  The whole tiles come first, in rounds of one per CU, and the cut ones fill the last, shorter round:
+// 640 tiles of 256 columns on 256 CUs are two rounds of whole tiles and one of 256 half tiles, with a second set of
+// partial sums for a fifth of the columns only (and 512 tiles of 320 columns are two rounds with nothing to cut).
+// Other tile shapes: bf16_tiled_store_ksplit, every tile cut.
+void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col, int* na) {
     *ks = bf16_tiled_store_ksplit(M, N, K, capacity_floats);
     *split_col = 0;
-    const int KB = K / 16;
-    if (!use_big_tile(M, N) || KB % 4 || KB / 2 < 8 * BSTAGES || (size_t)2 * M * N > capacity_floats) return;
-    const long cus = num_cus(), tn = (N + BN - 1) / BN, tm = (M + BM - 1) / BM;
-    double best = 1e30;
-    int best_s = -1;
-    for (long s = 0; s <= tn; ++s) {  // s columns of tiles cut in two
-        const long whole = (tn - s) * tm, cutn = 2 * s * tm;
-        // in units of one whole-k tile; a cut tile costs a little more than half (its own ramp and epilogue),
-        // and every cut column a second set of partial sums for the LayerNorm to read
-        const double cost = (double)((whole + cus - 1) / cus) + 0.52 * (double)((cutn + cus - 1) / cus) + 0.004 * s;
-        if (cost < best - 1e-9) { best = cost; best_s = (int)s; }
-    }
-    if (best_s == 0) { *ks = 1; return; }
-    *ks = 2;
-    *split_col = (int)(tn - best_s) * BN;
+    *na = 0;
+    if (!use_big_tile(M, N)) return;
+    const BigPlan g = big_plan(M, N, K / 16, (size_t)2 * M * N <= capacity_floats);
+    *ks = g.ks;
+    *split_col = g.split_col;
+    *na = g.na;
 }
 
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,
@@ -644,7 +713,7 @@ void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void*
     bf16_gemm_args st = a;
     st.out = part; st.out_split = part_split;
     const Epi ps = make_epi(M, N, st);
-    launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, ps, ksplit, a.split_col);
+    launch_tiled<MODE_STORE>(s, Wp, Xhi, K / 16, N, M, ps, ksplit, a.split_col, a.tile_na);
     if (mode == EPI_STORE) return;  // the consumer (a LayerNorm) adds the partial sums
     const Epi p = make_epi(M, N, a);
     const unsigned grid = (unsigned)(((size_t)M * (N / 4) + 255) / 256);

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(THREADS) void ln_row_kernel(float* __restrict__ r, 
             pb[j] = make_uint2(0, 0);
             if (i >= nq) continue;
             y0[j] = *reinterpret_cast<const float4*>(part + src * H + 4 * i);
-            // (columns before split_col have one whole sum; a multiple of 256, so the test is the same for a wavefront)
+            // (columns before split_col have one whole sum; a multiple of 256 or 320)
             if (ksplit == 2 && 4 * i >= split_col) y1[j] = *reinterpret_cast<const float4*>(part + part_split + src * H + 4 * i);
             pb[j] = *reinterpret_cast<const uint2*>(pbias + 4 * i);
         }
@@ -309,7 +309,7 @@ void bf16_wvec(hipStream_t s, const void* Wp, int N, int K, const void* gamma, c
 void bf16_ln(hipStream_t s, float* r, const float* part, int ksplit, size_t part_split, const void* pbias,
              const void* gamma, const void* beta, void* a_blocks, int rows, int H, float eps, int in_mul, int in_add,
              int writeback, int split_col) {
-    if (split_col && (ksplit != 2 || split_col % 256)) split_col = 0;  // (only the two-range form knows partly cut rows)
+    if (ksplit != 2) split_col = 0;  // (only the two-range form knows partly cut rows)
     const int nv = (H / 4 + 1023) / 1024, nv256 = (H / 4 + 255) / 256;
 #define HE_LN_ROW(NV, T)                                                                                                \
     ln_row_kernel<NV, T><<<(T == 256 ? (rows + 255) / 256 * 256 : rows), T, 0, s>>>(                                    \

@@ -269,9 +269,9 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
     const size_t split = (size_t)M * H;
     // k ranges per tile of the two GEMMs whose partial sums the next LayerNorm adds, and the first column whose
     // tiles are cut at all
-    int kso, sco, ks2, sc2;
-    bf16_tiled_store_split(M, H, H, e->part_floats, &kso, &sco);
-    bf16_tiled_store_split(M, H, F, e->part_floats, &ks2, &sc2);
+    int kso, sco, nao, ks2, sc2, na2;
+    bf16_tiled_store_split(M, H, H, e->part_floats, &kso, &sco, &nao);
+    bf16_tiled_store_split(M, H, F, e->part_floats, &ks2, &sc2, &na2);
     int pend_ks = 1, pend_sc = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const he_layer_weights& lw = e->layers[l];
@@ -282,12 +282,12 @@ void pass_tiled_bf16(he_engine* e, const int32_t* d_ids, int id_stride, int B, i
         bf16_gemm_tiled(s, EPI_QKV, tw.wqkv, e->ablk, M, 3 * H, H, a);
         if (l == c.n_layers - 1 && !full) break;
         bf16_attn(s, e->qbuf, e->kv, e->oblk, e->st, M, Sp, l, H, c.n_heads, c.max_batch, c.max_seq_len);
-        a = base; a.split_col = sco;
+        a = base; a.split_col = sco; a.tile_na = nao;
         bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.wo, e->oblk, M, H, H, kso, e->part, split, a);
         bf16_ln(s, e->resid, e->part, kso, split, lw.bo, lw.ln2_g, lw.ln2_b, e->ablk, M, H, c.ln_eps, 1, 0, 1, sco);
         a = base; a.bias = lw.b1; a.out_blocks = e->hblk;
         bf16_gemm_tiled(s, EPI_BIAS_RELU, tw.w1, e->ablk, M, F, H, a);
-        a = base; a.split_col = sc2;
+        a = base; a.split_col = sc2; a.tile_na = na2;
         bf16_gemm_tiled_ksplit(s, EPI_STORE, tw.w2, e->hblk, M, H, F, ks2, e->part, split, a);
         pend = e->part; pend_b = lw.b2; pend_ks = ks2; pend_sc = sc2;
     }

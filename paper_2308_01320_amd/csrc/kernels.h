@@ -46,7 +46,8 @@ struct bf16_gemm_args {
     const void* bias = nullptr;      // bf16 [N]
     float* out = nullptr;            // EPI_STORE: partials [ksplit][M][N]; EPI_QKV: q [M][H]
     size_t out_split = 0;            // elements between k-splits
-    int split_col = 0;               // EPI_STORE on 256 x 256 tiles with a k-split: first column that has one
+    int split_col = 0;               // EPI_STORE on the big tiles with a k-split: first column that has one
+    int tile_na = 0;                 // ... and the tiles' width as bf16_tiled_store_split planned it
     size_t out_capacity = 0;         // EPI_STORE_LN: floats `out` can hold (0 = not checked)
     void* out_blocks = nullptr;      // EPI_BIAS_RELU: tiled half output
     void* kv = nullptr;              // EPI_QKV
@@ -107,7 +108,8 @@ int bf16_tiled_ksplit(int M, int N, int K);
 // (1 if they do, or if ks x M x N partial sums do not fit capacity_floats)
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats);
 // ... and for the 256 x 256 tiles: *ks k ranges for the tiles of columns >= *split_col, one for the columns before
-void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col);
+// (*na: the tiles' width in 64 columns, to be handed on in bf16_gemm_args.tile_na; 0 for other tile shapes)
+void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col, int* na);
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, int ksplit,
                             float* part, size_t part_split, const bf16_gemm_args& a);
 // ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row
