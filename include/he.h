@@ -344,6 +344,14 @@ he_status he_decode_scratch_account(const he_config* cfg, int B, int which, int 
  * clears them all: between calls the answer is 0.  bf16, impl 0 only. */
 he_status he_arrival_counters_nonzero(he_engine* e, int* nonzero);
 
+/* Test hook, host logic only: how a GEMM of a prompt or scoring pass (M rows, [N, K] weights) is cut into tiles on
+ * `cus` compute units (0 = the current device's count, 256 if there is none).  *tile_cols: columns of a tile (256 or
+ * 320 with 256 rows; 0 if the pass is too small for these tiles and takes the 256 x 128 ones); *ksplit, *split_col:
+ * with may_cut (the out-projection and FC2, whose partial sums the following LayerNorm adds; scratch_floats floats
+ * of scratch, 0 = unlimited), the tiles of columns >= *split_col are cut into *ksplit k ranges (1: none are). */
+he_status he_plan_prompt_gemm(int M, int N, int K, int may_cut, size_t scratch_floats, int cus, int* tile_cols,
+                              int* ksplit, int* split_col);
+
 /* Measurement hook: a plain copy kernel (reads `bytes`, writes `bytes`, a multiple of 16,
  * device pointers, on `stream`).  Hardware byte counters (rocprofv3 FETCH_SIZE /
  * WRITE_SIZE) are scaled by what they read for this kernel of known size. */

@@ -131,6 +131,9 @@ def lib() -> C.CDLL:
     L.he_arrival_counters_nonzero.argtypes = [vp, C.POINTER(C.c_int)]
     L.he_last_step_rows.restype = C.c_int
     L.he_last_step_rows.argtypes = [vp]
+    L.he_plan_prompt_gemm.restype = C.c_int
+    L.he_plan_prompt_gemm.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_int, C.POINTER(C.c_int),
+                                      C.POINTER(C.c_int), C.POINTER(C.c_int)]
     L.he_kernel_sweep.restype = C.c_int
     L.he_kernel_sweep.argtypes = [vp, C.c_int, C.c_int]
     L.he_calibration_copy.restype = C.c_int
@@ -147,7 +150,8 @@ EXPORTS = ("he_workspace_bytes", "he_create", "he_refresh_weights", "he_prefill"
            "he_tile_matrix", "he_score", "he_prefill_ragged",
            "he_generate_ragged", "he_refresh_weights_lora", "he_release_arena", "he_acquire_arena",
            "he_tile_matrix_lora", "he_plan_decode_gemm", "he_fp8_quantize_rows", "he_decode_step_static",
-           "he_decode_scratch_account", "he_arrival_counters_nonzero", "he_last_step_rows")
+           "he_decode_scratch_account", "he_arrival_counters_nonzero", "he_last_step_rows",
+           "he_plan_prompt_gemm")
 
 KERNEL_CLASSES = ("layernorm", "qkv", "attention", "out_proj", "fc1", "fc2", "lm_head", "empty")
 
@@ -394,6 +398,15 @@ def he_plan_decode_gemm(M, N, K, ksplit_allowed=False, scratch_floats=0, cus=256
     if rc != HE_OK:
         raise HeError(rc, "he_plan_decode_gemm")
     return u.value, n.value, k.value
+
+
+def he_plan_prompt_gemm(M, N, K, may_cut=False, scratch_floats=0, cus=256):
+    """(tile columns, k ranges, first cut column) of a prompt-pass GEMM; host logic only."""
+    t, k, c = C.c_int(), C.c_int(), C.c_int()
+    rc = lib().he_plan_prompt_gemm(M, N, K, 1 if may_cut else 0, scratch_floats, cus, C.byref(t), C.byref(k), C.byref(c))
+    if rc != HE_OK:
+        raise HeError(rc, "he_plan_prompt_gemm")
+    return t.value, k.value, c.value
 
 
 def he_decode_scratch_account(cfg: he_config, B: int, which: int, cus: int = 256) -> he_scratch_account:

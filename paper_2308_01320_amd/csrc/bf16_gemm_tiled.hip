@@ -560,8 +560,10 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float2* __restr
 
 // Many rows (a prompt or scoring pass): 256 x 256 tiles, one workgroup per CU, once there are enough of them to
 // give every CU one.
+static int g_tiled_cus_override = 0;  // a planner query's CU count
+static int tiled_cus() { return g_tiled_cus_override > 0 ? g_tiled_cus_override : num_cus(); }
 static bool use_big_tile(int M, int N) {
-    return M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= num_cus();
+    return M >= 1024 && (long)((N + TN - 1) / TN) * ((M + 255) / 256) >= tiled_cus();
 }
 
 // How a many-row GEMM is cut into tiles of 256 rows: 64 na columns wide (na = 4 or 5), and, where the partial sums
@@ -569,7 +571,7 @@ static bool use_big_tile(int M, int N) {
 // rounds of one per CU and a partly empty round costs a full one; the cost is in units of a whole 256-column tile.
 struct BigPlan { int na, ks, split_col; };
 static BigPlan big_plan(int M, int N, int KB, bool may_cut) {
-    const long cus = num_cus(), tm = (M + BM - 1) / BM;
+    const long cus = tiled_cus(), tm = (M + BM - 1) / BM;
     may_cut = may_cut && KB % 4 == 0 && KB / 2 >= 8 * BSTAGES;
     BigPlan best{4, 1, 0};
     double best_cost = 1e30;
@@ -674,7 +676,7 @@ int bf16_tiled_ksplit(int M, int N, int K) {
 // last one fuller; the price is ks sets of partial sums for the following LayerNorm to add.
 int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats) {
     const bool big = use_big_tile(M, N);
-    const long slots = (big ? 1L : 2L) * num_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + (big ? 255 : 127)) / (big ? 256 : 128));
+    const long slots = (big ? 1L : 2L) * tiled_cus(), tiles = (long)((N + TN - 1) / TN) * ((M + (big ? 255 : 127)) / (big ? 256 : 128));
     const int KB = K / 16;
     if (tiles < slots || KB % 2) return 1;
     int best = 1;
@@ -702,6 +704,20 @@ void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks
     *ks = g.ks;
     *split_col = g.split_col;
     *na = g.na;
+}
+
+void bf16_tiled_plan_query(int M, int N, int K, int may_cut, size_t capacity_floats, int cus, int* tile_cols, int* ks,
+                           int* split_col) {
+    g_tiled_cus_override = cus;
+    *tile_cols = 0; *ks = 1; *split_col = 0;
+    if (use_big_tile(M, N)) {
+        const bool room = capacity_floats == 0 || (size_t)2 * M * N <= capacity_floats;
+        const BigPlan g = big_plan(M, N, K / 16, may_cut && room);
+        *tile_cols = 64 * g.na; *ks = g.ks; *split_col = g.split_col;
+    } else if (may_cut) {
+        *ks = bf16_tiled_store_ksplit(M, N, K, capacity_floats ? capacity_floats : (size_t)-1);
+    }
+    g_tiled_cus_override = 0;
 }
 
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* Xhi, int M, int N, int K,

@@ -1262,6 +1262,13 @@ he_status he_plan_decode_gemm(int M, int N, int K, int ksplit_allowed, size_t sc
     return HE_OK;
 }
 
+he_status he_plan_prompt_gemm(int M, int N, int K, int may_cut, size_t scratch_floats, int cus, int* tile_cols,
+                              int* ksplit, int* split_col) {
+    if (M < 1 || N < 1 || K < 1 || N % 32 || K % 32 || cus < 0 || !tile_cols || !ksplit || !split_col) return HE_ERR_INVALID_ARG;
+    bf16_tiled_plan_query(M, N, K, may_cut, scratch_floats, cus, tile_cols, ksplit, split_col);
+    return HE_OK;
+}
+
 he_status he_decode_scratch_account(const he_config* cfg, int B, int which, int cus, he_scratch_account* out) {
     if (!out || check_config(cfg) || check_shape(cfg) || !is_fast(*cfg)) return HE_ERR_INVALID_ARG;
     if (B < 1 || B > cfg->max_batch || B > 64 || (which != 0 && which != 1) || cus < 0) return HE_ERR_INVALID_ARG;

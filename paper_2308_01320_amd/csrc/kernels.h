@@ -110,6 +110,9 @@ int bf16_tiled_store_ksplit(int M, int N, int K, size_t capacity_floats);
 // ... and for the 256 x 256 tiles: *ks k ranges for the tiles of columns >= *split_col, one for the columns before
 // (*na: the tiles' width in 64 columns, to be handed on in bf16_gemm_args.tile_na; 0 for other tile shapes)
 void bf16_tiled_store_split(int M, int N, int K, size_t capacity_floats, int* ks, int* split_col, int* na);
+// The plan of a many-row GEMM for a planner query (cus: compute units to plan for, 0 = the current device's)
+void bf16_tiled_plan_query(int M, int N, int K, int may_cut, size_t capacity_floats, int cus, int* tile_cols, int* ks,
+                           int* split_col);
 void bf16_gemm_tiled_ksplit(hipStream_t s, int mode, const void* Wp, const void* X, int M, int N, int K, int ksplit,
                             float* part, size_t part_split, const bf16_gemm_args& a);
 // ---- 8-bit weight storage: E4M3 codes with one power-of-two scale per row

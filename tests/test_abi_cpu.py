@@ -105,6 +105,44 @@ def test_decode_gemm_plans_fit_the_chip_and_the_scratch():
         binding.he_plan_decode_gemm(32, 100, 64)
 
 
+def test_prompt_gemm_plans_fill_the_chip_in_whole_rounds():
+    """Host logic of the prompt-pass tile planner: tiles come in rounds of one per CU and a partly empty round costs a
+    full one, so the plan picks the tile width (256 or 320 columns) and, for the GEMMs whose partial sums a LayerNorm
+    adds, the columns to cut along k so that the rounds come out even."""
+    import math
+    # OPT-13B layer shape, batch 32 x prompt 256 = 8192 rows, 256 CUs: 320-column tiles divide everything
+    assert binding.he_plan_prompt_gemm(8192, 15360, 5120) == (320, 1, 0)            # QKV: 48 x 32 tiles = six rounds
+    assert binding.he_plan_prompt_gemm(8192, 20480, 5120) == (320, 1, 0)            # FC1: eight rounds
+    assert binding.he_plan_prompt_gemm(8192, 5120, 5120, True) == (320, 1, 0)       # out-projection: two rounds, no cut
+    assert binding.he_plan_prompt_gemm(8192, 5120, 20480, True) == (320, 1, 0)
+    # ... and the scoring pass over 16384 rows
+    assert binding.he_plan_prompt_gemm(16384, 5120, 20480, True) == (320, 1, 0)
+    # hidden size 4096 (16 x 256 prompt rows): 256-column tiles fill whole rounds as they are
+    assert binding.he_plan_prompt_gemm(4096, 12288, 4096) == (256, 1, 0)
+    assert binding.he_plan_prompt_gemm(4096, 4096, 4096, True) == (256, 1, 0)
+    # OPT-66B layer shape, 8 x 256 rows: 29 x 8 = 232 tiles of 320 columns are one round (288 of 256 columns: two)
+    assert binding.he_plan_prompt_gemm(2048, 9216, 9216, True) == (320, 1, 0)
+    # the same width with 32 x 256 rows: 36 x 32 = 1152 tiles of 256 columns; the last four columns of tiles are cut
+    # in two (four rounds of whole tiles, then 256 half tiles); without scratch for a second set of sums nothing can
+    # be cut, and 320-column tiles (928: four rounds) are the better of the whole-tile plans
+    assert binding.he_plan_prompt_gemm(8192, 9216, 9216, True) == (256, 2, 8192)
+    assert binding.he_plan_prompt_gemm(8192, 9216, 9216, True, 8192 * 9216) == (320, 1, 0)
+    assert binding.he_plan_prompt_gemm(8192, 9216, 9216, False) == (320, 1, 0)
+    # too few rows or tiles for the big tiles
+    assert binding.he_plan_prompt_gemm(512, 5120, 5120)[0] == 0
+    # general: whatever is picked, the whole tiles and the cut ones cover every column exactly once
+    for M in (1024, 2048, 4096, 8192, 16384):
+        for (N, K) in ((6144, 2048), (2048, 8192), (12288, 4096), (16384, 4096), (15360, 5120), (5120, 20480), (27648, 9216)):
+            for cus in (64, 256, 304):
+                cols, ks, split = binding.he_plan_prompt_gemm(M, N, K, True, 0, cus)
+                if cols == 0:
+                    continue
+                assert cols in (256, 320) and ks in (1, 2) and 0 <= split < cols * math.ceil(N / cols)
+                assert split % cols == 0 and (ks == 2 or split == 0), (M, N, K, cus, cols, ks, split)
+    with pytest.raises(binding.HeError):
+        binding.he_plan_prompt_gemm(8192, 100, 64)
+
+
 def test_ksplit_hand_off_stays_inside_what_he_create_reserves():
     """The invariant the k-split hand-off of the decode out-projection / FC2 rests on.  Partial sums cross
     workgroups inside one launch through scratch, every (column group, row slice, split) in words of its own, with
