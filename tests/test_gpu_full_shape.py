@@ -64,6 +64,50 @@ def test_headline_launch_shape_sampled_sequences_against_oracle():
     print("sampled sequences ok")
 
 
+@pytest.mark.parametrize("name,B,S,seqs", [
+    ("opt-66b", 8, 256, (0, 5)),     # 2048 rows: 320-column tiles whose last column of tiles hangs over the matrix
+    ("opt-6.7b", 16, 256, (3, 15)),  # 4096 rows: 256-column tiles in whole rounds
+    ("opt-1.3b", 32, 64, (0, 31)),   # 2048 rows at hidden size 2048: the big tiles with a short k range
+])
+def test_prompt_pass_at_other_benchmark_shapes_sampled_sequences(name, B, S, seqs):
+    """The prompt pass in the launch shapes of the other benchmark configurations (their batch and prompt length, one
+    layer): the whole batch through the engine, the oracle on two of its sequences alone; then two decode steps
+    teacher-forced on the engine's own ids."""
+    import torch
+    base = synth.CONFIGS[name]
+    G = 3
+    d = base.sliced(n_layers=1, batch=B, prompt_len=S, gen_len=G, max_positions=S + G)
+    w = synth.make_weights(d, seed=5)
+    prompts = synth.make_prompts(d, seed=6)
+    samp = binding.sampling("gumbel", 1.0, 42)
+    eng = util.make_engine(d, w, max_batch=B, max_seq_len=S + G)
+    p = torch.from_numpy(prompts).cuda()
+    ids, lgs = [], []
+    i, lp, lg = eng.he_prefill(p, samp, want_logits=True)
+    for n in range(G):
+        ids.append(i.cpu().numpy()), lgs.append(lg.cpu().numpy())
+        if n + 1 < G:
+            i, lp, lg = eng.he_decode_step(i, samp, want_logits=True)
+    torch.cuda.synchronize()
+    eng.he_destroy()
+    w64 = _f64(w)
+    for b in seqs:
+        dec = O.CachedDecoder(w64, d.n_heads, d.ln_eps, d.pos_offset)
+        z = dec.prefill(prompts[b:b + 1])
+        for n in range(G):
+            err = float(np.abs(lgs[n][b] - z[0]).max())
+            print(name, "sequence", b, "step", n, "logit err", err, flush=True)
+            assert err <= BF16_TOL, (b, n, err)
+            score = z[0] + O.gumbel_noise(42, b, n, d.vocab)
+            order = np.argsort(score)
+            if score[order[-1]] - score[order[-2]] > MARGIN:
+                assert ids[n][b] == order[-1], (b, n)
+            else:
+                assert ids[n][b] in (order[-1], order[-2]), (b, n)
+            if n + 1 < G:
+                z = dec.step(ids[n][b:b + 1])
+
+
 @pytest.mark.parametrize("name,B,S,G", [
     ("opt-13b", 2, 498, 15),   # 40 heads of 128: contexts 499 .. 512, the benchmark's last steps and its capacity limit
     ("opt-66b", 2, 300, 4),    # 72 heads of 128
