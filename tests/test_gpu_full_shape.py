@@ -66,6 +66,8 @@ def test_headline_launch_shape_sampled_sequences_against_oracle():
 
 @pytest.mark.parametrize("name,B,S,seqs", [
     ("opt-66b", 8, 256, (0, 5)),     # 2048 rows: 320-column tiles whose last column of tiles hangs over the matrix
+    ("opt-66b", 32, 256, (1, 30)),   # 8192 rows at that width: out-projection and FC2 on 256-column tiles whose last four
+                                     # columns of tiles are cut into two k ranges (the LayerNorm adds partly cut rows)
     ("opt-6.7b", 16, 256, (3, 15)),  # 4096 rows: 256-column tiles in whole rounds
     ("opt-1.3b", 32, 64, (0, 31)),   # 2048 rows at hidden size 2048: the big tiles with a short k range
 ])
