@@ -173,11 +173,12 @@ def test_bf16_real_layer_shapes(name, L, B, S, G):
 
 
 def test_generate_graph_replay_matches_step_by_step():
-    """he_generate on a stream of its own replays a captured decode step; on the NULL stream it
-    launches step by step.  Same kernels, so ids and log-probs must be bit-identical -- on
-    every one of several calls, with other work and synchronisations in between."""
+    """he_generate on a stream of its own replays captured decode steps (runs of eight steps per graph launch, single
+    steps for the remainder: 44 steps here are five runs and four single steps); on the NULL stream it launches step
+    by step.  Same kernels, so ids and log-probs must be bit-identical -- on every one of several calls, with other
+    work and synchronisations in between."""
     import torch
-    d = synth.ModelDims("x", 2, 256, 4, 512, 1000, 128, 5, 9, 12, "bf16", "gumbel")
+    d = synth.ModelDims("x", 2, 256, 4, 512, 1000, 128, 5, 9, 45, "bf16", "gumbel")
     w = synth.make_weights(d, seed=5)
     prompts = torch.from_numpy(synth.make_prompts(d, seed=6)).cuda()
     samp = binding.sampling("gumbel", 1.0, 11)
